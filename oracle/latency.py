@@ -1,0 +1,276 @@
+"""Oracle, part 2: the performance estimator.  TEST INFRASTRUCTURE.
+
+Follows the paper's Section 2.2.1 (wave quantisation: waves, tail, idle ratio), Section
+3.2.2 (SM-scaling roofline model, Eq. 1, and the calibration factor alpha, Eq. 2, with
+linear inter/extrapolation between sampled execution states), Section 3.2.3 (decode
+uses the bandwidth D_{p,sl} measured next to an sl-token prefill) — in the paper's
+order and notation. "SM" in the paper is "CU" here.
+
+All arithmetic on the decision path is integer (Python ints): nanoseconds, flop,
+bytes, flop/ns, bytes/ns and alpha in parts per million, with floor division, so that
+a second implementation can reproduce every number bit for bit.
+
+Readings where the paper is silent (listed in the design document):
+  * kernel flop/byte counts are closed forms of the layer shapes (the paper takes them
+    from a model viewer); activations and weights count 2 bytes per element
+  * wave quantisation enters as T'_k / (1 - idle_k) for prefill GEMM and attention
+    kernels before alpha is applied; a switch in the profile turns it off
+  * alpha is sampled on a rectilinear grid — prefill over (CUs, new tokens), decode over
+    (CUs, batch size, total context) — and interpolated multilinearly, extrapolated
+    from the nearest segment outside the grid, clamped to half the smallest sample
+  * a phase with zero CUs has latency INF_NS
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from fractions import Fraction
+
+INF_NS = 1 << 60
+PPM = 1_000_000
+
+
+# ------------------------------------------------------------------ Section 2.2.1
+def wave_quant(g: int, n: int, b: int = 1):
+    """Waves w, active units in the last wave `tail`, and the idle ratio (exact Fraction)
+    of a kernel with g workgroups on n units holding b workgroups each."""
+    w = -(-g // (b * n))
+    tail = -(-(g - b * n * (w - 1)) // b)          # ceil(g/b - n (w-1))
+    return w, tail, Fraction(n - tail, n * w)
+
+
+# ------------------------------------------------------------------ profile (hardware + samples)
+@dataclass
+class Grid:
+    """Samples on a rectilinear grid: axes[i] ascending ints, values nested lists."""
+    axes: list
+    values: list
+
+    def min_value(self):
+        def walk(v):
+            return min(walk(x) for x in v) if isinstance(v, list) else v
+        return walk(self.values)
+
+
+@dataclass
+class Profile:
+    n_cu: int = 256
+    granule: int = 32
+    c_peak: int = 2_500_000            # flop per ns at all CUs
+    d_peak: int = 8_000                # bytes per ns
+    n_d: int = 64                      # CUs at which memory bandwidth saturates
+    tile_m: int = 256
+    tile_n: int = 256
+    tile_q: int = 128
+    use_waveq: int = 1
+    bw: Grid | None = None             # D_{p,sl}: axes (decode CUs, co-running prefill tokens) -> bytes/ns
+    alpha_prefill: Grid = field(default_factory=lambda: Grid([[256], [2048]], [[PPM]]))
+    alpha_decode: Grid = field(default_factory=lambda: Grid([[256], [64], [65536]], [[[PPM]]]))
+
+
+@dataclass(frozen=True)
+class Shape:
+    n_layers: int
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    mlp: int
+    vocab: int
+
+
+def floor_div(a: int, b: int) -> int:
+    return a // b
+
+
+def interp(grid_axes, values, x) -> int:
+    """Multilinear interpolation on a rectilinear grid, first axis outermost; outside the
+    grid the nearest segment is extended. Integer arithmetic, floor at every stage."""
+    if not grid_axes:
+        return values
+    ax = grid_axes[0]
+    if len(ax) == 1:
+        return interp(grid_axes[1:], values[0], x[1:])
+    i = 0
+    while i + 2 < len(ax) and x[0] >= ax[i + 1]:
+        i += 1
+    v0 = interp(grid_axes[1:], values[i], x[1:])
+    v1 = interp(grid_axes[1:], values[i + 1], x[1:])
+    return v0 + floor_div((v1 - v0) * (x[0] - ax[i]), ax[i + 1] - ax[i])
+
+
+def alpha_at(grid: Grid, x) -> int:
+    return max(interp(grid.axes, grid.values, list(x)), grid.min_value() // 2, 1)
+
+
+# ------------------------------------------------------------------ kernel work counts
+def _cdiv(a, b):
+    return -(-a // b)
+
+
+def prefill_kernels(s: Shape, hw: Profile, reqs, with_head: bool):
+    """One layer of prefill for requests [(sl_i, p_i)]: (name, flop, bytes, workgroups or 0).
+    The head entry (final norm + LM head for one row per request) is appended when asked."""
+    h, d = s.hidden, s.head_dim
+    qd, kvd = s.n_q_heads * d, s.n_kv_heads * d
+    qkvn = qd + 2 * kvd
+    t = sum(sl for sl, _ in reqs)
+    tm, tn = hw.tile_m, hw.tile_n
+    rows = _cdiv(t, tm)
+    att_flop = sum(4 * qd * (sl * p + sl * (sl + 1) // 2) for sl, p in reqs)
+    att_mem = sum(2 * (2 * sl * qd + 2 * (p + sl) * kvd) for sl, p in reqs)
+    att_g = sum(_cdiv(sl, hw.tile_q) * s.n_q_heads for sl, _ in reqs)
+    ks = [("norm1", 4 * t * h, 4 * t * h, 0),
+          ("qkv", 2 * t * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * _cdiv(qkvn, tn)),
+          ("rope", 4 * t * qkvn, 4 * t * qkvn, 0),
+          ("attn", att_flop, att_mem, att_g),
+          ("o", 2 * t * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * _cdiv(h, tn)),
+          ("norm2", 4 * t * h, 4 * t * h, 0),
+          ("gateup", 4 * t * h * s.mlp, 2 * (2 * h * s.mlp + t * h + t * s.mlp), rows * _cdiv(2 * s.mlp, tn)),
+          ("down", 2 * t * s.mlp * h, 2 * (s.mlp * h + t * s.mlp + 2 * t * h), rows * _cdiv(h, tn))]
+    head = []
+    if with_head:
+        b = len(reqs)
+        head = [("head", 2 * b * h * s.vocab, 2 * (h * s.vocab + b * h + b * s.vocab), 0)]
+    return ks, head
+
+
+def decode_kernels(s: Shape, cls):
+    """One layer of a decode step for contexts cl_i (the new token attends to cl_i + 1
+    positions), and the head."""
+    h, d = s.hidden, s.head_dim
+    qd, kvd = s.n_q_heads * d, s.n_kv_heads * d
+    qkvn = qd + 2 * kvd
+    b = len(cls)
+    ctx = sum(c + 1 for c in cls)
+    ks = [("norm1", 4 * b * h, 4 * b * h, 0),
+          ("qkv", 2 * b * h * qkvn, 2 * (h * qkvn + b * h + b * qkvn), 0),
+          ("rope", 4 * b * qkvn, 4 * b * qkvn, 0),
+          ("attn", 4 * qd * ctx, 2 * (2 * kvd * ctx + 2 * b * qd), 0),
+          ("o", 2 * b * qd * h, 2 * (qd * h + b * qd + 2 * b * h), 0),
+          ("norm2", 4 * b * h, 4 * b * h, 0),
+          ("gateup", 4 * b * h * s.mlp, 2 * (2 * h * s.mlp + b * h + b * s.mlp), 0),
+          ("down", 2 * b * s.mlp * h, 2 * (s.mlp * h + b * s.mlp + 2 * b * h), 0)]
+    head = [("head", 2 * b * h * s.vocab, 2 * (h * s.vocab + b * h + b * s.vocab), 0)]
+    return ks, head
+
+
+# ------------------------------------------------------------------ Section 3.2.2, Eq. 1
+def srm_ns(flop: int, mem: int, n_p: int, hw: Profile, d_override: int | None = None) -> int:
+    """T'_k on n_p CUs: flop / min(flop/mem * D_p, C_p) == max(flop / C_p, mem / D_p), with
+    C_p = C_peak n_p / N and D_p = D_peak min(1, n_p / N_d) (or a measured D)."""
+    t_c = floor_div(flop * hw.n_cu, hw.c_peak * n_p)
+    if d_override is not None:
+        t_m = floor_div(mem, max(d_override, 1))
+    else:
+        t_m = floor_div(mem * hw.n_d, hw.d_peak * min(n_p, hw.n_d))
+    return max(t_c, t_m)
+
+
+def _waveq_adjust(t: int, g: int, n_p: int) -> int:
+    w, tail, _ = wave_quant(g, n_p, 1)
+    return floor_div(t * n_p * w, n_p * w - n_p + tail)
+
+
+def prefill_roofline_ns(s: Shape, hw: Profile, reqs, pm: int, layer_begin: int, n_layers_step: int) -> int:
+    """T'_{p,ES}: the sum of T'_k over the kernels of `n_layers_step` layers (and the head
+    if the slice ends at the last layer)."""
+    with_head = layer_begin + n_layers_step >= s.n_layers
+    ks, head = prefill_kernels(s, hw, reqs, with_head)
+    per_layer = 0
+    for _, flop, mem, g in ks:
+        t = srm_ns(flop, mem, pm, hw)
+        if hw.use_waveq and g > 0:
+            t = _waveq_adjust(t, g, pm)
+        per_layer += t
+    total = per_layer * n_layers_step
+    for _, flop, mem, _ in head:
+        total += srm_ns(flop, mem, pm, hw)
+    return total
+
+
+def decode_roofline_ns(s: Shape, hw: Profile, cls, dm: int, co_prefill_tokens: int) -> int:
+    d_meas = None
+    if hw.bw is not None:
+        d_meas = max(interp(hw.bw.axes, hw.bw.values, [dm, co_prefill_tokens]), 1)
+    ks, head = decode_kernels(s, cls)
+    per_layer = sum(srm_ns(flop, mem, dm, hw, d_meas) for _, flop, mem, _ in ks)
+    return per_layer * s.n_layers + sum(srm_ns(flop, mem, dm, hw, d_meas) for _, flop, mem, _ in head)
+
+
+# ------------------------------------------------------------------ Eq. 2 and the prediction
+def alpha_from_measurement(t_measured_ns: int, t_roofline_ns: int) -> int:
+    """alpha = T_measured / T', in parts per million."""
+    return floor_div(t_measured_ns * PPM, max(t_roofline_ns, 1))
+
+
+def predict_prefill_ns(s: Shape, hw: Profile, reqs, pm: int, layer_begin: int, n_layers_step: int) -> int:
+    if pm <= 0 or not reqs:
+        return INF_NS if reqs else 0
+    t = prefill_roofline_ns(s, hw, reqs, pm, layer_begin, n_layers_step)
+    a = alpha_at(hw.alpha_prefill, [pm, sum(sl for sl, _ in reqs)])
+    return floor_div(t * a, PPM)
+
+
+def predict_decode_ns(s: Shape, hw: Profile, cls, dm: int, co_prefill_tokens: int) -> int:
+    if not cls:
+        return 0
+    if dm <= 0:
+        return INF_NS
+    t = decode_roofline_ns(s, hw, cls, dm, co_prefill_tokens)
+    a = alpha_at(hw.alpha_decode, [dm, len(cls), sum(cls)])
+    return floor_div(t * a, PPM)
+
+
+def latency_query(s: Shape, hw: Profile, es: dict):
+    """es: prefill_len[], prefill_ctx[], decode_ctx[], prefill_cus, decode_cus, layer_begin,
+    n_layers_step. Returns (prefill_ns for the slice, decode_ns for one step)."""
+    reqs = list(zip(es["prefill_len"], es["prefill_ctx"]))
+    co = sum(es["prefill_len"]) if es["prefill_cus"] > 0 else 0
+    return (predict_prefill_ns(s, hw, reqs, es["prefill_cus"], es["layer_begin"], es["n_layers_step"]),
+            predict_decode_ns(s, hw, list(es["decode_ctx"]), es["decode_cus"], co))
+
+
+# ------------------------------------------------------------------ profile file (text)
+def _flatten(v):
+    return [y for x in v for y in _flatten(x)] if isinstance(v, list) else [v]
+
+
+def _nest(flat, dims):
+    if len(dims) == 1:
+        return list(flat)
+    step = len(flat) // dims[0]
+    return [_nest(flat[i * step:(i + 1) * step], dims[1:]) for i in range(dims[0])]
+
+
+def dump_profile(hw: Profile) -> str:
+    lines = ["sts-profile 1"]
+    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "use_waveq"):
+        lines.append(f"{k} {getattr(hw, k)}")
+    for name in ("bw", "alpha_prefill", "alpha_decode"):
+        g = getattr(hw, name)
+        if g is None:
+            continue
+        lines.append(f"grid {name} {len(g.axes)}")
+        for ax in g.axes:
+            lines.append("axis " + " ".join(str(a) for a in ax))
+        lines.append("values " + " ".join(str(v) for v in _flatten(g.values)))
+    return "\n".join(lines) + "\n"
+
+
+def parse_profile(text: str) -> Profile:
+    hw = Profile()
+    lines = [l.split() for l in text.splitlines() if l.strip() and not l.startswith("#")]
+    assert lines[0] == ["sts-profile", "1"]
+    i = 1
+    while i < len(lines):
+        t = lines[i]
+        if t[0] == "grid":
+            name, nd = t[1], int(t[2])
+            axes = [[int(x) for x in lines[i + 1 + j][1:]] for j in range(nd)]
+            flat = [int(x) for x in lines[i + 1 + nd][1:]]
+            setattr(hw, name, Grid(axes, _nest(flat, [len(a) for a in axes])))
+            i += nd + 2
+        else:
+            setattr(hw, t[0], int(t[1]))
+            i += 1
+    return hw

@@ -1,0 +1,139 @@
+"""Pins of the latency-model oracle: the paper's printed wave-quantisation table, the
+worked roofline example, Eq. 1's two equivalent forms, and interpolation properties."""
+import os
+from fractions import Fraction
+
+import pytest
+
+from oracle import latency as L
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_table1():
+    rows = []
+    for line in open(os.path.join(GOLD, "wave_quant_table1.txt")):
+        if line.strip() and not line.startswith("#"):
+            seq, kern, g, pct = line.split()
+            rows.append((int(seq), kern, int(g), pct))
+    return rows
+
+
+def test_wave_quant_reproduces_paper_table1():
+    """Table 1 (108 SMs, one block per SM): idle percentages as printed."""
+    for seq, kern, g, pct in read_table1():
+        _, _, idle = L.wave_quant(g, 108, 1)
+        assert f"{float(idle) * 100:.1f}" == pct, (seq, kern, g, float(idle))
+
+
+def test_wave_quant_definitions():
+    # exact multiple: no idle; one extra block: a whole wave for one unit
+    assert L.wave_quant(216, 108) == (2, 108, Fraction(0))
+    w, tail, idle = L.wave_quant(217, 108)
+    assert (w, tail) == (3, 1) and idle == Fraction(107, 324)
+    # b blocks per unit: 2 per SM, 300 blocks on 108 SMs -> 2 waves, tail ceil(300/2 - 108) = 42
+    assert L.wave_quant(300, 108, 2)[:2] == (2, 42)
+    # the O-projection bound quoted in Section 2.2.2: 100 - idle = 59 % and 79 %
+    assert round(100 * (1 - L.wave_quant(64, 108)[2])) == 59
+    assert round(100 * (1 - L.wave_quant(256, 108)[2])) == 79
+
+
+def test_srm_worked_example_section_3_2_2():
+    """N = 108, N_d = 30: at 54 SMs bandwidth stays at peak and the plateau halves; at 20
+    SMs both drop (slope to 2/3, plateau to 20/108)."""
+    hw = L.Profile(n_cu=108, c_peak=1000, d_peak=100, n_d=30)
+    big = 10 ** 9
+    # memory-bound kernel (no flops): time = mem / D_p
+    assert L.srm_ns(0, big, 108, hw) == big // 100
+    assert L.srm_ns(0, big, 54, hw) == big // 100
+    assert L.srm_ns(0, big, 20, hw) == big * 30 // (100 * 20)
+    # compute-bound kernel (no bytes): time = flop / C_p
+    assert L.srm_ns(big, 0, 54, hw) == 2 * big // 1000
+    assert L.srm_ns(big, 0, 20, hw) == big * 108 // (1000 * 20)
+
+
+@pytest.mark.parametrize("n_p", [20, 30, 54, 108])
+@pytest.mark.parametrize("flop,mem", [(10 ** 12, 10 ** 9), (10 ** 9, 10 ** 9), (5 * 10 ** 10, 3 * 10 ** 9)])
+def test_eq1_min_form_equals_max_form(n_p, flop, mem):
+    hw = L.Profile(n_cu=108, c_peak=312_000, d_peak=1_555, n_d=30)
+    c_p = Fraction(hw.c_peak * n_p, hw.n_cu)
+    d_p = Fraction(hw.d_peak) * min(Fraction(1), Fraction(n_p, hw.n_d))
+    t_eq1 = Fraction(flop) / min(Fraction(flop, mem) * d_p, c_p)       # Eq. 1 as printed
+    assert abs(L.srm_ns(flop, mem, n_p, hw) - t_eq1) < 1
+
+
+def test_interp_reproduces_samples_and_is_linear_between():
+    axes = [[32, 128], [64, 256, 1024]]
+    vals = [[1_500_000, 1_300_000, 1_200_000], [1_100_000, 1_050_000, 1_000_000]]
+    for i, a in enumerate(axes[0]):
+        for j, b in enumerate(axes[1]):
+            assert L.interp(axes, vals, [a, b]) == vals[i][j]
+    assert L.interp(axes, vals, [32, 160]) == 1_400_000            # midway on the second axis
+    assert L.interp(axes, vals, [80, 64]) == 1_300_000             # midway on the first axis
+    # two samples along CUs are enough: extrapolation continues the line
+    assert L.interp([[64, 128]], [2_000_000, 1_000_000], [192]) == 0
+    assert L.interp([[64, 128]], [2_000_000, 1_000_000], [32]) == 2_500_000
+    g = L.Grid([[64, 128]], [2_000_000, 1_000_000])
+    assert L.alpha_at(g, [192]) == 500_000                          # clamped to half the smallest sample
+
+
+def test_alpha_roundtrip_eq2():
+    s = L.Shape(32, 4096, 32, 8, 128, 14336, 128256)
+    hw = L.Profile()
+    t = L.prefill_roofline_ns(s, hw, [(2048, 0)], 128, 0, 1)
+    a = L.alpha_from_measurement(3 * t // 2, t)
+    assert abs(a - 1_500_000) <= 1
+    hw.alpha_prefill = L.Grid([[128], [2048]], [[a]])
+    assert abs(L.predict_prefill_ns(s, hw, [(2048, 0)], 128, 0, 1) - 3 * t // 2) <= 2
+
+
+def test_work_counts_against_hand_totals():
+    """8B-shaped layer, 2048 new tokens: 893.4 GFLOP of GEMM and 34.4 GFLOP of causal
+    attention; decode batch of 64: 436.2 MB of weights per layer."""
+    s = L.Shape(1, 4096, 32, 8, 128, 14336, 128256)
+    ks, _ = L.prefill_kernels(s, L.Profile(), [(2048, 0)], False)
+    d = {k[0]: k for k in ks}
+    gemm = sum(d[k][1] for k in ("qkv", "o", "gateup", "down"))
+    assert gemm == 2 * 2048 * 218_103_808
+    assert abs(d["attn"][1] - 34.4e9) < 0.1e9
+    assert d["qkv"][3] == 8 * 24 and d["gateup"][3] == 8 * 112 and d["attn"][3] == 16 * 32
+    kd, head = L.decode_kernels(s, [1000] * 64)
+    w_bytes = sum(x[2] for x in kd if x[0] in ("qkv", "o", "gateup", "down"))
+    assert 436_207_616 <= w_bytes <= 436_207_616 * 1.03
+    assert dict((x[0], x[2]) for x in kd)["attn"] >= 64 * 1001 * 4096
+    assert head[0][2] >= 2 * 4096 * 128256
+
+
+def test_prediction_monotone_in_cus_and_inf_when_suspended():
+    s = L.Shape(32, 4096, 32, 8, 128, 14336, 128256)
+    hw = L.Profile(use_waveq=0)
+    prev = None
+    for n in range(32, 257, 32):
+        t = L.predict_prefill_ns(s, hw, [(2048, 0)], n, 0, 4)
+        d = L.predict_decode_ns(s, hw, [1024] * 64, n, 0)
+        if prev:
+            assert t <= prev[0] and d <= prev[1]
+        prev = (t, d)
+    assert L.predict_prefill_ns(s, hw, [(2048, 0)], 0, 0, 4) == L.INF_NS
+    assert L.predict_decode_ns(s, hw, [1024] * 64, 0, 0) == L.INF_NS
+    assert L.predict_decode_ns(s, hw, [], 0, 0) == 0
+
+
+def test_contention_table_replaces_d_p_for_decode():
+    s = L.Shape(1, 4096, 32, 8, 128, 14336, 1024)
+    hw = L.Profile()
+    hw.bw = L.Grid([[64, 128], [0, 4096]], [[3000, 2000], [5000, 4000]])
+    solo = L.decode_roofline_ns(s, hw, [1024] * 64, 64, 0)
+    co = L.decode_roofline_ns(s, hw, [1024] * 64, 64, 4096)
+    assert 1.45 < co / solo < 1.55                                   # 3000 -> 2000 bytes/ns
+    ks, head = L.decode_kernels(s, [1024] * 64)
+    assert abs(solo - sum(k[2] for k in ks + head) / 3000) < len(ks) + 2
+
+
+def test_profile_text_roundtrip():
+    hw = L.Profile(n_d=112, c_peak=1_234_567)
+    hw.bw = L.Grid([[32, 64], [0, 2048, 8192]], [[1600, 1500, 1400], [2700, 2500, 2300]])
+    hw.alpha_decode = L.Grid([[32, 256], [8, 64], [1000, 100000]],
+                             [[[1, 2], [3, 4]], [[5, 6], [7, 8]]])
+    hw2 = L.parse_profile(L.dump_profile(hw))
+    assert hw2 == hw
