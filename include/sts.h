@@ -1,0 +1,238 @@
+/* libsts — spatial-temporal prefill/decode sharing on one MI355X (gfx950): C ABI.
+ *
+ * The calls follow the serving method of arXiv 2504.19516: a transformer step in which a
+ * compute-bound prefill pass and a memory-bound decode pass run at the same time on disjoint
+ * compute-unit (CU) partitions of one GPU (Sections 3.1, 3.4, 3.5), a performance estimator
+ * (the SM-scaling roofline model, Section 3.2) that predicts each phase's latency on its
+ * partition, and an SLO-aware scheduler (Section 3.3, Algorithm 1) that picks the prefill
+ * batch, the layer slice and the CU split for each step.
+ *
+ * Conventions
+ *   - Every function returns 0 (STS_OK) or a negative STS_E* code; sts_strerror() names it.
+ *     STS_EHIP means a HIP runtime call failed: sts_last_hip_error() returns its code.
+ *   - Pointers are HOST pointers unless a parameter says "device". Host buffers are owned by
+ *     the caller and are only read or written during the call. All device memory, streams
+ *     and KV pages are owned by the library (allocated in sts_init, released in sts_destroy).
+ *   - Calls are synchronous: outputs are complete when the call returns.
+ *   - One control thread per phase may call concurrently (sts_prefill_* next to
+ *     sts_decode_step) as long as they touch disjoint sequences; page allocation is
+ *     serialised internally (Section 3.5.1). Everything else is single-threaded.
+ *   - sts_profile_*, sts_latency_*, sts_wave_quant, sts_sched_* touch no GPU state and work on
+ *     a host without a GPU.
+ *   - Without a usable GPU sts_init fails with STS_EHIP; there is no CPU fallback.
+ */
+#ifndef STS_H
+#define STS_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { STS_OK = 0, STS_EINVAL = -1, STS_ENOMEM = -2, STS_ESTATE = -3, STS_EHIP = -4, STS_EIO = -5 };
+const char* sts_strerror(int code);
+int sts_last_hip_error(void);
+
+typedef struct sts_ctx sts_ctx;
+typedef struct sts_profile sts_profile;
+
+/* Model shape: Llama-style decoder blocks (Section 2.1: QKV projection, self-attention,
+ * output projection, MLP, element-wise operations between them) with RMSNorm, rotary
+ * embedding (half-split pairing), grouped-query attention, SwiGLU, no biases.
+ * Requirements: head_dim 64 or 128; page_tokens 16; hidden, mlp multiples of 64;
+ * (n_q_heads + 2 n_kv_heads) * head_dim, hidden, 2*mlp and vocab multiples of 128. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp, vocab, page_tokens;
+  float rope_theta, rms_eps;
+} sts_model_desc;
+
+typedef struct {
+  uint64_t weight_seed;        /* seed of the on-device weight generator */
+  int32_t init_weights;        /* 1: generate N(0,0.02)-like weights on device (norm gains = 1);
+                                  0: leave weights zero, caller uses sts_load_weights */
+  int32_t kv_pool_pages;       /* pages in the shared KV pool; a page holds page_tokens tokens of every layer */
+  int32_t max_prefill_tokens;  /* rows of the prefill activation workspace (sum over a batch) */
+  int32_t max_prefill_seqs;    /* sequences per prefill batch */
+  int32_t max_decode_batch;    /* requests per decode step */
+  int32_t max_seqs;            /* live sequences */
+  int32_t max_pages_per_seq;   /* block-table length */
+} sts_init_params;
+
+/* ---- lifetime (Section 3.5.1: weights and the KV pool are allocated once, before serving,
+ *      and shared by both phases) */
+int sts_init(const sts_model_desc* desc, const sts_init_params* params, sts_ctx** out);
+int sts_destroy(sts_ctx* ctx);
+
+/* Weights. `name`: "emb", "lm" (layer ignored), "wq","wk","wv","wo","wg","wu","wd" (matrices,
+ * row-major [out_features, in_features] fp32, rounded to bf16 on upload) or "g1","g2","gf"
+ * (gains, fp32 [hidden]). `count` = number of fp32 elements and must match the tensor. */
+int sts_load_weights(sts_ctx* ctx, int32_t layer, const char* name, const float* host, size_t count);
+int sts_read_weights(sts_ctx* ctx, int32_t layer, const char* name, float* host, size_t count);
+
+/* ---- sequences and the paged KV cache (Section 3.5.1). Token t of a sequence lives in page
+ *      block_table[t / page_tokens], slot t % page_tokens, in every layer. */
+int sts_seq_create(sts_ctx* ctx, int32_t* seq_out);
+int sts_seq_free(sts_ctx* ctx, int32_t seq);                       /* pages return to the pool */
+int sts_seq_length(sts_ctx* ctx, int32_t seq, int32_t* len_out);
+int sts_seq_reserve(sts_ctx* ctx, int32_t seq, int32_t n_tokens);  /* make pages cover n_tokens; STS_ENOMEM leaves state unchanged */
+int sts_pages_free(sts_ctx* ctx, int32_t* n_out);
+/* Test hooks. set_block_table: give an EMPTY sequence these pool pages, in this order (they are
+ * taken from the free list; STS_EINVAL if any is in use). get_block_table copies up to cap entries. */
+int sts_seq_set_block_table(sts_ctx* ctx, int32_t seq, const int32_t* pages, int32_t n);
+int sts_seq_get_block_table(sts_ctx* ctx, int32_t seq, int32_t* pages, int32_t cap, int32_t* n_out);
+/* Write / read K and V of positions [pos0, pos0+n) of one layer, fp32 [n, n_kv_heads, head_dim]
+ * (rounded to bf16 on write). kv_write extends the sequence length to pos0+n if shorter.
+ * kv_fill_random fills positions [0, n) of EVERY layer with unit-variance deviates of the
+ * library's counter-based generator (synthetic contexts) and sets the length to n. */
+int sts_kv_write(sts_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_t n, const float* k, const float* v);
+int sts_kv_read(sts_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_t n, float* k, float* v);
+int sts_kv_fill_random(sts_ctx* ctx, int32_t seq, int32_t n, uint64_t seed);
+
+/* ---- the step (Sections 3.3.1 and 3.5.2)
+ * Prefill: append lens[i] new tokens to sequence seqs[i] (after whatever it already caches)
+ * and run layers [layer_begin, layer_end) — the layer slice the scheduler launches per step.
+ * Slices of one batch must be issued in order, starting at 0, with the same batch; the hidden
+ * state stays on the device in between (STS_ESTATE otherwise). When layer_end == n_layers the
+ * sequences' lengths grow and, if `logits` is not NULL, the last token's logits of each
+ * sequence are written to logits[n_seqs, vocab] (fp32). tokens: all sequences' new tokens
+ * concatenated. STS_ENOMEM (pool exhausted) leaves every sequence unchanged. */
+int sts_prefill_batch(sts_ctx* ctx, int32_t n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                      int32_t layer_begin, int32_t layer_end, float* logits);
+int sts_prefill_append(sts_ctx* ctx, int32_t seq, const int32_t* tokens, int32_t n_tokens,
+                       int32_t layer_begin, int32_t layer_end, float* logits);
+/* Decode: one new token per request through all layers; request i feeds in_tokens[i] at
+ * position length(seqs[i]) and attends to everything cached plus itself; lengths grow by 1.
+ * logits [n, vocab] and next_tokens [n] (greedy, lowest index wins ties) may each be NULL;
+ * with both NULL the LM head is skipped. */
+int sts_decode_step(sts_ctx* ctx, const int32_t* seqs, const int32_t* in_tokens, int32_t n,
+                    float* logits, int32_t* next_tokens);
+/* Both at once: the prefill slice on the prefill partition's stream and the decode step on the
+ * decode partition's stream, launched back to back with no synchronisation between them, one
+ * join at the end (Section 3.3.1). The two must touch disjoint sequences. Either side may be
+ * empty (n == 0). */
+int sts_step_concurrent(sts_ctx* ctx,
+                        int32_t n_pseqs, const int32_t* pseqs, const int32_t* plens, const int32_t* ptokens,
+                        int32_t layer_begin, int32_t layer_end, float* plogits,
+                        const int32_t* dseqs, const int32_t* dtokens, int32_t n_decode,
+                        float* dlogits, int32_t* dnext);
+/* Device time of the last call's prefill part and decode part (HIP events on their own
+ * streams), and the wall-clock span of the call. A part that did not run reports 0. */
+int sts_last_timing(sts_ctx* ctx, int64_t* prefill_ns, int64_t* decode_ns, int64_t* wall_ns);
+/* Test hook: hidden state (residual stream) after the last call of a phase, fp32 [rows, hidden];
+ * phase 0 = prefill batch rows, 1 = decode rows. */
+int sts_read_hidden(sts_ctx* ctx, int32_t phase, float* out, int32_t rows);
+
+/* ---- CU partition (Section 3.4). prefill_cus / decode_cus: CUs given to each phase, each a
+ * multiple of 8 (every XCD must keep a CU of a partition) in [8, total], or 0 = phase
+ * suspended. Prefill takes CU-mask bits [0, prefill_cus), decode takes the top decode_cus
+ * bits; they are disjoint when prefill_cus + decode_cus <= total. prefill_cus == decode_cus
+ * == total is the time-multiplexed configuration (both phases see the whole GPU).
+ * Takes effect for the next call; masked streams are created on first use and cached. */
+int sts_set_partition(sts_ctx* ctx, int32_t prefill_cus, int32_t decode_cus);
+int sts_get_partition(sts_ctx* ctx, int32_t* prefill_cus, int32_t* decode_cus, int32_t* total_cus);
+
+/* ---- measurement hooks
+ * Per-kernel timing: when on, every kernel launch of both phases is bracketed by HIP events on
+ * its stream (this serialises nothing but adds event overhead; leave off when timing steps).
+ * kernel_times returns, per phase and kernel kind (STS_K_*), accumulated device ns and launch
+ * counts since the last reset. */
+enum { STS_K_EMBED = 0, STS_K_NORM, STS_K_QKV, STS_K_ROPE, STS_K_ATTN, STS_K_ATTN_MERGE, STS_K_O, STS_K_GATEUP,
+       STS_K_SWIGLU, STS_K_DOWN, STS_K_REDUCE, STS_K_HEAD, STS_K_SAMPLE, STS_K_COUNT };
+int sts_kernel_timing(sts_ctx* ctx, int32_t on);
+int sts_kernel_times(sts_ctx* ctx, int32_t phase, int64_t* ns /*[STS_K_COUNT]*/, int64_t* launches /*[STS_K_COUNT]*/, int32_t reset);
+const char* sts_kernel_name(int32_t kind);
+/* Copy-kernel bandwidth on `cus` CUs of a phase's partition side (0 = prefill side, 1 = decode
+ * side): the memory-copy probe of Section 3.2.2. Moves `bytes` (read + written = 2*bytes) per
+ * iteration; returns device ns for `iters` iterations. */
+int sts_probe_copy(sts_ctx* ctx, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out);
+
+/* ---- single operations on host data, for per-kernel parity tests. Inputs are fp32 and are
+ * rounded to bf16 on upload; outputs are the kernel's fp32 accumulators (or its bf16 result
+ * widened). They use the default stream and their own temporary device buffers. */
+/* C[M,N] = A[M,K] * W[N,K]^T. tile_cfg: STS_GEMM_*; epilogue 0 = bf16 store, 1 = fp32 store
+ * (split_k >= 1 partial sums are added up on the device), 2 = C += (C given in c_inout),
+ * 3 = SwiGLU: W holds gate rows then up rows ([2*N2, K]); output [M, N2]. */
+enum { STS_GEMM_256x256 = 0, STS_GEMM_128x128, STS_GEMM_256x128, STS_GEMM_64x256, STS_GEMM_32x256, STS_GEMM_64x128 };
+int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
+                int32_t tile_cfg, int32_t epilogue, int32_t split_k);
+/* Causal attention of a chunk: q [t, n_q, d], k and v [prior + t, n_kv, d]; query i sits at
+ * position prior + i. K,V go through a paged pool with the given page order (pages[] of
+ * ceil((prior+t)/16) distinct ids < n_pool_pages). out [t, n_q, d]. */
+int sts_op_attn_prefill(const float* q, const float* k, const float* v, float* out, int32_t t, int32_t prior,
+                        int32_t n_q, int32_t n_kv, int32_t d, const int32_t* pages, int32_t n_pool_pages);
+/* Decode attention: q [n, n_q, d]; request r has ctx[r] cached tokens given in k,v (concatenated
+ * over requests, [sum ctx, n_kv, d]) and attends to all of them. out [n, n_q, d]. */
+int sts_op_attn_decode(const float* q, const float* k, const float* v, float* out, int32_t n, const int32_t* ctx,
+                       int32_t n_q, int32_t n_kv, int32_t d, int32_t chunks);
+
+/* ---- performance estimator (Section 3.2) — host only, integer arithmetic.
+ * Wave quantisation (Section 2.2.1): g workgroups on n units, b workgroups per unit. */
+int sts_wave_quant(int64_t g, int64_t n, int64_t b, int64_t* waves, int64_t* tail, int64_t* idle_num, int64_t* idle_den);
+
+/* Profile = hardware constants (C_peak flop/ns, D_peak bytes/ns, inflection N_d, tile sizes)
+ * plus sample grids: bw (D_{p,sl}: decode CUs x co-running prefill tokens -> bytes/ns),
+ * alpha_prefill (CUs x tokens -> alpha ppm), alpha_decode (CUs x batch x total context -> ppm).
+ * Text format: see sts_profile_dump. */
+int sts_profile_parse(const char* text, sts_profile** out);
+int sts_profile_load(const char* path, sts_profile** out);
+int sts_profile_dump(const sts_profile* p, char* buf, size_t cap, size_t* needed);
+int sts_profile_free(sts_profile* p);
+
+/* Execution state ES (Section 3.2.1): prefill lengths sl_i with their cached contexts, prefill
+ * CUs pm, decode contexts cl_i (batch size = n_decode), decode CUs dm; plus the layer slice. */
+typedef struct {
+  int32_t n_prefill; const int32_t* prefill_len; const int32_t* prefill_ctx;
+  int32_t n_decode; const int32_t* decode_ctx;
+  int32_t prefill_cus, decode_cus;
+  int32_t layer_begin, n_layers_step;
+} sts_exec_state;
+#define STS_INF_NS ((int64_t)1 << 60)
+/* Eq. 1 summed over the kernels of the slice (prefill) / the whole step (decode), times the
+ * interpolated alpha of Eq. 2. A phase with work but zero CUs gets STS_INF_NS; no work -> 0. */
+int sts_latency_query(const sts_profile* p, const sts_model_desc* desc, const sts_exec_state* es,
+                      int64_t* prefill_ns, int64_t* decode_ns);
+/* The uncalibrated roofline sums T'_{p,ES} (alpha not applied): what a measurement is divided by
+ * to obtain alpha (Eq. 2). */
+int sts_latency_roofline(const sts_profile* p, const sts_model_desc* desc, const sts_exec_state* es,
+                         int64_t* prefill_ns, int64_t* decode_ns);
+
+/* ---- SLO-aware scheduler (Section 3.3, Algorithm 1) — host only, deterministic.
+ * Replays an arrival trace in simulated time (the clock advances by the estimator's
+ * predictions), logging one decision record per scheduling cycle. */
+typedef struct {
+  int64_t ttft_slo_ns, tpot_slo_ns;   /* Gamma_p, Gamma_d */
+  int32_t layers_per_step;            /* L_step */
+  int32_t max_batch_tokens;           /* prefill workspace rows */
+  int32_t max_decode_batch;
+  int32_t kv_pool_pages;
+  int32_t mode;                       /* 0 concurrent + Algorithm 1; 1 time-multiplexed (full GPU, serialised);
+                                         2 concurrent, fixed split (fixed_prefill_cus / rest) */
+  int32_t fixed_prefill_cus;
+} sts_sched_config;
+typedef struct {                      /* one scheduling cycle of the prefill scheduler */
+  int64_t t_ns;                       /* simulated time of the decision */
+  int32_t n_tasks;                    /* requests in next_tasks */
+  int32_t first_req;                  /* lowest request id in next_tasks, -1 if none */
+  int64_t tasks_hash;                 /* order-sensitive hash of the request ids in next_tasks */
+  int32_t layer_begin, layer_end;     /* L_exe, L_exe + L_step */
+  int32_t prefill_cus, decode_cus;    /* the split chosen */
+  int32_t branch;                     /* 0 none, 1 SetBalancedSM, 2 ReduceDecodeSM, 3 ReducePrefillSM */
+  int32_t decode_batch;               /* decode batch size seen */
+  int64_t predicted_ns;               /* predicted duration of the slice */
+} sts_decision;
+typedef struct {
+  int64_t n_requests, n_finished;
+  int64_t out_tokens, makespan_ns;
+  int64_t ttft_sum_ns, tpot_sum_ns, n_tpot;
+  int64_t n_slo_ok;                   /* TTFT <= Gamma_p and mean TPOT <= Gamma_d */
+  int64_t n_decisions;
+} sts_replay_stats;
+/* trace: n rows of (arrival_ns, in_len, out_len). decisions: caller's array of cap records (may
+ * be NULL with cap 0); the first min(cap, n_decisions) are written. */
+int sts_sched_replay(const sts_profile* p, const sts_model_desc* desc, const sts_sched_config* cfg,
+                     const int64_t* trace, int64_t n, sts_decision* decisions, int64_t cap, sts_replay_stats* stats);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,402 @@
+// Memory-bound kernels between the contractions: weight generation, embedding, RMSNorm,
+// rotary embedding + KV page writes, split-K reductions fused with residual/norm/SwiGLU,
+// greedy argmax, and the copy kernel used as the bandwidth probe.
+#include "kernels.h"
+
+namespace sts {
+
+// ------------------------------------------------------------------ counter-based generator
+// Twelve-term Irwin-Hall approximation of a normal deviate from three 64-bit hashes of
+// (seed, tensor id, element index): integer arithmetic plus one fp32 multiply, so a host
+// implementation of the same recipe reproduces every value exactly.
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__device__ __forceinline__ int irwin_hall12(uint64_t base, uint64_t i) {
+  int s = 0;
+#pragma unroll
+  for (int j = 0; j < 3; j++) {
+    uint64_t r = mix64(base ^ (4 * i + j));
+    s += (int)(r & 0xFFFF) + (int)((r >> 16) & 0xFFFF) + (int)((r >> 32) & 0xFFFF) + (int)(r >> 48);
+  }
+  return s - 393210;
+}
+
+__device__ __forceinline__ int phys_row(int r, int row_offset, int ib, int phase) {
+  return ib > 0 ? (r / ib) * 2 * ib + phase * ib + r % ib : row_offset + r;
+}
+
+__global__ void init_weight_kernel(bf16* dst, int ld, uint64_t base, int rows, int cols, int row_offset, int ib, int phase) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * cols) return;
+  int r = (int)(i / cols), c = (int)(i % cols);
+  float w = (float)irwin_hall12(base, i) * 0.02f * 1.52587890625e-05f;   // * 2^-16, exact
+  dst[(size_t)phys_row(r, row_offset, ib, phase) * ld + c] = f2bf(w);
+}
+hipError_t init_weight(hipStream_t s, bf16* dst, int ld, uint64_t seed, uint64_t tensor_id, int rows, int cols,
+                       int row_offset, int ib, int phase) {
+  size_t n = (size_t)rows * cols;
+  uint64_t base = mix64(seed ^ mix64(tensor_id));
+  hipLaunchKernelGGL(init_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, ld, base, rows, cols, row_offset, ib, phase);
+  return hipGetLastError();
+}
+
+__global__ void convert_weight_kernel(bf16* dst, int ld, const float* src, int rows, int cols, int row_offset, int ib, int phase) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * cols) return;
+  int r = (int)(i / cols), c = (int)(i % cols);
+  dst[(size_t)phys_row(r, row_offset, ib, phase) * ld + c] = f2bf(src[i]);
+}
+hipError_t convert_weight(hipStream_t s, bf16* dst, int ld, const float* src, int rows, int cols, int row_offset, int ib, int phase) {
+  size_t n = (size_t)rows * cols;
+  hipLaunchKernelGGL(convert_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, ld, src, rows, cols, row_offset, ib, phase);
+  return hipGetLastError();
+}
+__global__ void export_weight_kernel(float* dst, const bf16* src, int ld, int rows, int cols, int row_offset, int ib, int phase) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * cols) return;
+  int r = (int)(i / cols), c = (int)(i % cols);
+  dst[i] = bf2f(src[(size_t)phys_row(r, row_offset, ib, phase) * ld + c]);
+}
+hipError_t export_weight(hipStream_t s, float* dst, const bf16* src, int ld, int rows, int cols, int row_offset, int ib, int phase) {
+  size_t n = (size_t)rows * cols;
+  hipLaunchKernelGGL(export_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, src, ld, rows, cols, row_offset, ib, phase);
+  return hipGetLastError();
+}
+
+__global__ void fill_f32_kernel(float* dst, float v, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = v;
+}
+hipError_t fill_f32(hipStream_t s, float* dst, float v, size_t n) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, v, n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ embedding, gather
+__global__ void embed_kernel(float* X, const bf16* emb, const int* tokens, int h) {
+  const int row = blockIdx.x;
+  const bf16* e = emb + (size_t)tokens[row] * h;
+  for (int c = threadIdx.x * 8; c < h; c += blockDim.x * 8) {
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(e + c);
+    float* o = X + (size_t)row * h + c;
+#pragma unroll
+    for (int j = 0; j < 8; j++) o[j] = bf2f(v[j]);
+  }
+}
+hipError_t embed_rows(hipStream_t s, float* X, const bf16* emb, const int* tokens, int n, int h) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(embed_kernel, dim3(n), dim3(256), 0, s, X, emb, tokens, h);
+  return hipGetLastError();
+}
+__global__ void gather_rows_kernel(float* dst, const float* src, const int* rows, int h) {
+  const float* a = src + (size_t)rows[blockIdx.x] * h;
+  for (int c = threadIdx.x; c < h; c += blockDim.x) dst[(size_t)blockIdx.x * h + c] = a[c];
+}
+hipError_t gather_rows_f32(hipStream_t s, float* dst, const float* src, const int* rows, int n, int h) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(n), dim3(256), 0, s, dst, src, rows, h);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ RMSNorm
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+__global__ void __launch_bounds__(256) rmsnorm_kernel(bf16* out, const float* X, const float* gain, float eps, int h) {
+  __shared__ float red[4];
+  const float* x = X + (size_t)blockIdx.x * h;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < h; c += 1024) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  }
+  const float inv = rsqrtf(block_sum_256(ss, red) / (float)h + eps);
+  for (int c = threadIdx.x * 4; c < h; c += 1024) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
+    f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
+    bf16x4 o;
+#pragma unroll
+    for (int j = 0; j < 4; j++) o[j] = f2bf(v[j] * inv * g[j]);
+    *reinterpret_cast<bf16x4*>(out + (size_t)blockIdx.x * h + c) = o;
+  }
+}
+hipError_t rmsnorm_rows(hipStream_t s, bf16* out, const float* X, const float* gain, float eps, int n, int h) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3(n), dim3(256), 0, s, out, X, gain, eps, h);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ rotary + KV page write (prefill)
+// One workgroup per token row. cos/sin of the row's position are computed once (in double:
+// positions reach tens of thousands of radians) and applied to every head. Q is rotated in
+// place; K is rotated and scattered to its page; V is scattered transposed.
+__global__ void __launch_bounds__(256) rope_kv_prefill_kernel(bf16* qkv, int ld, const PrefillSeq* seqs, int n_seqs,
+                                                              const int* block_tables, const double* inv_freq,
+                                                              bf16* pool, KvGeom geo, int n_q) {
+  __shared__ float cs[128], sn[128];
+  const int row = blockIdx.x, d = geo.d, half = d >> 1;
+  int si = 0;
+  while (si + 1 < n_seqs && row >= seqs[si + 1].row0) si++;
+  const PrefillSeq sq = seqs[si];
+  const int pos = sq.p + (row - sq.row0);
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    double sv, cv;
+    sincos((double)pos * inv_freq[i], &sv, &cv);
+    cs[i] = (float)cv; sn[i] = (float)sv;
+  }
+  __syncthreads();
+  const int page = block_tables[sq.bt_off + pos / geo.page_tokens], slot = pos % geo.page_tokens;
+  bf16* r = qkv + (size_t)row * ld;
+  const int n_rot = (n_q + geo.n_kv) * half;
+  for (int t = threadIdx.x; t < n_rot; t += blockDim.x) {
+    const int hd = t / half, i = t % half;
+    const float a = bf2f(r[hd * d + i]), b = bf2f(r[hd * d + i + half]);
+    const bf16 ya = f2bf(a * cs[i] - b * sn[i]), yb = f2bf(a * sn[i] + b * cs[i]);
+    if (hd < n_q) {
+      r[hd * d + i] = ya; r[hd * d + i + half] = yb;
+    } else {
+      bf16* k = pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
+      k[i] = ya; k[i + half] = yb;
+    }
+  }
+  const bf16* vsrc = r + (n_q + geo.n_kv) * d;
+  for (int t = threadIdx.x; t < geo.n_kv * d; t += blockDim.x) {
+    const int hd = t / d, dd = t % d;
+    bf16* v = pool + ((size_t)page * geo.n_kv + hd) * geo.head_elems() + (size_t)geo.page_tokens * d;
+    v[(size_t)dd * geo.page_tokens + slot] = vsrc[t];
+  }
+}
+hipError_t rope_kv_write_prefill(hipStream_t s, bf16* qkv, int ld, const PrefillSeq* seqs, int n_seqs,
+                                 const int* block_tables, const double* inv_freq, bf16* pool, KvGeom geo,
+                                 int n_rows, int n_q) {
+  if (n_rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(rope_kv_prefill_kernel, dim3(n_rows), dim3(256), 0, s, qkv, ld, seqs, n_seqs, block_tables,
+                     inv_freq, pool, geo, n_q);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ decode: QKV finish
+// Sums the split-K partials of the QKV projection, rotates q and k for position cl, stores q
+// (bf16) for the attention kernel and appends k and v to the request's last page.
+__global__ void __launch_bounds__(256) decode_qkv_finish_kernel(const float* partials, int splits, long long split_stride, int ld,
+                                                                const DecodeSeq* seqs, const int* block_tables,
+                                                                const double* inv_freq, bf16* q_out, bf16* pool,
+                                                                KvGeom geo, int n_q) {
+  __shared__ float cs[128], sn[128];
+  const int row = blockIdx.x, d = geo.d, half = d >> 1;
+  const DecodeSeq sq = seqs[row];
+  const int pos = sq.cl;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    double sv, cv;
+    sincos((double)pos * inv_freq[i], &sv, &cv);
+    cs[i] = (float)cv; sn[i] = (float)sv;
+  }
+  __syncthreads();
+  const int page = block_tables[sq.bt_off + pos / geo.page_tokens], slot = pos % geo.page_tokens;
+  const float* pr = partials + (size_t)row * ld;
+  const int n_rot = (n_q + geo.n_kv) * half;
+  for (int t = threadIdx.x; t < n_rot; t += blockDim.x) {
+    const int hd = t / half, i = t % half;
+    float a = 0.f, b = 0.f;
+    for (int z = 0; z < splits; z++) { a += pr[z * split_stride + hd * d + i]; b += pr[z * split_stride + hd * d + i + half]; }
+    // the projection's result is rounded to bf16 before the rotation, as in the prefill path
+    a = bf2f(f2bf(a)); b = bf2f(f2bf(b));
+    const bf16 ya = f2bf(a * cs[i] - b * sn[i]), yb = f2bf(a * sn[i] + b * cs[i]);
+    if (hd < n_q) {
+      q_out[(size_t)row * n_q * d + hd * d + i] = ya; q_out[(size_t)row * n_q * d + hd * d + i + half] = yb;
+    } else {
+      bf16* k = pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
+      k[i] = ya; k[i + half] = yb;
+    }
+  }
+  const int voff = (n_q + geo.n_kv) * d;
+  for (int t = threadIdx.x; t < geo.n_kv * d; t += blockDim.x) {
+    const int hd = t / d, dd = t % d;
+    float a = 0.f;
+    for (int z = 0; z < splits; z++) a += pr[z * split_stride + voff + t];
+    bf16* v = pool + ((size_t)page * geo.n_kv + hd) * geo.head_elems() + (size_t)geo.page_tokens * d;
+    v[(size_t)dd * geo.page_tokens + slot] = f2bf(a);
+  }
+}
+hipError_t decode_qkv_finish(hipStream_t s, const float* partials, int splits, long long split_stride, int ld,
+                             const DecodeSeq* seqs, const int* block_tables, const double* inv_freq,
+                             bf16* q_out, bf16* pool, KvGeom geo, int n, int n_q) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(decode_qkv_finish_kernel, dim3(n), dim3(256), 0, s, partials, splits, split_stride, ld, seqs,
+                     block_tables, inv_freq, q_out, pool, geo, n_q);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ split-K reductions
+// X[row] += sum of partials; optionally out = rmsnorm(X[row]) * gain (bf16).
+__global__ void __launch_bounds__(256) reduce_resid_norm_kernel(float* X, const float* partials, int splits, long long split_stride,
+                                                                bf16* out, const float* gain, float eps, int h) {
+  __shared__ float red[4];
+  float* x = X + (size_t)blockIdx.x * h;
+  const float* p = partials + (size_t)blockIdx.x * h;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < h; c += 1024) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
+    for (int z = 0; z < splits; z++) {
+      f32x4 q = *reinterpret_cast<const f32x4*>(p + z * split_stride + c);
+      v += q;
+    }
+    *reinterpret_cast<f32x4*>(x + c) = v;
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  }
+  if (out == nullptr) return;
+  const float inv = rsqrtf(block_sum_256(ss, red) / (float)h + eps);
+  for (int c = threadIdx.x * 4; c < h; c += 1024) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(x + c);     // this thread wrote these itself
+    f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
+    bf16x4 o;
+#pragma unroll
+    for (int j = 0; j < 4; j++) o[j] = f2bf(v[j] * inv * g[j]);
+    *reinterpret_cast<bf16x4*>(out + (size_t)blockIdx.x * h + c) = o;
+  }
+}
+hipError_t reduce_resid_norm(hipStream_t s, float* X, const float* partials, int splits, long long split_stride,
+                             bf16* out_norm, const float* gain, float eps, int n, int h) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(n), dim3(256), 0, s, X, partials, splits, split_stride, out_norm, gain, eps, h);
+  return hipGetLastError();
+}
+
+// H[row][j] = silu(sum gate_j) * sum up_j; gate/up columns are interleaved in blocks of 32.
+__global__ void reduce_swiglu_kernel(bf16* H, const float* partials, int splits, long long split_stride, int mlp) {
+  const int row = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= mlp) return;
+  const float* p = partials + (size_t)row * 2 * mlp + (j >> 5) * 64 + (j & 31);
+  float g = 0.f, u = 0.f;
+  for (int z = 0; z < splits; z++) { g += p[z * split_stride]; u += p[z * split_stride + 32]; }
+  H[(size_t)row * mlp + j] = f2bf(g / (1.f + __expf(-g)) * u);
+}
+hipError_t reduce_swiglu(hipStream_t s, bf16* H, const float* partials, int splits, long long split_stride, int n, int mlp) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((mlp + 255) / 256, n), dim3(256), 0, s, H, partials, splits, split_stride, mlp);
+  return hipGetLastError();
+}
+
+__global__ void reduce_f32_kernel(float* out, const float* partials, int splits, long long split_stride, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float a = 0.f;
+  for (int z = 0; z < splits; z++) a += partials[z * split_stride + i];
+  out[i] = a;
+}
+hipError_t reduce_f32(hipStream_t s, float* out, const float* partials, int splits, long long split_stride, size_t n) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, out, partials, splits, split_stride, n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ greedy sampling
+__global__ void __launch_bounds__(256) argmax_kernel(int* out, const float* logits, int vocab) {
+  __shared__ float bv[256];
+  __shared__ int bi[256];
+  const float* l = logits + (size_t)blockIdx.x * vocab;
+  float best = -INFINITY; int idx = 0x7FFFFFFF;
+  for (int c = threadIdx.x; c < vocab; c += 256) {
+    const float v = l[c];
+    if (v > best) { best = v; idx = c; }           // ascending c: first maximum wins
+  }
+  bv[threadIdx.x] = best; bi[threadIdx.x] = idx;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) {
+      const float v = bv[threadIdx.x + o]; const int i = bi[threadIdx.x + o];
+      if (v > bv[threadIdx.x] || (v == bv[threadIdx.x] && i < bi[threadIdx.x])) { bv[threadIdx.x] = v; bi[threadIdx.x] = i; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = bi[0];
+}
+hipError_t argmax_rows(hipStream_t s, int* out, const float* logits, int n, int vocab) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(256), 0, s, out, logits, vocab);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bandwidth probe
+__global__ void __launch_bounds__(256) copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+  size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+  }
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+hipError_t copy_probe(hipStream_t s, void* dst, const void* src, size_t bytes, int grid) {
+  hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, bytes / 16);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ KV pool access (tests, synthetic contexts)
+__device__ __forceinline__ void kv_addr(const KvGeom& geo, const int* bt, int pos, int hd, int dd, size_t& ki, size_t& vi) {
+  const int page = bt[pos / geo.page_tokens], slot = pos % geo.page_tokens;
+  const size_t base = ((size_t)page * geo.n_kv + hd) * geo.head_elems();
+  ki = base + (size_t)slot * geo.d + dd;
+  vi = base + (size_t)geo.page_tokens * geo.d + (size_t)dd * geo.page_tokens + slot;
+}
+// Element (pos, head, dd) of K (V) is deviate number ((pos*n_kv + head)*d + dd) of the stream
+// keyed by tensor id 0x4B000000 + 2*layer (+1 for V): unit variance, rounded to bf16.
+__global__ void kv_fill_kernel(bf16* pool, KvGeom geo, const int* bt, int pos0, int n, uint64_t kbase, uint64_t vbase) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t per = (size_t)geo.n_kv * geo.d;
+  if (i >= (size_t)n * per) return;
+  const int pos = pos0 + (int)(i / per), hd = (int)(i % per) / geo.d, dd = (int)(i % per) % geo.d;
+  const uint64_t e = (uint64_t)pos * per + (i % per);
+  size_t ki, vi; kv_addr(geo, bt, pos, hd, dd, ki, vi);
+  pool[ki] = f2bf((float)irwin_hall12(kbase, e) * 1.52587890625e-05f);
+  pool[vi] = f2bf((float)irwin_hall12(vbase, e) * 1.52587890625e-05f);
+}
+hipError_t kv_fill_random(hipStream_t s, bf16* pool, KvGeom geo, const int* bt, int pos0, int n, uint64_t seed, int layer) {
+  size_t tot = (size_t)n * geo.n_kv * geo.d;
+  if (tot == 0) return hipSuccess;
+  const uint64_t kb = mix64(seed ^ mix64(0x4B000000ull + 2 * (uint64_t)layer)), vb = mix64(seed ^ mix64(0x4B000000ull + 2 * (uint64_t)layer + 1));
+  hipLaunchKernelGGL(kv_fill_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, pool, geo, bt, pos0, n, kb, vb);
+  return hipGetLastError();
+}
+__global__ void kv_write_kernel(bf16* pool, KvGeom geo, const int* bt, int pos0, int n, const float* k, const float* v) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t per = (size_t)geo.n_kv * geo.d;
+  if (i >= (size_t)n * per) return;
+  const int pos = pos0 + (int)(i / per), hd = (int)(i % per) / geo.d, dd = (int)(i % per) % geo.d;
+  size_t ki, vi; kv_addr(geo, bt, pos, hd, dd, ki, vi);
+  pool[ki] = f2bf(k[i]); pool[vi] = f2bf(v[i]);
+}
+hipError_t kv_write_tokens(hipStream_t s, bf16* pool, KvGeom geo, const int* bt, int pos0, int n, const float* k, const float* v) {
+  size_t tot = (size_t)n * geo.n_kv * geo.d;
+  if (tot == 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_write_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, pool, geo, bt, pos0, n, k, v);
+  return hipGetLastError();
+}
+__global__ void kv_read_kernel(const bf16* pool, KvGeom geo, const int* bt, int pos0, int n, float* k, float* v) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t per = (size_t)geo.n_kv * geo.d;
+  if (i >= (size_t)n * per) return;
+  const int pos = pos0 + (int)(i / per), hd = (int)(i % per) / geo.d, dd = (int)(i % per) % geo.d;
+  size_t ki, vi; kv_addr(geo, bt, pos, hd, dd, ki, vi);
+  k[i] = bf2f(pool[ki]); v[i] = bf2f(pool[vi]);
+}
+hipError_t kv_read_tokens(hipStream_t s, const bf16* pool, KvGeom geo, const int* bt, int pos0, int n, float* k, float* v) {
+  size_t tot = (size_t)n * geo.n_kv * geo.d;
+  if (tot == 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_read_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, pool, geo, bt, pos0, n, k, v);
+  return hipGetLastError();
+}
+
+}  // namespace sts

@@ -1,0 +1,820 @@
+// Concurrent execution engine: owns weights, the shared paged KV pool, the per-phase
+// workspaces and the CU-masked streams, and drives the kernels of a prefill layer slice and of
+// a decode step (paper Sections 3.4 and 3.5). Everything here is host code; the kernels live in
+// gemm.hip, attn_prefill.hip, attn_decode.hip and elementwise.hip.
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "sts.h"
+
+using namespace sts;
+
+static int g_hip_err = 0;
+#define HIPCK(x)                                                 \
+  do {                                                           \
+    hipError_t e_ = (x);                                         \
+    if (e_ != hipSuccess) { g_hip_err = (int)e_; return STS_EHIP; } \
+  } while (0)
+#define STSCK(x) do { int r_ = (x); if (r_ != STS_OK) return r_; } while (0)
+
+extern "C" const char* sts_strerror(int code) {
+  switch (code) {
+    case STS_OK: return "ok";
+    case STS_EINVAL: return "invalid argument";
+    case STS_ENOMEM: return "KV page pool or workspace exhausted";
+    case STS_ESTATE: return "call out of order for the current state";
+    case STS_EHIP: return "HIP runtime error (see sts_last_hip_error)";
+    case STS_EIO: return "file or parse error";
+    default: return "unknown error";
+  }
+}
+extern "C" int sts_last_hip_error(void) { return g_hip_err; }
+
+static const char* kKernelNames[STS_K_COUNT] = {"embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup",
+                                                "swiglu", "down", "reduce", "head", "sample"};
+extern "C" const char* sts_kernel_name(int32_t kind) { return (kind >= 0 && kind < STS_K_COUNT) ? kKernelNames[kind] : "?"; }
+
+namespace {
+
+struct LayerW { bf16 *wqkv, *wo, *wgu, *wd; float *g1, *g2; };
+
+struct Seq { bool used = false; int len = 0; std::vector<int> pages; };
+
+struct Phase {
+  int side = 0;
+  int cus = 0;
+  hipStream_t stream = nullptr;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  bool ran = false;
+  // device workspace
+  float* X = nullptr; bf16* Xn = nullptr; bf16* QKV = nullptr; bf16* A = nullptr; bf16* H = nullptr;
+  float* part = nullptr; float* attn_ws = nullptr; bf16* Q = nullptr;
+  float* Xlast = nullptr; bf16* Xlast_n = nullptr; float* logits = nullptr; int* next = nullptr;
+  int* d_tokens = nullptr; int* d_bt = nullptr; int* d_rows = nullptr;
+  PrefillSeq* d_pseq = nullptr; DecodeSeq* d_dseq = nullptr; AttnItem* d_items = nullptr;
+  // pinned staging
+  int* h_tokens = nullptr; int* h_bt = nullptr; int* h_rows = nullptr;
+  PrefillSeq* h_pseq = nullptr; DecodeSeq* h_dseq = nullptr; AttnItem* h_items = nullptr;
+  float* h_logits = nullptr; int* h_next = nullptr;
+  int rows = 0;                               // rows of the last call
+  // per-kernel timing
+  std::vector<hipEvent_t> kev; std::vector<int> kkind; size_t kused = 0;
+  int64_t kns[STS_K_COUNT] = {0}, kcnt[STS_K_COUNT] = {0};
+};
+
+}  // namespace
+
+struct sts_ctx {
+  sts_model_desc d;
+  sts_init_params p;
+  int n_cu = 0;
+  int qd = 0, kvd = 0, qkvn = 0;
+  KvGeom geo;
+  bf16 *emb = nullptr, *lm = nullptr; float* gf = nullptr;
+  std::vector<LayerW> layers;
+  bf16* pool = nullptr; size_t pool_layer_elems = 0;
+  double* inv_freq = nullptr;
+  std::mutex alloc_mu;                         // serialises page allocation / release
+  std::mutex state_mu;                         // guards the in-flight prefill batch description
+  std::vector<int> free_pages; std::vector<char> page_used;
+  std::vector<Seq> seqs;
+  Phase ph[2];
+  int part_cus[2] = {0, 0};
+  std::map<std::pair<int, int>, hipStream_t> streams;
+  bool ktiming = false;
+  // in-flight layer-sliced prefill batch
+  bool pf_active = false; int pf_next_layer = 0; std::vector<int> pf_seqs, pf_lens;
+  int64_t last_wall_ns = 0;
+  void* probe_src = nullptr; void* probe_dst = nullptr; size_t probe_bytes = 0;
+  std::vector<void*> allocs;
+};
+
+namespace {
+
+template <typename T>
+int dev_alloc(sts_ctx* c, T** out, size_t count) {
+  void* p = nullptr;
+  HIPCK(hipMalloc(&p, std::max<size_t>(count, 1) * sizeof(T)));
+  c->allocs.push_back(p);
+  *out = reinterpret_cast<T*>(p);
+  return STS_OK;
+}
+template <typename T>
+int host_alloc(T** out, size_t count) {
+  void* p = nullptr;
+  HIPCK(hipHostMalloc(&p, std::max<size_t>(count, 1) * sizeof(T), hipHostMallocDefault));
+  *out = reinterpret_cast<T*>(p);
+  return STS_OK;
+}
+
+int get_stream(sts_ctx* c, int side, int cus, hipStream_t* out) {
+  auto key = std::make_pair(side, cus);
+  auto it = c->streams.find(key);
+  if (it != c->streams.end()) { *out = it->second; return STS_OK; }
+  // A mask that leaves some XCD without a CU makes stream creation fail (and crashes some
+  // runtime versions): contiguous runs of >= 8 bits always cover all 8 XCDs because mask bit i
+  // belongs to XCD i % 8.
+  if (cus < 8 || cus > c->n_cu || cus % 8 != 0) return STS_EINVAL;
+  const int words = (c->n_cu + 31) / 32;
+  std::vector<uint32_t> mask(words, 0);
+  const int lo = side == 0 ? 0 : c->n_cu - cus;
+  for (int b = lo; b < lo + cus; b++) mask[b / 32] |= 1u << (b % 32);
+  hipStream_t s = nullptr;
+  HIPCK(hipExtStreamCreateWithCUMask(&s, words, mask.data()));
+  c->streams[key] = s;
+  *out = s;
+  return STS_OK;
+}
+
+int select_streams(sts_ctx* c) {
+  for (int side = 0; side < 2; side++) {
+    Phase& ph = c->ph[side];
+    if (c->part_cus[side] == 0) { ph.stream = nullptr; ph.cus = 0; continue; }
+    STSCK(get_stream(c, side, c->part_cus[side], &ph.stream));
+    ph.cus = c->part_cus[side];
+  }
+  return STS_OK;
+}
+
+// ---- per-kernel timing
+int k_begin(sts_ctx* c, Phase& ph, int kind) {
+  if (!c->ktiming) return STS_OK;
+  if (ph.kused + 2 > ph.kev.size()) {
+    for (int i = 0; i < 256; i++) { hipEvent_t e; HIPCK(hipEventCreate(&e)); ph.kev.push_back(e); }
+  }
+  ph.kkind.push_back(kind);
+  HIPCK(hipEventRecord(ph.kev[ph.kused], ph.stream));
+  return STS_OK;
+}
+int k_end(sts_ctx* c, Phase& ph) {
+  if (!c->ktiming) return STS_OK;
+  HIPCK(hipEventRecord(ph.kev[ph.kused + 1], ph.stream));
+  ph.kused += 2;
+  return STS_OK;
+}
+int k_collect(sts_ctx* c, Phase& ph) {
+  if (!c->ktiming) return STS_OK;
+  for (size_t i = 0; i < ph.kkind.size(); i++) {
+    float ms = 0.f;
+    HIPCK(hipEventElapsedTime(&ms, ph.kev[2 * i], ph.kev[2 * i + 1]));
+    ph.kns[ph.kkind[i]] += (int64_t)(ms * 1e6);
+    ph.kcnt[ph.kkind[i]] += 1;
+  }
+  ph.kkind.clear(); ph.kused = 0;
+  return STS_OK;
+}
+#define KL(ph, kind, expr)                \
+  do {                                    \
+    STSCK(k_begin(c, ph, kind));          \
+    HIPCK(expr);                          \
+    STSCK(k_end(c, ph));                  \
+  } while (0)
+
+int pick_cfg(int m, int n) {
+  const bool n256 = n % 256 == 0;
+  if (m <= 32 && n256) return GEMM_32x256;
+  if (m <= 64) return n256 ? GEMM_64x256 : GEMM_64x128;
+  if (m <= 128 || !n256) return GEMM_128x128;
+  return GEMM_256x256;
+}
+int pick_splits(int cfg, int m, int n, int k, int cus) {
+  const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
+  int s = (2 * std::max(cus, 8) + tiles - 1) / tiles;
+  s = std::min(s, std::max(1, k / 512));
+  return std::max(1, std::min(s, 8));
+}
+
+bool valid_seq(sts_ctx* c, int s) { return s >= 0 && s < (int)c->seqs.size() && c->seqs[s].used; }
+
+// Make `seq` own enough pages for n_tokens; caller holds no lock.
+int reserve_pages(sts_ctx* c, const std::vector<std::pair<int, int>>& wants) {   // (seq, tokens)
+  std::lock_guard<std::mutex> g(c->alloc_mu);
+  size_t need = 0;
+  for (auto& w : wants) {
+    const int np = (w.second + c->geo.page_tokens - 1) / c->geo.page_tokens;
+    if (np > c->p.max_pages_per_seq) return STS_EINVAL;
+    need += std::max(0, np - (int)c->seqs[w.first].pages.size());
+  }
+  if (need > c->free_pages.size()) return STS_ENOMEM;
+  for (auto& w : wants) {
+    const int np = (w.second + c->geo.page_tokens - 1) / c->geo.page_tokens;
+    Seq& s = c->seqs[w.first];
+    while ((int)s.pages.size() < np) {
+      const int pg = c->free_pages.back(); c->free_pages.pop_back();
+      c->page_used[pg] = 1; s.pages.push_back(pg);
+    }
+  }
+  return STS_OK;
+}
+
+bf16* layer_pool(sts_ctx* c, int l) { return c->pool + (size_t)l * c->pool_layer_elems; }
+
+// ------------------------------------------------------------------------------------ prefill
+int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                    int lb, int le, bool want_logits) {
+  Phase& ph = c->ph[0];
+  const sts_model_desc& d = c->d;
+  if (n_seqs < 1 || n_seqs > c->p.max_prefill_seqs || !seqs || !lens) return STS_EINVAL;
+  if (lb < 0 || le <= lb || le > d.n_layers) return STS_EINVAL;
+  if (ph.stream == nullptr) return STS_ESTATE;               // prefill suspended (0 CUs)
+  int rows = 0;
+  for (int i = 0; i < n_seqs; i++) {
+    if (!valid_seq(c, seqs[i]) || lens[i] < 1) return STS_EINVAL;
+    for (int j = 0; j < i; j++) if (seqs[j] == seqs[i]) return STS_EINVAL;
+    rows += lens[i];
+  }
+  if (rows > c->p.max_prefill_tokens) return STS_EINVAL;
+  if (lb == 0) {
+    if (!tokens) return STS_EINVAL;
+    for (int i = 0; i < rows; i++) if (tokens[i] < 0 || tokens[i] >= d.vocab) return STS_EINVAL;
+    if (c->pf_active) return STS_ESTATE;
+    std::vector<std::pair<int, int>> wants;
+    for (int i = 0; i < n_seqs; i++) wants.push_back({seqs[i], c->seqs[seqs[i]].len + lens[i]});
+    STSCK(reserve_pages(c, wants));
+    std::lock_guard<std::mutex> g(c->state_mu);
+    c->pf_active = true; c->pf_next_layer = 0;
+    c->pf_seqs.assign(seqs, seqs + n_seqs); c->pf_lens.assign(lens, lens + n_seqs);
+  } else {
+    if (!c->pf_active || lb != c->pf_next_layer || (int)c->pf_seqs.size() != n_seqs) return STS_ESTATE;
+    for (int i = 0; i < n_seqs; i++) if (c->pf_seqs[i] != seqs[i] || c->pf_lens[i] != lens[i]) return STS_ESTATE;
+  }
+  // ---- stage metadata
+  const int mp = c->p.max_pages_per_seq, bq = attn_prefill_tile_q();
+  int r0 = 0, n_items = 0;
+  for (int i = 0; i < n_seqs; i++) {
+    const Seq& s = c->seqs[seqs[i]];
+    ph.h_pseq[i] = PrefillSeq{r0, lens[i], s.len, i * mp, (int)s.pages.size()};
+    std::memcpy(ph.h_bt + (size_t)i * mp, s.pages.data(), s.pages.size() * sizeof(int));
+    for (int q0 = 0; q0 < lens[i]; q0 += bq) ph.h_items[n_items++] = AttnItem{i, q0};
+    ph.h_rows[i] = r0 + lens[i] - 1;
+    r0 += lens[i];
+  }
+  // heaviest query tiles first: the tail of the launch is then made of short ones
+  std::stable_sort(ph.h_items, ph.h_items + n_items, [&](const AttnItem& a, const AttnItem& b) {
+    return ph.h_pseq[a.seq].p + a.q0 > ph.h_pseq[b.seq].p + b.q0;
+  });
+  hipStream_t st = ph.stream;
+  HIPCK(hipEventRecord(ph.ev0, st));
+  HIPCK(hipMemcpyAsync(ph.d_pseq, ph.h_pseq, n_seqs * sizeof(PrefillSeq), hipMemcpyHostToDevice, st));
+  HIPCK(hipMemcpyAsync(ph.d_bt, ph.h_bt, (size_t)n_seqs * mp * sizeof(int), hipMemcpyHostToDevice, st));
+  HIPCK(hipMemcpyAsync(ph.d_items, ph.h_items, n_items * sizeof(AttnItem), hipMemcpyHostToDevice, st));
+  HIPCK(hipMemcpyAsync(ph.d_rows, ph.h_rows, n_seqs * sizeof(int), hipMemcpyHostToDevice, st));
+  if (lb == 0) {
+    std::memcpy(ph.h_tokens, tokens, rows * sizeof(int));
+    HIPCK(hipMemcpyAsync(ph.d_tokens, ph.h_tokens, rows * sizeof(int), hipMemcpyHostToDevice, st));
+    KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, rows, d.hidden));
+  }
+  const int h = d.hidden;
+  for (int l = lb; l < le; l++) {
+    const LayerW& w = c->layers[l];
+    KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g1, d.rms_eps, rows, h));
+    KL(ph, STS_K_QKV, gemm_bf16(st, pick_cfg(rows, c->qkvn), EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h, 1, 0));
+    KL(ph, STS_K_ROPE, rope_kv_write_prefill(st, ph.QKV, c->qkvn, ph.d_pseq, n_seqs, ph.d_bt, c->inv_freq, layer_pool(c, l), c->geo, rows, d.n_q_heads));
+    KL(ph, STS_K_ATTN, attn_prefill(st, ph.QKV, c->qkvn, ph.A, c->qd, ph.d_pseq, ph.d_items, n_items, ph.d_bt, layer_pool(c, l), c->geo, d.n_q_heads));
+    KL(ph, STS_K_O, gemm_bf16(st, pick_cfg(rows, h), EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd, 1, 0));
+    KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g2, d.rms_eps, rows, h));
+    KL(ph, STS_K_GATEUP, gemm_bf16(st, pick_cfg(rows, 2 * d.mlp) == GEMM_64x128 ? GEMM_128x128 : pick_cfg(rows, 2 * d.mlp), EPI_SWIGLU_BF16,
+                                   ph.Xn, h, w.wgu, h, ph.H, d.mlp, rows, 2 * d.mlp, h, 1, 0));
+    KL(ph, STS_K_DOWN, gemm_bf16(st, pick_cfg(rows, h), EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp, 1, 0));
+  }
+  if (le == d.n_layers && want_logits) {
+    KL(ph, STS_K_HEAD, gather_rows_f32(st, ph.Xlast, ph.X, ph.d_rows, n_seqs, h));
+    KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xlast_n, ph.Xlast, c->gf, d.rms_eps, n_seqs, h));
+    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n_seqs, d.vocab), EPI_F32, ph.Xlast_n, h, c->lm, h, ph.logits, d.vocab, n_seqs, d.vocab, h, 1, 0));
+    HIPCK(hipMemcpyAsync(ph.h_logits, ph.logits, (size_t)n_seqs * d.vocab * sizeof(float), hipMemcpyDeviceToHost, st));
+  }
+  HIPCK(hipEventRecord(ph.ev1, st));
+  ph.ran = true; ph.rows = rows;
+  return STS_OK;
+}
+
+int prefill_finish(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, int le, float* logits) {
+  Phase& ph = c->ph[0];
+  HIPCK(hipStreamSynchronize(ph.stream));
+  STSCK(k_collect(c, ph));
+  c->pf_next_layer = le;
+  if (le == c->d.n_layers) {
+    for (int i = 0; i < n_seqs; i++) c->seqs[seqs[i]].len += lens[i];
+    { std::lock_guard<std::mutex> g(c->state_mu); c->pf_active = false; }
+    if (logits) std::memcpy(logits, ph.h_logits, (size_t)n_seqs * c->d.vocab * sizeof(float));
+  }
+  return STS_OK;
+}
+
+// ------------------------------------------------------------------------------------ decode
+int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int n, bool want_logits, bool want_next) {
+  Phase& ph = c->ph[1];
+  const sts_model_desc& d = c->d;
+  if (n < 1 || n > c->p.max_decode_batch || !seqs || !in_tokens) return STS_EINVAL;
+  if (ph.stream == nullptr) return STS_ESTATE;               // decode suspended (0 CUs)
+  for (int i = 0; i < n; i++) {
+    if (!valid_seq(c, seqs[i]) || in_tokens[i] < 0 || in_tokens[i] >= d.vocab) return STS_EINVAL;
+    for (int j = 0; j < i; j++) if (seqs[j] == seqs[i]) return STS_EINVAL;
+  }
+  {
+    std::lock_guard<std::mutex> g(c->state_mu);                                        // a request is in one phase only
+    if (c->pf_active) for (int i = 0; i < n; i++) for (int s : c->pf_seqs) if (s == seqs[i]) return STS_EINVAL;
+  }
+  std::vector<std::pair<int, int>> wants;
+  for (int i = 0; i < n; i++) wants.push_back({seqs[i], c->seqs[seqs[i]].len + 1});
+  STSCK(reserve_pages(c, wants));
+  const int mp = c->p.max_pages_per_seq, pt = c->geo.page_tokens;
+  int max_pages = 1;
+  for (int i = 0; i < n; i++) {
+    const Seq& s = c->seqs[seqs[i]];
+    const int np = (s.len + 1 + pt - 1) / pt;
+    ph.h_dseq[i] = DecodeSeq{s.len, i * mp, np};
+    std::memcpy(ph.h_bt + (size_t)i * mp, s.pages.data(), np * sizeof(int));
+    max_pages = std::max(max_pages, np);
+    ph.h_tokens[i] = in_tokens[i];
+  }
+  const int chunk_pages = attn_decode_max_chunk_tokens() / pt;
+  const int max_chunks = std::max(1, (mp + chunk_pages - 1) / chunk_pages);
+  int chunks = (max_pages + chunk_pages - 1) / chunk_pages;                                 // what the longest context needs
+  chunks = std::max(chunks, std::min((4 * ph.cus + n * d.n_kv_heads - 1) / (n * d.n_kv_heads), (max_pages + 3) / 4));   // fill the partition
+  chunks = std::max(1, std::min(chunks, std::max(max_chunks, 16)));
+  hipStream_t st = ph.stream;
+  HIPCK(hipEventRecord(ph.ev0, st));
+  HIPCK(hipMemcpyAsync(ph.d_dseq, ph.h_dseq, n * sizeof(DecodeSeq), hipMemcpyHostToDevice, st));
+  HIPCK(hipMemcpyAsync(ph.d_bt, ph.h_bt, (size_t)n * mp * sizeof(int), hipMemcpyHostToDevice, st));
+  HIPCK(hipMemcpyAsync(ph.d_tokens, ph.h_tokens, n * sizeof(int), hipMemcpyHostToDevice, st));
+  KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, n, d.hidden));
+  const int h = d.hidden;
+  KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, c->layers[0].g1, d.rms_eps, n, h));
+  auto skinny = [&](int kind, const bf16* A, int lda, const bf16* W, int N, int K, int* splits_out, long long* stride_out) -> int {
+    const int cfg = pick_cfg(n, N);
+    const int splits = pick_splits(cfg, n, N, K, ph.cus);
+    const long long stride = (long long)n * N;
+    *splits_out = splits; *stride_out = stride;
+    KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
+    return STS_OK;
+  };
+  for (int l = 0; l < d.n_layers; l++) {
+    const LayerW& w = c->layers[l];
+    int sp; long long ss;
+    STSCK(skinny(STS_K_QKV, ph.Xn, h, w.wqkv, c->qkvn, h, &sp, &ss));
+    KL(ph, STS_K_ROPE, decode_qkv_finish(st, ph.part, sp, ss, c->qkvn, ph.d_dseq, ph.d_bt, c->inv_freq, ph.Q, layer_pool(c, l), c->geo, n, d.n_q_heads));
+    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunks, ph.attn_ws));
+    STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
+    KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
+    STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
+    KL(ph, STS_K_SWIGLU, reduce_swiglu(st, ph.H, ph.part, sp, ss, n, d.mlp));
+    STSCK(skinny(STS_K_DOWN, ph.H, d.mlp, w.wd, h, d.mlp, &sp, &ss));
+    const float* next_gain = (l + 1 < d.n_layers) ? c->layers[l + 1].g1 : c->gf;
+    KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, next_gain, d.rms_eps, n, h));
+  }
+  if (want_logits || want_next) {
+    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n, d.vocab), EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
+    if (want_next) {
+      KL(ph, STS_K_SAMPLE, argmax_rows(st, ph.next, ph.logits, n, d.vocab));
+      HIPCK(hipMemcpyAsync(ph.h_next, ph.next, n * sizeof(int), hipMemcpyDeviceToHost, st));
+    }
+    if (want_logits) HIPCK(hipMemcpyAsync(ph.h_logits, ph.logits, (size_t)n * d.vocab * sizeof(float), hipMemcpyDeviceToHost, st));
+  }
+  HIPCK(hipEventRecord(ph.ev1, st));
+  ph.ran = true; ph.rows = n;
+  return STS_OK;
+}
+
+int decode_finish(sts_ctx* c, const int32_t* seqs, int n, float* logits, int32_t* next) {
+  Phase& ph = c->ph[1];
+  HIPCK(hipStreamSynchronize(ph.stream));
+  STSCK(k_collect(c, ph));
+  for (int i = 0; i < n; i++) c->seqs[seqs[i]].len += 1;
+  if (logits) std::memcpy(logits, ph.h_logits, (size_t)n * c->d.vocab * sizeof(float));
+  if (next) std::memcpy(next, ph.h_next, n * sizeof(int));
+  return STS_OK;
+}
+
+int64_t now_ns() {
+  return std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+int alloc_phase(sts_ctx* c, int side) {
+  Phase& ph = c->ph[side];
+  ph.side = side;
+  const sts_model_desc& d = c->d;
+  const size_t rows = side == 0 ? c->p.max_prefill_tokens : c->p.max_decode_batch;
+  const size_t nseq = side == 0 ? c->p.max_prefill_seqs : c->p.max_decode_batch;
+  const size_t mp = c->p.max_pages_per_seq;
+  HIPCK(hipEventCreate(&ph.ev0)); HIPCK(hipEventCreate(&ph.ev1));
+  STSCK(dev_alloc(c, &ph.X, rows * d.hidden));
+  STSCK(dev_alloc(c, &ph.Xn, rows * d.hidden));
+  STSCK(dev_alloc(c, &ph.A, rows * c->qd));
+  STSCK(dev_alloc(c, &ph.H, rows * d.mlp));
+  STSCK(dev_alloc(c, &ph.Xlast, nseq * d.hidden));
+  STSCK(dev_alloc(c, &ph.Xlast_n, nseq * d.hidden));
+  STSCK(dev_alloc(c, &ph.logits, nseq * d.vocab));
+  STSCK(dev_alloc(c, &ph.next, nseq));
+  STSCK(dev_alloc(c, &ph.d_tokens, rows));
+  STSCK(dev_alloc(c, &ph.d_bt, nseq * mp));
+  STSCK(dev_alloc(c, &ph.d_rows, nseq));
+  STSCK(host_alloc(&ph.h_tokens, rows));
+  STSCK(host_alloc(&ph.h_bt, nseq * mp));
+  STSCK(host_alloc(&ph.h_rows, nseq));
+  STSCK(host_alloc(&ph.h_logits, nseq * d.vocab));
+  STSCK(host_alloc(&ph.h_next, nseq));
+  if (side == 0) {
+    const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
+    STSCK(dev_alloc(c, &ph.QKV, rows * c->qkvn));
+    STSCK(dev_alloc(c, &ph.d_pseq, nseq));
+    STSCK(dev_alloc(c, &ph.d_items, items));
+    STSCK(host_alloc(&ph.h_pseq, nseq));
+    STSCK(host_alloc(&ph.h_items, items));
+  } else {
+    const size_t widest = std::max<size_t>(std::max(c->qkvn, 2 * d.mlp), d.hidden);
+    const int chunk_pages = attn_decode_max_chunk_tokens() / c->geo.page_tokens;
+    const size_t max_chunks = std::max<size_t>(16, (mp + chunk_pages - 1) / chunk_pages);
+    STSCK(dev_alloc(c, &ph.part, 8 * rows * widest));
+    STSCK(dev_alloc(c, &ph.Q, rows * c->qd));
+    STSCK(dev_alloc(c, &ph.attn_ws, attn_decode_ws_floats((int)rows, d.n_q_heads, d.head_dim, (int)max_chunks)));
+    STSCK(dev_alloc(c, &ph.d_dseq, nseq));
+    STSCK(host_alloc(&ph.h_dseq, nseq));
+  }
+  return STS_OK;
+}
+
+struct TensorRef { bf16* w = nullptr; float* g = nullptr; int ld = 0, rows = 0, cols = 0, row_off = 0, ib = 0, phase = 0; uint64_t tid = 0; };
+
+int find_tensor(sts_ctx* c, int layer, const char* name, TensorRef* t) {
+  const sts_model_desc& d = c->d;
+  const std::string n(name ? name : "");
+  if (n == "emb") { *t = TensorRef{c->emb, nullptr, d.hidden, d.vocab, d.hidden, 0, 0, 0, 0}; return STS_OK; }
+  if (n == "lm") { *t = TensorRef{c->lm, nullptr, d.hidden, d.vocab, d.hidden, 0, 0, 0, 1}; return STS_OK; }
+  if (n == "gf") { *t = TensorRef{nullptr, c->gf, 0, 1, d.hidden}; return STS_OK; }
+  if (layer < 0 || layer >= d.n_layers) return STS_EINVAL;
+  LayerW& w = c->layers[layer];
+  const uint64_t base = (uint64_t)(layer + 1) * 16;
+  if (n == "g1") { *t = TensorRef{nullptr, w.g1, 0, 1, d.hidden}; return STS_OK; }
+  if (n == "g2") { *t = TensorRef{nullptr, w.g2, 0, 1, d.hidden}; return STS_OK; }
+  if (n == "wq") { *t = TensorRef{w.wqkv, nullptr, d.hidden, c->qd, d.hidden, 0, 0, 0, base + 0}; return STS_OK; }
+  if (n == "wk") { *t = TensorRef{w.wqkv, nullptr, d.hidden, c->kvd, d.hidden, c->qd, 0, 0, base + 1}; return STS_OK; }
+  if (n == "wv") { *t = TensorRef{w.wqkv, nullptr, d.hidden, c->kvd, d.hidden, c->qd + c->kvd, 0, 0, base + 2}; return STS_OK; }
+  if (n == "wo") { *t = TensorRef{w.wo, nullptr, c->qd, d.hidden, c->qd, 0, 0, 0, base + 3}; return STS_OK; }
+  if (n == "wg") { *t = TensorRef{w.wgu, nullptr, d.hidden, d.mlp, d.hidden, 0, 32, 0, base + 4}; return STS_OK; }
+  if (n == "wu") { *t = TensorRef{w.wgu, nullptr, d.hidden, d.mlp, d.hidden, 0, 32, 1, base + 5}; return STS_OK; }
+  if (n == "wd") { *t = TensorRef{w.wd, nullptr, d.mlp, d.hidden, d.mlp, 0, 0, 0, base + 6}; return STS_OK; }
+  return STS_EINVAL;
+}
+
+}  // namespace
+
+// ======================================================================================= C ABI
+extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* params, sts_ctx** out) {
+  if (!desc || !params || !out) return STS_EINVAL;
+  const sts_model_desc& d = *desc;
+  if (d.n_layers < 1 || d.hidden < 64 || d.hidden % 128 || d.mlp % 64 || (2 * d.mlp) % 128 || d.vocab % 128) return STS_EINVAL;
+  if ((d.head_dim != 64 && d.head_dim != 128) || d.page_tokens != 16) return STS_EINVAL;
+  if (d.n_kv_heads < 1 || d.n_q_heads % d.n_kv_heads) return STS_EINVAL;
+  const int grp = d.n_q_heads / d.n_kv_heads;
+  if (!(grp == 1 || grp == 4 || (grp == 8 && d.head_dim == 128))) return STS_EINVAL;
+  if (((d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim) % 128 || (d.n_q_heads * d.head_dim) % 64 || d.mlp % 32) return STS_EINVAL;
+  if (params->kv_pool_pages < 1 || params->max_prefill_tokens < 1 || params->max_prefill_seqs < 1 ||
+      params->max_decode_batch < 1 || params->max_seqs < 1 || params->max_pages_per_seq < 1) return STS_EINVAL;
+  int ndev = 0;
+  HIPCK(hipGetDeviceCount(&ndev));
+  if (ndev < 1) { g_hip_err = (int)hipErrorNoDevice; return STS_EHIP; }
+  HIPCK(hipSetDevice(0));
+  hipDeviceProp_t prop;
+  HIPCK(hipGetDeviceProperties(&prop, 0));
+  sts_ctx* c = new sts_ctx();
+  c->d = d; c->p = *params; c->n_cu = prop.multiProcessorCount;
+  c->qd = d.n_q_heads * d.head_dim; c->kvd = d.n_kv_heads * d.head_dim; c->qkvn = c->qd + 2 * c->kvd;
+  c->geo = KvGeom{d.n_kv_heads, d.head_dim, d.page_tokens};
+  auto fail = [&](int rc) { sts_destroy(c); return rc; };
+  int rc;
+  // weights
+  if ((rc = dev_alloc(c, &c->emb, (size_t)d.vocab * d.hidden)) || (rc = dev_alloc(c, &c->lm, (size_t)d.vocab * d.hidden)) ||
+      (rc = dev_alloc(c, &c->gf, d.hidden))) return fail(rc);
+  c->layers.resize(d.n_layers);
+  for (auto& w : c->layers) {
+    if ((rc = dev_alloc(c, &w.wqkv, (size_t)c->qkvn * d.hidden)) || (rc = dev_alloc(c, &w.wo, (size_t)d.hidden * c->qd)) ||
+        (rc = dev_alloc(c, &w.wgu, (size_t)2 * d.mlp * d.hidden)) || (rc = dev_alloc(c, &w.wd, (size_t)d.hidden * d.mlp)) ||
+        (rc = dev_alloc(c, &w.g1, d.hidden)) || (rc = dev_alloc(c, &w.g2, d.hidden))) return fail(rc);
+  }
+  // KV pool
+  c->pool_layer_elems = (size_t)params->kv_pool_pages * c->geo.page_elems();
+  if ((rc = dev_alloc(c, &c->pool, c->pool_layer_elems * d.n_layers))) return fail(rc);
+  if (hipMemset(c->pool, 0, c->pool_layer_elems * d.n_layers * sizeof(bf16)) != hipSuccess) return fail(STS_EHIP);
+  c->page_used.assign(params->kv_pool_pages, 0);
+  for (int pg = params->kv_pool_pages - 1; pg >= 0; pg--) c->free_pages.push_back(pg);   // pop_back hands out page 0 first
+  c->seqs.resize(params->max_seqs);
+  // rotary frequencies theta^(-2i/d), in double
+  {
+    std::vector<double> f(d.head_dim / 2);
+    for (int i = 0; i < d.head_dim / 2; i++) f[i] = std::pow((double)d.rope_theta, -2.0 * i / d.head_dim);
+    if ((rc = dev_alloc(c, &c->inv_freq, f.size()))) return fail(rc);
+    if (hipMemcpy(c->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess) return fail(STS_EHIP);
+  }
+  for (int side = 0; side < 2; side++) if ((rc = alloc_phase(c, side))) return fail(rc);
+  // gains = 1, weights generated or zero
+  auto ones = [&](float* g) { return fill_f32(nullptr, g, 1.0f, d.hidden) == hipSuccess ? STS_OK : STS_EHIP; };
+  if ((rc = ones(c->gf))) return fail(rc);
+  for (auto& w : c->layers) if ((rc = ones(w.g1)) || (rc = ones(w.g2))) return fail(rc);
+  const char* mats[] = {"emb", "lm", "wq", "wk", "wv", "wo", "wg", "wu", "wd"};
+  for (int l = 0; l < d.n_layers; l++) {
+    for (const char* name : mats) {
+      const bool global = !std::strcmp(name, "emb") || !std::strcmp(name, "lm");
+      if (global && l > 0) continue;
+      TensorRef t;
+      if ((rc = find_tensor(c, l, name, &t))) return fail(rc);
+      hipError_t e;
+      if (params->init_weights) e = init_weight(nullptr, t.w, t.ld, params->weight_seed, t.tid, t.rows, t.cols, t.row_off, t.ib, t.phase);
+      else e = hipMemset(t.w + (size_t)(t.ib ? 0 : t.row_off) * t.ld, 0, (size_t)(t.ib ? 2 * t.rows : t.rows) * t.ld * sizeof(bf16));
+      if (e != hipSuccess) { g_hip_err = (int)e; return fail(STS_EHIP); }
+    }
+  }
+  if (hipDeviceSynchronize() != hipSuccess) return fail(STS_EHIP);
+  // default partition: the whole GPU for both phases (time-multiplexed) until told otherwise
+  c->part_cus[0] = c->part_cus[1] = c->n_cu;
+  if ((rc = select_streams(c))) return fail(rc);
+  *out = c;
+  return STS_OK;
+}
+
+extern "C" int sts_destroy(sts_ctx* c) {
+  if (!c) return STS_EINVAL;
+  (void)hipDeviceSynchronize();
+  for (auto& kv : c->streams) (void)hipStreamDestroy(kv.second);
+  for (int side = 0; side < 2; side++) {
+    Phase& ph = c->ph[side];
+    if (ph.ev0) (void)hipEventDestroy(ph.ev0);
+    if (ph.ev1) (void)hipEventDestroy(ph.ev1);
+    for (hipEvent_t e : ph.kev) (void)hipEventDestroy(e);
+    void* hosts[] = {ph.h_tokens, ph.h_bt, ph.h_rows, ph.h_pseq, ph.h_dseq, ph.h_items, ph.h_logits, ph.h_next};
+    for (void* p : hosts) if (p) (void)hipHostFree(p);
+  }
+  for (void* p : c->allocs) (void)hipFree(p);
+  if (c->probe_src) (void)hipFree(c->probe_src);
+  if (c->probe_dst) (void)hipFree(c->probe_dst);
+  delete c;
+  return STS_OK;
+}
+
+extern "C" int sts_load_weights(sts_ctx* c, int32_t layer, const char* name, const float* host, size_t count) {
+  if (!c || !host) return STS_EINVAL;
+  TensorRef t;
+  STSCK(find_tensor(c, layer, name, &t));
+  if (count != (size_t)t.rows * t.cols) return STS_EINVAL;
+  if (t.g) { HIPCK(hipMemcpy(t.g, host, count * sizeof(float), hipMemcpyHostToDevice)); return STS_OK; }
+  float* tmp = nullptr;
+  HIPCK(hipMalloc(&tmp, count * sizeof(float)));
+  hipError_t e = hipMemcpy(tmp, host, count * sizeof(float), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = convert_weight(nullptr, t.w, t.ld, tmp, t.rows, t.cols, t.row_off, t.ib, t.phase);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  (void)hipFree(tmp);
+  HIPCK(e);
+  return STS_OK;
+}
+
+extern "C" int sts_read_weights(sts_ctx* c, int32_t layer, const char* name, float* host, size_t count) {
+  if (!c || !host) return STS_EINVAL;
+  TensorRef t;
+  STSCK(find_tensor(c, layer, name, &t));
+  if (count != (size_t)t.rows * t.cols) return STS_EINVAL;
+  if (t.g) { HIPCK(hipMemcpy(host, t.g, count * sizeof(float), hipMemcpyDeviceToHost)); return STS_OK; }
+  float* tmp = nullptr;
+  HIPCK(hipMalloc(&tmp, count * sizeof(float)));
+  hipError_t e = export_weight(nullptr, tmp, t.w, t.ld, t.rows, t.cols, t.row_off, t.ib, t.phase);
+  if (e == hipSuccess) e = hipMemcpy(host, tmp, count * sizeof(float), hipMemcpyDeviceToHost);
+  (void)hipFree(tmp);
+  HIPCK(e);
+  return STS_OK;
+}
+
+// ---- sequences
+extern "C" int sts_seq_create(sts_ctx* c, int32_t* seq_out) {
+  if (!c || !seq_out) return STS_EINVAL;
+  std::lock_guard<std::mutex> g(c->alloc_mu);
+  for (size_t i = 0; i < c->seqs.size(); i++)
+    if (!c->seqs[i].used) { c->seqs[i] = Seq(); c->seqs[i].used = true; *seq_out = (int)i; return STS_OK; }
+  return STS_ENOMEM;
+}
+extern "C" int sts_seq_free(sts_ctx* c, int32_t seq) {
+  if (!c || !valid_seq(c, seq)) return STS_EINVAL;
+  {
+    std::lock_guard<std::mutex> g(c->state_mu);
+    if (c->pf_active) for (int s : c->pf_seqs) if (s == seq) return STS_ESTATE;
+  }
+  std::lock_guard<std::mutex> g(c->alloc_mu);
+  for (int pg : c->seqs[seq].pages) { c->page_used[pg] = 0; c->free_pages.push_back(pg); }
+  c->seqs[seq] = Seq();
+  return STS_OK;
+}
+extern "C" int sts_seq_length(sts_ctx* c, int32_t seq, int32_t* len_out) {
+  if (!c || !valid_seq(c, seq) || !len_out) return STS_EINVAL;
+  *len_out = c->seqs[seq].len;
+  return STS_OK;
+}
+extern "C" int sts_seq_reserve(sts_ctx* c, int32_t seq, int32_t n_tokens) {
+  if (!c || !valid_seq(c, seq) || n_tokens < 0) return STS_EINVAL;
+  return reserve_pages(c, {{seq, n_tokens}});
+}
+extern "C" int sts_pages_free(sts_ctx* c, int32_t* n_out) {
+  if (!c || !n_out) return STS_EINVAL;
+  std::lock_guard<std::mutex> g(c->alloc_mu);
+  *n_out = (int)c->free_pages.size();
+  return STS_OK;
+}
+extern "C" int sts_seq_set_block_table(sts_ctx* c, int32_t seq, const int32_t* pages, int32_t n) {
+  if (!c || !valid_seq(c, seq) || !pages || n < 0 || n > c->p.max_pages_per_seq) return STS_EINVAL;
+  std::lock_guard<std::mutex> g(c->alloc_mu);
+  Seq& s = c->seqs[seq];
+  if (s.len != 0 || !s.pages.empty()) return STS_ESTATE;
+  for (int i = 0; i < n; i++) {
+    if (pages[i] < 0 || pages[i] >= c->p.kv_pool_pages || c->page_used[pages[i]]) return STS_EINVAL;
+    for (int j = 0; j < i; j++) if (pages[j] == pages[i]) return STS_EINVAL;
+  }
+  for (int i = 0; i < n; i++) {
+    c->page_used[pages[i]] = 1;
+    c->free_pages.erase(std::find(c->free_pages.begin(), c->free_pages.end(), pages[i]));
+    s.pages.push_back(pages[i]);
+  }
+  return STS_OK;
+}
+extern "C" int sts_seq_get_block_table(sts_ctx* c, int32_t seq, int32_t* pages, int32_t cap, int32_t* n_out) {
+  if (!c || !valid_seq(c, seq) || !n_out) return STS_EINVAL;
+  const Seq& s = c->seqs[seq];
+  *n_out = (int)s.pages.size();
+  for (int i = 0; i < std::min<int>(cap, (int)s.pages.size()); i++) pages[i] = s.pages[i];
+  return STS_OK;
+}
+
+namespace {
+int upload_bt(sts_ctx* c, const Seq& s, int** d_bt) {
+  HIPCK(hipMalloc(d_bt, std::max<size_t>(1, s.pages.size()) * sizeof(int)));
+  HIPCK(hipMemcpy(*d_bt, s.pages.data(), s.pages.size() * sizeof(int), hipMemcpyHostToDevice));
+  return STS_OK;
+}
+}  // namespace
+
+extern "C" int sts_kv_write(sts_ctx* c, int32_t layer, int32_t seq, int32_t pos0, int32_t n, const float* k, const float* v) {
+  if (!c || !valid_seq(c, seq) || layer < 0 || layer >= c->d.n_layers || pos0 < 0 || n < 1 || !k || !v) return STS_EINVAL;
+  STSCK(reserve_pages(c, {{seq, pos0 + n}}));
+  Seq& s = c->seqs[seq];
+  const size_t cnt = (size_t)n * c->kvd;
+  int* d_bt = nullptr; float *dk = nullptr, *dv = nullptr;
+  STSCK(upload_bt(c, s, &d_bt));
+  HIPCK(hipMalloc(&dk, cnt * sizeof(float))); HIPCK(hipMalloc(&dv, cnt * sizeof(float)));
+  HIPCK(hipMemcpy(dk, k, cnt * sizeof(float), hipMemcpyHostToDevice));
+  HIPCK(hipMemcpy(dv, v, cnt * sizeof(float), hipMemcpyHostToDevice));
+  HIPCK(kv_write_tokens(nullptr, layer_pool(c, layer), c->geo, d_bt, pos0, n, dk, dv));
+  HIPCK(hipDeviceSynchronize());
+  (void)hipFree(d_bt); (void)hipFree(dk); (void)hipFree(dv);
+  s.len = std::max(s.len, pos0 + n);
+  return STS_OK;
+}
+extern "C" int sts_kv_read(sts_ctx* c, int32_t layer, int32_t seq, int32_t pos0, int32_t n, float* k, float* v) {
+  if (!c || !valid_seq(c, seq) || layer < 0 || layer >= c->d.n_layers || pos0 < 0 || n < 1 || !k || !v) return STS_EINVAL;
+  Seq& s = c->seqs[seq];
+  if ((size_t)(pos0 + n + c->geo.page_tokens - 1) / c->geo.page_tokens > s.pages.size()) return STS_EINVAL;
+  const size_t cnt = (size_t)n * c->kvd;
+  int* d_bt = nullptr; float *dk = nullptr, *dv = nullptr;
+  STSCK(upload_bt(c, s, &d_bt));
+  HIPCK(hipMalloc(&dk, cnt * sizeof(float))); HIPCK(hipMalloc(&dv, cnt * sizeof(float)));
+  HIPCK(kv_read_tokens(nullptr, layer_pool(c, layer), c->geo, d_bt, pos0, n, dk, dv));
+  HIPCK(hipMemcpy(k, dk, cnt * sizeof(float), hipMemcpyDeviceToHost));
+  HIPCK(hipMemcpy(v, dv, cnt * sizeof(float), hipMemcpyDeviceToHost));
+  (void)hipFree(d_bt); (void)hipFree(dk); (void)hipFree(dv);
+  return STS_OK;
+}
+extern "C" int sts_kv_fill_random(sts_ctx* c, int32_t seq, int32_t n, uint64_t seed) {
+  if (!c || !valid_seq(c, seq) || n < 1) return STS_EINVAL;
+  STSCK(reserve_pages(c, {{seq, n}}));
+  Seq& s = c->seqs[seq];
+  int* d_bt = nullptr;
+  STSCK(upload_bt(c, s, &d_bt));
+  for (int l = 0; l < c->d.n_layers; l++) HIPCK(kv_fill_random(nullptr, layer_pool(c, l), c->geo, d_bt, 0, n, seed, l));
+  HIPCK(hipDeviceSynchronize());
+  (void)hipFree(d_bt);
+  s.len = n;
+  return STS_OK;
+}
+
+// ---- the step
+extern "C" int sts_prefill_batch(sts_ctx* c, int32_t n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                                 int32_t lb, int32_t le, float* logits) {
+  if (!c) return STS_EINVAL;
+  const int64_t t0 = now_ns();
+  STSCK(prefill_enqueue(c, n_seqs, seqs, lens, tokens, lb, le, logits != nullptr));
+  STSCK(prefill_finish(c, n_seqs, seqs, lens, le, logits));
+  c->last_wall_ns = now_ns() - t0;
+  return STS_OK;
+}
+extern "C" int sts_prefill_append(sts_ctx* c, int32_t seq, const int32_t* tokens, int32_t n_tokens, int32_t lb, int32_t le, float* logits) {
+  return sts_prefill_batch(c, 1, &seq, &n_tokens, tokens, lb, le, logits);
+}
+extern "C" int sts_decode_step(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int32_t n, float* logits, int32_t* next) {
+  if (!c) return STS_EINVAL;
+  const int64_t t0 = now_ns();
+  STSCK(decode_enqueue(c, seqs, in_tokens, n, logits != nullptr, next != nullptr));
+  STSCK(decode_finish(c, seqs, n, logits, next));
+  c->last_wall_ns = now_ns() - t0;
+  return STS_OK;
+}
+extern "C" int sts_step_concurrent(sts_ctx* c, int32_t n_pseqs, const int32_t* pseqs, const int32_t* plens, const int32_t* ptokens,
+                                   int32_t lb, int32_t le, float* plogits, const int32_t* dseqs, const int32_t* dtokens,
+                                   int32_t n_decode, float* dlogits, int32_t* dnext) {
+  if (!c || n_pseqs < 0 || n_decode < 0 || (n_pseqs == 0 && n_decode == 0)) return STS_EINVAL;
+  for (int i = 0; i < n_pseqs; i++) for (int j = 0; j < n_decode; j++) if (pseqs && dseqs && pseqs[i] == dseqs[j]) return STS_EINVAL;
+  const int64_t t0 = now_ns();
+  c->ph[0].ran = c->ph[1].ran = false;
+  if (n_pseqs > 0) STSCK(prefill_enqueue(c, n_pseqs, pseqs, plens, ptokens, lb, le, plogits != nullptr));
+  int rc = STS_OK;
+  if (n_decode > 0) rc = decode_enqueue(c, dseqs, dtokens, n_decode, dlogits != nullptr, dnext != nullptr);
+  if (n_pseqs > 0) { int r2 = prefill_finish(c, n_pseqs, pseqs, plens, le, plogits); if (rc == STS_OK) rc = r2; else return rc; }
+  STSCK(rc);
+  if (n_decode > 0) STSCK(decode_finish(c, dseqs, n_decode, dlogits, dnext));
+  c->last_wall_ns = now_ns() - t0;
+  return STS_OK;
+}
+extern "C" int sts_last_timing(sts_ctx* c, int64_t* prefill_ns, int64_t* decode_ns, int64_t* wall_ns) {
+  if (!c) return STS_EINVAL;
+  int64_t t[2] = {0, 0};
+  for (int side = 0; side < 2; side++) {
+    if (!c->ph[side].ran) continue;
+    float ms = 0.f;
+    HIPCK(hipEventElapsedTime(&ms, c->ph[side].ev0, c->ph[side].ev1));
+    t[side] = (int64_t)((double)ms * 1e6);
+  }
+  if (prefill_ns) *prefill_ns = t[0];
+  if (decode_ns) *decode_ns = t[1];
+  if (wall_ns) *wall_ns = c->last_wall_ns;
+  return STS_OK;
+}
+extern "C" int sts_read_hidden(sts_ctx* c, int32_t phase, float* out, int32_t rows) {
+  if (!c || phase < 0 || phase > 1 || !out || rows < 1 || rows > c->ph[phase].rows) return STS_EINVAL;
+  HIPCK(hipMemcpy(out, c->ph[phase].X, (size_t)rows * c->d.hidden * sizeof(float), hipMemcpyDeviceToHost));
+  return STS_OK;
+}
+
+// ---- partition
+extern "C" int sts_set_partition(sts_ctx* c, int32_t prefill_cus, int32_t decode_cus) {
+  if (!c) return STS_EINVAL;
+  const int v[2] = {prefill_cus, decode_cus};
+  for (int x : v) if (x != 0 && (x < 8 || x > c->n_cu || x % 8 != 0)) return STS_EINVAL;
+  const int old[2] = {c->part_cus[0], c->part_cus[1]};
+  c->part_cus[0] = prefill_cus; c->part_cus[1] = decode_cus;
+  const int rc = select_streams(c);
+  if (rc != STS_OK) { c->part_cus[0] = old[0]; c->part_cus[1] = old[1]; (void)select_streams(c); }
+  return rc;
+}
+extern "C" int sts_get_partition(sts_ctx* c, int32_t* prefill_cus, int32_t* decode_cus, int32_t* total_cus) {
+  if (!c) return STS_EINVAL;
+  if (prefill_cus) *prefill_cus = c->part_cus[0];
+  if (decode_cus) *decode_cus = c->part_cus[1];
+  if (total_cus) *total_cus = c->n_cu;
+  return STS_OK;
+}
+
+// ---- measurement hooks
+extern "C" int sts_kernel_timing(sts_ctx* c, int32_t on) {
+  if (!c) return STS_EINVAL;
+  c->ktiming = on != 0;
+  return STS_OK;
+}
+extern "C" int sts_kernel_times(sts_ctx* c, int32_t phase, int64_t* ns, int64_t* launches, int32_t reset) {
+  if (!c || phase < 0 || phase > 1) return STS_EINVAL;
+  Phase& ph = c->ph[phase];
+  for (int k = 0; k < STS_K_COUNT; k++) {
+    if (ns) ns[k] = ph.kns[k];
+    if (launches) launches[k] = ph.kcnt[k];
+    if (reset) { ph.kns[k] = 0; ph.kcnt[k] = 0; }
+  }
+  return STS_OK;
+}
+extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out) {
+  if (!c || side < 0 || side > 1 || bytes < 4096 || bytes % 16 || iters < 1 || !ns_out) return STS_EINVAL;
+  hipStream_t st;
+  STSCK(get_stream(c, side, cus, &st));
+  if (c->probe_bytes < bytes) {
+    if (c->probe_src) { (void)hipFree(c->probe_src); (void)hipFree(c->probe_dst); c->probe_src = c->probe_dst = nullptr; c->probe_bytes = 0; }
+    HIPCK(hipMalloc(&c->probe_src, bytes)); HIPCK(hipMalloc(&c->probe_dst, bytes));
+    HIPCK(hipMemset(c->probe_src, 1, bytes)); HIPCK(hipMemset(c->probe_dst, 0, bytes));
+    HIPCK(hipDeviceSynchronize());
+    c->probe_bytes = bytes;
+  }
+  hipEvent_t e0, e1;
+  HIPCK(hipEventCreate(&e0)); HIPCK(hipEventCreate(&e1));
+  const int grid = cus * 8;
+  HIPCK(copy_probe(st, c->probe_dst, c->probe_src, bytes, grid));   // warm-up
+  HIPCK(hipEventRecord(e0, st));
+  for (int i = 0; i < iters; i++) HIPCK(copy_probe(st, c->probe_dst, c->probe_src, bytes, grid));
+  HIPCK(hipEventRecord(e1, st));
+  HIPCK(hipEventSynchronize(e1));
+  float ms = 0.f;
+  HIPCK(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  *ns_out = (int64_t)((double)ms * 1e6);
+  return STS_OK;
+}
