@@ -8,6 +8,8 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -90,7 +92,6 @@ struct sts_ctx {
   std::vector<Seq> seqs;
   Phase ph[2];
   int part_cus[2] = {0, 0};
-  std::map<std::pair<int, int>, hipStream_t> streams;
   bool ktiming = false;
   // in-flight layer-sliced prefill batch
   bool pf_active = false; int pf_next_layer = 0; std::vector<int> pf_seqs, pf_lens;
@@ -117,10 +118,22 @@ int host_alloc(T** out, size_t count) {
   return STS_OK;
 }
 
+// CU-masked streams are a process-wide pool: one stream per (side, CU count), created on first
+// use and kept until the process ends. Repartitioning is then a pointer switch, engines that
+// come and go reuse the same hardware queues, and no masked queue is ever torn down.
+std::mutex g_stream_mu;
+std::map<std::pair<int, int>, hipStream_t> g_streams;
+
+void trace(const char* what) {
+  static const bool on = std::getenv("STS_TRACE") != nullptr;
+  if (on) { std::fprintf(stderr, "[sts] %s\n", what); std::fflush(stderr); }
+}
+
 int get_stream(sts_ctx* c, int side, int cus, hipStream_t* out) {
+  std::lock_guard<std::mutex> g(g_stream_mu);
   auto key = std::make_pair(side, cus);
-  auto it = c->streams.find(key);
-  if (it != c->streams.end()) { *out = it->second; return STS_OK; }
+  auto it = g_streams.find(key);
+  if (it != g_streams.end()) { *out = it->second; return STS_OK; }
   // A mask that leaves some XCD without a CU makes stream creation fail (and crashes some
   // runtime versions): contiguous runs of >= 8 bits always cover all 8 XCDs because mask bit i
   // belongs to XCD i % 8.
@@ -131,7 +144,7 @@ int get_stream(sts_ctx* c, int side, int cus, hipStream_t* out) {
   for (int b = lo; b < lo + cus; b++) mask[b / 32] |= 1u << (b % 32);
   hipStream_t s = nullptr;
   HIPCK(hipExtStreamCreateWithCUMask(&s, words, mask.data()));
-  c->streams[key] = s;
+  g_streams[key] = s;
   *out = s;
   return STS_OK;
 }
@@ -544,8 +557,9 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
 
 extern "C" int sts_destroy(sts_ctx* c) {
   if (!c) return STS_EINVAL;
-  (void)hipDeviceSynchronize();
-  for (auto& kv : c->streams) (void)hipStreamDestroy(kv.second);
+  trace("destroy: sync phase streams");
+  for (int side = 0; side < 2; side++) if (c->ph[side].stream) (void)hipStreamSynchronize(c->ph[side].stream);
+  trace("destroy: events and pinned buffers");
   for (int side = 0; side < 2; side++) {
     Phase& ph = c->ph[side];
     if (ph.ev0) (void)hipEventDestroy(ph.ev0);
@@ -554,10 +568,12 @@ extern "C" int sts_destroy(sts_ctx* c) {
     void* hosts[] = {ph.h_tokens, ph.h_bt, ph.h_rows, ph.h_pseq, ph.h_dseq, ph.h_items, ph.h_logits, ph.h_next};
     for (void* p : hosts) if (p) (void)hipHostFree(p);
   }
+  trace("destroy: device memory");
   for (void* p : c->allocs) (void)hipFree(p);
   if (c->probe_src) (void)hipFree(c->probe_src);
   if (c->probe_dst) (void)hipFree(c->probe_dst);
   delete c;
+  trace("destroy: done");
   return STS_OK;
 }
 

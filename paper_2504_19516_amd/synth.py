@@ -210,3 +210,20 @@ def poisson_trace(seed: int, rate_per_s: float, window_s: float, in_dist: dict, 
     out[:, 1] = draw(in_dist, 1)
     out[:, 2] = draw(out_dist, 2)
     return out
+
+
+def kv_values(seed: int, layer: int, which: str, pos0: int, n: int, n_kv: int, d: int) -> np.ndarray:
+    """Synthetic cached K (which="k") or V ("v") of positions [pos0, pos0+n): unit-variance
+    deviates of the same generator as the weights (stream id 0x4B000000 + 2*layer, +1 for V;
+    element index (pos*n_kv + head)*d + dd; no 0.02 factor), rounded to bf16. [n, n_kv, d]."""
+    tid = 0x4B000000 + 2 * layer + (1 if which == "v" else 0)
+    base = _mix_scalar((seed ^ _mix_scalar(tid)) & ((1 << 64) - 1))
+    per = n_kv * d
+    i4 = (np.arange(pos0 * per, (pos0 + n) * per, dtype=np.uint64) << U64(2))
+    acc = np.zeros(n * per, dtype=np.int64)
+    for j in range(3):
+        r = _mix(U64(base) ^ (i4 + U64(j)))
+        for sh in (0, 16, 32, 48):
+            acc += ((r >> U64(sh)) & U64(0xFFFF)).astype(np.int64)
+    v = (acc - 393210).astype(np.float32) * np.float32(2.0 ** -16)
+    return to_bf16(v).reshape(n, n_kv, d)
