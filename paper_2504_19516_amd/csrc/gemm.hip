@@ -71,49 +71,71 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  uint4 ra[A_CH], rb[B_CH];
+  u32x4 ra[A_CH], rb[B_CH];
 #pragma unroll
-  for (int j = 0; j < A_CH; j++) ra[j] = *reinterpret_cast<const uint4*>(a_src[j] + kbeg);
+  for (int j = 0; j < A_CH; j++) ra[j] = *reinterpret_cast<const u32x4*>(a_src[j] + kbeg);
 #pragma unroll
-  for (int j = 0; j < B_CH; j++) rb[j] = *reinterpret_cast<const uint4*>(b_src[j] + kbeg);
+  for (int j = 0; j < B_CH; j++) rb[j] = *reinterpret_cast<const u32x4*>(b_src[j] + kbeg);
 #pragma unroll
-  for (int j = 0; j < A_CH; j++) *reinterpret_cast<uint4*>(As + a_dst[j]) = ra[j];
+  for (int j = 0; j < A_CH; j++) *reinterpret_cast<u32x4*>(As + a_dst[j]) = ra[j];
 #pragma unroll
-  for (int j = 0; j < B_CH; j++) *reinterpret_cast<uint4*>(Bs + b_dst[j]) = rb[j];
+  for (int j = 0; j < B_CH; j++) *reinterpret_cast<u32x4*>(Bs + b_dst[j]) = rb[j];
   __syncthreads();
 
   int cur = 0;
   for (int k = kbeg; k < kend; k += BK) {
-    const bool more = k + BK < kend;
-    if (more) {
+    // Prefetch the next K tile into registers while this one is consumed from LDS. The last
+    // iteration re-reads its own tile (in bounds, never used) so the loop body has no branch.
+    const int kn = min(k + BK, kend - BK);
 #pragma unroll
-      for (int j = 0; j < A_CH; j++) ra[j] = *reinterpret_cast<const uint4*>(a_src[j] + k + BK);
+    for (int j = 0; j < A_CH; j++) ra[j] = *reinterpret_cast<const u32x4*>(a_src[j] + kn);
 #pragma unroll
-      for (int j = 0; j < B_CH; j++) rb[j] = *reinterpret_cast<const uint4*>(b_src[j] + k + BK);
-    }
+    for (int j = 0; j < B_CH; j++) rb[j] = *reinterpret_cast<const u32x4*>(b_src[j] + kn);
+    __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the MFMA block (the scheduler would sink them)
     const bf16* Ac = As + cur * BM * LS + (wm * WTM + l32) * LS + 8 * lh;
     const bf16* Bc = Bs + cur * BN * LS + (wn * WTN + l32) * LS + 8 * lh;
+    // operand fragments are double buffered in registers: the LDS reads of step kk+1 are in
+    // flight while the MFMAs of step kk issue
+    bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * LS);
+#pragma unroll
+    for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * LS);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; kk++) {
-      bf16x8 af[TM], bfr[TN];
+      if (kk + 1 < BK / 16) {
 #pragma unroll
-      for (int i = 0; i < TM; i++) af[i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * LS + kk * 16);
+        for (int i = 0; i < TM; i++) af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * LS + (kk + 1) * 16);
 #pragma unroll
-      for (int j = 0; j < TN; j++) bfr[j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * LS + kk * 16);
+        for (int j = 0; j < TN; j++) bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * LS + (kk + 1) * 16);
+      }
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      bf16* An = As + (cur ^ 1) * BM * LS;
-      bf16* Bn = Bs + (cur ^ 1) * BN * LS;
+    // scheduling recipe: first the TM+TN fragment reads of step 0, then per step one LDS read
+    // slotted between every MPR MFMAs, the last step pure MFMA
+    {
+      constexpr int MPR = (TM * TN + TM + TN - 1) / (TM + TN);
+      __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
 #pragma unroll
-      for (int j = 0; j < A_CH; j++) *reinterpret_cast<uint4*>(An + a_dst[j]) = ra[j];
+      for (int kk = 0; kk + 1 < BK / 16; kk++)
 #pragma unroll
-      for (int j = 0; j < B_CH; j++) *reinterpret_cast<uint4*>(Bn + b_dst[j]) = rb[j];
+        for (int x = 0; x < TM + TN; x++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    bf16* An = As + (cur ^ 1) * BM * LS;
+    bf16* Bn = Bs + (cur ^ 1) * BN * LS;
+#pragma unroll
+    for (int j = 0; j < A_CH; j++) *reinterpret_cast<u32x4*>(An + a_dst[j]) = ra[j];
+#pragma unroll
+    for (int j = 0; j < B_CH; j++) *reinterpret_cast<u32x4*>(Bn + b_dst[j]) = rb[j];
     __syncthreads();
     cur ^= 1;
   }

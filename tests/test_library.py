@@ -1,0 +1,105 @@
+"""CPU-side checks of the built library: it loads, exports every symbol the header declares,
+and its host-only parts (performance estimator) agree with the oracle bit for bit."""
+import os
+import re
+
+import pytest
+
+from oracle import latency as L
+from paper_2504_19516_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sts():
+    from paper_2504_19516_amd import sts as m
+    if not os.path.exists(m.LIB_PATH):
+        from paper_2504_19516_amd import build
+        build.build()
+    m.lib()
+    return m
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sts.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sts_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(sts):
+    names = declared_symbols()
+    assert len(names) >= 35
+    for n in names:
+        assert hasattr(sts.lib(), n), n
+    assert sorted(sts.EXPORTS) == names
+
+
+def test_error_strings(sts):
+    assert sts.lib().sts_strerror(0) == b"ok"
+    assert b"invalid" in sts.lib().sts_strerror(sts.EINVAL)
+
+
+@pytest.mark.skipif(os.path.exists("/dev/kfd"), reason="a GPU is present")
+def test_init_fails_loudly_without_gpu(sts):
+    with pytest.raises(sts.StsError) as e:
+        sts.Engine(synth.tiny_model(), kv_pool_pages=8)
+    assert e.value.code == sts.EHIP
+
+
+def test_wave_quant_matches_oracle(sts):
+    for g, n, b in [(64, 108, 1), (256, 108, 1), (217, 108, 1), (300, 108, 2), (896, 224, 1), (3584, 512, 1), (5, 256, 3)]:
+        w, tail, idle = L.wave_quant(g, n, b)
+        cw, ct, num, den = sts.wave_quant(g, n, b)
+        assert (cw, ct) == (w, tail) and idle == L.Fraction(num, den)
+
+
+def sample_profile():
+    hw = L.Profile(n_cu=256, granule=32, c_peak=1_000_000, d_peak=5_000, n_d=112, tile_m=128, tile_n=128, tile_q=128, use_waveq=1)
+    hw.bw = L.Grid([[32, 64, 128, 256], [0, 2048, 8192]],
+                   [[1500, 1300, 1200], [2600, 2300, 2100], [4500, 4000, 3700], [5200, 4800, 4400]])
+    hw.alpha_prefill = L.Grid([[32, 128, 256], [256, 2048, 16384]],
+                              [[2_400_000, 1_900_000, 1_700_000], [2_300_000, 1_800_000, 1_650_000], [2_500_000, 2_000_000, 1_800_000]])
+    hw.alpha_decode = L.Grid([[32, 256], [8, 64, 256], [4096, 262144]],
+                             [[[3_000_000, 2_000_000], [2_500_000, 1_800_000], [2_200_000, 1_700_000]],
+                              [[6_000_000, 3_000_000], [4_000_000, 2_500_000], [3_000_000, 2_100_000]]])
+    return hw
+
+
+def test_profile_text_roundtrip_between_implementations(sts):
+    hw = sample_profile()
+    text = L.dump_profile(hw)
+    p = sts.Profile(text=text)
+    assert L.parse_profile(p.dump()) == hw
+    with pytest.raises(sts.StsError) as e:
+        sts.Profile(text="not a profile")
+    assert e.value.code == sts.EIO
+
+
+@pytest.mark.parametrize("waveq", [0, 1])
+def test_latency_query_bit_exact_vs_oracle(sts, waveq):
+    import numpy as np
+    hw = sample_profile()
+    hw.use_waveq = waveq
+    p = sts.Profile(text=L.dump_profile(hw))
+    rng = np.random.default_rng(5)
+    for desc in (synth.llama8b_model(), synth.llama70b_model(), synth.tiny_model()):
+        shape = L.Shape(desc.n_layers, desc.hidden, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.mlp, desc.vocab)
+        for _ in range(60):
+            npre, ndec = int(rng.integers(0, 5)), int(rng.integers(0, 40))
+            es = dict(prefill_len=[int(x) for x in rng.integers(1, 20000, npre)],
+                      prefill_ctx=[int(x) for x in rng.integers(0, 5000, npre)],
+                      decode_ctx=[int(x) for x in rng.integers(0, 30000, ndec)],
+                      prefill_cus=int(rng.choice([0, 8, 32, 96, 224, 256])), decode_cus=int(rng.choice([0, 8, 32, 160, 256])),
+                      layer_begin=int(rng.integers(0, desc.n_layers)), n_layers_step=int(rng.integers(1, 5)))
+            assert p.query(desc, es) == L.latency_query(shape, hw, es), es
+            reqs = list(zip(es["prefill_len"], es["prefill_ctx"]))
+            if npre and es["prefill_cus"]:
+                want = L.prefill_roofline_ns(shape, hw, reqs, es["prefill_cus"], es["layer_begin"], es["n_layers_step"])
+                assert p.query(desc, es, roofline=True)[0] == want
+
+
+def test_latency_query_rejects_bad_state(sts):
+    p = sts.Profile(text=L.dump_profile(sample_profile()))
+    with pytest.raises(sts.StsError):
+        p.query(synth.tiny_model(), dict(prefill_len=[0], prefill_ctx=[0], prefill_cus=32))
