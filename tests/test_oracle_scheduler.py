@@ -1,0 +1,130 @@
+"""Pins of the scheduler oracle: cases whose branch can be read off by inspection, the
+nearest-rank percentile, and invariants that hold for any trace."""
+import numpy as np
+import pytest
+
+from oracle import latency as L
+from oracle import scheduler as S
+from paper_2504_19516_amd import synth
+
+SHAPE = L.Shape(32, 4096, 32, 8, 128, 14336, 128256)
+
+
+def profile():
+    hw = L.Profile(n_cu=256, granule=32, c_peak=1_000_000, d_peak=4_000, n_d=112, tile_m=128, tile_n=128, tile_q=128)
+    hw.alpha_prefill = L.Grid([[32, 256], [256, 8192]], [[1_600_000, 1_300_000], [1_700_000, 1_400_000]])
+    hw.alpha_decode = L.Grid([[32, 256], [1, 64], [1024, 131072]], [[[2_500_000, 1_500_000], [2_000_000, 1_400_000]],
+                                                                    [[5_000_000, 2_000_000], [3_000_000, 1_800_000]]])
+    return hw
+
+
+def config(**kw):
+    c = dict(ttft_slo_ns=1_000_000_000, tpot_slo_ns=50_000_000, layers_per_step=4, max_batch_tokens=16384,
+             max_decode_batch=256, kv_pool_pages=40000, mode=0, fixed_prefill_cus=0)
+    c.update(kw)
+    return S.Config(**c)
+
+
+def test_p90_is_nearest_rank():
+    assert S.p90([]) == 0 and S.p90([5]) == 5
+    assert S.p90(list(range(1, 11))) == 9                 # ceil(0.9 * 10) = 9th smallest
+    assert S.p90(list(range(11, 0, -1))) == 10            # ceil(0.9 * 11) = 10th smallest
+    assert S.p90([3, 1]) == 3
+
+
+def test_single_request_gets_whole_gpu_and_layers_in_order():
+    dec, st = S.replay(SHAPE, profile(), config(), [(0, 2048, 1)])
+    assert [(d[4], d[5]) for d in dec] == [(l, l + 4) for l in range(0, 32, 4)]
+    for d in dec:
+        assert d[1] == 1 and d[2] == 0            # one task, request 0
+        assert (d[6], d[7], d[8]) == (256, 0, 2)  # no decode work: ReduceDecodeSM gives decode nothing
+    assert st["n_finished"] == 1 and st["out_tokens"] == 1
+    # simulated clock: TTFT is exactly the sum of the predicted slices
+    assert st["ttft_sum_ns"] == sum(d[10] for d in dec) == st["makespan_ns"]
+
+
+def test_decode_is_given_the_minimum_that_meets_tpot():
+    """Second request arrives while the first decodes: decode keeps the smallest CU count whose
+    predicted P90 TPOT is within the SLO (Section 3.3.1), prefill the rest."""
+    hw, cfg = profile(), config()
+    dec, st = S.replay(SHAPE, hw, cfg, [(0, 512, 200), (100_000_000, 4096, 4)])
+    second = [d for d in dec if d[2] == 1]
+    assert second and all(d[8] == 2 for d in second)
+    dms = {d[7] for d in second}
+    assert dms == {32}                             # a batch of one decodes within 50 ms on the smallest partition
+    assert all(d[6] + d[7] == 256 for d in second)
+    assert st["n_finished"] == 2 and st["n_slo_ok"] == 2
+
+
+def test_tight_tpot_pushes_cus_to_decode_and_overload_balances():
+    hw = profile()
+    trace = [(0, 256, 400)] * 48 + [(400_000_000 + i, 8000, 8) for i in range(12)]
+    loose = S.replay(SHAPE, hw, config(), trace)[0]
+    tight = S.replay(SHAPE, hw, config(tpot_slo_ns=12_000_000), trace)[0]
+    late_loose = [d for d in loose if d[0] > 400_000_000 and d[9] > 0]
+    late_tight = [d for d in tight if d[0] > 400_000_000 and d[9] > 0]
+    assert max(d[7] for d in late_tight) > max(d[7] for d in late_loose)
+    # impossible SLOs on both sides: every late decision is the balanced branch
+    over = S.replay(SHAPE, hw, config(ttft_slo_ns=1_000_000, tpot_slo_ns=1_000_000), trace)[0]
+    late_over = [d for d in over if d[0] > 400_000_000 and d[9] > 0]
+    assert late_over and all(d[8] == 1 for d in late_over)
+    assert all(0 < d[7] < 256 for d in late_over)
+
+
+def check_invariants(shape, hw, cfg, trace):
+    dec, st = S.replay(shape, hw, cfg, trace)
+    n = len(trace)
+    assert st["n_finished"] == n and st["out_tokens"] == int(sum(t[2] for t in trace))
+    started = [d for d in dec if d[4] == 0]
+    assert sum(d[1] for d in started) == n                     # every request enters exactly one batch
+    by_batch = {}
+    for d in dec:
+        by_batch.setdefault((d[3], d[2]), []).append((d[4], d[5]))
+    for slices in by_batch.values():                           # layers run in order, all of them
+        assert slices[0][0] == 0 and slices[-1][1] == shape.n_layers
+        assert all(a[1] == b[0] for a, b in zip(slices, slices[1:]))
+    for d in dec:
+        if cfg.mode == 1:
+            assert d[6] == d[7] == hw.n_cu
+        else:
+            assert d[6] + d[7] == hw.n_cu and d[6] >= hw.granule and d[6] % hw.granule == 0
+    assert all(a[0] <= b[0] for a, b in zip(dec, dec[1:]))
+    return dec, st
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("rate", [2.0, 12.0])
+def test_invariants_on_poisson_trace(mode, rate):
+    trace = synth.poisson_trace(7, rate, 8.0, dict(kind="lognormal", median=600, sigma=1.0, cap=8192),
+                                dict(kind="lognormal", median=250, sigma=0.9, cap=2048))
+    cfg = config(mode=mode, fixed_prefill_cus=160)
+    check_invariants(SHAPE, profile(), cfg, [tuple(int(x) for x in r) for r in trace])
+
+
+def test_reorder_does_not_starve_long_request():
+    hw = profile()
+    trace = [(0, 8000, 2)] + [(1000 + i, 64, 2) for i in range(40)]
+    dec, st = check_invariants(SHAPE, hw, config(ttft_slo_ns=2_000_000_000), trace)
+    first_batches = [d for d in dec if d[4] == 0]
+    assert first_batches[0][2] == 0                           # it arrived alone and starts at once
+    # with a long request queued behind many short ones the guard still brings it forward in time
+    trace2 = [(0, 64, 2)] + [(10, 8000, 2)] + [(20 + i, 64, 2) for i in range(200)]
+    dec2, st2 = check_invariants(SHAPE, hw, config(ttft_slo_ns=400_000_000), trace2)
+    start_long = [d[0] for d in dec2 if d[4] == 0 and d[2] <= 1 and d[3] == S.tasks_hash([1])]
+    assert start_long and start_long[0] <= 400_000_000
+
+
+def test_small_pool_serialises_admission_without_deadlock():
+    trace = [(i * 1000, 1000, 50) for i in range(12)]
+    dec, st = check_invariants(SHAPE, profile(), config(kv_pool_pages=200), trace)   # three requests fit at a time
+    assert st["n_finished"] == 12
+
+
+def test_time_multiplexed_is_slower_under_load():
+    trace = synth.poisson_trace(9, 10.0, 6.0, dict(kind="lognormal", median=600, sigma=1.0, cap=8192),
+                                dict(kind="lognormal", median=250, sigma=0.9, cap=2048))
+    tr = [tuple(int(x) for x in r) for r in trace]
+    a = S.replay(SHAPE, profile(), config(mode=0), tr)[1]
+    b = S.replay(SHAPE, profile(), config(mode=1), tr)[1]
+    assert a["n_finished"] == b["n_finished"] == len(tr)
+    assert a["ttft_sum_ns"] < b["ttft_sum_ns"]
