@@ -1,4 +1,291 @@
-// placeholder until the scheduler is in place
+// SLO-aware scheduler (paper Section 3.3, Algorithm 1) and its trace replay in simulated time.
+// Host only, integer arithmetic, deterministic: the decisions are a pure function of the
+// profile, the trace and the configuration.
+//
+// Per prefill scheduling cycle: estimate TTFT of the in-flight batch P and of the queue Q under
+// the current execution state; reorder Q by least estimated latency unless that would push a
+// request past its TTFT SLO; continue P, or batch from Q until the batch's arithmetic intensity
+// reaches the roofline ridge; then one of SetBalancedSM / ReduceDecodeSM / ReducePrefillSM picks
+// the CU split on the grid {0, g, ..., N-g} of decode CUs; the slice [L_exe, L_exe + L_step) is
+// launched. Each decode step merges the newly prefilled requests and runs on the CUs the last
+// decision left to decode (all CUs when prefill has no work).
+#include <algorithm>
+#include <cstdint>
+#include <vector>
+
+#include "latency.h"
 #include "sts.h"
-extern "C" int sts_sched_replay(const sts_profile*, const sts_model_desc*, const sts_sched_config*, const int64_t*, int64_t,
-                                sts_decision*, int64_t, sts_replay_stats*) { return STS_EINVAL; }
+
+namespace sts {
+namespace {
+
+constexpr int PAGE = 16;
+
+struct Req {
+  int64_t arrival; int32_t in_len, out_len;
+  int32_t pages = 0; int64_t first_token = -1; int32_t n_dec = 0; int64_t finish = -1;
+};
+
+int64_t p90(std::vector<int64_t> v) {
+  if (v.empty()) return 0;
+  std::sort(v.begin(), v.end());
+  return v[(9 * v.size() + 9) / 10 - 1];
+}
+
+struct Replay {
+  const sts_model_desc& s; const Profile& hw; const sts_sched_config& cfg;
+  std::vector<Req> reqs;
+  int n, g;
+  int64_t now = 0; size_t next_arrival = 0;
+  std::vector<int> Q, P, H, D, decode_batch;
+  int l_exe = 0; int64_t pages_free;
+  int pm, dm;
+  int64_t prefill_done_at = -1, decode_done_at = -1;
+  bool turn_decode = false;
+  std::vector<sts_decision> decisions;
+
+  Replay(const sts_model_desc& s_, const Profile& hw_, const sts_sched_config& c_, const int64_t* trace, int64_t cnt)
+      : s(s_), hw(hw_), cfg(c_), n((int)hw_.n_cu), g((int)hw_.granule), pages_free(c_.kv_pool_pages) {
+    reqs.resize(cnt);
+    for (int64_t i = 0; i < cnt; i++) { reqs[i].arrival = trace[3 * i]; reqs[i].in_len = (int32_t)trace[3 * i + 1]; reqs[i].out_len = (int32_t)trace[3 * i + 2]; }
+    if (cfg.mode == 1) { pm = n; dm = n; } else { pm = 0; dm = n; }
+  }
+
+  int64_t t_prefill(const std::vector<int>& ids, int pm_, int l0, int nl) const {
+    std::vector<int32_t> sl(ids.size()), p(ids.size(), 0);
+    for (size_t i = 0; i < ids.size(); i++) sl[i] = reqs[ids[i]].in_len;
+    return predict_prefill_ns(s, hw, sl.data(), p.data(), (int)ids.size(), pm_, l0, nl);
+  }
+  int64_t t_decode(const std::vector<int>& ids, int dm_, int64_t co) const {
+    std::vector<int32_t> cl(ids.size());
+    for (size_t i = 0; i < ids.size(); i++) cl[i] = reqs[ids[i]].in_len + reqs[ids[i]].n_dec;
+    return predict_decode_ns(s, hw, cl.data(), (int)ids.size(), dm_, co);
+  }
+  // One layer's flop and bytes of the batch (the same closed forms the estimator sums).
+  bool intensity_below_ridge(const std::vector<int>& ids, int pm_) const {
+    const int64_t h = s.hidden, d = s.head_dim, qd = (int64_t)s.n_q_heads * d, kvd = (int64_t)s.n_kv_heads * d, qkvn = qd + 2 * kvd, mlp = s.mlp;
+    int64_t t = 0; __int128 flop = 0, mem = 0;
+    for (int i : ids) {
+      const int64_t l = reqs[i].in_len;
+      t += l;
+      flop += 4 * qd * (l * (l + 1) / 2);
+      mem += 2 * (2 * l * qd + 2 * l * kvd);
+    }
+    flop += (__int128)4 * t * h + 2 * t * h * qkvn + 4 * t * qkvn + 2 * t * qd * h + 4 * t * h + 4 * t * h * mlp + 2 * t * mlp * h;
+    mem += (__int128)4 * t * h + 2 * (h * qkvn + t * h + t * qkvn) + 4 * t * qkvn + 2 * (qd * h + t * qd + 2 * t * h) + 4 * t * h +
+           2 * (2 * h * mlp + t * h + t * mlp) + 2 * (mlp * h + t * mlp + 2 * t * h);
+    return flop * hw.d_peak * std::min<int64_t>(pm_, hw.n_d) * hw.n_cu < mem * hw.c_peak * pm_ * hw.n_d;
+  }
+
+  // Algorithm 1. Returns the predicted duration of the slice it launches, or -1 if nothing can
+  // be admitted yet (KV pool full).
+  int64_t schedule() {
+    const int n_layers = s.n_layers;
+    const int pm_cur = pm > 0 ? pm : n;
+    const int64_t t_p = P.empty() ? 0 : t_prefill(P, pm_cur, l_exe, n_layers - l_exe);
+    std::vector<int64_t> est(reqs.size(), 0);
+    for (int i : Q) est[i] = t_prefill(std::vector<int>{i}, pm_cur, 0, n_layers);
+    const std::vector<int> fcfs = Q;
+    std::vector<int> sjf = Q;
+    std::sort(sjf.begin(), sjf.end(), [&](int a, int b) {
+      if (est[a] != est[b]) return est[a] < est[b];
+      if (reqs[a].arrival != reqs[b].arrival) return reqs[a].arrival < reqs[b].arrival;
+      return a < b;
+    });
+    std::vector<int64_t> ttft(reqs.size(), 0), t_fcfs(reqs.size(), 0), t_sjf(reqs.size(), 0);
+    auto ttfts = [&](const std::vector<int>& order, std::vector<int64_t>& out) {
+      int64_t acc = t_p;
+      for (int i : order) { acc += est[i]; out[i] = now - reqs[i].arrival + acc; }
+    };
+    ttfts(fcfs, t_fcfs); ttfts(sjf, t_sjf);
+    std::vector<char> is_hurt(reqs.size(), 0);
+    std::vector<int> q2;
+    for (int i : fcfs) if (t_sjf[i] > cfg.ttft_slo_ns && cfg.ttft_slo_ns >= t_fcfs[i]) { is_hurt[i] = 1; q2.push_back(i); }
+    for (int i : sjf) if (!is_hurt[i]) q2.push_back(i);
+    Q = q2;
+    ttfts(Q, ttft);
+    for (int i : P) ttft[i] = now - reqs[i].arrival + t_p;
+
+    bool satisfy;
+    std::vector<int> next_tasks;
+    if (!P.empty()) {
+      satisfy = true;
+      for (int i : P) if (ttft[i] > cfg.ttft_slo_ns) satisfy = false;
+      next_tasks = P;
+    } else {
+      std::vector<int64_t> qt;
+      for (int i : Q) qt.push_back(ttft[i]);
+      satisfy = p90(qt) <= cfg.ttft_slo_ns;
+      int64_t tokens = 0;
+      while (!Q.empty() && (next_tasks.empty() || intensity_below_ridge(next_tasks, pm_cur))) {
+        const int i = Q.front();
+        const int64_t need = ((int64_t)reqs[i].in_len + reqs[i].out_len + PAGE - 1) / PAGE;
+        if (!next_tasks.empty() && tokens + reqs[i].in_len > cfg.max_batch_tokens) break;
+        if (need > pages_free) break;
+        Q.erase(Q.begin());
+        reqs[i].pages = (int32_t)need; pages_free -= need;
+        next_tasks.push_back(i); tokens += reqs[i].in_len;
+      }
+      if (next_tasks.empty()) return -1;
+      P = next_tasks; l_exe = 0;
+    }
+    const int l_eff = std::min<int>(cfg.layers_per_step, n_layers - l_exe);
+    std::vector<int> dec = D;
+    dec.insert(dec.end(), H.begin(), H.end());
+    int64_t co = 0;
+    for (int i : next_tasks) co += reqs[i].in_len;
+    const int half = std::max(g, (n / 2) / g * g);
+
+    auto tpot90 = [&](int dm_c) -> int64_t {
+      if (dec.empty()) return 0;
+      int64_t extra;
+      if (dm_c > 0) extra = t_decode(dec, dm_c, co);
+      else extra = t_prefill(next_tasks, n, l_exe, l_eff) + t_decode(dec, half, co);
+      std::vector<int64_t> v;
+      for (int i : dec) v.push_back((now - reqs[i].first_token + extra) / (reqs[i].n_dec + 1));
+      return p90(v);
+    };
+    auto ttft_max = [&](int pm_c) -> int64_t {
+      const int64_t t = t_prefill(next_tasks, pm_c, l_exe, n_layers - l_exe);
+      int64_t m = INT64_MIN;
+      for (int i : next_tasks) m = std::max(m, now - reqs[i].arrival + t);
+      return m;
+    };
+    std::vector<int> grid;
+    for (int x = 0; x < n; x += g) grid.push_back(x);
+
+    int branch = 0, pm_new, dm_new;
+    if (cfg.mode == 1) { pm_new = n; dm_new = n; }
+    else if (cfg.mode == 2) { pm_new = cfg.fixed_prefill_cus; dm_new = n - cfg.fixed_prefill_cus; }
+    else {
+      const int cur_dm = (pm > 0 && dm < n) ? dm : half;
+      const int64_t tp_now = tpot90(cur_dm);
+      auto balanced = [&]() -> int {
+        bool have = false; __int128 best = 0; int best_dm = dec.empty() ? grid[0] : grid[1];
+        for (size_t k = dec.empty() ? 0 : 1; k < grid.size(); k++) {
+          const __int128 a = (__int128)ttft_max(n - grid[k]) * cfg.tpot_slo_ns, b = (__int128)tpot90(grid[k]) * cfg.ttft_slo_ns;
+          const __int128 v = a > b ? a : b;
+          if (!have || v < best) { have = true; best = v; best_dm = grid[k]; }
+        }
+        return best_dm;
+      };
+      auto smallest_dm_meeting_tpot = [&]() -> int {
+        for (size_t k = (dec.empty() || !satisfy) ? 0 : 1; k < grid.size(); k++)
+          if (tpot90(grid[k]) <= cfg.tpot_slo_ns) return grid[k];
+        return -1;
+      };
+      if (!satisfy && tp_now > cfg.tpot_slo_ns) { branch = 1; dm_new = balanced(); }
+      else if (tp_now <= cfg.tpot_slo_ns) {
+        branch = 2; dm_new = smallest_dm_meeting_tpot();
+        if (dm_new < 0) dm_new = balanced();
+      } else {
+        branch = 3; dm_new = smallest_dm_meeting_tpot();
+        if (dm_new < 0) {
+          for (int k = (int)grid.size() - 1; k >= 0; k--) if (ttft_max(n - grid[k]) <= cfg.ttft_slo_ns) { dm_new = grid[k]; break; }
+          if (dm_new < 0) dm_new = balanced();
+        }
+      }
+      pm_new = n - dm_new;
+    }
+    pm = pm_new; dm = dm_new;
+    const int64_t dur = t_prefill(next_tasks, pm, l_exe, l_eff);
+    sts_decision r{};
+    r.t_ns = now; r.n_tasks = (int32_t)next_tasks.size();
+    r.first_req = *std::min_element(next_tasks.begin(), next_tasks.end());
+    int64_t hsh = 0;
+    for (int i : next_tasks) hsh = (int64_t)(((__int128)hsh * 1000003 + i + 1) % ((__int128)1 << 62));
+    r.tasks_hash = hsh; r.layer_begin = l_exe; r.layer_end = l_exe + l_eff; r.prefill_cus = pm; r.decode_cus = dm;
+    r.branch = branch; r.decode_batch = (int32_t)dec.size(); r.predicted_ns = dur;
+    decisions.push_back(r);
+    return dur;
+  }
+
+  void finish(int i) { reqs[i].finish = now; pages_free += reqs[i].pages; }
+
+  void run() {
+    const bool serial = cfg.mode == 1;
+    for (;;) {
+      while (next_arrival < reqs.size() && reqs[next_arrival].arrival <= now) {
+        const Req& r = reqs[next_arrival];
+        if (((int64_t)r.in_len + r.out_len + PAGE - 1) / PAGE <= cfg.kv_pool_pages && r.in_len <= cfg.max_batch_tokens) Q.push_back((int)next_arrival);
+        next_arrival++;
+      }
+      bool busy = prefill_done_at >= 0 || decode_done_at >= 0;
+      if (prefill_done_at < 0 && (!P.empty() || !Q.empty()) && !(serial && (busy || (turn_decode && (!D.empty() || !H.empty()))))) {
+        const int64_t dur = schedule();
+        if (dur >= 0) { prefill_done_at = now + dur; busy = true; }
+      }
+      if (decode_done_at < 0 && !(serial && busy)) {
+        while (!H.empty() && (int)D.size() < cfg.max_decode_batch) { D.push_back(H.front()); H.erase(H.begin()); }
+        if (!D.empty()) {
+          const bool prefill_running = prefill_done_at >= 0;
+          const int dm_eff = (serial || !prefill_running) ? n : dm;
+          if (dm_eff > 0) {
+            int64_t co = 0;
+            if (prefill_running && !serial) for (int i : P) co += reqs[i].in_len;
+            decode_batch = D;
+            decode_done_at = now + t_decode(D, dm_eff, co);
+          }
+        }
+      }
+      int64_t next = -1;
+      auto consider = [&](int64_t t) { if (t >= 0 && (next < 0 || t < next)) next = t; };
+      consider(prefill_done_at); consider(decode_done_at);
+      if (next_arrival < reqs.size()) consider(reqs[next_arrival].arrival);
+      if (next < 0) break;
+      now = std::max(now, next);
+      if (prefill_done_at >= 0 && prefill_done_at <= now) {
+        prefill_done_at = -1; turn_decode = true;
+        l_exe = std::min<int>(l_exe + cfg.layers_per_step, s.n_layers);
+        if (l_exe == s.n_layers) {
+          for (int i : P) {
+            reqs[i].first_token = now;
+            if (reqs[i].out_len <= 1) finish(i); else H.push_back(i);
+          }
+          P.clear(); l_exe = 0;
+        }
+      }
+      if (decode_done_at >= 0 && decode_done_at <= now) {
+        decode_done_at = -1; turn_decode = false;
+        for (int i : decode_batch) {
+          reqs[i].n_dec += 1;
+          if (reqs[i].n_dec >= reqs[i].out_len - 1) { finish(i); D.erase(std::find(D.begin(), D.end(), i)); }
+        }
+      }
+    }
+  }
+};
+
+}  // namespace
+}  // namespace sts
+
+extern "C" int sts_sched_replay(const sts_profile* p, const sts_model_desc* desc, const sts_sched_config* cfg,
+                                const int64_t* trace, int64_t n, sts_decision* decisions, int64_t cap, sts_replay_stats* stats) {
+  using namespace sts;
+  if (!p || !desc || !cfg || (n > 0 && !trace) || n < 0 || cap < 0 || (cap > 0 && !decisions)) return STS_EINVAL;
+  const Profile& hw = *sts_profile_get(p);
+  if (cfg->layers_per_step < 1 || cfg->max_batch_tokens < 1 || cfg->max_decode_batch < 1 || cfg->kv_pool_pages < 1 ||
+      cfg->mode < 0 || cfg->mode > 2 || cfg->ttft_slo_ns < 1 || cfg->tpot_slo_ns < 1) return STS_EINVAL;
+  if (hw.n_cu % hw.granule != 0 || hw.n_cu / hw.granule < 2) return STS_EINVAL;
+  if (cfg->mode == 2 && (cfg->fixed_prefill_cus < hw.granule || cfg->fixed_prefill_cus >= hw.n_cu || cfg->fixed_prefill_cus % hw.granule)) return STS_EINVAL;
+  for (int64_t i = 0; i < n; i++) {
+    if (trace[3 * i + 1] < 1 || trace[3 * i + 2] < 1 || trace[3 * i] < 0 || (i > 0 && trace[3 * i] < trace[3 * (i - 1)])) return STS_EINVAL;
+  }
+  Replay r(*desc, hw, *cfg, trace, n);
+  r.run();
+  for (int64_t i = 0; i < std::min<int64_t>(cap, (int64_t)r.decisions.size()); i++) decisions[i] = r.decisions[i];
+  if (stats) {
+    sts_replay_stats st{};
+    st.n_requests = n; st.n_decisions = (int64_t)r.decisions.size();
+    for (const auto& q : r.reqs) {
+      if (q.finish < 0) continue;
+      st.n_finished++; st.out_tokens += q.out_len; st.makespan_ns = std::max(st.makespan_ns, q.finish);
+      st.ttft_sum_ns += q.first_token - q.arrival;
+      int64_t tp = 0;
+      if (q.n_dec > 0) { tp = (q.finish - q.first_token) / q.n_dec; st.tpot_sum_ns += tp; st.n_tpot++; }
+      if (q.first_token - q.arrival <= cfg->ttft_slo_ns && tp <= cfg->tpot_slo_ns) st.n_slo_ok++;
+    }
+    *stats = st;
+  }
+  return STS_OK;
+}
