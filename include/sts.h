@@ -100,6 +100,9 @@ int sts_prefill_batch(sts_ctx* ctx, int32_t n_seqs, const int32_t* seqs, const i
                       int32_t layer_begin, int32_t layer_end, float* logits);
 int sts_prefill_append(sts_ctx* ctx, int32_t seq, const int32_t* tokens, int32_t n_tokens,
                        int32_t layer_begin, int32_t layer_end, float* logits);
+/* Drop the in-flight layer-sliced batch, if any: its sequences keep their old lengths (the pages
+ * reserved for the new tokens stay with them until they are freed). */
+int sts_prefill_abort(sts_ctx* ctx);
 /* Decode: one new token per request through all layers; request i feeds in_tokens[i] at
  * position length(seqs[i]) and attends to everything cached plus itself; lengths grow by 1.
  * logits [n, vocab] and next_tokens [n] (greedy, lowest index wins ties) may each be NULL;
@@ -152,7 +155,7 @@ int sts_probe_copy(sts_ctx* ctx, int32_t side, int32_t cus, size_t bytes, int32_
 /* C[M,N] = A[M,K] * W[N,K]^T. tile_cfg: STS_GEMM_*; epilogue 0 = bf16 store, 1 = fp32 store
  * (split_k >= 1 partial sums are added up on the device), 2 = C += (C given in c_inout),
  * 3 = SwiGLU: W holds gate rows then up rows ([2*N2, K]); output [M, N2]. */
-enum { STS_GEMM_256x256 = 0, STS_GEMM_128x128, STS_GEMM_256x128, STS_GEMM_64x256, STS_GEMM_32x256, STS_GEMM_64x128 };
+enum { STS_GEMM_256x256 = 0, STS_GEMM_128x128, STS_GEMM_256x128, STS_GEMM_64x256, STS_GEMM_32x256, STS_GEMM_64x128, STS_GEMM_64x64 };
 int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                 int32_t tile_cfg, int32_t epilogue, int32_t split_k);
 /* Causal attention of a chunk: q [t, n_q, d], k and v [prior + t, n_kv, d]; query i sits at
@@ -161,9 +164,10 @@ int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32
 int sts_op_attn_prefill(const float* q, const float* k, const float* v, float* out, int32_t t, int32_t prior,
                         int32_t n_q, int32_t n_kv, int32_t d, const int32_t* pages, int32_t n_pool_pages);
 /* Decode attention: q [n, n_q, d]; request r has ctx[r] cached tokens given in k,v (concatenated
- * over requests, [sum ctx, n_kv, d]) and attends to all of them. out [n, n_q, d]. */
+ * over requests, [sum ctx, n_kv, d]) and attends to all of them. A context is processed in chunks
+ * of chunk_pages pages (1..32) whose partial results are merged. out [n, n_q, d]. */
 int sts_op_attn_decode(const float* q, const float* k, const float* v, float* out, int32_t n, const int32_t* ctx,
-                       int32_t n_q, int32_t n_kv, int32_t d, int32_t chunks);
+                       int32_t n_q, int32_t n_kv, int32_t d, int32_t chunk_pages);
 
 /* ---- performance estimator (Section 3.2) — host only, integer arithmetic.
  * Wave quantisation (Section 2.2.1): g workgroups on n units, b workgroups per unit. */
@@ -171,7 +175,7 @@ int sts_wave_quant(int64_t g, int64_t n, int64_t b, int64_t* waves, int64_t* tai
 
 /* Profile = hardware constants (C_peak flop/ns, D_peak bytes/ns, inflection N_d, tile sizes)
  * plus sample grids: bw (D_{p,sl}: decode CUs x co-running prefill tokens -> bytes/ns),
- * alpha_prefill (CUs x tokens -> alpha ppm), alpha_decode (CUs x batch x total context -> ppm).
+ * alpha_prefill (CUs x tokens -> alpha ppm), alpha_decode (CUs x batch x mean context per request -> ppm).
  * Text format: see sts_profile_dump. */
 int sts_profile_parse(const char* text, sts_profile** out);
 int sts_profile_load(const char* path, sts_profile** out);

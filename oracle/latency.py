@@ -16,7 +16,7 @@ Readings where the paper is silent (listed in the design document):
   * wave quantisation enters as T'_k / (1 - idle_k) for prefill GEMM and attention
     kernels before alpha is applied; a switch in the profile turns it off
   * alpha is sampled on a rectilinear grid — prefill over (CUs, new tokens), decode over
-    (CUs, batch size, total context) — and interpolated multilinearly, extrapolated
+    (CUs, batch size, mean context per request) — and interpolated multilinearly, extrapolated
     from the nearest segment outside the grid, clamped to half the smallest sample
   * a phase with zero CUs has latency INF_NS
 """
@@ -61,6 +61,7 @@ class Profile:
     tile_m: int = 256
     tile_n: int = 256
     tile_q: int = 128
+    wgs_per_cu: int = 1                # b of Section 2.2.1: workgroups resident per CU
     use_waveq: int = 1
     bw: Grid | None = None             # D_{p,sl}: axes (decode CUs, co-running prefill tokens) -> bytes/ns
     alpha_prefill: Grid = field(default_factory=lambda: Grid([[256], [2048]], [[PPM]]))
@@ -166,8 +167,8 @@ def srm_ns(flop: int, mem: int, n_p: int, hw: Profile, d_override: int | None = 
     return max(t_c, t_m)
 
 
-def _waveq_adjust(t: int, g: int, n_p: int) -> int:
-    w, tail, _ = wave_quant(g, n_p, 1)
+def _waveq_adjust(t: int, g: int, n_p: int, b: int = 1) -> int:
+    w, tail, _ = wave_quant(g, n_p, b)
     return floor_div(t * n_p * w, n_p * w - n_p + tail)
 
 
@@ -180,7 +181,7 @@ def prefill_roofline_ns(s: Shape, hw: Profile, reqs, pm: int, layer_begin: int, 
     for _, flop, mem, g in ks:
         t = srm_ns(flop, mem, pm, hw)
         if hw.use_waveq and g > 0:
-            t = _waveq_adjust(t, g, pm)
+            t = _waveq_adjust(t, g, pm, hw.wgs_per_cu)
         per_layer += t
     total = per_layer * n_layers_step
     for _, flop, mem, _ in head:
@@ -217,7 +218,7 @@ def predict_decode_ns(s: Shape, hw: Profile, cls, dm: int, co_prefill_tokens: in
     if dm <= 0:
         return INF_NS
     t = decode_roofline_ns(s, hw, cls, dm, co_prefill_tokens)
-    a = alpha_at(hw.alpha_decode, [dm, len(cls), sum(cls)])
+    a = alpha_at(hw.alpha_decode, [dm, len(cls), sum(cls) // len(cls)])
     return floor_div(t * a, PPM)
 
 
@@ -244,7 +245,7 @@ def _nest(flat, dims):
 
 def dump_profile(hw: Profile) -> str:
     lines = ["sts-profile 1"]
-    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "use_waveq"):
+    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq"):
         lines.append(f"{k} {getattr(hw, k)}")
     for name in ("bw", "alpha_prefill", "alpha_decode"):
         g = getattr(hw, name)

@@ -2,11 +2,12 @@
 //
 // HBM-bound: every K and V byte of a request's context is read exactly once per KV head —
 // the G query heads that share a KV head are processed together. Work is split over
-// (request, kv head, context chunk) so that a few long contexts still fill the CUs; a small
-// second kernel merges the chunks' (max, sum, weighted V) partials.
+// (request, kv head, context chunk of a fixed number of pages) so that a few long contexts
+// still fill the CUs while short ones cost few workgroups; a small second kernel merges the
+// chunks' (max, sum, weighted V) partials.
 //
 // Inside a workgroup (4 waves):
-//   1. scores: waves take pages in turn; a lane reads a contiguous 1/4 of one token's K row
+//   1. scores: waves take pages in turn, two in flight each; a lane reads a contiguous 1/4 of one token's K row
 //      (64 bytes for d = 128), so a wave reads one 4 KiB page chunk fully coalesced, and
 //      accumulates q.k with v_dot2_f32_bf16 (no conversions); 4-lane reduction.
 //   2. softmax over the chunk in LDS (exact within the chunk; chunks merge by rescaling).
@@ -25,7 +26,8 @@ __device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
 template <int D, int G>
 __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict__ q, const DecodeSeq* __restrict__ seqs,
                                                           const int* __restrict__ block_tables, const bf16* __restrict__ pool,
-                                                          KvGeom geo, int n_q, int chunks, float* __restrict__ ws, float scale_log2e) {
+                                                          KvGeom geo, int n_q, int chunk_pages, int max_chunks,
+                                                          float* __restrict__ ws, float scale_log2e) {
   constexpr int SEG = D / 4;              // K elements per lane (a token's row is split over 4 lanes)
   constexpr int SEGW = SEG / 2;           // ... as packed bf16 pairs
   constexpr int ROWS = D / 64;            // V^T rows per lane
@@ -38,14 +40,10 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   const DecodeSeq sq = seqs[req];
   const int len = sq.cl + 1;
   const int n_pages = (len + 15) >> 4;
-  const int ppc = (n_pages + chunks - 1) / chunks;
-  const int pg0 = chunk * ppc, pg1 = min(n_pages, pg0 + ppc);
+  const int pg0 = chunk * chunk_pages, pg1 = min(n_pages, pg0 + chunk_pages);
+  if (pg0 >= pg1) return;                 // this request has fewer chunks (the merge knows)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  float* wout = ws + (((size_t)req * geo.n_kv + kvh) * chunks + chunk) * G * (D + 2);
-  if (pg0 >= pg1) {                       // empty chunk: neutral element of the merge
-    for (int i = tid; i < G * (D + 2); i += 256) wout[i] = ((i % (D + 2)) == D) ? -INFINITY : 0.f;
-    return;
-  }
+  float* wout = ws + (((size_t)req * geo.n_kv + kvh) * max_chunks + chunk) * G * (D + 2);
   const int t0 = pg0 * 16, nt = min(len, pg1 * 16) - t0;
   const int* bt = block_tables + sq.bt_off;
   const size_t head_elems = geo.head_elems();
@@ -60,31 +58,36 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
 #pragma unroll
       for (int i = 0; i < SEGW; i++) qr[g][i] = qp[i];
     }
-    for (int pg = pg0 + wave; pg < pg1; pg += 4) {
-      const uint4* kp = reinterpret_cast<const uint4*>(pool + ((size_t)bt[pg] * geo.n_kv + kvh) * head_elems + (size_t)tok * D + seg * SEG);
-      uint4 kr[SEGW / 4];
+    for (int pg = pg0 + wave; pg < pg1; pg += 8) {
+      const bool two = pg + 4 < pg1;                    // wave-uniform
+      const uint4* kp0 = reinterpret_cast<const uint4*>(pool + ((size_t)bt[pg] * geo.n_kv + kvh) * head_elems + (size_t)tok * D + seg * SEG);
+      const uint4* kp1 = reinterpret_cast<const uint4*>(pool + ((size_t)bt[two ? pg + 4 : pg] * geo.n_kv + kvh) * head_elems + (size_t)tok * D + seg * SEG);
+      uint4 kr[2][SEGW / 4];
 #pragma unroll
-      for (int i = 0; i < SEGW / 4; i++) kr[i] = kp[i];
-      float acc[G];
+      for (int i = 0; i < SEGW / 4; i++) { kr[0][i] = kp0[i]; kr[1][i] = kp1[i]; }
 #pragma unroll
-      for (int g = 0; g < G; g++) {
-        float a = 0.f;
+      for (int u = 0; u < 2; u++) {
+        if (u == 1 && !two) break;
+        float acc[G];
 #pragma unroll
-        for (int i = 0; i < SEGW / 4; i++) {
-          a = dot2(kr[i].x, qr[g][4 * i + 0], a);
-          a = dot2(kr[i].y, qr[g][4 * i + 1], a);
-          a = dot2(kr[i].z, qr[g][4 * i + 2], a);
-          a = dot2(kr[i].w, qr[g][4 * i + 3], a);
+        for (int g = 0; g < G; g++) {
+          float a = 0.f;
+#pragma unroll
+          for (int i = 0; i < SEGW / 4; i++) {
+            a = dot2(kr[u][i].x, qr[g][4 * i + 0], a);
+            a = dot2(kr[u][i].y, qr[g][4 * i + 1], a);
+            a = dot2(kr[u][i].z, qr[g][4 * i + 2], a);
+            a = dot2(kr[u][i].w, qr[g][4 * i + 3], a);
+          }
+          a += __shfl_xor(a, 1, 64);
+          a += __shfl_xor(a, 2, 64);
+          acc[g] = a;
         }
-        a += __shfl_xor(a, 1, 64);
-        a += __shfl_xor(a, 2, 64);
-        acc[g] = a;
-      }
-      if (seg == 0) {
-        const int t = (pg - pg0) * 16 + tok;
-        const bool valid = t0 + t < len;
+        if (seg == 0) {
+          const int t = (pg + 4 * u - pg0) * 16 + tok;
 #pragma unroll
-        for (int g = 0; g < G; g++) if (t < nt) S[g][t] = valid ? acc[g] * scale_log2e : -INFINITY;
+          for (int g = 0; g < G; g++) if (t < nt) S[g][t] = acc[g] * scale_log2e;
+        }
       }
     }
   }
@@ -114,27 +117,35 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   for (int g = 0; g < G; g++)
 #pragma unroll
     for (int r = 0; r < ROWS; r++) acc[g][r] = 0.f;
-  for (int pg = pg0 + wave; pg < pg1; pg += 4) {
-    const bf16* vbase = pool + ((size_t)bt[pg] * geo.n_kv + kvh) * head_elems + (size_t)16 * D;
-    uint4 vr[ROWS][2];
+  for (int pg = pg0 + wave; pg < pg1; pg += 8) {
+    const bool two = pg + 4 < pg1;
+    uint4 vr[2][ROWS][2];
 #pragma unroll
-    for (int r = 0; r < ROWS; r++) {
-      const uint4* vp = reinterpret_cast<const uint4*>(vbase + (size_t)(lane + 64 * r) * 16);
-      vr[r][0] = vp[0]; vr[r][1] = vp[1];
-    }
-    const int tb = (pg - pg0) * 16;
-#pragma unroll
-    for (int g = 0; g < G; g++) {
-      const uint4 p0 = *reinterpret_cast<const uint4*>(&P[g][tb]);
-      const uint4 p1 = *reinterpret_cast<const uint4*>(&P[g][tb + 8]);
+    for (int u = 0; u < 2; u++) {
+      const bf16* vbase = pool + ((size_t)bt[(u == 1 && two) ? pg + 4 : pg] * geo.n_kv + kvh) * head_elems + (size_t)16 * D;
 #pragma unroll
       for (int r = 0; r < ROWS; r++) {
-        float a = acc[g][r];
-        a = dot2(vr[r][0].x, p0.x, a); a = dot2(vr[r][0].y, p0.y, a);
-        a = dot2(vr[r][0].z, p0.z, a); a = dot2(vr[r][0].w, p0.w, a);
-        a = dot2(vr[r][1].x, p1.x, a); a = dot2(vr[r][1].y, p1.y, a);
-        a = dot2(vr[r][1].z, p1.z, a); a = dot2(vr[r][1].w, p1.w, a);
-        acc[g][r] = a;
+        const uint4* vp = reinterpret_cast<const uint4*>(vbase + (size_t)(lane + 64 * r) * 16);
+        vr[u][r][0] = vp[0]; vr[u][r][1] = vp[1];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+      if (u == 1 && !two) break;
+      const int tb = (pg + 4 * u - pg0) * 16;
+#pragma unroll
+      for (int g = 0; g < G; g++) {
+        const uint4 p0 = *reinterpret_cast<const uint4*>(&P[g][tb]);
+        const uint4 p1 = *reinterpret_cast<const uint4*>(&P[g][tb + 8]);
+#pragma unroll
+        for (int r = 0; r < ROWS; r++) {
+          float a = acc[g][r];
+          a = dot2(vr[u][r][0].x, p0.x, a); a = dot2(vr[u][r][0].y, p0.y, a);
+          a = dot2(vr[u][r][0].z, p0.z, a); a = dot2(vr[u][r][0].w, p0.w, a);
+          a = dot2(vr[u][r][1].x, p1.x, a); a = dot2(vr[u][r][1].y, p1.y, a);
+          a = dot2(vr[u][r][1].z, p1.z, a); a = dot2(vr[u][r][1].w, p1.w, a);
+          acc[g][r] = a;
+        }
       }
     }
   }
@@ -152,10 +163,13 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
 
 // Merge the chunks of one (request, query head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 template <int D>
-__global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, int n_q, int n_kv, int G, int chunks) {
+__global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
+                                         int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
   const int head = blockIdx.x, req = blockIdx.y, dd = threadIdx.x;
   const int kvh = head / G, g = head % G;
-  const float* base = ws + (((size_t)req * n_kv + kvh) * chunks) * G * (D + 2) + g * (D + 2);
+  const int n_pages = (seqs[req].cl + 1 + 15) >> 4;
+  const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
+  const float* base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * G * (D + 2) + g * (D + 2);
   const size_t cstride = (size_t)G * (D + 2);
   float m = -INFINITY;
   for (int c = 0; c < chunks; c++) m = fmaxf(m, base[c * cstride + D]);
@@ -173,25 +187,25 @@ size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks) { return (size_t
 
 template <int D, int G>
 static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const int* bt, const bf16* pool,
-                          KvGeom geo, int n, int n_q, int chunks, float* ws, float sc) {
-  hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(chunks, geo.n_kv, n), dim3(256), 0, s, q, seqs, bt, pool, geo, n_q, chunks, ws, sc);
-  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, n_q, geo.n_kv, G, chunks);
+                          KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
+  hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(max_chunks, geo.n_kv, n), dim3(256), 0, s, q, seqs, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
 }
 
-// q, out: [n, n_q * d] bf16 (q already rotated). `chunks` must satisfy
-// ceil(pages of the longest context / chunks) * 16 <= attn_decode_max_chunk_tokens().
-// ws: attn_decode_ws_floats(...) floats of scratch.
+// q, out: [n, n_q * d] bf16 (q already rotated). A context is cut into chunks of `chunk_pages`
+// pages (1..32: at most attn_decode_max_chunk_tokens() tokens); `max_chunks` must be at least
+// the chunk count of the longest context. ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
 hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const int* block_tables,
-                       const bf16* pool, KvGeom geo, int n, int n_q, int chunks, float* ws) {
+                       const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws) {
   if (n == 0) return hipSuccess;
-  if (geo.page_tokens != 16 || n_q % geo.n_kv != 0 || chunks < 1) return hipErrorInvalidValue;
+  if (geo.page_tokens != 16 || n_q % geo.n_kv != 0 || chunk_pages < 1 || chunk_pages * 16 > MAX_CHUNK_TOKENS || max_chunks < 1) return hipErrorInvalidValue;
   const int G = n_q / geo.n_kv;
   const float sc = 1.4426950408889634f / sqrtf((float)geo.d);
-  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunks, ws, sc);
-  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunks, ws, sc);
-  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunks, ws, sc);
-  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunks, ws, sc);
-  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunks, ws, sc);
+  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -194,17 +194,17 @@ int k_collect(sts_ctx* c, Phase& ph) {
   } while (0)
 
 int pick_cfg(int m, int n) {
-  const bool n256 = n % 256 == 0;
-  if (m <= 32 && n256) return GEMM_32x256;
-  if (m <= 64) return n256 ? GEMM_64x256 : GEMM_64x128;
+  // decode batches: 64x128 tiles keep two workgroups (8 waves) per CU streaming weights, which
+  // measured faster than 64x256 / 32x256 (one workgroup per CU) at every partition size
+  if (m <= 64) return GEMM_64x128;
   // 128x128 tiles leave room for two workgroups per CU (two waves per SIMD), which hides LDS
   // and global latency better than one 256x256 workgroup; measured faster on every layer shape
   return GEMM_128x128;
 }
 int pick_splits(int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
-  int s = (2 * std::max(cus, 8) + tiles - 1) / tiles;
-  s = std::min(s, std::max(1, k / 512));
+  int s = (2 * std::max(cus, 8) + tiles - 1) / tiles;          // two workgroups per CU of the partition
+  s = std::min(s, std::max(1, k / 512));                        // at least 8 K-steps per slice
   return std::max(1, std::min(s, 8));
 }
 
@@ -352,11 +352,17 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     max_pages = std::max(max_pages, np);
     ph.h_tokens[i] = in_tokens[i];
   }
-  const int chunk_pages = attn_decode_max_chunk_tokens() / pt;
-  const int max_chunks = std::max(1, (mp + chunk_pages - 1) / chunk_pages);
-  int chunks = (max_pages + chunk_pages - 1) / chunk_pages;                                 // what the longest context needs
-  chunks = std::max(chunks, std::min((4 * ph.cus + n * d.n_kv_heads - 1) / (n * d.n_kv_heads), (max_pages + 3) / 4));   // fill the partition
-  chunks = std::max(1, std::min(chunks, std::max(max_chunks, 16)));
+  // Context chunks of a fixed page count: the largest of 32/16/8/4 pages that still yields about
+  // four workgroups per CU of the partition, never more than 128 chunks for the longest context.
+  int chunk_pages = attn_decode_max_chunk_tokens() / pt;
+  const int floor_pages = std::max(4, (max_pages + 127) / 128);
+  while (chunk_pages / 2 >= floor_pages) {
+    long long wgs = 0;
+    for (int i = 0; i < n; i++) wgs += (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages;
+    if (wgs * d.n_kv_heads >= 4LL * ph.cus) break;
+    chunk_pages /= 2;
+  }
+  const int max_chunks = (max_pages + chunk_pages - 1) / chunk_pages;
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
   HIPCK(hipMemcpyAsync(ph.d_dseq, ph.h_dseq, n * sizeof(DecodeSeq), hipMemcpyHostToDevice, st));
@@ -366,10 +372,11 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   const int h = d.hidden;
   KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, c->layers[0].g1, d.rms_eps, n, h));
   auto skinny = [&](int kind, const bf16* A, int lda, const bf16* W, int N, int K, int* splits_out, long long* stride_out) -> int {
+    const long long stride = (long long)n * N;
+    *stride_out = stride;
     const int cfg = pick_cfg(n, N);
     const int splits = pick_splits(cfg, n, N, K, ph.cus);
-    const long long stride = (long long)n * N;
-    *splits_out = splits; *stride_out = stride;
+    *splits_out = splits;
     KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
     return STS_OK;
   };
@@ -378,7 +385,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     int sp; long long ss;
     STSCK(skinny(STS_K_QKV, ph.Xn, h, w.wqkv, c->qkvn, h, &sp, &ss));
     KL(ph, STS_K_ROPE, decode_qkv_finish(st, ph.part, sp, ss, c->qkvn, ph.d_dseq, ph.d_bt, c->inv_freq, ph.Q, layer_pool(c, l), c->geo, n, d.n_q_heads));
-    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunks, ph.attn_ws));
+    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
     STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
     STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
@@ -447,8 +454,7 @@ int alloc_phase(sts_ctx* c, int side) {
     STSCK(host_alloc(&ph.h_items, items));
   } else {
     const size_t widest = std::max<size_t>(std::max(c->qkvn, 2 * d.mlp), d.hidden);
-    const int chunk_pages = attn_decode_max_chunk_tokens() / c->geo.page_tokens;
-    const size_t max_chunks = std::max<size_t>(16, (mp + chunk_pages - 1) / chunk_pages);
+    const size_t max_chunks = std::min<size_t>(128, (mp + 3) / 4);     // see decode_enqueue: chunks of >= 4 pages, <= 128 chunks
     STSCK(dev_alloc(c, &ph.part, 8 * rows * widest));
     STSCK(dev_alloc(c, &ph.Q, rows * c->qd));
     STSCK(dev_alloc(c, &ph.attn_ws, attn_decode_ws_floats((int)rows, d.n_q_heads, d.head_dim, (int)max_chunks)));
@@ -730,6 +736,12 @@ extern "C" int sts_prefill_batch(sts_ctx* c, int32_t n_seqs, const int32_t* seqs
 }
 extern "C" int sts_prefill_append(sts_ctx* c, int32_t seq, const int32_t* tokens, int32_t n_tokens, int32_t lb, int32_t le, float* logits) {
   return sts_prefill_batch(c, 1, &seq, &n_tokens, tokens, lb, le, logits);
+}
+extern "C" int sts_prefill_abort(sts_ctx* c) {
+  if (!c) return STS_EINVAL;
+  std::lock_guard<std::mutex> g(c->state_mu);
+  c->pf_active = false; c->pf_next_layer = 0; c->pf_seqs.clear(); c->pf_lens.clear();
+  return STS_OK;
 }
 extern "C" int sts_decode_step(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int32_t n, float* logits, int32_t* next) {
   if (!c) return STS_EINVAL;

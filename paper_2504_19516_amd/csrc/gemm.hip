@@ -203,6 +203,7 @@ static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int spli
     case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI>(s, g, splits);
     case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits);
     case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI>(s, g, splits);
+    case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits);
     default: return hipErrorInvalidValue;
   }
 }
@@ -210,6 +211,7 @@ static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int spli
 int gemm_tile_n(int cfg) {
   switch (cfg) {
     case GEMM_256x256: case GEMM_64x256: case GEMM_32x256: return 256;
+    case GEMM_64x64: return 64;
     default: return 128;
   }
 }
@@ -229,7 +231,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
                      void* C, int ldc, int M, int N, int K, int splits, long long split_stride) {
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
-  if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128)) return hipErrorInvalidValue;   // wave tile of one block
+  if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128 || cfg == GEMM_64x64)) return hipErrorInvalidValue;   // wave tile of one block
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.split_stride = split_stride;

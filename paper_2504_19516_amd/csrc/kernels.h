@@ -6,7 +6,7 @@ namespace sts {
 
 // ---- GEMM -------------------------------------------------------------------------------
 enum GemmEpilogue { EPI_BF16 = 0, EPI_F32 = 1, EPI_RESID_F32 = 2, EPI_SWIGLU_BF16 = 3 };
-enum GemmConfig { GEMM_256x256 = 0, GEMM_128x128 = 1, GEMM_256x128 = 2, GEMM_64x256 = 3, GEMM_32x256 = 4, GEMM_64x128 = 5, GEMM_NCFG = 6 };
+enum GemmConfig { GEMM_256x256 = 0, GEMM_128x128 = 1, GEMM_256x128 = 2, GEMM_64x256 = 3, GEMM_32x256 = 4, GEMM_64x128 = 5, GEMM_64x64 = 6, GEMM_NCFG = 7 };
 int gemm_tile_m(int cfg);
 int gemm_tile_n(int cfg);
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
@@ -75,9 +75,9 @@ hipError_t attn_prefill(hipStream_t s, const bf16* qkv, int ld, bf16* out, int l
                         const AttnItem* items, int n_items, const int* block_tables, const bf16* pool,
                         KvGeom geo, int n_q);
 int attn_prefill_tile_q();
-size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks);
+size_t attn_decode_ws_floats(int n, int n_q, int d, int max_chunks);
 hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const int* block_tables,
-                       const bf16* pool, KvGeom geo, int n, int n_q, int chunks, float* ws);
+                       const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws);
 int attn_decode_max_chunk_tokens();
 
 }  // namespace sts

@@ -102,9 +102,9 @@ int64_t srm_ns(int64_t flop, int64_t mem, int64_t n_p, const Profile& hw, int64_
   return std::max(t_c, t_m);
 }
 
-static int64_t waveq_adjust(int64_t t, int64_t g, int64_t n_p) {
+static int64_t waveq_adjust(int64_t t, int64_t g, int64_t n_p, int64_t b) {
   int64_t w, tail;
-  wave_quant(g, n_p, 1, &w, &tail);
+  wave_quant(g, n_p, b, &w, &tail);
   return floor_div((i128)t * n_p * w, n_p * w - n_p + tail);
 }
 
@@ -115,7 +115,7 @@ int64_t prefill_roofline_ns(const sts_model_desc& s, const Profile& hw, const in
   int64_t per_layer = 0;
   for (const Kern& k : ks) {
     int64_t t = srm_ns(k.flop, k.mem, pm, hw, -1);
-    if (hw.use_waveq && k.g > 0) t = waveq_adjust(t, k.g, pm);
+    if (hw.use_waveq && k.g > 0) t = waveq_adjust(t, k.g, pm, hw.wgs_per_cu);
     per_layer += t;
   }
   int64_t total = per_layer * n_layers_step;
@@ -153,7 +153,7 @@ int64_t predict_decode_ns(const sts_model_desc& s, const Profile& hw, const int3
   const int64_t t = decode_roofline_ns(s, hw, cl, n, dm, co_tokens);
   int64_t ctx = 0;
   for (int i = 0; i < n; i++) ctx += cl[i];
-  const int64_t x[3] = {dm, n, ctx};
+  const int64_t x[3] = {dm, n, ctx / n};
   return floor_div((i128)t * alpha_at(hw.alpha_decode, x), PPM);
 }
 
@@ -204,11 +204,11 @@ bool parse_profile(const std::string& text, Profile* hw) {
     if (!(ls >> v)) return false;
     if (key == "n_cu") hw->n_cu = v; else if (key == "granule") hw->granule = v; else if (key == "c_peak") hw->c_peak = v;
     else if (key == "d_peak") hw->d_peak = v; else if (key == "n_d") hw->n_d = v; else if (key == "tile_m") hw->tile_m = v;
-    else if (key == "tile_n") hw->tile_n = v; else if (key == "tile_q") hw->tile_q = v; else if (key == "use_waveq") hw->use_waveq = v;
+    else if (key == "tile_n") hw->tile_n = v; else if (key == "tile_q") hw->tile_q = v; else if (key == "wgs_per_cu") hw->wgs_per_cu = v; else if (key == "use_waveq") hw->use_waveq = v;
     else return false;
   }
   return header && hw->n_cu > 0 && hw->granule > 0 && hw->c_peak > 0 && hw->d_peak > 0 && hw->n_d > 0 && hw->tile_m > 0 &&
-         hw->tile_n > 0 && hw->tile_q > 0;
+         hw->tile_n > 0 && hw->tile_q > 0 && hw->wgs_per_cu > 0;
 }
 
 static void dump_grid(std::ostringstream& o, const char* name, const Grid& g) {
@@ -221,7 +221,7 @@ std::string dump_profile(const Profile& hw) {
   std::ostringstream o;
   o << "sts-profile 1\n";
   o << "n_cu " << hw.n_cu << "\ngranule " << hw.granule << "\nc_peak " << hw.c_peak << "\nd_peak " << hw.d_peak << "\nn_d " << hw.n_d
-    << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nuse_waveq " << hw.use_waveq << "\n";
+    << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nwgs_per_cu " << hw.wgs_per_cu << "\nuse_waveq " << hw.use_waveq << "\n";
   dump_grid(o, "bw", hw.bw);
   dump_grid(o, "alpha_prefill", hw.alpha_prefill);
   dump_grid(o, "alpha_decode", hw.alpha_decode);

@@ -87,9 +87,9 @@ extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32
     if (!part || !dC) return STS_EHIP;
     e = gemm_bf16(nullptr, tile_cfg, EPI_F32, dA, k, dW, k, part, n, m, n, k, split_k, (long long)m * n);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
-    // a split count the K extent cannot feed leaves trailing partials unwritten: clear first
-    // is not needed because gemm_bf16 clamps the grid; sum exactly the launched splits
-    const int ksteps = k / 64, per = (ksteps + split_k - 1) / split_k, used = (ksteps + per - 1) / per;
+    // the tiled kernel launches only as many splits as the K extent can feed: sum exactly those
+    const int ksteps = k / 64, per = (ksteps + split_k - 1) / split_k;
+    const int used = (ksteps + per - 1) / per;
     if (reduce_f32(nullptr, dC, part, used, (long long)m * n, (size_t)m * n) != hipSuccess) return STS_EHIP;
     if (hipMemcpy(c_inout, dC, (size_t)m * n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) return STS_EHIP;
   } else {
@@ -141,8 +141,8 @@ extern "C" int sts_op_attn_prefill(const float* q, const float* k, const float* 
 }
 
 extern "C" int sts_op_attn_decode(const float* q, const float* k, const float* v, float* out, int32_t n, const int32_t* ctx,
-                                  int32_t n_q, int32_t n_kv, int32_t d, int32_t chunks) {
-  if (!q || !k || !v || !out || !ctx || n < 1 || n_q < 1 || n_kv < 1 || n_q % n_kv || (d != 64 && d != 128) || chunks < 1) return STS_EINVAL;
+                                  int32_t n_q, int32_t n_kv, int32_t d, int32_t chunk_pages) {
+  if (!q || !k || !v || !out || !ctx || n < 1 || n_q < 1 || n_kv < 1 || n_q % n_kv || (d != 64 && d != 128) || chunk_pages < 1) return STS_EINVAL;
   size_t total = 0; int max_pages = 0, tot_pages = 0;
   for (int i = 0; i < n; i++) {
     if (ctx[i] < 1) return STS_EINVAL;
@@ -150,7 +150,8 @@ extern "C" int sts_op_attn_decode(const float* q, const float* k, const float* v
     const int np = (ctx[i] + 15) / 16;
     max_pages = std::max(max_pages, np); tot_pages += np;
   }
-  if ((max_pages + chunks - 1) / chunks * 16 > attn_decode_max_chunk_tokens()) return STS_EINVAL;
+  if (chunk_pages * 16 > attn_decode_max_chunk_tokens()) return STS_EINVAL;
+  const int max_chunks = (max_pages + chunk_pages - 1) / chunk_pages;
   DevBufs b;
   KvGeom geo{n_kv, d, 16};
   bf16* pool = b.get<bf16>((size_t)tot_pages * geo.page_elems());
@@ -160,7 +161,7 @@ extern "C" int sts_op_attn_decode(const float* q, const float* k, const float* v
   float* dv = b.get<float>(total * n_kv * d);
   bf16* dq = upload_bf16(b, q, (size_t)n * n_q * d);
   bf16* dout = b.get<bf16>((size_t)n * n_q * d);
-  float* ws = b.get<float>(attn_decode_ws_floats(n, n_q, d, chunks));
+  float* ws = b.get<float>(attn_decode_ws_floats(n, n_q, d, max_chunks));
   if (!pool || !d_bt || !d_seq || !dk || !dv || !dq || !dout || !ws) return STS_EHIP;
   std::vector<int> bt((size_t)n * max_pages, 0);
   std::vector<DecodeSeq> seqs(n);
@@ -181,7 +182,7 @@ extern "C" int sts_op_attn_decode(const float* q, const float* k, const float* v
     if (kv_write_tokens(nullptr, pool, geo, d_bt + (size_t)i * max_pages, 0, ctx[i], dk + off * n_kv * d, dv + off * n_kv * d) != hipSuccess) return STS_EHIP;
     off += ctx[i];
   }
-  hipError_t e = attn_decode(nullptr, dq, dout, d_seq, d_bt, pool, geo, n, n_q, chunks, ws);
+  hipError_t e = attn_decode(nullptr, dq, dout, d_seq, d_bt, pool, geo, n, n_q, chunk_pages, max_chunks, ws);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
   int rc = download_bf16(b, out, dout, (size_t)n * n_q * d);
   if (hipDeviceSynchronize() != hipSuccess) return STS_EHIP;

@@ -1,0 +1,247 @@
+"""Offline profiling for the performance estimator (paper Section 3.2.4): one sweep of memory
+and compute throughput over CU counts builds the SM-scaling roofline (D_peak, N_d, C_peak,
+D_{p,sl}), then a sparse set of execution states calibrates alpha (Eq. 2). Writes the profile
+text that `sts_profile_load` reads, and can score a profile on held-out execution states.
+
+    python -m paper_2504_19516_amd.profiler --model 8b --layers 32 --out profiles/mi355x_llama8b.profile
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import threading
+import time
+
+import numpy as np
+
+from . import sts, synth
+
+PPM = 1_000_000
+
+
+def profile_text(hw: dict, grids: dict) -> str:
+    lines = ["sts-profile 1"]
+    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq"):
+        lines.append(f"{k} {int(hw[k])}")
+    for name in ("bw", "alpha_prefill", "alpha_decode"):
+        if name not in grids:
+            continue
+        axes, values = grids[name]
+        lines.append(f"grid {name} {len(axes)}")
+        for ax in axes:
+            lines.append("axis " + " ".join(str(int(a)) for a in ax))
+        lines.append("values " + " ".join(str(int(v)) for v in np.asarray(values).reshape(-1)))
+    return "\n".join(lines) + "\n"
+
+
+class Profiler:
+    def __init__(self, desc, max_tokens=8192, max_batch=64, max_ctx=8192, granule=32):
+        self.desc, self.granule = desc, granule
+        pages = (max_batch * (max_ctx + 64) + 2 * max_tokens) // 16 + 64
+        self.eng = sts.Engine(desc, weight_seed=1, init_weights=True, kv_pool_pages=pages, max_prefill_tokens=max_tokens,
+                              max_prefill_seqs=4, max_decode_batch=max_batch, max_seqs=max_batch + 8,
+                              max_pages_per_seq=(max_ctx + 128) // 16)
+        self.n_cu = self.eng.get_partition()[2]
+        self.hw = dict(n_cu=self.n_cu, granule=granule, c_peak=2_500_000, d_peak=8_000, n_d=self.n_cu, tile_m=128, tile_n=128,
+                       tile_q=128, wgs_per_cu=2, use_waveq=1)
+        self.grids = {}
+
+    def close(self):
+        self.eng.close()
+
+    # ---- raw measurements ------------------------------------------------------------------
+    def copy_bw(self, cus, nbytes=1 << 28, iters=8):
+        """bytes/ns moved (read + written) by the copy probe on `cus` CUs of the decode side."""
+        ns = self.eng.probe_copy(1, cus, nbytes, iters)
+        return 2 * nbytes * iters / ns
+
+    def prefill_ns(self, pm, tokens, ctx=0, layers=4, reps=2):
+        eng = self.eng
+        eng.set_partition(pm, self.n_cu)
+        layers = min(layers, self.desc.n_layers)
+        toks = synth.tokens(3, tokens, self.desc.vocab)
+        best = None
+        for _ in range(reps + 1):
+            s = eng.seq_create()
+            if ctx:
+                eng.kv_fill_random(s, ctx, 77)
+            eng.prefill_append(s, toks, 0, layers, want_logits=False)
+            t = eng.last_timing()[0]
+            if layers < self.desc.n_layers:
+                eng.prefill_abort()
+            eng.seq_free(s)
+            best = t if best is None else min(best, t)
+        return best, layers
+
+    def make_decode_batch(self, ctxs):
+        seqs = []
+        for i, c in enumerate(ctxs):
+            s = self.eng.seq_create()
+            self.eng.kv_fill_random(s, int(c), 500 + i)
+            self.eng.seq_reserve(s, int(c) + 32)
+            seqs.append(s)
+        return seqs
+
+    def decode_ns(self, dm, seqs, reps=3):
+        eng = self.eng
+        eng.set_partition(self.n_cu, dm)
+        toks = synth.tokens(4, len(seqs), self.desc.vocab)
+        best = None
+        for _ in range(reps + 1):
+            eng.decode_step(seqs, toks, want_logits=False, want_next=True)
+            t = eng.last_timing()[1]
+            best = t if best is None else min(best, t)
+        return best
+
+    def corun_copy_bw(self, dm, prefill_tokens):
+        """Copy bandwidth on dm decode CUs while a prefill of `prefill_tokens` runs on the rest."""
+        if prefill_tokens == 0:
+            return self.copy_bw(dm)
+        eng = self.eng
+        pm = self.n_cu - dm
+        eng.set_partition(pm, dm)
+        toks = synth.tokens(3, prefill_tokens, self.desc.vocab)
+        s = eng.seq_create()
+        # size the prefill slice so it outlasts the probe
+        layers = self.desc.n_layers
+        th = threading.Thread(target=lambda: eng.prefill_append(s, toks, 0, layers, want_logits=False))
+        th.start()
+        time.sleep(0.004)
+        bw = self.copy_bw(dm, nbytes=1 << 27, iters=6)
+        th.join()
+        eng.seq_free(s)
+        return bw
+
+    # ---- the sweep -----------------------------------------------------------------------
+    def sweep_hardware(self, log=print):
+        g, n = self.granule, self.n_cu
+        cus = list(range(g, n + 1, g))
+        bws = {c: self.copy_bw(c) for c in cus}
+        d_peak = max(bws.values())
+        n_d = next(c for c in cus if bws[c] >= 0.95 * d_peak)
+        self.hw.update(d_peak=int(d_peak), n_d=n_d)
+        log(f"copy bandwidth bytes/ns by CUs: { {c: round(b) for c, b in bws.items()} } -> D_peak {d_peak:.0f}, N_d {n_d}")
+        # compute peak: the largest prefill GEMM at full GPU
+        self.eng.kernel_timing(True)
+        self.eng.kernel_times(0, reset=True)
+        t, layers = self.prefill_ns(n, 4096, layers=2, reps=1)
+        kt = self.eng.kernel_times(0, reset=True)
+        self.eng.kernel_timing(False)
+        gu_ns, cnt = kt["gateup"]
+        flop = 2 * 4096 * self.desc.hidden * 2 * self.desc.mlp
+        c_peak = flop / (gu_ns / cnt)
+        self.hw.update(c_peak=int(c_peak))
+        log(f"gate/up GEMM at {n} CUs: {c_peak / 1e3:.0f} TFLOP/s -> C_peak {c_peak:.0f} flop/ns")
+        return bws
+
+    def sweep_contention(self, dms=(32, 64, 128, 192), sls=(0, 2048, 8192), log=print):
+        vals = [[int(self.corun_copy_bw(dm, sl)) for sl in sls] for dm in dms]
+        # a full-GPU decode never co-runs: repeat the solo figure
+        full = int(self.copy_bw(self.n_cu))
+        dms = list(dms) + [self.n_cu]
+        vals.append([full] * len(sls))
+        self.grids["bw"] = ([dms, list(sls)], vals)
+        log(f"D_p,sl bytes/ns (rows: decode CUs {dms}, cols: co-running prefill tokens {list(sls)}): {vals}")
+
+    def _roofline(self, es):
+        text = profile_text(self.hw, {k: v for k, v in self.grids.items() if k == "bw"})
+        return sts.Profile(text=text).query(self.desc, es, roofline=True)
+
+    def calibrate_prefill(self, pms=(32, 64, 128, 192, 256), tokens=(256, 1024, 2048, 8192), log=print):
+        vals = []
+        for pm in pms:
+            row = []
+            for t in tokens:
+                ns, layers = self.prefill_ns(pm, t)
+                es = dict(prefill_len=[t], prefill_ctx=[0], prefill_cus=pm, decode_cus=0, layer_begin=0, n_layers_step=layers)
+                if layers >= self.desc.n_layers:
+                    es["n_layers_step"] = self.desc.n_layers
+                roof = self._roofline(es)[0]
+                # slices that stop before the last layer carry no LM head in the roofline either
+                row.append(max(1, ns * PPM // max(roof, 1)))
+            vals.append(row)
+            log(f"alpha_prefill pm={pm}: {[round(v / PPM, 3) for v in row]}")
+        self.grids["alpha_prefill"] = ([list(pms), list(tokens)], vals)
+
+    def calibrate_decode(self, dms=(32, 64, 128, 256), batches=(8, 64), mean_ctx=(256, 2048), log=print):
+        vals = np.zeros((len(dms), len(batches), len(mean_ctx)), dtype=np.int64)
+        ctx_axis = None
+        for bi, b in enumerate(batches):
+            for ci, mc in enumerate(mean_ctx):
+                ctxs = [mc] * b
+                seqs = self.make_decode_batch(ctxs)
+                for di, dm in enumerate(dms):
+                    ns = self.decode_ns(dm, seqs)
+                    cur = [self.eng.seq_length(s) for s in seqs]
+                    es = dict(decode_ctx=cur, decode_cus=dm, prefill_cus=0)
+                    roof = self._roofline(es)[1]
+                    vals[di, bi, ci] = max(1, ns * PPM // max(roof, 1))
+                for s in seqs:
+                    self.eng.seq_free(s)
+        self.grids["alpha_decode"] = ([list(dms), list(batches), [int(mc) for mc in mean_ctx]], vals.tolist())
+        for di, dm in enumerate(dms):
+            log(f"alpha_decode dm={dm}: {np.round(vals[di] / PPM, 3).tolist()}")
+
+    def text(self):
+        return profile_text(self.hw, self.grids)
+
+
+def evaluate(prof_text, profiler: Profiler, log=print):
+    """MAPE of the profile's predictions on execution states outside the calibration grid."""
+    p = sts.Profile(text=prof_text)
+    desc = profiler.desc
+    errs_p, errs_d = [], []
+    for pm, t in ((96, 512), (160, 1536), (224, 3000), (256, 6000), (64, 4096), (128, 700)):
+        ns, layers = profiler.prefill_ns(pm, t)
+        es = dict(prefill_len=[t], prefill_ctx=[0], prefill_cus=pm, decode_cus=0, layer_begin=0, n_layers_step=layers)
+        pred = p.query(desc, es)[0]
+        errs_p.append(abs(pred - ns) / ns)
+        log(f"prefill pm={pm} tokens={t}: measured {ns / 1e6:.3f} ms predicted {pred / 1e6:.3f} ms")
+    for dm, b, mc in ((96, 32, 1024), (160, 16, 512), (224, 48, 1500), (64, 64, 700), (256, 24, 3000)):
+        rng = np.random.default_rng(b)
+        ctxs = np.clip(rng.normal(mc, mc / 4, b), 16, 8000).astype(int)
+        seqs = profiler.make_decode_batch(ctxs)
+        ns = profiler.decode_ns(dm, seqs)
+        es = dict(decode_ctx=[profiler.eng.seq_length(s) for s in seqs], decode_cus=dm, prefill_cus=0)
+        pred = p.query(desc, es)[1]
+        errs_d.append(abs(pred - ns) / ns)
+        log(f"decode dm={dm} batch={b} mean ctx={mc}: measured {ns / 1e6:.3f} ms predicted {pred / 1e6:.3f} ms")
+        for s in seqs:
+            profiler.eng.seq_free(s)
+    return float(np.mean(errs_p)), float(np.mean(errs_d))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--model", default="8b", choices=["8b", "70b", "tiny"])
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--vocab", type=int, default=128256)
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--report", default=None)
+    args = ap.parse_args()
+    desc = {"8b": synth.llama8b_model, "70b": synth.llama70b_model}.get(args.model, None)
+    desc = desc(args.layers, args.vocab) if desc else synth.tiny_model()
+    lines = []
+
+    def log(msg):
+        print(msg, flush=True)
+        lines.append(msg)
+
+    pr = Profiler(desc)
+    pr.sweep_hardware(log)
+    pr.sweep_contention(log=log)
+    pr.calibrate_prefill(log=log)
+    pr.calibrate_decode(log=log)
+    text = pr.text()
+    with open(args.out, "w") as f:
+        f.write(text)
+    mp, md = evaluate(text, pr, log)
+    log(f"MAPE on held-out execution states: prefill {100 * mp:.1f} %, decode {100 * md:.1f} %")
+    if args.report:
+        with open(args.report, "w") as f:
+            f.write("\n".join(lines) + "\n")
+    pr.close()
+
+
+if __name__ == "__main__":
+    main()

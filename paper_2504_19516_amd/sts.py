@@ -17,7 +17,7 @@ _lib = None
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 K_NAMES = ["embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup", "swiglu", "down", "reduce", "head", "sample"]
-GEMM_CFGS = {"256x256": 0, "128x128": 1, "256x128": 2, "64x256": 3, "32x256": 4, "64x128": 5}
+GEMM_CFGS = {"256x256": 0, "128x128": 1, "256x128": 2, "64x256": 3, "32x256": 4, "64x128": 5, "64x64": 6}
 INF_NS = 1 << 60
 
 
@@ -65,7 +65,7 @@ EXPORTS = [
     "sts_strerror", "sts_last_hip_error", "sts_init", "sts_destroy", "sts_load_weights", "sts_read_weights",
     "sts_seq_create", "sts_seq_free", "sts_seq_length", "sts_seq_reserve", "sts_pages_free", "sts_seq_set_block_table",
     "sts_seq_get_block_table", "sts_kv_write", "sts_kv_read", "sts_kv_fill_random", "sts_prefill_batch",
-    "sts_prefill_append", "sts_decode_step", "sts_step_concurrent", "sts_last_timing", "sts_read_hidden",
+    "sts_prefill_append", "sts_prefill_abort", "sts_decode_step", "sts_step_concurrent", "sts_last_timing", "sts_read_hidden",
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
@@ -209,6 +209,9 @@ class Engine:
         _ck(lib().sts_prefill_append(self._ctx, seq, _p(toks), toks.size, layer_begin, layer_end, _p(logits, C.c_float)), "sts_prefill_append")
         return logits
 
+    def prefill_abort(self):
+        _ck(lib().sts_prefill_abort(self._ctx), "sts_prefill_abort")
+
     def decode_step(self, seqs, in_tokens, want_logits=True, want_next=True):
         seqs, toks = _i32(seqs), _i32(in_tokens)
         logits = np.empty((len(seqs), self.desc.vocab), np.float32) if want_logits else None
@@ -282,12 +285,12 @@ def op_attn_prefill(q, k, v, prior, pages, n_pool_pages):
     return out
 
 
-def op_attn_decode(q, k, v, ctx, chunks):
+def op_attn_decode(q, k, v, ctx, chunk_pages):
     q, k, v, ctx = _f32(q), _f32(k), _f32(v), _i32(ctx)
     n, n_q, d = q.shape
     out = np.empty_like(q)
     _ck(lib().sts_op_attn_decode(_p(q, C.c_float), _p(k, C.c_float), _p(v, C.c_float), _p(out, C.c_float), n, _p(ctx),
-                                 n_q, k.shape[1], d, chunks), "sts_op_attn_decode")
+                                 n_q, k.shape[1], d, chunk_pages), "sts_op_attn_decode")
     return out
 
 

@@ -28,7 +28,7 @@ def sts():
 
 
 @pytest.mark.parametrize("cfg,m", [("256x256", 300), ("128x128", 300), ("256x128", 257), ("64x256", 70), ("32x256", 20),
-                                   ("64x128", 64), ("128x128", 1)])
+                                   ("64x128", 64), ("128x128", 1), ("64x64", 50)])
 def test_gemm_fp32_accumulators(sts, cfg, m):
     n, k = 512, 320
     a = synth.normal_bf16(1, (m, k))
@@ -39,7 +39,7 @@ def test_gemm_fp32_accumulators(sts, cfg, m):
     assert rel(got, ref) <= 1e-5          # in practice fp32 accumulation of 320 terms
 
 
-@pytest.mark.parametrize("cfg,m,split", [("64x256", 64, 4), ("32x256", 8, 8), ("128x128", 130, 2), ("64x128", 33, 3)])
+@pytest.mark.parametrize("cfg,m,split", [("64x256", 64, 4), ("32x256", 8, 8), ("128x128", 130, 2), ("64x128", 33, 3), ("64x64", 64, 8)])
 def test_gemm_split_k(sts, cfg, m, split):
     n, k = 256, 1024
     a = synth.normal_bf16(3, (m, k))
@@ -99,10 +99,11 @@ def test_prefill_attention(sts, t, prior, nq, nkv, d):
     assert np.array_equal(got, got2)
 
 
-@pytest.mark.parametrize("nq,nkv,d,ctx,chunks", [(4, 4, 64, [32, 256, 1, 17, 100], 1), (4, 4, 64, [250, 33], 4),
-                                                 (32, 8, 128, [1000, 40, 513, 16], 3), (8, 1, 128, [700], 2),
-                                                 (32, 8, 128, [2048, 100], 16)])
+@pytest.mark.parametrize("nq,nkv,d,ctx,chunks", [(4, 4, 64, [32, 256, 1, 17, 100], 32), (4, 4, 64, [250, 33], 4),
+                                                 (32, 8, 128, [1000, 40, 513, 16], 8), (8, 1, 128, [700], 5),
+                                                 (32, 8, 128, [2048, 100], 16), (4, 4, 64, [129, 3], 1)])
 def test_decode_attention(sts, nq, nkv, d, ctx, chunks):
+    """`chunks` = pages per context chunk."""
     n = len(ctx)
     q = synth.normal_bf16(15, (n, nq, d))
     k = synth.normal_bf16(16, (sum(ctx), nkv, d))

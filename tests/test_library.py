@@ -55,7 +55,7 @@ def test_wave_quant_matches_oracle(sts):
 
 
 def sample_profile():
-    hw = L.Profile(n_cu=256, granule=32, c_peak=1_000_000, d_peak=5_000, n_d=112, tile_m=128, tile_n=128, tile_q=128, use_waveq=1)
+    hw = L.Profile(n_cu=256, granule=32, c_peak=1_000_000, d_peak=5_000, n_d=112, tile_m=128, tile_n=128, tile_q=128, wgs_per_cu=2, use_waveq=1)
     hw.bw = L.Grid([[32, 64, 128, 256], [0, 2048, 8192]],
                    [[1500, 1300, 1200], [2600, 2300, 2100], [4500, 4000, 3700], [5200, 4800, 4400]])
     hw.alpha_prefill = L.Grid([[32, 128, 256], [256, 2048, 16384]],

@@ -130,8 +130,16 @@ def test_contention_table_replaces_d_p_for_decode():
     assert abs(solo - sum(k[2] for k in ks + head) / 3000) < len(ks) + 2
 
 
+def test_wave_quant_adjustment_uses_workgroups_per_cu():
+    """224 CUs x 2 resident workgroups: 512 tiles need 2 waves of 448 slots, the second one
+    running on 64/2 = 32 CUs -> 1 - idle = (224*2 - 224 + 32) / (224*2)."""
+    assert L._waveq_adjust(1_000_000, 512, 224, 2) == 1_000_000 * 448 // 256
+    assert L._waveq_adjust(1_000_000, 512, 256, 2) == 1_000_000          # exactly one wave
+    assert L._waveq_adjust(1_000_000, 512, 224, 1) == 1_000_000 * 672 // 512
+
+
 def test_profile_text_roundtrip():
-    hw = L.Profile(n_d=112, c_peak=1_234_567)
+    hw = L.Profile(n_d=112, c_peak=1_234_567, wgs_per_cu=2)
     hw.bw = L.Grid([[32, 64], [0, 2048, 8192]], [[1600, 1500, 1400], [2700, 2500, 2300]])
     hw.alpha_decode = L.Grid([[32, 256], [8, 64], [1000, 100000]],
                              [[[1, 2], [3, 4]], [[5, 6], [7, 8]]])
