@@ -104,24 +104,25 @@ hipError_t gather_rows_f32(hipStream_t s, float* dst, const float* src, const in
 }
 
 // ------------------------------------------------------------------ RMSNorm
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
+__device__ __forceinline__ float block_sum(float v, float* red) {   // red: one float per wave (<= 16)
   v = wave_sum(v);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  float t = red[0] + red[1] + red[2] + red[3];
+  float t = 0.f;
+  for (int w = 0; w < (int)(blockDim.x >> 6); w++) t += red[w];
   __syncthreads();
   return t;
 }
 
 __global__ void __launch_bounds__(256) rmsnorm_kernel(bf16* out, const float* X, const float* gain, float eps, int h) {
-  __shared__ float red[4];
+  __shared__ float red[16];
   const float* x = X + (size_t)blockIdx.x * h;
   float ss = 0.f;
   for (int c = threadIdx.x * 4; c < h; c += 1024) {
     f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
     ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
-  const float inv = rsqrtf(block_sum_256(ss, red) / (float)h + eps);
+  const float inv = rsqrtf(block_sum(ss, red) / (float)h + eps);
   for (int c = threadIdx.x * 4; c < h; c += 1024) {
     f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
     f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
@@ -193,60 +194,67 @@ __global__ void __launch_bounds__(256) decode_qkv_finish_kernel(const float* par
                                                                 const DecodeSeq* seqs, const int* block_tables,
                                                                 const double* inv_freq, bf16* q_out, bf16* pool,
                                                                 KvGeom geo, int n_q) {
+  // blockIdx.x = request, blockIdx.y = group of 8 head slots out of n_q (Q) + n_kv (K) + n_kv (V)
   __shared__ float cs[128], sn[128];
   const int row = blockIdx.x, d = geo.d, half = d >> 1;
+  const int slot0 = blockIdx.y * 8, n_slots = n_q + 2 * geo.n_kv, slot1 = min(n_slots, slot0 + 8);
   const DecodeSeq sq = seqs[row];
   const int pos = sq.cl;
-  for (int i = threadIdx.x; i < half; i += blockDim.x) {
-    double sv, cv;
-    sincos((double)pos * inv_freq[i], &sv, &cv);
-    cs[i] = (float)cv; sn[i] = (float)sv;
+  if (slot0 < n_q + geo.n_kv) {               // this group holds rotated heads
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+      double sv, cv;
+      sincos((double)pos * inv_freq[i], &sv, &cv);
+      cs[i] = (float)cv; sn[i] = (float)sv;
+    }
   }
   __syncthreads();
   const int page = block_tables[sq.bt_off + pos / geo.page_tokens], slot = pos % geo.page_tokens;
   const float* pr = partials + (size_t)row * ld;
-  const int n_rot = (n_q + geo.n_kv) * half;
-  for (int t = threadIdx.x; t < n_rot; t += blockDim.x) {
-    const int hd = t / half, i = t % half;
-    float a = 0.f, b = 0.f;
-    for (int z = 0; z < splits; z++) { a += pr[z * split_stride + hd * d + i]; b += pr[z * split_stride + hd * d + i + half]; }
-    // the projection's result is rounded to bf16 before the rotation, as in the prefill path
-    a = bf2f(f2bf(a)); b = bf2f(f2bf(b));
-    const bf16 ya = f2bf(a * cs[i] - b * sn[i]), yb = f2bf(a * sn[i] + b * cs[i]);
-    if (hd < n_q) {
-      q_out[(size_t)row * n_q * d + hd * d + i] = ya; q_out[(size_t)row * n_q * d + hd * d + i + half] = yb;
-    } else {
-      bf16* k = pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
-      k[i] = ya; k[i + half] = yb;
+  for (int t = threadIdx.x; t < (slot1 - slot0) * half; t += blockDim.x) {
+    const int hd = slot0 + t / half, i = t % half;
+    if (hd < n_q + geo.n_kv) {
+      float a = 0.f, b = 0.f;
+      for (int z = 0; z < splits; z++) { a += pr[z * split_stride + hd * d + i]; b += pr[z * split_stride + hd * d + i + half]; }
+      // the projection's result is rounded to bf16 before the rotation, as in the prefill path
+      a = bf2f(f2bf(a)); b = bf2f(f2bf(b));
+      const bf16 ya = f2bf(a * cs[i] - b * sn[i]), yb = f2bf(a * sn[i] + b * cs[i]);
+      if (hd < n_q) {
+        q_out[(size_t)row * n_q * d + hd * d + i] = ya; q_out[(size_t)row * n_q * d + hd * d + i + half] = yb;
+      } else {
+        bf16* k = pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
+        k[i] = ya; k[i + half] = yb;
+      }
+    } else {                                   // a V head: two elements per work item, no rotation
+      const int vh = hd - n_q - geo.n_kv;
+      bf16* v = pool + ((size_t)page * geo.n_kv + vh) * geo.head_elems() + (size_t)geo.page_tokens * d;
+      for (int e = 0; e < 2; e++) {
+        const int dd = i + e * half;
+        float a = 0.f;
+        for (int z = 0; z < splits; z++) a += pr[z * split_stride + hd * d + dd];
+        v[(size_t)dd * geo.page_tokens + slot] = f2bf(a);
+      }
     }
-  }
-  const int voff = (n_q + geo.n_kv) * d;
-  for (int t = threadIdx.x; t < geo.n_kv * d; t += blockDim.x) {
-    const int hd = t / d, dd = t % d;
-    float a = 0.f;
-    for (int z = 0; z < splits; z++) a += pr[z * split_stride + voff + t];
-    bf16* v = pool + ((size_t)page * geo.n_kv + hd) * geo.head_elems() + (size_t)geo.page_tokens * d;
-    v[(size_t)dd * geo.page_tokens + slot] = f2bf(a);
   }
 }
 hipError_t decode_qkv_finish(hipStream_t s, const float* partials, int splits, long long split_stride, int ld,
                              const DecodeSeq* seqs, const int* block_tables, const double* inv_freq,
                              bf16* q_out, bf16* pool, KvGeom geo, int n, int n_q) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(decode_qkv_finish_kernel, dim3(n), dim3(256), 0, s, partials, splits, split_stride, ld, seqs,
+  hipLaunchKernelGGL(decode_qkv_finish_kernel, dim3(n, (n_q + 2 * geo.n_kv + 7) / 8), dim3(256), 0, s, partials, splits, split_stride, ld, seqs,
                      block_tables, inv_freq, q_out, pool, geo, n_q);
   return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ split-K reductions
 // X[row] += sum of partials; optionally out = rmsnorm(X[row]) * gain (bf16).
-__global__ void __launch_bounds__(256) reduce_resid_norm_kernel(float* X, const float* partials, int splits, long long split_stride,
-                                                                bf16* out, const float* gain, float eps, int h) {
-  __shared__ float red[4];
+__global__ void __launch_bounds__(1024) reduce_resid_norm_kernel(float* X, const float* partials, int splits, long long split_stride,
+                                                                 bf16* out, const float* gain, float eps, int h) {
+  __shared__ float red[16];
   float* x = X + (size_t)blockIdx.x * h;
   const float* p = partials + (size_t)blockIdx.x * h;
+  const int step = blockDim.x * 4;
   float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < h; c += 1024) {
+  for (int c = threadIdx.x * 4; c < h; c += step) {
     f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
     for (int z = 0; z < splits; z++) {
       f32x4 q = *reinterpret_cast<const f32x4*>(p + z * split_stride + c);
@@ -256,8 +264,8 @@ __global__ void __launch_bounds__(256) reduce_resid_norm_kernel(float* X, const 
     ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
   if (out == nullptr) return;
-  const float inv = rsqrtf(block_sum_256(ss, red) / (float)h + eps);
-  for (int c = threadIdx.x * 4; c < h; c += 1024) {
+  const float inv = rsqrtf(block_sum(ss, red) / (float)h + eps);
+  for (int c = threadIdx.x * 4; c < h; c += step) {
     f32x4 v = *reinterpret_cast<const f32x4*>(x + c);     // this thread wrote these itself
     f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
     bf16x4 o;
@@ -269,7 +277,8 @@ __global__ void __launch_bounds__(256) reduce_resid_norm_kernel(float* X, const 
 hipError_t reduce_resid_norm(hipStream_t s, float* X, const float* partials, int splits, long long split_stride,
                              bf16* out_norm, const float* gain, float eps, int n, int h) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(n), dim3(256), 0, s, X, partials, splits, split_stride, out_norm, gain, eps, h);
+  const int threads = h >= 4096 ? 1024 : (h >= 2048 ? 512 : 256);      // one float4 per thread where the row allows
+  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(n), dim3(threads), 0, s, X, partials, splits, split_stride, out_norm, gain, eps, h);
   return hipGetLastError();
 }
 
