@@ -100,6 +100,18 @@ int sts_prefill_batch(sts_ctx* ctx, int32_t n_seqs, const int32_t* seqs, const i
                       int32_t layer_begin, int32_t layer_end, float* logits);
 int sts_prefill_append(sts_ctx* ctx, int32_t seq, const int32_t* tokens, int32_t n_tokens,
                        int32_t layer_begin, int32_t layer_end, float* logits);
+/* The same two calls split into launch / poll / finish, so that one control thread can keep a
+ * prefill slice and a decode step in flight at once and react to whichever ends first
+ * (Section 3.3.1: the two phases advance independently). A phase has at most one launch
+ * outstanding (STS_ESTATE otherwise); the blocking calls and sts_step_concurrent refuse to run
+ * while one is. *_finish waits for the launch, updates sequence lengths and copies the outputs
+ * that the launch asked for (pass NULL for the others). */
+int sts_prefill_launch(sts_ctx* ctx, int32_t n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                       int32_t layer_begin, int32_t layer_end, int32_t want_logits);
+int sts_decode_launch(sts_ctx* ctx, const int32_t* seqs, const int32_t* in_tokens, int32_t n, int32_t want_logits, int32_t want_next);
+int sts_phase_done(sts_ctx* ctx, int32_t phase /*0 prefill, 1 decode*/, int32_t* done);
+int sts_prefill_finish(sts_ctx* ctx, float* logits);
+int sts_decode_finish(sts_ctx* ctx, float* logits, int32_t* next_tokens);
 /* Drop the in-flight layer-sliced batch, if any: its sequences keep their old lengths (the pages
  * reserved for the new tokens stay with them until they are freed). */
 int sts_prefill_abort(sts_ctx* ctx);
@@ -129,7 +141,8 @@ int sts_read_hidden(sts_ctx* ctx, int32_t phase, float* out, int32_t rows);
  * multiple of 8 (every XCD must keep a CU of a partition) in [8, total], or 0 = phase
  * suspended. Prefill takes CU-mask bits [0, prefill_cus), decode takes the top decode_cus
  * bits; they are disjoint when prefill_cus + decode_cus <= total. prefill_cus == decode_cus
- * == total is the time-multiplexed configuration (both phases see the whole GPU).
+ * == total is the time-multiplexed configuration (both phases see the whole GPU). -1 leaves
+ * that phase as it is; a phase with a launch outstanding cannot be changed (STS_ESTATE).
  * Takes effect for the next call; masked streams are created on first use and cached. */
 int sts_set_partition(sts_ctx* ctx, int32_t prefill_cus, int32_t decode_cus);
 int sts_get_partition(sts_ctx* ctx, int32_t* prefill_cus, int32_t* decode_cus, int32_t* total_cus);
@@ -231,6 +244,33 @@ typedef struct {
   int64_t n_slo_ok;                   /* TTFT <= Gamma_p and mean TPOT <= Gamma_d */
   int64_t n_decisions;
 } sts_replay_stats;
+/* One scheduling cycle of Algorithm 1 on a caller-maintained system state S = (ES, PS, RS)
+ * (Section 3.3.2), for serving loops that run the real kernels. queue: Q in arrival order;
+ * inflight: P with layers_done = L_exe; decode: the running decode batch followed by the requests
+ * prefilled but not merged yet. The choice lists next_tasks (ids, in batch order), the queue
+ * that remains (reordered ids), whether next_tasks were newly admitted from the queue (the caller
+ * then reserves ceil((in_len + out_len) / 16) KV pages for each), the layer slice and the split.
+ * n_tasks == 0 means nothing can be admitted yet (KV pool full) or there is no prefill work. */
+typedef struct { int32_t id; int32_t in_len, out_len; int64_t arrival_ns; } sts_sched_req;
+typedef struct { int32_t in_len, n_dec; int64_t first_token_ns; } sts_sched_dec;
+typedef struct {
+  int64_t now_ns;
+  int32_t n_queue; const sts_sched_req* queue;
+  int32_t n_inflight; const sts_sched_req* inflight; int32_t layers_done;
+  int32_t n_decode; const sts_sched_dec* decode;
+  int32_t pages_free;
+  int32_t cur_prefill_cus, cur_decode_cus;      /* the split in force (0/total before the first decision) */
+} sts_sched_state;
+typedef struct {
+  int32_t cap_tasks; int32_t* task_ids;        /* caller's arrays */
+  int32_t cap_queue; int32_t* queue_ids;       /* cap_queue >= n_queue */
+  int32_t n_tasks, n_queue, admitted;
+  int32_t layer_begin, layer_end, prefill_cus, decode_cus, branch;
+  int64_t predicted_ns;
+} sts_sched_choice;
+int sts_sched_decide(const sts_profile* p, const sts_model_desc* desc, const sts_sched_config* cfg,
+                     const sts_sched_state* state, sts_sched_choice* choice);
+
 /* trace: n rows of (arrival_ns, in_len, out_len). decisions: caller's array of cap records (may
  * be NULL with cap 0); the first min(cap, n_decisions) are written. */
 int sts_sched_replay(const sts_profile* p, const sts_model_desc* desc, const sts_sched_config* cfg,

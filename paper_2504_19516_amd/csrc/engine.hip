@@ -96,6 +96,9 @@ struct sts_ctx {
   // in-flight layer-sliced prefill batch
   bool pf_active = false; int pf_next_layer = 0; std::vector<int> pf_seqs, pf_lens;
   int64_t last_wall_ns = 0;
+  // launches whose finish call is still due (non-blocking API)
+  bool pend_prefill = false, pend_decode = false;
+  std::vector<int> pend_pseqs, pend_plens, pend_dseqs; int pend_le = 0;
   void* probe_src = nullptr; void* probe_dst = nullptr; size_t probe_bytes = 0;
   std::vector<void*> allocs;
 };
@@ -728,6 +731,7 @@ extern "C" int sts_kv_fill_random(sts_ctx* c, int32_t seq, int32_t n, uint64_t s
 extern "C" int sts_prefill_batch(sts_ctx* c, int32_t n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
                                  int32_t lb, int32_t le, float* logits) {
   if (!c) return STS_EINVAL;
+  if (c->pend_prefill) return STS_ESTATE;
   const int64_t t0 = now_ns();
   STSCK(prefill_enqueue(c, n_seqs, seqs, lens, tokens, lb, le, logits != nullptr));
   STSCK(prefill_finish(c, n_seqs, seqs, lens, le, logits));
@@ -737,6 +741,45 @@ extern "C" int sts_prefill_batch(sts_ctx* c, int32_t n_seqs, const int32_t* seqs
 extern "C" int sts_prefill_append(sts_ctx* c, int32_t seq, const int32_t* tokens, int32_t n_tokens, int32_t lb, int32_t le, float* logits) {
   return sts_prefill_batch(c, 1, &seq, &n_tokens, tokens, lb, le, logits);
 }
+// ---- the same step, split into launch / poll / finish for serving loops that keep both phases in
+// flight from one control thread
+extern "C" int sts_prefill_launch(sts_ctx* c, int32_t n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                                  int32_t lb, int32_t le, int32_t want_logits) {
+  if (!c) return STS_EINVAL;
+  if (c->pend_prefill) return STS_ESTATE;
+  STSCK(prefill_enqueue(c, n_seqs, seqs, lens, tokens, lb, le, want_logits != 0));
+  c->pend_prefill = true; c->pend_le = le;
+  c->pend_pseqs.assign(seqs, seqs + n_seqs); c->pend_plens.assign(lens, lens + n_seqs);
+  return STS_OK;
+}
+extern "C" int sts_decode_launch(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int32_t n, int32_t want_logits, int32_t want_next) {
+  if (!c) return STS_EINVAL;
+  if (c->pend_decode) return STS_ESTATE;
+  STSCK(decode_enqueue(c, seqs, in_tokens, n, want_logits != 0, want_next != 0));
+  c->pend_decode = true; c->pend_dseqs.assign(seqs, seqs + n);
+  return STS_OK;
+}
+extern "C" int sts_phase_done(sts_ctx* c, int32_t phase, int32_t* done) {
+  if (!c || phase < 0 || phase > 1 || !done) return STS_EINVAL;
+  if (!(phase == 0 ? c->pend_prefill : c->pend_decode)) return STS_ESTATE;
+  const hipError_t e = hipEventQuery(c->ph[phase].ev1);
+  if (e == hipSuccess) *done = 1;
+  else if (e == hipErrorNotReady) *done = 0;
+  else { g_hip_err = (int)e; return STS_EHIP; }
+  return STS_OK;
+}
+extern "C" int sts_prefill_finish(sts_ctx* c, float* logits) {
+  if (!c) return STS_EINVAL;
+  if (!c->pend_prefill) return STS_ESTATE;
+  c->pend_prefill = false;
+  return prefill_finish(c, (int)c->pend_pseqs.size(), c->pend_pseqs.data(), c->pend_plens.data(), c->pend_le, logits);
+}
+extern "C" int sts_decode_finish(sts_ctx* c, float* logits, int32_t* next) {
+  if (!c) return STS_EINVAL;
+  if (!c->pend_decode) return STS_ESTATE;
+  c->pend_decode = false;
+  return decode_finish(c, c->pend_dseqs.data(), (int)c->pend_dseqs.size(), logits, next);
+}
 extern "C" int sts_prefill_abort(sts_ctx* c) {
   if (!c) return STS_EINVAL;
   std::lock_guard<std::mutex> g(c->state_mu);
@@ -745,6 +788,7 @@ extern "C" int sts_prefill_abort(sts_ctx* c) {
 }
 extern "C" int sts_decode_step(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int32_t n, float* logits, int32_t* next) {
   if (!c) return STS_EINVAL;
+  if (c->pend_decode) return STS_ESTATE;
   const int64_t t0 = now_ns();
   STSCK(decode_enqueue(c, seqs, in_tokens, n, logits != nullptr, next != nullptr));
   STSCK(decode_finish(c, seqs, n, logits, next));
@@ -755,6 +799,7 @@ extern "C" int sts_step_concurrent(sts_ctx* c, int32_t n_pseqs, const int32_t* p
                                    int32_t lb, int32_t le, float* plogits, const int32_t* dseqs, const int32_t* dtokens,
                                    int32_t n_decode, float* dlogits, int32_t* dnext) {
   if (!c || n_pseqs < 0 || n_decode < 0 || (n_pseqs == 0 && n_decode == 0)) return STS_EINVAL;
+  if (c->pend_prefill || c->pend_decode) return STS_ESTATE;
   for (int i = 0; i < n_pseqs; i++) for (int j = 0; j < n_decode; j++) if (pseqs && dseqs && pseqs[i] == dseqs[j]) return STS_EINVAL;
   const int64_t t0 = now_ns();
   c->ph[0].ran = c->ph[1].ran = false;
@@ -790,9 +835,12 @@ extern "C" int sts_read_hidden(sts_ctx* c, int32_t phase, float* out, int32_t ro
 // ---- partition
 extern "C" int sts_set_partition(sts_ctx* c, int32_t prefill_cus, int32_t decode_cus) {
   if (!c) return STS_EINVAL;
+  const int old[2] = {c->part_cus[0], c->part_cus[1]};
+  if (prefill_cus == -1) prefill_cus = old[0];
+  if (decode_cus == -1) decode_cus = old[1];
   const int v[2] = {prefill_cus, decode_cus};
   for (int x : v) if (x != 0 && (x < 8 || x > c->n_cu || x % 8 != 0)) return STS_EINVAL;
-  const int old[2] = {c->part_cus[0], c->part_cus[1]};
+  if ((c->pend_prefill && prefill_cus != old[0]) || (c->pend_decode && decode_cus != old[1])) return STS_ESTATE;
   c->part_cus[0] = prefill_cus; c->part_cus[1] = decode_cus;
   const int rc = select_streams(c);
   if (rc != STS_OK) { c->part_cus[0] = old[0]; c->part_cus[1] = old[1]; (void)select_streams(c); }

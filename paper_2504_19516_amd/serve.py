@@ -1,0 +1,228 @@
+"""Live serving of an arrival trace on the GPU (paper Sections 3.3 and 3.5.2): one control thread
+keeps a layer-sliced prefill batch and a decode step in flight on their CU partitions, asks the
+library's Algorithm 1 (`sts_sched_decide`) for the next prefill tasks and CU split at every
+prefill cycle, and hands prefilled requests over to the decode batch without moving any KV.
+
+Modes: "concurrent" (Algorithm 1 picks the split), "tm" (time-multiplexed: same kernels, whole
+GPU, prefill slices and decode steps strictly alternate), "fixed:<prefill CUs>" (concurrent with
+a static split). Arrivals follow the trace in real time. Token values are random (weights are
+random too): output lengths come from the trace, so argmax flips cannot change the workload.
+
+    python -m paper_2504_19516_amd.serve --model 8b --rate 8 --window 20 --mode concurrent \
+        --profile paper_2504_19516_amd/data/mi355x_llama8b.profile
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import time
+
+import numpy as np
+
+from . import sts, synth
+
+PAGE = 16
+
+
+class Req:
+    __slots__ = ("rid", "arrival", "in_len", "out_len", "seq", "tokens", "first_token", "n_dec", "finish")
+
+    def __init__(self, rid, arrival, in_len, out_len):
+        self.rid, self.arrival, self.in_len, self.out_len = rid, int(arrival), int(in_len), int(out_len)
+        self.seq, self.tokens, self.first_token, self.n_dec, self.finish = -1, None, -1, 0, -1
+
+
+class LiveServer:
+    def __init__(self, desc, profile_text, cfg, kv_pool_pages, max_batch_tokens=16384, max_decode_batch=256, max_ctx=10240):
+        self.desc, self.cfg = desc, dict(cfg)
+        self.cfg.update(max_batch_tokens=max_batch_tokens, max_decode_batch=max_decode_batch, kv_pool_pages=kv_pool_pages)
+        self.profile = sts.Profile(text=profile_text)
+        self.eng = sts.Engine(desc, weight_seed=1234, init_weights=True, kv_pool_pages=kv_pool_pages,
+                              max_prefill_tokens=max_batch_tokens, max_prefill_seqs=64, max_decode_batch=max_decode_batch,
+                              max_seqs=max_decode_batch + 80, max_pages_per_seq=(max_ctx + PAGE - 1) // PAGE)
+        self.n_cu = self.eng.get_partition()[2]
+        self.max_ctx = max_ctx
+
+    def close(self):
+        self.eng.close()
+
+    def run(self, trace, mode="concurrent", seed=0, log_every=0):
+        eng, desc, cfg = self.eng, self.desc, dict(self.cfg)
+        serial = mode == "tm"
+        cfg["mode"] = 1 if serial else (2 if mode.startswith("fixed") else 0)
+        if mode.startswith("fixed"):
+            cfg["fixed_prefill_cus"] = int(mode.split(":")[1])
+        n = self.n_cu
+        rng = np.random.default_rng(seed)
+        reqs = [Req(i, a, il, ol) for i, (a, il, ol) in enumerate(trace)]
+        Q, P, H, D = [], [], [], []
+        l_exe, pm, dm = 0, (n if serial else 0), n
+        prefill_busy = decode_busy = turn_decode = False
+        decode_batch, cur_slice = [], None
+        next_arrival, rejected = 0, 0
+        timeline, decisions = [], []
+        eng.set_partition(n, n)
+        t0 = time.perf_counter_ns()
+        clock = lambda: time.perf_counter_ns() - t0
+
+        def finish(r, now):
+            r.finish = now
+            eng.seq_free(r.seq)
+
+        while True:
+            now = clock()
+            while next_arrival < len(reqs) and reqs[next_arrival].arrival <= now:
+                r = reqs[next_arrival]
+                total = r.in_len + r.out_len
+                if (total + PAGE - 1) // PAGE > cfg["kv_pool_pages"] or r.in_len > cfg["max_batch_tokens"] or total > self.max_ctx:
+                    rejected += 1
+                else:
+                    Q.append(r)
+                next_arrival += 1
+            # ---- prefill engine: one scheduling cycle of Algorithm 1
+            if not prefill_busy and (P or Q) and not (serial and (decode_busy or (turn_decode and (D or H)))):
+                ch = self.profile.decide(desc, cfg, now, [(r.rid, r.arrival, r.in_len, r.out_len) for r in Q],
+                                         [(r.rid, r.arrival, r.in_len, r.out_len) for r in P], l_exe,
+                                         [(r.first_token, r.n_dec, r.in_len) for r in D + H], eng.pages_free(), pm, dm)
+                by_id = {r.rid: r for r in Q}
+                Q = [by_id[i] for i in ch["queue"]]
+                if ch["tasks"]:
+                    if ch["admitted"]:
+                        P = [by_id[i] for i in ch["tasks"]]
+                        l_exe = 0
+                        for r in P:
+                            r.seq = eng.seq_create()
+                            eng.seq_reserve(r.seq, r.in_len + r.out_len)      # the pages Algorithm 1 accounted for
+                            r.tokens = rng.integers(0, desc.vocab, r.in_len, dtype=np.int32)
+                    pm, dm = ch["prefill_cus"], ch["decode_cus"]
+                    if not serial:
+                        eng.set_partition(pm, -1)
+                    lb, le = ch["layer_begin"], ch["layer_end"]
+                    eng.prefill_launch([r.seq for r in P], [r.tokens for r in P], lb, le, want_logits=(le == desc.n_layers))
+                    prefill_busy, cur_slice = True, (now, lb, le, ch["predicted_ns"])
+                    decisions.append((now, len(P), sum(r.in_len for r in P), lb, le, pm, dm, ch["branch"], len(D) + len(H), len(Q)))
+            # ---- decode engine: merge hand-offs, one step on the CUs left to it
+            if not decode_busy and not (serial and prefill_busy):
+                while H and len(D) < cfg["max_decode_batch"]:
+                    D.append(H.pop(0))
+                if D:
+                    dm_eff = n if (serial or not prefill_busy) else dm
+                    if dm_eff > 0:
+                        if not serial:
+                            eng.set_partition(-1, dm_eff)
+                        decode_batch = list(D)
+                        eng.decode_launch([r.seq for r in D], rng.integers(0, desc.vocab, len(D), dtype=np.int32), want_next=True)
+                        decode_busy = True
+            # ---- wait for the next event
+            if not prefill_busy and not decode_busy:
+                if next_arrival >= len(reqs) and not (P or Q or H or D):
+                    break
+                if next_arrival < len(reqs):
+                    wait = reqs[next_arrival].arrival - clock()
+                    if wait > 0:
+                        time.sleep(wait * 1e-9)
+                continue
+            pdone = ddone = False
+            while True:
+                if prefill_busy and eng.phase_done(0):
+                    pdone = True
+                if decode_busy and eng.phase_done(1):
+                    ddone = True
+                if pdone or ddone:
+                    break
+                if next_arrival < len(reqs) and reqs[next_arrival].arrival <= clock() and not (prefill_busy and decode_busy):
+                    break
+                time.sleep(20e-6)
+            now = clock()
+            if pdone:
+                eng.prefill_finish()
+                prefill_busy, turn_decode = False, True
+                l_exe = cur_slice[2]
+                timeline.append((now, "prefill", pm, sum(r.in_len for r in P), cur_slice[1], cur_slice[2], now - cur_slice[0], cur_slice[3]))
+                if l_exe == desc.n_layers:
+                    for r in P:
+                        r.first_token = now
+                        if r.out_len <= 1:
+                            finish(r, now)
+                        else:
+                            H.append(r)
+                    P, l_exe = [], 0
+            if ddone:
+                eng.decode_finish(len(decode_batch))
+                decode_busy, turn_decode = False, False
+                for r in decode_batch:
+                    r.n_dec += 1
+                    if r.n_dec >= r.out_len - 1:
+                        finish(r, now)
+                        D.remove(r)
+                if log_every and len(timeline) % log_every == 0:
+                    timeline.append((now, "decode", eng.get_partition()[1], len(decode_batch)))
+        eng.set_partition(n, n)
+        return self.stats(reqs, rejected, cfg), decisions, timeline
+
+    @staticmethod
+    def stats(reqs, rejected, cfg):
+        done = [r for r in reqs if r.finish >= 0]
+        ttft = np.array([r.first_token - r.arrival for r in done], dtype=np.float64)
+        tpot = np.array([(r.finish - r.first_token) / r.n_dec for r in done if r.n_dec > 0], dtype=np.float64)
+        ok = sum(1 for r in done if (r.first_token - r.arrival) <= cfg["ttft_slo_ns"] and
+                 (r.n_dec == 0 or (r.finish - r.first_token) / r.n_dec <= cfg["tpot_slo_ns"]))
+        span = max((r.finish for r in done), default=0)
+        out_tokens = sum(r.out_len for r in done)
+        in_tokens = sum(r.in_len for r in done)
+        pct = lambda a, q: float(np.percentile(a, q)) / 1e6 if len(a) else 0.0
+        return dict(n_requests=len(reqs), n_finished=len(done), rejected=rejected, makespan_s=span / 1e9,
+                    out_tokens=out_tokens, in_tokens=in_tokens, out_tokens_per_s=out_tokens / max(span, 1) * 1e9,
+                    total_tokens_per_s=(out_tokens + in_tokens) / max(span, 1) * 1e9, requests_per_s=len(done) / max(span, 1) * 1e9,
+                    ttft_mean_ms=float(ttft.mean()) / 1e6 if len(ttft) else 0.0, ttft_p90_ms=pct(ttft, 90),
+                    tpot_mean_ms=float(tpot.mean()) / 1e6 if len(tpot) else 0.0, tpot_p90_ms=pct(tpot, 90),
+                    slo_attainment=ok / max(1, len(reqs)))
+
+
+WORKLOADS = {
+    "conversation": (dict(kind="lognormal", median=600, sigma=1.0, cap=8192), dict(kind="lognormal", median=250, sigma=0.9, cap=2048)),
+    "long": (dict(kind="uniform", lo=8192, hi=32768), dict(kind="uniform", lo=64, hi=512)),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--model", default="8b", choices=["8b", "70b", "tiny"])
+    ap.add_argument("--layers", type=int, default=0)
+    ap.add_argument("--workload", default="conversation", choices=list(WORKLOADS))
+    ap.add_argument("--rates", default="4,8")
+    ap.add_argument("--window", type=float, default=15.0)
+    ap.add_argument("--modes", default="concurrent,tm")
+    ap.add_argument("--profile", required=True)
+    ap.add_argument("--ttft-ms", type=float, default=1000.0)
+    ap.add_argument("--tpot-ms", type=float, default=50.0)
+    ap.add_argument("--layers-per-step", type=int, default=4)
+    ap.add_argument("--pool-pages", type=int, default=40000)
+    ap.add_argument("--max-ctx", type=int, default=10240)
+    ap.add_argument("--out", default=None)
+    args = ap.parse_args()
+    make = {"8b": synth.llama8b_model, "70b": synth.llama70b_model}.get(args.model)
+    desc = (make(args.layers) if args.layers else make()) if make else synth.tiny_model()
+    cfg = dict(ttft_slo_ns=int(args.ttft_ms * 1e6), tpot_slo_ns=int(args.tpot_ms * 1e6), layers_per_step=args.layers_per_step)
+    srv = LiveServer(desc, open(args.profile).read(), cfg, args.pool_pages, max_ctx=args.max_ctx,
+                     max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0))
+    ind, outd = WORKLOADS[args.workload]
+    results = []
+    for rate in [float(x) for x in args.rates.split(",")]:
+        trace = synth.poisson_trace(int(rate * 10) + 1, rate, args.window, ind, outd)
+        for mode in args.modes.split(","):
+            st, dec, tl = srv.run([tuple(int(x) for x in r) for r in trace], mode)
+            splits = {}
+            for d in dec:
+                splits[d[5]] = splits.get(d[5], 0) + 1
+            row = dict(rate=rate, mode=mode, **st, prefill_cus_histogram=splits)
+            print(json.dumps(row), flush=True)
+            results.append(row)
+    if args.out:
+        with open(args.out, "w") as f:
+            json.dump(results, f, indent=1)
+    srv.close()
+
+
+if __name__ == "__main__":
+    main()

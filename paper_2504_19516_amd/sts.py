@@ -50,6 +50,28 @@ class SchedConfig(C.Structure):
         "layers_per_step", "max_batch_tokens", "max_decode_batch", "kv_pool_pages", "mode", "fixed_prefill_cus")]
 
 
+class SchedReq(C.Structure):
+    _fields_ = [("id", C.c_int32), ("in_len", C.c_int32), ("out_len", C.c_int32), ("arrival_ns", C.c_int64)]
+
+
+class SchedDec(C.Structure):
+    _fields_ = [("in_len", C.c_int32), ("n_dec", C.c_int32), ("first_token_ns", C.c_int64)]
+
+
+class SchedState(C.Structure):
+    _fields_ = [("now_ns", C.c_int64), ("n_queue", C.c_int32), ("queue", C.POINTER(SchedReq)),
+                ("n_inflight", C.c_int32), ("inflight", C.POINTER(SchedReq)), ("layers_done", C.c_int32),
+                ("n_decode", C.c_int32), ("decode", C.POINTER(SchedDec)), ("pages_free", C.c_int32),
+                ("cur_prefill_cus", C.c_int32), ("cur_decode_cus", C.c_int32)]
+
+
+class SchedChoice(C.Structure):
+    _fields_ = [("cap_tasks", C.c_int32), ("task_ids", C.POINTER(C.c_int32)), ("cap_queue", C.c_int32), ("queue_ids", C.POINTER(C.c_int32)),
+                ("n_tasks", C.c_int32), ("n_queue", C.c_int32), ("admitted", C.c_int32), ("layer_begin", C.c_int32),
+                ("layer_end", C.c_int32), ("prefill_cus", C.c_int32), ("decode_cus", C.c_int32), ("branch", C.c_int32),
+                ("predicted_ns", C.c_int64)]
+
+
 class Decision(C.Structure):
     _fields_ = [("t_ns", C.c_int64), ("n_tasks", C.c_int32), ("first_req", C.c_int32), ("tasks_hash", C.c_int64),
                 ("layer_begin", C.c_int32), ("layer_end", C.c_int32), ("prefill_cus", C.c_int32), ("decode_cus", C.c_int32),
@@ -65,11 +87,12 @@ EXPORTS = [
     "sts_strerror", "sts_last_hip_error", "sts_init", "sts_destroy", "sts_load_weights", "sts_read_weights",
     "sts_seq_create", "sts_seq_free", "sts_seq_length", "sts_seq_reserve", "sts_pages_free", "sts_seq_set_block_table",
     "sts_seq_get_block_table", "sts_kv_write", "sts_kv_read", "sts_kv_fill_random", "sts_prefill_batch",
-    "sts_prefill_append", "sts_prefill_abort", "sts_decode_step", "sts_step_concurrent", "sts_last_timing", "sts_read_hidden",
+    "sts_prefill_append", "sts_prefill_launch", "sts_decode_launch", "sts_phase_done", "sts_prefill_finish",
+    "sts_decode_finish", "sts_prefill_abort", "sts_decode_step", "sts_step_concurrent", "sts_last_timing", "sts_read_hidden",
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_replay",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay",
 ]
 
 
@@ -209,6 +232,34 @@ class Engine:
         _ck(lib().sts_prefill_append(self._ctx, seq, _p(toks), toks.size, layer_begin, layer_end, _p(logits, C.c_float)), "sts_prefill_append")
         return logits
 
+    # launch / poll / finish
+    def prefill_launch(self, seqs, token_lists, layer_begin, layer_end, want_logits=False):
+        seqs = _i32(seqs)
+        lens = _i32([len(t) for t in token_lists])
+        toks = _i32(np.concatenate([np.asarray(t, dtype=np.int32) for t in token_lists])) if layer_begin == 0 else None
+        _ck(lib().sts_prefill_launch(self._ctx, len(seqs), _p(seqs), _p(lens), _p(toks), layer_begin, layer_end, int(want_logits)),
+            "sts_prefill_launch")
+
+    def decode_launch(self, seqs, in_tokens, want_logits=False, want_next=True):
+        seqs, toks = _i32(seqs), _i32(in_tokens)
+        _ck(lib().sts_decode_launch(self._ctx, _p(seqs), _p(toks), len(seqs), int(want_logits), int(want_next)), "sts_decode_launch")
+
+    def phase_done(self, phase):
+        d = C.c_int32()
+        _ck(lib().sts_phase_done(self._ctx, phase, C.byref(d)), "sts_phase_done")
+        return bool(d.value)
+
+    def prefill_finish(self, n_seqs=0, want_logits=False):
+        logits = np.empty((n_seqs, self.desc.vocab), np.float32) if want_logits else None
+        _ck(lib().sts_prefill_finish(self._ctx, _p(logits, C.c_float)), "sts_prefill_finish")
+        return logits
+
+    def decode_finish(self, n, want_logits=False, want_next=True):
+        logits = np.empty((n, self.desc.vocab), np.float32) if want_logits else None
+        nxt = np.empty(n, np.int32) if want_next else None
+        _ck(lib().sts_decode_finish(self._ctx, _p(logits, C.c_float), _p(nxt)), "sts_decode_finish")
+        return logits, nxt
+
     def prefill_abort(self):
         _ck(lib().sts_prefill_abort(self._ctx), "sts_prefill_abort")
 
@@ -335,10 +386,31 @@ class Profile:
         _ck(fn(self._p, C.byref(d), C.byref(st), C.byref(a), C.byref(b)), "sts_latency_query")
         return a.value, b.value
 
+    @staticmethod
+    def _sched_config(cfg):
+        return SchedConfig(cfg["ttft_slo_ns"], cfg["tpot_slo_ns"], cfg["layers_per_step"], cfg["max_batch_tokens"],
+                           cfg["max_decode_batch"], cfg["kv_pool_pages"], cfg.get("mode", 0), cfg.get("fixed_prefill_cus", 0))
+
+    def decide(self, desc, cfg: dict, now_ns, queue, inflight, layers_done, decode, pages_free, cur_pm, cur_dm):
+        """One cycle of Algorithm 1. queue / inflight: lists of (id, arrival_ns, in_len, out_len);
+        decode: list of (first_token_ns, n_dec, in_len). Returns a dict."""
+        q = (SchedReq * max(1, len(queue)))(*[SchedReq(i, il, ol, a) for i, a, il, ol in queue])
+        p = (SchedReq * max(1, len(inflight)))(*[SchedReq(i, il, ol, a) for i, a, il, ol in inflight])
+        d = (SchedDec * max(1, len(decode)))(*[SchedDec(il, nd, ft) for ft, nd, il in decode])
+        st = SchedState(now_ns, len(queue), q, len(inflight), p, layers_done, len(decode), d, pages_free, cur_pm, cur_dm)
+        cap = len(queue) + len(inflight) + 1
+        tids, qids = (C.c_int32 * cap)(), (C.c_int32 * cap)()
+        ch = SchedChoice(cap, tids, cap, qids)
+        sc = self._sched_config(cfg)
+        md = model_desc(desc)
+        _ck(lib().sts_sched_decide(self._p, C.byref(md), C.byref(sc), C.byref(st), C.byref(ch)), "sts_sched_decide")
+        return dict(tasks=list(tids[:ch.n_tasks]), queue=list(qids[:ch.n_queue]), admitted=bool(ch.admitted),
+                    layer_begin=ch.layer_begin, layer_end=ch.layer_end, prefill_cus=ch.prefill_cus, decode_cus=ch.decode_cus,
+                    branch=ch.branch, predicted_ns=ch.predicted_ns)
+
     def replay(self, desc, cfg: dict, trace, max_decisions=1 << 20):
         tr = np.ascontiguousarray(trace, dtype=np.int64)
-        sc = SchedConfig(cfg["ttft_slo_ns"], cfg["tpot_slo_ns"], cfg["layers_per_step"], cfg["max_batch_tokens"],
-                         cfg["max_decode_batch"], cfg["kv_pool_pages"], cfg.get("mode", 0), cfg.get("fixed_prefill_cus", 0))
+        sc = self._sched_config(cfg)
         dec = (Decision * max_decisions)()
         stats = ReplayStats()
         d = model_desc(desc)

@@ -289,3 +289,64 @@ def test_error_paths_leave_state_unchanged(sts, tiny):
     eng.seq_free(s)
     assert eng.pages_free() == 6
     eng.close()
+
+
+def test_launch_poll_finish_equals_blocking_calls(sts, tiny, eng):
+    desc, w = tiny
+    _, ctx_tokens, dec_tokens, pre_tokens = build_case(desc, w)
+    import time
+    outs = []
+    for mode in ("blocking", "async"):
+        dseqs = gpu_contexts(eng, ctx_tokens)
+        pseq = eng.seq_create()
+        eng.set_partition(160, 96)
+        if mode == "blocking":
+            plog, dlog, dnext = eng.step_concurrent([pseq], [pre_tokens], 0, desc.n_layers, dseqs, dec_tokens)
+            plog = plog[0]
+        else:
+            eng.prefill_launch([pseq], [pre_tokens], 0, 1)
+            eng.decode_launch(dseqs, dec_tokens, want_logits=True, want_next=True)
+            with pytest.raises(sts.StsError) as e:
+                eng.decode_launch(dseqs, dec_tokens)                  # one launch per phase at a time
+            assert e.value.code == sts.ESTATE
+            with pytest.raises(sts.StsError):
+                eng.set_partition(-1, 64)                              # decode is in flight
+            deadline = time.time() + 20
+            while not (eng.phase_done(0) and eng.phase_done(1)):
+                assert time.time() < deadline
+                time.sleep(1e-4)
+            assert eng.prefill_finish() is None and eng.seq_length(pseq) == 0
+            dlog, dnext = eng.decode_finish(len(dseqs), want_logits=True)
+            eng.set_partition(256, -1)                                 # the second slice on another partition
+            eng.prefill_launch([pseq], [pre_tokens], 1, 2, want_logits=True)
+            plog = eng.prefill_finish(1, want_logits=True)[0]
+            assert eng.seq_length(pseq) == 128
+        outs.append((plog, dlog, dnext))
+        free_all(eng, dseqs + [pseq])
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
+
+
+@pytest.mark.parametrize("mode", ["concurrent", "tm", "fixed:192"])
+def test_live_serving_of_a_short_trace(sts, tiny, mode):
+    """The serving loop on the tiny model: every request is prefilled layer slice by layer slice,
+    handed over, decoded to its output length, and its pages come back."""
+    from oracle import latency as L
+    from paper_2504_19516_amd import serve
+    desc, _ = tiny
+    hw = L.Profile(n_cu=256, granule=32, c_peak=200_000, d_peak=2_000, n_d=128, tile_m=128, tile_n=128, wgs_per_cu=2)
+    cfg = dict(ttft_slo_ns=200_000_000, tpot_slo_ns=20_000_000, layers_per_step=1)
+    srv = serve.LiveServer(desc, L.dump_profile(hw), cfg, kv_pool_pages=600, max_batch_tokens=512, max_decode_batch=16, max_ctx=640)
+    trace = synth.poisson_trace(3, 60.0, 0.5, dict(kind="lognormal", median=100, sigma=0.6, cap=400),
+                                dict(kind="lognormal", median=20, sigma=0.5, cap=100))
+    st, dec, tl = srv.run([tuple(int(x) for x in r) for r in trace], mode)
+    assert st["n_finished"] == len(trace) and st["rejected"] == 0
+    assert st["out_tokens"] == int(trace[:, 2].sum())
+    assert srv.eng.pages_free() == 600
+    assert all(d[3] < d[4] <= desc.n_layers for d in dec)
+    if mode == "tm":
+        assert all(d[5] == 256 and d[6] == 256 for d in dec)
+    elif mode.startswith("fixed"):
+        assert all(d[5] == 192 and d[6] == 64 for d in dec)
+    else:
+        assert all(d[5] + d[6] == 256 for d in dec)
+    srv.close()

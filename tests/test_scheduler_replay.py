@@ -67,3 +67,45 @@ def test_replay_rejects_bad_input(sts):
         p.replay(synth.llama8b_model(), dict(CFG3, layers_per_step=0), np.array([[0, 10, 10]]))
     with pytest.raises(sts.StsError):
         p.replay(synth.llama8b_model(), CFG3, np.array([[5, 10, 10], [1, 10, 10]]))     # arrivals not sorted
+
+
+def test_single_cycle_decide_matches_oracle_on_built_states(sts):
+    """sts_sched_decide on caller-built states against the oracle's schedule() on the same state."""
+    desc, hw = synth.llama8b_model(), sample_profile()
+    p = sts.Profile(text=L.dump_profile(hw))
+    rng = np.random.default_rng(11)
+    for case in range(40):
+        n = int(rng.integers(2, 30))
+        trace = [(int(rng.integers(0, 2_000_000_000)), int(rng.integers(16, 9000)), int(rng.integers(1, 600))) for _ in range(n)]
+        trace.sort()
+        cfg = dict(CFG3, ttft_slo_ns=int(rng.choice([300_000_000, 1_000_000_000])), tpot_slo_ns=int(rng.choice([8_000_000, 50_000_000])),
+                   kv_pool_pages=int(rng.choice([3000, 60000])))
+        r = S.Replay(shape_of(desc), hw, S.Config(**cfg), trace)
+        ids = list(range(n))
+        rng.shuffle(ids)
+        n_dec, n_p = int(rng.integers(0, n // 2 + 1)), int(rng.integers(0, 2))
+        dec_ids, rest = ids[:n_dec], ids[n_dec:]
+        p_ids = sorted(rest[:n_p * int(rng.integers(1, 3))])
+        q_ids = sorted(set(rest) - set(p_ids))
+        r.now = 2_100_000_000 + int(rng.integers(0, 500_000_000))
+        r.D, r.H = dec_ids[: len(dec_ids) // 2], dec_ids[len(dec_ids) // 2:]
+        for i in dec_ids:
+            r.reqs[i].first_token = r.now - int(rng.integers(1_000_000, 900_000_000))
+            r.reqs[i].n_dec = int(rng.integers(0, 300))
+        r.P, r.Q = list(p_ids), list(q_ids)
+        r.l_exe = int(rng.integers(0, 8)) * 4 if p_ids else 0
+        r.pages_free = int(rng.integers(100, cfg["kv_pool_pages"]))
+        r.pm, r.dm = [(0, 256), (224, 32), (128, 128), (256, 0)][int(rng.integers(0, 4))]
+        args = (r.now, [(i, trace[i][0], trace[i][1], trace[i][2]) for i in r.Q], [(i, trace[i][0], trace[i][1], trace[i][2]) for i in r.P],
+                r.l_exe, [(r.reqs[i].first_token, r.reqs[i].n_dec, r.reqs[i].in_len) for i in r.D + r.H], r.pages_free, r.pm, r.dm)
+        had_p = bool(r.P)
+        got = p.decide(desc, cfg, *args)
+        dur = r.schedule()
+        assert got["queue"] == r.Q, case
+        if dur is None:
+            assert got["tasks"] == [] and got["predicted_ns"] == -1
+            continue
+        d = r.decisions[-1]
+        assert got["tasks"] == r.P and got["admitted"] == (not had_p)
+        assert (got["layer_begin"], got["layer_end"], got["prefill_cus"], got["decode_cus"], got["branch"], got["predicted_ns"]) == \
+               (d[4], d[5], d[6], d[7], d[8], d[10]), case
