@@ -204,6 +204,25 @@ int pick_cfg(int m, int n) {
   // and global latency better than one 256x256 workgroup; measured faster on every layer shape
   return GEMM_128x128;
 }
+// Prefill GEMM tile choice for a partition of `cus` CUs: the candidate whose number of full
+// waves of workgroups times its per-wave time is smallest (wave quantisation, paper Section
+// 2.2.1, is what differs between them at a given CU count). Rates are measured busy-CU
+// throughputs in TFLOP/s per CU: 128x128 tiles run two workgroups per CU, 256x256 (8 waves) one.
+int pick_prefill_cfg(int m, int n, int cus) {
+  if (m <= 64) return GEMM_64x128;
+  struct Cand { int cfg, tm, tn, slots; double rate; };
+  const Cand cands[2] = {{GEMM_128x128, 128, 128, 2, 3.9}, {GEMM_256x256_W8, 256, 256, 1, 4.5}};
+  int best = GEMM_128x128; double best_cost = 1e300;
+  for (const Cand& c : cands) {
+    if (n % c.tn != 0) continue;
+    const long long tiles = (long long)((m + c.tm - 1) / c.tm) * (n / c.tn);
+    const long long slots = (long long)c.slots * std::max(cus, 8);
+    const long long waves = (tiles + slots - 1) / slots;
+    const double cost = (double)waves * c.tm * c.tn * c.slots / c.rate;
+    if (cost < best_cost) { best_cost = cost; best = c.cfg; }
+  }
+  return best;
+}
 int pick_splits(int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
   int s = (2 * std::max(cus, 8) + tiles - 1) / tiles;          // two workgroups per CU of the partition
@@ -295,14 +314,14 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
   for (int l = lb; l < le; l++) {
     const LayerW& w = c->layers[l];
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g1, d.rms_eps, rows, h));
-    KL(ph, STS_K_QKV, gemm_bf16(st, pick_cfg(rows, c->qkvn), EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h, 1, 0));
+    KL(ph, STS_K_QKV, gemm_bf16(st, pick_prefill_cfg(rows, c->qkvn, ph.cus), EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h, 1, 0));
     KL(ph, STS_K_ROPE, rope_kv_write_prefill(st, ph.QKV, c->qkvn, ph.d_pseq, n_seqs, ph.d_bt, c->inv_freq, layer_pool(c, l), c->geo, rows, d.n_q_heads));
     KL(ph, STS_K_ATTN, attn_prefill(st, ph.QKV, c->qkvn, ph.A, c->qd, ph.d_pseq, ph.d_items, n_items, ph.d_bt, layer_pool(c, l), c->geo, d.n_q_heads));
-    KL(ph, STS_K_O, gemm_bf16(st, pick_cfg(rows, h), EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd, 1, 0));
+    KL(ph, STS_K_O, gemm_bf16(st, pick_prefill_cfg(rows, h, ph.cus), EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd, 1, 0));
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g2, d.rms_eps, rows, h));
-    KL(ph, STS_K_GATEUP, gemm_bf16(st, pick_cfg(rows, 2 * d.mlp) == GEMM_64x128 ? GEMM_128x128 : pick_cfg(rows, 2 * d.mlp), EPI_SWIGLU_BF16,
+    KL(ph, STS_K_GATEUP, gemm_bf16(st, rows <= 64 ? GEMM_128x128 : pick_prefill_cfg(rows, 2 * d.mlp, ph.cus), EPI_SWIGLU_BF16,
                                    ph.Xn, h, w.wgu, h, ph.H, d.mlp, rows, 2 * d.mlp, h, 1, 0));
-    KL(ph, STS_K_DOWN, gemm_bf16(st, pick_cfg(rows, h), EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp, 1, 0));
+    KL(ph, STS_K_DOWN, gemm_bf16(st, pick_prefill_cfg(rows, h, ph.cus), EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp, 1, 0));
   }
   if (le == d.n_layers && want_logits) {
     KL(ph, STS_K_HEAD, gather_rows_f32(st, ph.Xlast, ph.X, ph.d_rows, n_seqs, h));

@@ -204,20 +204,21 @@ static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int spli
     case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits);
     case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI>(s, g, splits);
     case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits);
+    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI>(s, g, splits);
     default: return hipErrorInvalidValue;
   }
 }
 
 int gemm_tile_n(int cfg) {
   switch (cfg) {
-    case GEMM_256x256: case GEMM_64x256: case GEMM_32x256: return 256;
+    case GEMM_256x256: case GEMM_256x256_W8: case GEMM_64x256: case GEMM_32x256: return 256;
     case GEMM_64x64: return 64;
     default: return 128;
   }
 }
 int gemm_tile_m(int cfg) {
   switch (cfg) {
-    case GEMM_256x256: case GEMM_256x128: return 256;
+    case GEMM_256x256: case GEMM_256x256_W8: case GEMM_256x128: return 256;
     case GEMM_128x128: return 128;
     case GEMM_32x256: return 32;
     default: return 64;
@@ -242,6 +243,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
     case EPI_SWIGLU_BF16:
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
         case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1);
+        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16>(s, g, 1);
         case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1);
         case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1);
         case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1);

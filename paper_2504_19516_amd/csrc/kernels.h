@@ -6,7 +6,7 @@ namespace sts {
 
 // ---- GEMM -------------------------------------------------------------------------------
 enum GemmEpilogue { EPI_BF16 = 0, EPI_F32 = 1, EPI_RESID_F32 = 2, EPI_SWIGLU_BF16 = 3 };
-enum GemmConfig { GEMM_256x256 = 0, GEMM_128x128 = 1, GEMM_256x128 = 2, GEMM_64x256 = 3, GEMM_32x256 = 4, GEMM_64x128 = 5, GEMM_64x64 = 6, GEMM_NCFG = 7 };
+enum GemmConfig { GEMM_256x256 = 0, GEMM_128x128 = 1, GEMM_256x128 = 2, GEMM_64x256 = 3, GEMM_32x256 = 4, GEMM_64x128 = 5, GEMM_64x64 = 6, GEMM_256x256_W8 = 7, GEMM_NCFG = 8 };
 int gemm_tile_m(int cfg);
 int gemm_tile_n(int cfg);
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,

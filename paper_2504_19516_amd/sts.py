@@ -17,7 +17,7 @@ _lib = None
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 K_NAMES = ["embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup", "swiglu", "down", "reduce", "head", "sample"]
-GEMM_CFGS = {"256x256": 0, "128x128": 1, "256x128": 2, "64x256": 3, "32x256": 4, "64x128": 5, "64x64": 6}
+GEMM_CFGS = {"256x256": 0, "128x128": 1, "256x128": 2, "64x256": 3, "32x256": 4, "64x128": 5, "64x64": 6, "256x256w8": 7}
 INF_NS = 1 << 60
 
 

@@ -28,7 +28,7 @@ def sts():
 
 
 @pytest.mark.parametrize("cfg,m", [("256x256", 300), ("128x128", 300), ("256x128", 257), ("64x256", 70), ("32x256", 20),
-                                   ("64x128", 64), ("128x128", 1), ("64x64", 50)])
+                                   ("64x128", 64), ("128x128", 1), ("64x64", 50), ("256x256w8", 300)])
 def test_gemm_fp32_accumulators(sts, cfg, m):
     n, k = 512, 320
     a = synth.normal_bf16(1, (m, k))
@@ -48,7 +48,7 @@ def test_gemm_split_k(sts, cfg, m, split):
     assert rel(sts.op_gemm(a, w, cfg, epilogue=1, split_k=split), ref) <= 1e-5
 
 
-@pytest.mark.parametrize("cfg", ["256x256", "128x128"])
+@pytest.mark.parametrize("cfg", ["256x256", "128x128", "256x256w8"])
 def test_gemm_bf16_store_and_residual(sts, cfg):
     m, n, k = 200, 256, 192
     a = synth.normal_bf16(5, (m, k))
@@ -62,7 +62,7 @@ def test_gemm_bf16_store_and_residual(sts, cfg):
     assert rel(got2, x.astype(np.float64) + ref) <= 1e-5
 
 
-@pytest.mark.parametrize("cfg,m", [("256x256", 260), ("128x128", 100), ("64x256", 40), ("32x256", 5)])
+@pytest.mark.parametrize("cfg,m", [("256x256", 260), ("128x128", 100), ("64x256", 40), ("32x256", 5), ("256x256w8", 513)])
 def test_gemm_swiglu_epilogue(sts, cfg, m):
     n2, k = 256, 128
     a = synth.normal_bf16(8, (m, k))
