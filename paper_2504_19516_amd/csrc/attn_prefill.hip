@@ -3,7 +3,9 @@
 // tokens needs no separate path).
 //
 // A workgroup of 4 waves owns 128 consecutive query rows of one head of one sequence; each
-// wave owns 32 of them. Per 64-key tile staged through LDS:
+// wave owns 32 of them. The block-table slice and the Q tile sit in LDS for the whole kernel; the
+// next 64-key K/V tile is fetched into registers while the current one is consumed, then
+// written to the (single) LDS tile buffers between two barriers. Per 64-key tile:
 //   S^T[key, q] = K[key, :] . Q[q, :]          v_mfma_f32_32x32x16_bf16, A = K rows, B = Q rows
 //   online softmax down the key axis: a lane holds one query column (16 keys per 32x32
 //   block per lane half), so the running max/sum need one cross-half shuffle only
@@ -11,24 +13,32 @@
 //   B = P^T taken straight from the S^T accumulator registers (no LDS round trip).
 // The k index inside one MFMA is a free permutation as long as A and B agree: for P^T the
 // eight values a lane already holds (registers 8j..8j+7 of a block) are keys
-// {16j + 4*half + 0..3} and {16j + 8 + 4*half + 0..3}; the V^T operand is read from LDS in
-// that same order (two 8-byte reads).
+// {16j + 4*half + 0..3} and {16j + 8 + 4*half + 0..3}; the V^T tile is laid out in LDS in
+// that same order, so the operand is one 16-byte read.
 #include "kernels.h"
 
 namespace sts {
 
 constexpr int BQ = 128, BKV = 64;
 
+constexpr float RESCALE_LOG2 = 8.f;
+constexpr int BT_CACHE = 2080;   // block-table entries kept in LDS (contexts up to 33280 tokens; beyond that read from global)
+
 template <int D>
-__global__ void __launch_bounds__(256) attn_prefill_kernel(const bf16* __restrict__ qkv, int ld, bf16* __restrict__ out, int ldo,
+__global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __restrict__ qkv, int ld, bf16* __restrict__ out, int ldo,
                                                            const PrefillSeq* __restrict__ seqs, const AttnItem* __restrict__ items,
                                                            const int* __restrict__ block_tables, const bf16* __restrict__ pool,
                                                            KvGeom geo, int n_q, float scale_log2e) {
-  constexpr int KS = D + 8;       // K tile row stride (elements): 16-byte reads, conflict free
-  constexpr int VS = BKV + 4;     // V^T tile row stride: 8-byte reads, conflict free
+  constexpr int KS = D + 8;       // K and Q tile row stride (elements): 16-byte reads, conflict free
+  constexpr int VS = BKV + 8;     // V^T tile row stride; inside each 16-key group the keys are stored in the
+                                  // order 0-3, 8-11, 4-7, 12-15 so that a lane's MFMA operand is one 16-byte read
   constexpr int KSTEPS = D / 16, DB = D / 32;
+  constexpr int KCH = BKV * D / 8 / 256;                  // 16-byte chunks of the K tile per thread
+  constexpr int VCH = D * BKV / 8 / 256;                  // ... of the V^T tile
+  __shared__ __align__(16) bf16 Qs[BQ * KS];
   __shared__ __align__(16) bf16 Ks[BKV * KS];
   __shared__ __align__(16) bf16 Vs[D * VS];
+  __shared__ int bts[BT_CACHE];
 
   const int head = blockIdx.x % n_q;
   const AttnItem it = items[blockIdx.x / n_q];
@@ -41,121 +51,158 @@ __global__ void __launch_bounds__(256) attn_prefill_kernel(const bf16* __restric
   const int qloc = it.q0 + wave * 32 + l32;              // row inside the chunk
   const bool q_valid = qloc < sq.sl;
   const int qpos = sq.p + qloc;                          // absolute position (causal limit)
-  const bf16* qp = qkv + (size_t)(sq.row0 + min(qloc, sq.sl - 1)) * ld + head * D + 8 * lh;
-  bf16x8 qf[KSTEPS];
-#pragma unroll
-  for (int j = 0; j < KSTEPS; j++) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 16 * j);
-
   const int wave_min_qpos = sq.p + it.q0 + wave * 32;
   const int wave_max_qpos = wave_min_qpos + 31;
   const int k_end = sq.p + min(it.q0 + BQ, sq.sl);       // keys [0, k_end) are needed by this workgroup
   const int n_tiles = (k_end + BKV - 1) / BKV;
+  const int pages_needed = min(sq.n_pages, (k_end + 15) / 16);
+
+  // ---- stage the block table slice and the Q tile (rows past the chunk repeat its last row)
+  for (int i = tid; i < min(pages_needed, BT_CACHE); i += 256) bts[i] = bt[i];
+  for (int c = tid; c < BQ * (D / 8); c += 256) {
+    const int row = c / (D / 8), cc = c % (D / 8);
+    const bf16* src = qkv + (size_t)(sq.row0 + min(it.q0 + row, sq.sl - 1)) * ld + head * D + cc * 8;
+    *reinterpret_cast<u32x4*>(Qs + row * KS + cc * 8) = *reinterpret_cast<const u32x4*>(src);
+  }
+  __syncthreads();
+
+  // global -> register staging of one K/V tile
+  u32x4 kreg[KCH], vreg[VCH];
+  auto load_tile = [&](int kt) {
+#pragma unroll
+    for (int j = 0; j < KCH; j++) {
+      const int c = tid + j * 256, key = c / (D / 8), cc = c % (D / 8);
+      const int kpos = kt * BKV + key, pg = kpos >> 4;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (pg < pages_needed) {
+        const int page = pg < BT_CACHE ? bts[pg] : bt[pg];
+        v = *reinterpret_cast<const u32x4*>(pool + ((size_t)page * geo.n_kv + kvh) * head_elems + (size_t)(kpos & 15) * D + cc * 8);
+      }
+      kreg[j] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < VCH; j++) {
+      const int c = tid + j * 256, pgl = c / (D * 2), rem = c % (D * 2), dd = rem >> 1, hf = rem & 1;
+      const int pg = kt * (BKV / 16) + pgl;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (pg < pages_needed) {
+        const int page = pg < BT_CACHE ? bts[pg] : bt[pg];
+        v = *reinterpret_cast<const u32x4*>(pool + ((size_t)page * geo.n_kv + kvh) * head_elems + (size_t)16 * D + dd * 16 + hf * 8);
+      }
+      vreg[j] = v;
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int j = 0; j < KCH; j++) {
+      const int c = tid + j * 256, key = c / (D / 8), cc = c % (D / 8);
+      *reinterpret_cast<u32x4*>(Ks + key * KS + cc * 8) = kreg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < VCH; j++) {
+      const int c = tid + j * 256, pgl = c / (D * 2), rem = c % (D * 2), dd = rem >> 1, hf = rem & 1;
+      bf16* dst = Vs + dd * VS + pgl * 16 + hf * 4;       // keys 8hf..8hf+3 -> slot 4hf, keys 8hf+4..8hf+7 -> slot 8+4hf
+      *reinterpret_cast<u32x2*>(dst) = u32x2{vreg[j][0], vreg[j][1]};
+      *reinterpret_cast<u32x2*>(dst + 8) = u32x2{vreg[j][2], vreg[j][3]};
+    }
+  };
 
   f32x16 o[DB];
 #pragma unroll
   for (int b = 0; b < DB; b++)
 #pragma unroll
     for (int r = 0; r < 16; r++) o[b][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;
 
+  load_tile(0);
+  store_tile();
+  __syncthreads();
+
+  const bf16* qrow = Qs + (wave * 32 + l32) * KS + 8 * lh;
   for (int kt = 0; kt < n_tiles; kt++) {
-    __syncthreads();                                      // everyone is done with the previous tile
-    // ---- stage K tile [64 keys][D] and V^T tile [D][64 keys]
-    constexpr int KCH = BKV * D / 8;                      // 16-byte chunks in the K tile
-#pragma unroll
-    for (int c = tid; c < KCH; c += 256) {
-      const int key = c / (D / 8), cc = c % (D / 8);
-      const int kpos = kt * BKV + key, pg = kpos / 16;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (pg < sq.n_pages)
-        v = *reinterpret_cast<const uint4*>(pool + ((size_t)bt[pg] * geo.n_kv + kvh) * head_elems + (size_t)(kpos % 16) * D + cc * 8);
-      *reinterpret_cast<uint4*>(Ks + key * KS + cc * 8) = v;
-    }
-    constexpr int VCH = D * BKV / 8;
-#pragma unroll
-    for (int c = tid; c < VCH; c += 256) {
-      const int pgl = c / (D * 2), rem = c % (D * 2), dd = rem >> 1, hf = rem & 1;
-      const int pg = kt * (BKV / 16) + pgl;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (pg < sq.n_pages)
-        v = *reinterpret_cast<const uint4*>(pool + ((size_t)bt[pg] * geo.n_kv + kvh) * head_elems + (size_t)16 * D + dd * 16 + hf * 8);
-      uint2* dst = reinterpret_cast<uint2*>(Vs + dd * VS + pgl * 16 + hf * 8);
-      dst[0] = make_uint2(v.x, v.y);
-      dst[1] = make_uint2(v.z, v.w);
-    }
-    __syncthreads();
-    if (kt * BKV > wave_max_qpos) continue;               // wave-uniform: every key of the tile is masked
+    const bool more = kt + 1 < n_tiles;                   // uniform
+    if (more) load_tile(kt + 1);                          // in flight while this tile is consumed
 
-    // ---- S^T = K Q^T  (two 32-key blocks)
-    f32x16 s[2];
+    if (kt * BKV <= wave_max_qpos) {                      // wave-uniform: otherwise every key of the tile is masked
+      // ---- S^T = K Q^T  (two 32-key blocks)
+      f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
+      for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) s[kb][r] = 0.f;
+        for (int r = 0; r < 16; r++) s[kb][r] = 0.f;
 #pragma unroll
       for (int j = 0; j < KSTEPS; j++) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + l32) * KS + j * 16 + 8 * lh);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], s[kb], 0, 0, 0);
-      }
-    }
-    // ---- scale, causal mask, online softmax
-    const bool need_mask = kt * BKV + BKV - 1 > wave_min_qpos;
-    float mx = -INFINITY;
+        const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * j);
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        float v = s[kb][r] * scale_log2e;
-        if (need_mask) {
-          const int key = kt * BKV + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          if (key > qpos) v = -INFINITY;
+        for (int kb = 0; kb < 2; kb++) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + l32) * KS + j * 16 + 8 * lh);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf, s[kb], 0, 0, 0);
         }
-        s[kb][r] = v;
-        mx = fmaxf(mx, v);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
-    float rs = 0.f;
+      // ---- causal mask and online softmax on the raw scores; the scale rides in the exponent's
+      // fused multiply-add. The reference maximum m_ref is only moved when the tile maximum
+      // exceeds it by more than 2^RESCALE_LOG2 (probabilities then stay below that factor, far
+      // inside fp32/bf16 range), so the rescale of O and l is skipped on most tiles.
+      if (kt * BKV + BKV - 1 > wave_min_qpos) {
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++)
+        for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_use);
-        s[kb][r] = p;
-        rs += p;
+          for (int r = 0; r < 16; r++) {
+            const int key = kt * BKV + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (key > qpos) s[kb][r] = -INFINITY;
+          }
       }
-    rs += __shfl_xor(rs, 32, 64);
-    l_run = l_run * corr + rs;
-    m_run = m_new;
+      float mx = -INFINITY;
 #pragma unroll
-    for (int b = 0; b < DB; b++)
+      for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) o[b][r] *= corr;
+        for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[kb][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const bool grow = (mx - m_ref) * scale_log2e > RESCALE_LOG2;     // false when both are -inf (NaN)
+      if (__any(grow)) {                                               // wave-uniform
+        const float m_upd = grow ? mx : m_ref;
+        const float corr = (m_upd == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_upd) * scale_log2e);
+        m_ref = m_upd;
+        l_run *= corr;
+#pragma unroll
+        for (int b = 0; b < DB; b++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) o[b][r] *= corr;
+      }
+      const float nm = (m_ref == -INFINITY) ? 0.f : -m_ref * scale_log2e;
+      float rs = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2e, nm));
+          s[kb][r] = p;
+          rs += p;
+        }
+      l_run += rs;                                                      // this half's keys; halves are added at the end
 
-    // ---- O^T += V^T P^T
+      // ---- O^T += V^T P^T
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++)
+      for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-      for (int j2 = 0; j2 < 2; j2++) {
-        bf16x8 pb;
+        for (int j2 = 0; j2 < 2; j2++) {
+          bf16x8 pb;
 #pragma unroll
-        for (int e = 0; e < 8; e++) pb[e] = f2bf(s[kb][8 * j2 + e]);
+          for (int e = 0; e < 8; e++) pb[e] = f2bf(s[kb][8 * j2 + e]);
 #pragma unroll
-        for (int b = 0; b < DB; b++) {
-          const bf16* vrow = Vs + (b * 32 + l32) * VS + kb * 32 + 16 * j2 + 4 * lh;
-          const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vrow);
-          const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vrow + 8);
-          bf16x8 a;
-#pragma unroll
-          for (int e = 0; e < 4; e++) { a[e] = v0[e]; a[e + 4] = v1[e]; }
-          o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[b], 0, 0, 0);
+          for (int b = 0; b < DB; b++) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vs + (b * 32 + l32) * VS + kb * 32 + 16 * j2 + 8 * lh);
+            o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[b], 0, 0, 0);
+          }
         }
-      }
+    }
+    __syncthreads();                                      // everyone is done reading this tile
+    if (more) store_tile();
+    __syncthreads();
   }
 
   if (!q_valid) return;
+  l_run += __shfl_xor(l_run, 32, 64);
   const float inv_l = 1.f / l_run;
   bf16* orow = out + (size_t)(sq.row0 + qloc) * ldo + head * D + 4 * lh;
 #pragma unroll
