@@ -3,7 +3,7 @@
 // tokens needs no separate path).
 //
 // A workgroup of 4 waves owns 128 consecutive query rows of one head of one sequence; each
-// wave owns 32 of them. The block-table slice and the Q tile sit in LDS for the whole kernel; the
+// wave owns 32 of them. A window of the block table and the Q tile sit in LDS; the
 // next 64-key K/V tile is fetched into registers while the current one is consumed, then
 // written to the (single) LDS tile buffers between two barriers. Per 64-key tile:
 //   S^T[key, q] = K[key, :] . Q[q, :]          v_mfma_f32_32x32x16_bf16, A = K rows, B = Q rows
@@ -22,7 +22,14 @@ namespace sts {
 constexpr int BQ = 128, BKV = 64;
 
 constexpr float RESCALE_LOG2 = 8.f;
-constexpr int BT_CACHE = 2080;   // block-table entries kept in LDS (contexts up to 33280 tokens; beyond that read from global)
+constexpr int BT_CACHE = 1024;   // block-table window kept in LDS (16384 tokens), refilled as the key loop crosses it
+
+// max over a lane and its partner 32 lanes away (v_permlane32_swap: the upper half of the first
+// operand trades places with the lower half of the second)
+__device__ __forceinline__ float half_swap_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 template <int D>
 __global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __restrict__ qkv, int ld, bf16* __restrict__ out, int ldo,
@@ -57,8 +64,15 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __rest
   const int n_tiles = (k_end + BKV - 1) / BKV;
   const int pages_needed = min(sq.n_pages, (k_end + 15) / 16);
 
-  // ---- stage the block table slice and the Q tile (rows past the chunk repeat its last row)
-  for (int i = tid; i < min(pages_needed, BT_CACHE); i += 256) bts[i] = bt[i];
+  // ---- stage a window of the block table and the Q tile (rows past the chunk repeat its last row).
+  // Window entries past the last needed page repeat that page: the K/V loads are then
+  // unconditional, and what they fetch for positions beyond the context is causally masked
+  // (the pool only ever holds finite values, so 0 * V stays 0).
+  auto fill_bt_window = [&](int first) {
+    const int n = min(BT_CACHE, (pages_needed - first + 3) & ~3);
+    for (int i = tid; i < n; i += 256) bts[i] = bt[min(first + i, pages_needed - 1)];
+  };
+  fill_bt_window(0);
   for (int c = tid; c < BQ * (D / 8); c += 256) {
     const int row = c / (D / 8), cc = c % (D / 8);
     const bf16* src = qkv + (size_t)(sq.row0 + min(it.q0 + row, sq.sl - 1)) * ld + head * D + cc * 8;
@@ -66,30 +80,29 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __rest
   }
   __syncthreads();
 
-  // global -> register staging of one K/V tile
+  // global -> register staging of one K/V tile. A tile spans 4 pages; chunk j of a thread lies in
+  // page slot j * (4 / KCH) + a per-thread constant, at a per-thread constant offset inside the page.
+  const size_t page_stride = (size_t)geo.n_kv * head_elems;
+  const bf16* pool_h = pool + (size_t)kvh * head_elems;
+  const int kslot0 = (tid / (D / 8)) >> 4, vslot0 = tid / (2 * D);
+  const int koff = ((tid / (D / 8)) & 15) * D + (tid % (D / 8)) * 8;
+  const int voff = 16 * D + ((tid % (2 * D)) >> 1) * 16 + (tid & 1) * 8;
   u32x4 kreg[KCH], vreg[VCH];
   auto load_tile = [&](int kt) {
+    const i32x4 pg = *reinterpret_cast<const i32x4*>(bts + (kt * 4) % BT_CACHE);
 #pragma unroll
     for (int j = 0; j < KCH; j++) {
-      const int c = tid + j * 256, key = c / (D / 8), cc = c % (D / 8);
-      const int kpos = kt * BKV + key, pg = kpos >> 4;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (pg < pages_needed) {
-        const int page = pg < BT_CACHE ? bts[pg] : bt[pg];
-        v = *reinterpret_cast<const u32x4*>(pool + ((size_t)page * geo.n_kv + kvh) * head_elems + (size_t)(kpos & 15) * D + cc * 8);
-      }
-      kreg[j] = v;
+      int page;
+      if constexpr (D == 128) page = pg[j];
+      else page = kslot0 ? pg[2 * j + 1] : pg[2 * j];
+      kreg[j] = *reinterpret_cast<const u32x4*>(pool_h + (size_t)page * page_stride + koff);
     }
 #pragma unroll
     for (int j = 0; j < VCH; j++) {
-      const int c = tid + j * 256, pgl = c / (D * 2), rem = c % (D * 2), dd = rem >> 1, hf = rem & 1;
-      const int pg = kt * (BKV / 16) + pgl;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (pg < pages_needed) {
-        const int page = pg < BT_CACHE ? bts[pg] : bt[pg];
-        v = *reinterpret_cast<const u32x4*>(pool + ((size_t)page * geo.n_kv + kvh) * head_elems + (size_t)16 * D + dd * 16 + hf * 8);
-      }
-      vreg[j] = v;
+      int page;
+      if constexpr (D == 128) page = pg[j];
+      else page = vslot0 ? pg[2 * j + 1] : pg[2 * j];
+      vreg[j] = *reinterpret_cast<const u32x4*>(pool_h + (size_t)page * page_stride + voff);
     }
   };
   auto store_tile = [&]() {
@@ -121,24 +134,56 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __rest
   const bf16* qrow = Qs + (wave * 32 + l32) * KS + 8 * lh;
   for (int kt = 0; kt < n_tiles; kt++) {
     const bool more = kt + 1 < n_tiles;                   // uniform
-    if (more) load_tile(kt + 1);                          // in flight while this tile is consumed
+    if (more) {
+      if (((kt + 1) * 4) % BT_CACHE == 0) {               // uniform: slide the block-table window
+        __syncthreads();
+        fill_bt_window((kt + 1) * 4);
+        __syncthreads();
+      }
+      load_tile(kt + 1);                                  // in flight while this tile is consumed
+    }
 
     if (kt * BKV <= wave_max_qpos) {                      // wave-uniform: otherwise every key of the tile is masked
-      // ---- S^T = K Q^T  (two 32-key blocks)
+      // ---- S^T = K Q^T  (two 32-key blocks); operand fragments of step j+1 are read from LDS
+      // while the MFMAs of step j run
       f32x16 s[2];
 #pragma unroll
       for (int kb = 0; kb < 2; kb++)
 #pragma unroll
         for (int r = 0; r < 16; r++) s[kb][r] = 0.f;
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        bf16x8 qf[2], kf[2][2];
+        const bf16* krow = Ks + l32 * KS + 8 * lh;
+        qf[0] = *reinterpret_cast<const bf16x8*>(qrow);
+        kf[0][0] = *reinterpret_cast<const bf16x8*>(krow);
+        kf[0][1] = *reinterpret_cast<const bf16x8*>(krow + 32 * KS);
 #pragma unroll
-      for (int j = 0; j < KSTEPS; j++) {
-        const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * j);
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + l32) * KS + j * 16 + 8 * lh);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf, s[kb], 0, 0, 0);
+        for (int j = 0; j < KSTEPS; j++) {
+          const int c = j & 1, n = c ^ 1;
+          if (j + 1 < KSTEPS) {
+            qf[n] = *reinterpret_cast<const bf16x8*>(qrow + 16 * (j + 1));
+            kf[n][0] = *reinterpret_cast<const bf16x8*>(krow + 16 * (j + 1));
+            kf[n][1] = *reinterpret_cast<const bf16x8*>(krow + 32 * KS + 16 * (j + 1));
+          }
+          s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c][0], qf[c], s[0], 0, 0, 0);
+          s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c][1], qf[c], s[1], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+        for (int j = 0; j + 1 < KSTEPS; j++) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      // first V^T operands: in flight during the softmax arithmetic
+      bf16x8 vf[2][DB];
+      const bf16* vrow = Vs + l32 * VS + 8 * lh;
+#pragma unroll
+      for (int b = 0; b < DB; b++) vf[0][b] = *reinterpret_cast<const bf16x8*>(vrow + b * 32 * VS);
+      __builtin_amdgcn_sched_barrier(0);
       // ---- causal mask and online softmax on the raw scores; the scale rides in the exponent's
       // fused multiply-add. The reference maximum m_ref is only moved when the tile maximum
       // exceeds it by more than 2^RESCALE_LOG2 (probabilities then stay below that factor, far
@@ -157,7 +202,7 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __rest
       for (int kb = 0; kb < 2; kb++)
 #pragma unroll
         for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[kb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = half_swap_max(mx);
       const bool grow = (mx - m_ref) * scale_log2e > RESCALE_LOG2;     // false when both are -inf (NaN)
       if (__any(grow)) {                                               // wave-uniform
         const float m_upd = grow ? mx : m_ref;
@@ -181,20 +226,29 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_kernel(const bf16* __rest
         }
       l_run += rs;                                                      // this half's keys; halves are added at the end
 
-      // ---- O^T += V^T P^T
+      // ---- O^T += V^T P^T, four groups of 16 keys; the next group's V^T operands are read
+      // while the current group's MFMAs run
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kb = 0; kb < 2; kb++)
+      for (int g = 0; g < 4; g++) {
+        const int c = g & 1, n = c ^ 1;
+        if (g + 1 < 4) {
 #pragma unroll
-        for (int j2 = 0; j2 < 2; j2++) {
-          bf16x8 pb;
-#pragma unroll
-          for (int e = 0; e < 8; e++) pb[e] = f2bf(s[kb][8 * j2 + e]);
-#pragma unroll
-          for (int b = 0; b < DB; b++) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vs + (b * 32 + l32) * VS + kb * 32 + 16 * j2 + 8 * lh);
-            o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[b], 0, 0, 0);
-          }
+          for (int b = 0; b < DB; b++) vf[n][b] = *reinterpret_cast<const bf16x8*>(vrow + b * 32 * VS + 16 * (g + 1));
         }
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; e++) pb[e] = f2bf(s[g >> 1][8 * (g & 1) + e]);
+#pragma unroll
+        for (int b = 0; b < DB; b++) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c][b], pb, o[b], 0, 0, 0);
+      }
+#pragma unroll
+      for (int g = 0; g + 1 < 4; g++) {
+        __builtin_amdgcn_sched_group_barrier(0x100, DB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();                                      // everyone is done reading this tile
     if (more) store_tile();
