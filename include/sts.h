@@ -167,11 +167,14 @@ int sts_probe_copy(sts_ctx* ctx, int32_t side, int32_t cus, size_t bytes, int32_
  * widened). They use the default stream and their own temporary device buffers. */
 /* C[M,N] = A[M,K] * W[N,K]^T. tile_cfg: STS_GEMM_*; epilogue 0 = bf16 store, 1 = fp32 store
  * (split_k >= 1 partial sums are added up on the device), 2 = C += (C given in c_inout),
- * 3 = SwiGLU: W holds gate rows then up rows ([2*N2, K]); output [M, N2]. */
+ * 3 = SwiGLU: W holds gate rows then up rows ([2*N2, K]); output [M, N2].
+ * tail_slots > 0 (needs split_k == 1): launch as on a partition that holds tail_slots
+ * workgroups at once -- the tiles of the last, partly filled wave (Section 2.2.1) are cut along
+ * K into pieces that fill the wave, and a second kernel sums the pieces. 0 = whole tiles only. */
 enum { STS_GEMM_256x256 = 0, STS_GEMM_128x128, STS_GEMM_256x128, STS_GEMM_64x256, STS_GEMM_32x256, STS_GEMM_64x128, STS_GEMM_64x64,
        STS_GEMM_256x256_W8 /* 256x256 tile, 8 waves */ };
 int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
-                int32_t tile_cfg, int32_t epilogue, int32_t split_k);
+                int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots);
 /* Causal attention of a chunk: q [t, n_q, d], k and v [prior + t, n_kv, d]; query i sits at
  * position prior + i. K,V go through a paged pool with the given page order (pages[] of
  * ceil((prior+t)/16) distinct ids < n_pool_pages). out [t, n_q, d]. */

@@ -61,6 +61,7 @@ struct Phase {
   // device workspace
   float* X = nullptr; bf16* Xn = nullptr; bf16* QKV = nullptr; bf16* A = nullptr; bf16* H = nullptr;
   float* part = nullptr; float* attn_ws = nullptr; bf16* Q = nullptr;
+  float* tail_ws = nullptr; size_t tail_ws_bytes = 0;         // prefill GEMM tail pieces
   float* Xlast = nullptr; bf16* Xlast_n = nullptr; float* logits = nullptr; int* next = nullptr;
   int* d_tokens = nullptr; int* d_bt = nullptr; int* d_rows = nullptr;
   PrefillSeq* d_pseq = nullptr; DecodeSeq* d_dseq = nullptr; AttnItem* d_items = nullptr;
@@ -204,24 +205,45 @@ int pick_cfg(int m, int n) {
   // and global latency better than one 256x256 workgroup; measured faster on every layer shape
   return GEMM_128x128;
 }
-// Prefill GEMM tile choice for a partition of `cus` CUs: the candidate whose number of full
-// waves of workgroups times its per-wave time is smallest (wave quantisation, paper Section
-// 2.2.1, is what differs between them at a given CU count). Rates are measured busy-CU
-// throughputs in TFLOP/s per CU: 128x128 tiles run two workgroups per CU, 256x256 (8 waves) one.
-int pick_prefill_cfg(int m, int n, int cus) {
+// Prefill GEMM tile choice for a partition of `cus` CUs: the candidate with the smallest
+// estimated time, which is where wave quantisation (paper Section 2.2.1) enters -- complete
+// waves of workgroups at the tile's busy-CU rate, then the last wave, whole or cut along K.
+// Rates are measured busy-CU throughputs in TFLOP/s per CU: 128x128 tiles run two workgroups
+// per CU, 256x256 (8 waves) one.
+int pick_prefill_cfg(int m, int n, int k, int cus, size_t tail_ws_bytes) {
   if (m <= 64) return GEMM_64x128;
-  struct Cand { int cfg, tm, tn, slots; double rate; };
-  const Cand cands[2] = {{GEMM_128x128, 128, 128, 2, 3.9}, {GEMM_256x256_W8, 256, 256, 1, 4.5}};
+  struct Cand { int cfg; double rate; };
+  const Cand cands[2] = {{GEMM_128x128, 3.9}, {GEMM_256x256_W8, 4.5}};
   int best = GEMM_128x128; double best_cost = 1e300;
   for (const Cand& c : cands) {
-    if (n % c.tn != 0) continue;
-    const long long tiles = (long long)((m + c.tm - 1) / c.tm) * (n / c.tn);
-    const long long slots = (long long)c.slots * std::max(cus, 8);
-    const long long waves = (tiles + slots - 1) / slots;
-    const double cost = (double)waves * c.tm * c.tn * c.slots / c.rate;
+    const int tm = gemm_tile_m(c.cfg), tn = gemm_tile_n(c.cfg), per_cu = gemm_wgs_per_cu(c.cfg);
+    if (n % tn != 0) continue;
+    const int tiles = ((m + tm - 1) / tm) * (n / tn);
+    const int slots = per_cu * std::max(cus, 8);
+    int n_full, f;
+    gemm_tail_plan(tiles, k / 64, slots, (long long)(tail_ws_bytes / ((size_t)tm * tn * sizeof(float))), &n_full, &f);
+    // in units of this configuration's tile time: complete waves, then the last wave -- whole, or
+    // in rounds of 1/f with a start-up charge per round, plus the partial tiles written and read
+    // back (4 bytes out, 4 in per element and piece, at about 20 GB/s per CU)
+    const double tile_s = 2.0 * tm * tn * k / (c.rate * 1e12 / per_cu);
+    double t;
+    if (f > 1) {
+      const int rest = tiles - n_full, rounds = (rest * f + slots - 1) / slots;
+      t = (n_full / slots + rounds * (1.0 / f + 0.03)) * tile_s + (double)rest * f * tm * tn * 8.0 / (std::max(cus, 8) * 20e9) + 6e-6;
+    } else {
+      t = (double)((tiles + slots - 1) / slots) * tile_s;
+    }
+    const double cost = t;
     if (cost < best_cost) { best_cost = cost; best = c.cfg; }
   }
   return best;
+}
+// A prefill GEMM on the phase's partition: tile choice, and the last wave of tiles cut along K.
+hipError_t prefill_gemm(Phase& ph, int epi, const bf16* A, int lda, const bf16* W, int ldw, void* C, int ldc, int m, int n, int k) {
+  int cfg = pick_prefill_cfg(m, n, k, ph.cus, ph.tail_ws_bytes);
+  if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_64x128) cfg = GEMM_128x128;    // the wave tile must hold gate/up block pairs
+  const GemmTail tail{gemm_wgs_per_cu(cfg) * ph.cus, ph.tail_ws, ph.tail_ws_bytes};
+  return gemm_bf16(ph.stream, cfg, epi, A, lda, W, ldw, C, ldc, m, n, k, 1, 0, &tail);
 }
 int pick_splits(int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
@@ -314,14 +336,13 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
   for (int l = lb; l < le; l++) {
     const LayerW& w = c->layers[l];
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g1, d.rms_eps, rows, h));
-    KL(ph, STS_K_QKV, gemm_bf16(st, pick_prefill_cfg(rows, c->qkvn, ph.cus), EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h, 1, 0));
+    KL(ph, STS_K_QKV, prefill_gemm(ph, EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h));
     KL(ph, STS_K_ROPE, rope_kv_write_prefill(st, ph.QKV, c->qkvn, ph.d_pseq, n_seqs, ph.d_bt, c->inv_freq, layer_pool(c, l), c->geo, rows, d.n_q_heads));
     KL(ph, STS_K_ATTN, attn_prefill(st, ph.QKV, c->qkvn, ph.A, c->qd, ph.d_pseq, ph.d_items, n_items, ph.d_bt, layer_pool(c, l), c->geo, d.n_q_heads));
-    KL(ph, STS_K_O, gemm_bf16(st, pick_prefill_cfg(rows, h, ph.cus), EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd, 1, 0));
+    KL(ph, STS_K_O, prefill_gemm(ph, EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd));
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g2, d.rms_eps, rows, h));
-    KL(ph, STS_K_GATEUP, gemm_bf16(st, rows <= 64 ? GEMM_128x128 : pick_prefill_cfg(rows, 2 * d.mlp, ph.cus), EPI_SWIGLU_BF16,
-                                   ph.Xn, h, w.wgu, h, ph.H, d.mlp, rows, 2 * d.mlp, h, 1, 0));
-    KL(ph, STS_K_DOWN, gemm_bf16(st, pick_prefill_cfg(rows, h, ph.cus), EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp, 1, 0));
+    KL(ph, STS_K_GATEUP, prefill_gemm(ph, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, rows, 2 * d.mlp, h));
+    KL(ph, STS_K_DOWN, prefill_gemm(ph, EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp));
   }
   if (le == d.n_layers && want_logits) {
     KL(ph, STS_K_HEAD, gather_rows_f32(st, ph.Xlast, ph.X, ph.d_rows, n_seqs, h));
@@ -472,6 +493,9 @@ int alloc_phase(sts_ctx* c, int side) {
     STSCK(dev_alloc(c, &ph.QKV, rows * c->qkvn));
     STSCK(dev_alloc(c, &ph.d_pseq, nseq));
     STSCK(dev_alloc(c, &ph.d_items, items));
+    const size_t tail_floats = (size_t)c->n_cu * 256 * 256;   // one wave of partial tiles at the largest tile on every CU
+    STSCK(dev_alloc(c, &ph.tail_ws, tail_floats));
+    ph.tail_ws_bytes = tail_floats * sizeof(float);
     STSCK(host_alloc(&ph.h_pseq, nseq));
     STSCK(host_alloc(&ph.h_items, items));
   } else {

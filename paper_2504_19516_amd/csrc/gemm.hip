@@ -16,10 +16,26 @@ struct GemmArgs {
   const bf16* A; const bf16* W; void* C;
   int lda, ldw, ldc;
   int M, N, K;
-  int tiles_m, tiles_n, per_xcd, group_m;
+  int tiles_m, tiles_n, group_m;
   int k_per_split;            // K range handled by one blockIdx.y
   long long split_stride;     // elements between consecutive split-K partial outputs
+  // Tail splitting. Tiles [0, n_full) are computed whole. The remaining tiles -- the last,
+  // partly filled wave of workgroups on the partition -- are cut along K into tail_f pieces each,
+  // so that wave takes 1/tail_f of a tile time; pieces leave fp32 partial tiles in tail_ws and a
+  // second small kernel adds them up in a fixed order and applies the epilogue.
+  int n_full, full_per_xcd, tail_f, n_pieces, piece_per_xcd;
+  float* tail_ws;
 };
+
+// tile index -> tile coordinates: tiles are walked in groups of group_m tile rows so that
+// workgroups resident together share operand rows in L2
+__device__ __forceinline__ void tile_coords(const GemmArgs& g, int v, int* tm, int* tn) {
+  const int gsz = g.group_m * g.tiles_n;
+  const int first_m = (v / gsz) * g.group_m;
+  const int gm = min(g.tiles_m - first_m, g.group_m);
+  *tm = first_m + (v % gsz) % gm;
+  *tn = (v % gsz) / gm;
+}
 
 template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
 __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
@@ -34,14 +50,26 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
   bf16* As = reinterpret_cast<bf16*>(smem);        // [2][BM][LS]
   bf16* Bs = As + 2 * BM * LS;                     // [2][BN][LS]
 
-  const int v = xcd_contiguous(blockIdx.x, g.per_xcd);
-  if (v >= g.tiles_m * g.tiles_n) return;
-  const int gsz = g.group_m * g.tiles_n;
-  const int first_m = (v / gsz) * g.group_m;
-  const int gm = min(g.tiles_m - first_m, g.group_m);
-  const int tm = first_m + (v % gsz) % gm, tn = (v % gsz) / gm;
+  // Workgroups are dealt round-robin to the 8 XCDs, in order: each XCD first gets a contiguous
+  // run of whole tiles (neighbours share operands in its L2), then its share of the tail pieces.
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  int v, kbeg, kend, piece = -1;
+  if (local < g.full_per_xcd) {
+    v = xcd * g.full_per_xcd + local;
+    if (v >= g.n_full) return;
+    kbeg = blockIdx.y * g.k_per_split;
+    kend = min(g.K, kbeg + g.k_per_split);
+  } else {
+    piece = xcd * g.piece_per_xcd + (local - g.full_per_xcd);
+    if (piece >= g.n_pieces) return;
+    v = g.n_full + piece / g.tail_f;
+    const int z = piece % g.tail_f, ksteps = g.K / BK;
+    kbeg = (int)((long long)ksteps * z / g.tail_f) * BK;
+    kend = (int)((long long)ksteps * (z + 1) / g.tail_f) * BK;
+  }
+  int tm, tn;
+  tile_coords(g, v, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
-  const int kbeg = blockIdx.y * g.k_per_split, kend = min(g.K, kbeg + g.k_per_split);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
@@ -140,6 +168,18 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
     cur ^= 1;
   }
 
+  // ---- a tail piece stores its partial tile, row-major [BM][BN]
+  if (piece >= 0) {
+    float* part = g.tail_ws + (size_t)piece * (BM * BN) + (size_t)(wm * WTM + 4 * lh) * BN + wn * WTN + l32;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) part[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * BN + j * 32] = acc[i][j][r];
+    return;
+  }
+
   // ---- epilogue
   const int rbase = m0 + wm * WTM + 4 * lh;
   const int cbase = n0 + wn * WTN + l32;
@@ -170,8 +210,67 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
   }
 }
 
+// Adds the tail pieces of each split tile in piece order and applies the epilogue. One thread per
+// four consecutive columns.
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(256) gemm_tail_fixup(GemmArgs g) {
+  const int t = blockIdx.x;                                   // tail tile
+  const int e = blockIdx.y * 256 + threadIdx.x;
+  const int r = e / (BN / 4), c = (e % (BN / 4)) * 4;
+  int tm, tn;
+  tile_coords(g, g.n_full + t, &tm, &tn);
+  const int row = tm * BM + r;
+  if (row >= g.M) return;
+  if (EPI == EPI_SWIGLU_BF16 && ((c >> 5) & 1)) return;      // "up" columns are consumed by their gate thread
+  const float* p = g.tail_ws + (size_t)t * g.tail_f * (BM * BN) + (size_t)r * BN + c;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(p), up = {0.f, 0.f, 0.f, 0.f};
+  if (EPI == EPI_SWIGLU_BF16) up = *reinterpret_cast<const f32x4*>(p + 32);
+  for (int z = 1; z < g.tail_f; z++) {
+    sum += *reinterpret_cast<const f32x4*>(p + (size_t)z * (BM * BN));
+    if (EPI == EPI_SWIGLU_BF16) up += *reinterpret_cast<const f32x4*>(p + (size_t)z * (BM * BN) + 32);
+  }
+  const int col = tn * BN + c;
+  if constexpr (EPI == EPI_SWIGLU_BF16) {
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; i++) o[i] = f2bf(sum[i] / (1.f + __expf(-sum[i])) * up[i]);
+    const int ocol = ((tn * BN + (c & ~63)) >> 1) + (c & 31);
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.C) + (size_t)row * g.ldc + ocol) = o;
+  } else if constexpr (EPI == EPI_BF16) {
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; i++) o[i] = f2bf(sum[i]);
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.C) + (size_t)row * g.ldc + col) = o;
+  } else {
+    f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + (size_t)row * g.ldc + col);
+    if constexpr (EPI == EPI_RESID_F32) *dst += sum;
+    else *dst = sum;
+  }
+}
+
+// How the tiles of one launch are divided when the partition holds `slots` workgroups of this
+// configuration at once: n_full tiles run whole (complete waves), the `rest` tiles of the last
+// wave are cut into f pieces (f = 1: no cut). rest * f pieces take ceil(rest * f / slots) rounds
+// of 1/f tile time each; every piece also pays a fixed start-up and partial-store cost, taken as
+// 3 % of a tile time. The cut is made only if it saves at least a tenth of a tile time.
+void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int* n_full, int* f) {
+  *n_full = tiles; *f = 1;
+  if (slots <= 0) return;
+  const int full = tiles / slots * slots, rest = tiles - full;
+  if (rest == 0) return;
+  int best = 1; double best_t = 1.0;
+  for (int cut = 2; cut <= std::min(ksteps / 4, 16); cut++) {
+    if ((long long)rest * cut > max_pieces) break;               // partial tiles must fit the scratch buffer
+    const int rounds = (rest * cut + slots - 1) / slots;
+    const double t = rounds * (1.0 / cut + 0.03);
+    if (t < best_t - 1e-9) { best_t = t; best = cut; }
+  }
+  if (best_t > 0.9) return;
+  *n_full = full; *f = best;
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
-static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits) {
+static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTail* tail) {
   constexpr int NT = WGM * WGN * 64;
   constexpr size_t lds = 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
   auto kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
@@ -184,27 +283,39 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits) {
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = g.N / BN;
   const int tiles = g.tiles_m * g.tiles_n;
-  g.per_xcd = (tiles + 7) / 8;
   g.group_m = 8;
   const int ksteps = g.K / BK;
+  g.n_full = tiles; g.tail_f = 1; g.n_pieces = 0; g.piece_per_xcd = 0; g.tail_ws = nullptr;
+  if (tail && tail->ws && splits == 1 && g.ldc % 4 == 0) {
+    int n_full, f;
+    gemm_tail_plan(tiles, ksteps, tail->slots, (long long)(tail->ws_bytes / (BM * BN * sizeof(float))), &n_full, &f);
+    if (f > 1) {
+      g.n_full = n_full; g.tail_f = f; g.n_pieces = (tiles - n_full) * f;
+      g.piece_per_xcd = (g.n_pieces + 7) / 8;
+      g.tail_ws = tail->ws;
+    }
+  }
+  g.full_per_xcd = (g.n_full + 7) / 8;
   const int per = (ksteps + splits - 1) / splits;
   g.k_per_split = per * BK;
   const int ny = (ksteps + per - 1) / per;
-  hipLaunchKernelGGL(kern, dim3(g.per_xcd * 8, ny), dim3(NT), lds, s, g);
+  hipLaunchKernelGGL(kern, dim3((g.full_per_xcd + g.piece_per_xcd) * 8, ny), dim3(NT), lds, s, g);
+  if (g.n_pieces > 0)
+    hipLaunchKernelGGL((gemm_tail_fixup<BM, BN, EPI>), dim3(tiles - g.n_full, BM * BN / 1024), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 
 template <int EPI>
-static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int splits) {
+static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int splits, const GemmTail* tail) {
   switch (cfg) {
-    case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI>(s, g, splits);
-    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI>(s, g, splits);
-    case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI>(s, g, splits);
-    case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI>(s, g, splits);
-    case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits);
-    case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI>(s, g, splits);
-    case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits);
-    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI>(s, g, splits);
+    case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI>(s, g, splits, tail);
+    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI>(s, g, splits, tail);
+    case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI>(s, g, splits, tail);
+    case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI>(s, g, splits, tail);
+    case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits, tail);
+    case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI>(s, g, splits, tail);
+    case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits, tail);
+    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI>(s, g, splits, tail);
     default: return hipErrorInvalidValue;
   }
 }
@@ -227,9 +338,12 @@ int gemm_tile_m(int cfg) {
 
 // C = A * W^T with the chosen tile configuration and epilogue. Requirements (checked):
 // K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1.
-// With splits > 1 (EPI_F32 only) partial sums go to C + z * split_stride.
+// With splits > 1 (EPI_F32 only) partial sums go to C + z * split_stride. With `tail` (splits == 1)
+// the tiles of the last, partly filled wave of workgroups are cut along K (see GemmArgs).
+int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_256x256_W8 || cfg == GEMM_256x128 ? 1 : 2; }
+
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
-                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride) {
+                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail) {
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128 || cfg == GEMM_64x64)) return hipErrorInvalidValue;   // wave tile of one block
@@ -237,17 +351,17 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.split_stride = split_stride;
   switch (epi) {
-    case EPI_BF16: return launch_epi<EPI_BF16>(s, cfg, g, splits);
-    case EPI_F32: return launch_epi<EPI_F32>(s, cfg, g, splits);
-    case EPI_RESID_F32: return launch_epi<EPI_RESID_F32>(s, cfg, g, splits);
+    case EPI_BF16: return launch_epi<EPI_BF16>(s, cfg, g, splits, tail);
+    case EPI_F32: return launch_epi<EPI_F32>(s, cfg, g, splits, tail);
+    case EPI_RESID_F32: return launch_epi<EPI_RESID_F32>(s, cfg, g, splits, tail);
     case EPI_SWIGLU_BF16:
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
-        case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1);
-        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16>(s, g, 1);
-        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1);
-        case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1);
-        case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1);
-        case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1);
+        case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
         default: return hipErrorInvalidValue;
       }
     default: return hipErrorInvalidValue;

@@ -9,8 +9,13 @@ enum GemmEpilogue { EPI_BF16 = 0, EPI_F32 = 1, EPI_RESID_F32 = 2, EPI_SWIGLU_BF1
 enum GemmConfig { GEMM_256x256 = 0, GEMM_128x128 = 1, GEMM_256x128 = 2, GEMM_64x256 = 3, GEMM_32x256 = 4, GEMM_64x128 = 5, GEMM_64x64 = 6, GEMM_256x256_W8 = 7, GEMM_NCFG = 8 };
 int gemm_tile_m(int cfg);
 int gemm_tile_n(int cfg);
+int gemm_wgs_per_cu(int cfg);                       // resident workgroups per CU of this configuration
+// Tail splitting: `slots` = workgroups the stream's CU partition holds at once, `ws` = fp32 scratch.
+struct GemmTail { int slots; float* ws; size_t ws_bytes; };
+void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int* n_full, int* f);
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
-                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride);
+                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride,
+                     const GemmTail* tail = nullptr);
 
 // ---- paged KV layout ----------------------------------------------------------------------
 // One layer's pool is [n_pages][n_kv_heads][ K: page_tokens x d | V^T: d x page_tokens ] bf16.

@@ -52,10 +52,17 @@ int download_bf16(DevBufs& b, float* host, const bf16* dev, size_t n) {
 }  // namespace
 
 extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
-                           int32_t tile_cfg, int32_t epilogue, int32_t split_k) {
+                           int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots) {
   if (!a || !w || !c_inout || m < 1 || n < 1 || k < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;
-  if (epilogue < 0 || epilogue > 3 || split_k < 1 || split_k > 8) return STS_EINVAL;
+  if (epilogue < 0 || epilogue > 3 || split_k < 1 || split_k > 8 || tail_slots < 0 || (tail_slots > 0 && split_k != 1)) return STS_EINVAL;
   DevBufs b;
+  GemmTail tail{tail_slots, nullptr, 0};
+  if (tail_slots > 0) {                                            // room for one partial tile per slot
+    tail.ws_bytes = (size_t)tail_slots * gemm_tile_m(tile_cfg) * gemm_tile_n(tile_cfg) * sizeof(float);
+    tail.ws = b.get<float>(tail.ws_bytes / sizeof(float));
+    if (!tail.ws) return STS_EHIP;
+  }
+  const GemmTail* tp = tail_slots > 0 ? &tail : nullptr;
   const int wn = epilogue == EPI_SWIGLU_BF16 ? 2 * n : n;          // physical rows of W
   bf16* dA = upload_bf16(b, a, (size_t)m * k);
   bf16* dW = b.get<bf16>((size_t)wn * k);
@@ -78,14 +85,14 @@ extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32
   if (epilogue == EPI_BF16 || epilogue == EPI_SWIGLU_BF16) {
     bf16* dC = b.get<bf16>((size_t)m * n);
     if (!dC) return STS_EHIP;
-    e = gemm_bf16(nullptr, tile_cfg, epilogue, dA, k, dW, k, dC, n, m, wn, k, 1, 0);
+    e = gemm_bf16(nullptr, tile_cfg, epilogue, dA, k, dW, k, dC, n, m, wn, k, 1, 0, tp);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
     rc = download_bf16(b, c_inout, dC, (size_t)m * n);
   } else if (epilogue == EPI_F32) {
     float* part = b.get<float>((size_t)split_k * m * n);
     float* dC = b.get<float>((size_t)m * n);
     if (!part || !dC) return STS_EHIP;
-    e = gemm_bf16(nullptr, tile_cfg, EPI_F32, dA, k, dW, k, part, n, m, n, k, split_k, (long long)m * n);
+    e = gemm_bf16(nullptr, tile_cfg, EPI_F32, dA, k, dW, k, part, n, m, n, k, split_k, (long long)m * n, tp);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
     // the tiled kernel launches only as many splits as the K extent can feed: sum exactly those
     const int ksteps = k / 64, per = (ksteps + split_k - 1) / split_k;
@@ -95,7 +102,7 @@ extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32
   } else {
     float* dC = b.get<float>((size_t)m * n);
     if (!dC || hipMemcpy(dC, c_inout, (size_t)m * n * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) return STS_EHIP;
-    e = gemm_bf16(nullptr, tile_cfg, EPI_RESID_F32, dA, k, dW, k, dC, n, m, n, k, 1, 0);
+    e = gemm_bf16(nullptr, tile_cfg, EPI_RESID_F32, dA, k, dW, k, dC, n, m, n, k, 1, 0, tp);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
     if (hipMemcpy(c_inout, dC, (size_t)m * n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) return STS_EHIP;
   }

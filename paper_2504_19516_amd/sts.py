@@ -318,12 +318,12 @@ class Engine:
 
 
 # ---- single operations
-def op_gemm(a, w, tile_cfg="128x128", epilogue=1, split_k=1, c_in=None):
+def op_gemm(a, w, tile_cfg="128x128", epilogue=1, split_k=1, c_in=None, tail_slots=0):
     a, w = _f32(a), _f32(w)
     m, k = a.shape
     n = w.shape[0] // 2 if epilogue == 3 else w.shape[0]
     c = _f32(c_in).copy() if c_in is not None else np.zeros((m, n), np.float32)
-    _ck(lib().sts_op_gemm(_p(a, C.c_float), _p(w, C.c_float), _p(c, C.c_float), m, n, k, GEMM_CFGS[tile_cfg], epilogue, split_k), "sts_op_gemm")
+    _ck(lib().sts_op_gemm(_p(a, C.c_float), _p(w, C.c_float), _p(c, C.c_float), m, n, k, GEMM_CFGS[tile_cfg], epilogue, split_k, tail_slots), "sts_op_gemm")
     return c
 
 

@@ -74,6 +74,36 @@ def test_gemm_swiglu_epilogue(sts, cfg, m):
     assert rel(got, ref) <= BF16_TOL
 
 
+@pytest.mark.parametrize("cfg,m,n,slots", [("128x128", 300, 512, 8), ("128x128", 300, 512, 10), ("128x128", 300, 512, 40),
+                                           ("128x128", 300, 512, 16), ("256x256w8", 513, 512, 4), ("256x256w8", 513, 512, 15),
+                                           ("64x128", 64, 640, 4)])
+@pytest.mark.parametrize("epilogue", [0, 1, 2, 3])
+def test_gemm_tail_wave_split(sts, cfg, m, n, slots, epilogue):
+    """The tiles of the last, partly filled wave of workgroups (Section 2.2.1) are cut along K and
+    summed by a second kernel: same results as whole tiles, for every epilogue."""
+    if epilogue == 3 and cfg == "64x128":
+        pytest.skip("SwiGLU needs a wave tile of two 32-column blocks")
+    k = 1024
+    a = synth.normal_bf16(40, (m, k))
+    a64 = a.astype(np.float64)
+    if epilogue == 3:
+        wg = synth.normal_bf16(41, (n // 2, k), 0.05)
+        wu = synth.normal_bf16(42, (n // 2, k), 0.05)
+        ref = T.silu(T.op_linear(a64, wg.astype(np.float64))) * T.op_linear(a64, wu.astype(np.float64))
+        got = sts.op_gemm(a, np.concatenate([wg, wu]), cfg, epilogue=3, tail_slots=slots)
+        assert rel(got, ref) <= BF16_TOL
+        return
+    w = synth.normal_bf16(43, (n, k), 0.05)
+    ref = T.op_linear(a64, w.astype(np.float64))
+    if epilogue == 2:
+        x = np.random.default_rng(44).standard_normal((m, n)).astype(np.float32)
+        got = sts.op_gemm(a, w, cfg, epilogue=2, c_in=x, tail_slots=slots)
+        assert rel(got, x.astype(np.float64) + ref) <= 1e-5
+    else:
+        got = sts.op_gemm(a, w, cfg, epilogue=epilogue, tail_slots=slots)
+        assert rel(got, ref) <= (BF16_TOL if epilogue == 0 else 1e-5)
+
+
 def test_gemm_rejects_bad_shapes(sts):
     a = np.zeros((4, 100), np.float32); w = np.zeros((256, 100), np.float32)
     with pytest.raises(sts.StsError) as e:
