@@ -6,11 +6,17 @@
 // the 16-byte operand reads are bank-conflict free) and each wave accumulates a
 // (BM/WGM) x (BN/WGN) sub-tile in 32x32 MFMA blocks.
 //
+// Two main loops share the tile mapping and the epilogue: gemm_kernel stages tiles through
+// registers into padded LDS rows (small and skinny tiles), gemm_dl_kernel moves them
+// global -> LDS directly into swizzled rows (the large prefill tiles).
+//
 // Lane layout of the 32x32 accumulator block (register r of lane l):
 //   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
 #include "kernels.h"
 
 namespace sts {
+
+constexpr int GEMM_DL_LDS_BASE = 1024;   // the direct-to-LDS arena stays clear of LDS address 0
 
 struct GemmArgs {
   const bf16* A; const bf16* W; void* C;
@@ -37,6 +43,76 @@ __device__ __forceinline__ void tile_coords(const GemmArgs& g, int v, int* tm, i
   *tn = (v % gsz) / gm;
 }
 
+// Workgroups are dealt round-robin to the 8 XCDs, in order: each XCD first gets a contiguous
+// run of whole tiles (neighbours share operands in its L2), then its share of the tail pieces.
+// Returns false for a padding workgroup. piece < 0 for a whole tile.
+template <int BK>
+__device__ __forceinline__ bool block_work(const GemmArgs& g, int* v, int* kbeg, int* kend, int* piece) {
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  *piece = -1;
+  if (local < g.full_per_xcd) {
+    *v = xcd * g.full_per_xcd + local;
+    if (*v >= g.n_full) return false;
+    *kbeg = blockIdx.y * g.k_per_split;
+    *kend = min(g.K, *kbeg + g.k_per_split);
+  } else {
+    *piece = xcd * g.piece_per_xcd + (local - g.full_per_xcd);
+    if (*piece >= g.n_pieces) return false;
+    *v = g.n_full + *piece / g.tail_f;
+    const int z = *piece % g.tail_f, ksteps = g.K / BK;
+    *kbeg = (int)((long long)ksteps * z / g.tail_f) * BK;
+    *kend = (int)((long long)ksteps * (z + 1) / g.tail_f) * BK;
+  }
+  return true;
+}
+
+// Epilogue of one workgroup tile (or the partial-tile store of a tail piece).
+template <int BM, int BN, int WGM, int WGN, int EPI>
+__device__ __forceinline__ void store_tile(const GemmArgs& g, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], int m0, int n0, int piece,
+                                           int wm, int wn, int l32, int lh) {
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+  // a tail piece stores its partial tile, row-major [BM][BN]
+  if (piece >= 0) {
+    float* part = g.tail_ws + (size_t)piece * (BM * BN) + (size_t)(wm * WTM + 4 * lh) * BN + wn * WTN + l32;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) part[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * BN + j * 32] = acc[i][j][r];
+    return;
+  }
+
+  // ---- epilogue
+  const int rbase = m0 + wm * WTM + 4 * lh;
+  const int cbase = n0 + wn * WTN + l32;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+      if (row >= g.M) continue;
+      if constexpr (EPI == EPI_SWIGLU_BF16) {
+        bf16* out = reinterpret_cast<bf16*>(g.C) + (size_t)row * g.ldc + ((n0 + wn * WTN) >> 1) + l32;
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+          const float gate = acc[i][j][r], up = acc[i][j + 1][r];
+          out[(j >> 1) * 32] = f2bf(gate / (1.f + __expf(-gate)) * up);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          const size_t idx = (size_t)row * g.ldc + cbase + j * 32;
+          if constexpr (EPI == EPI_BF16) reinterpret_cast<bf16*>(g.C)[idx] = f2bf(acc[i][j][r]);
+          else if constexpr (EPI == EPI_F32)
+            reinterpret_cast<float*>(g.C)[(size_t)blockIdx.y * g.split_stride + idx] = acc[i][j][r];
+          else reinterpret_cast<float*>(g.C)[idx] += acc[i][j][r];
+        }
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
 __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
   constexpr int NT = WGM * WGN * 64;
@@ -50,23 +126,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
   bf16* As = reinterpret_cast<bf16*>(smem);        // [2][BM][LS]
   bf16* Bs = As + 2 * BM * LS;                     // [2][BN][LS]
 
-  // Workgroups are dealt round-robin to the 8 XCDs, in order: each XCD first gets a contiguous
-  // run of whole tiles (neighbours share operands in its L2), then its share of the tail pieces.
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  int v, kbeg, kend, piece = -1;
-  if (local < g.full_per_xcd) {
-    v = xcd * g.full_per_xcd + local;
-    if (v >= g.n_full) return;
-    kbeg = blockIdx.y * g.k_per_split;
-    kend = min(g.K, kbeg + g.k_per_split);
-  } else {
-    piece = xcd * g.piece_per_xcd + (local - g.full_per_xcd);
-    if (piece >= g.n_pieces) return;
-    v = g.n_full + piece / g.tail_f;
-    const int z = piece % g.tail_f, ksteps = g.K / BK;
-    kbeg = (int)((long long)ksteps * z / g.tail_f) * BK;
-    kend = (int)((long long)ksteps * (z + 1) / g.tail_f) * BK;
-  }
+  int v, kbeg, kend, piece;
+  if (!block_work<BK>(g, &v, &kbeg, &kend, &piece)) return;
   int tm, tn;
   tile_coords(g, v, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
@@ -144,17 +205,21 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
     }
     // scheduling recipe: first the TM+TN fragment reads of step 0, then per step one LDS read
-    // slotted between every MPR MFMAs, the last step pure MFMA
+    // after every MPR MFMAs (all reads of the next step are out before this step's last MFMAs),
+    // the last step pure MFMA
     {
-      constexpr int MPR = (TM * TN + TM + TN - 1) / (TM + TN);
+      constexpr int MPR = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;
+      constexpr int REST = TM * TN > MPR * (TM + TN) ? TM * TN - MPR * (TM + TN) : 0;
       __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
 #pragma unroll
-      for (int kk = 0; kk + 1 < BK / 16; kk++)
+      for (int kk = 0; kk + 1 < BK / 16; kk++) {
 #pragma unroll
         for (int x = 0; x < TM + TN; x++) {
           __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+      }
       __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -168,46 +233,162 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
     cur ^= 1;
   }
 
-  // ---- a tail piece stores its partial tile, row-major [BM][BN]
-  if (piece >= 0) {
-    float* part = g.tail_ws + (size_t)piece * (BM * BN) + (size_t)(wm * WTM + 4 * lh) * BN + wn * WTN + l32;
+  store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
+}
+
+// ---- direct-to-LDS main loop ---------------------------------------------------------------
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave writes at
+// lds_dst + 16 * l (lds_dst must be wave-uniform); completion is counted by vmcnt.
+__device__ __forceinline__ void load_to_lds16(const void* gsrc, void* lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+#endif
+}
+__device__ __forceinline__ void wait_vmem_all() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0); the other counters are left alone
+#endif
+}
+
+// Tiles go global -> LDS without passing through registers (no staging VGPRs, no LDS store
+// instructions). A tile row is 128 bytes (BK = 64) and unpadded; the 16-byte K-chunk c of row r
+// is stored at slot c ^ ((r >> 1) & 7), which keeps the 16-byte operand reads bank-conflict
+// free. One wave instruction fills 64 consecutive slots (8 rows), so the swizzle is applied on
+// the global side: each lane fetches the chunk that belongs in its slot.
+//
+// Schedule of one K tile (four 16-wide steps): steps 0-2 run from the current LDS buffer; then
+// the wave waits for its own loads of the next tile and meets the others at the barrier, which
+// both publishes the next tile and retires the current buffer (the operands of step 3 are
+// already in registers); the loads of the tile after next go out right behind the barrier, a
+// whole iteration ahead of their use; step 3 runs while the first operands of the next tile
+// are read. The LDS arena starts 1 KB above address 0.
+template <int BM, int BN, int WGM, int WGN, int EPI>
+__global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
+  constexpr int BK = 64, NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+  constexpr int ROWB = BK * 2;                               // bytes per tile row
+  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;      // 16-byte chunks per thread
+  constexpr int STAGE = (BM + BN) * ROWB;
+  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/thread mismatch");
+  static_assert(EPI != EPI_SWIGLU_BF16 || TN % 2 == 0, "swiglu needs gate/up block pairs");
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* arena = smem + GEMM_DL_LDS_BASE;
+
+  int v, kbeg, kend, piece;
+  if (!block_work<BK>(g, &v, &kbeg, &kend, &piece)) return;
+  int tm, tn;
+  tile_coords(g, v, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // slot q = j * NT + tid of a tile: row q / 8, holds K-chunk (q % 8) ^ ((row >> 1) & 7)
+  const bf16* a_src[A_CH];
+  const bf16* b_src[B_CH];
+#pragma unroll
+  for (int j = 0; j < A_CH; j++) {
+    const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
+    a_src[j] = g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + ch * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < B_CH; j++) {
+    const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
+    b_src[j] = g.W + (size_t)(n0 + row) * g.ldw + ch * 8;
+  }
+  auto issue = [&](int stage, int k) {
+    unsigned char* sa = arena + stage * STAGE + wave * 1024;
+    unsigned char* sb = sa + BM * ROWB;
+#pragma unroll
+    for (int j = 0; j < A_CH; j++) load_to_lds16(a_src[j] + k, sa + j * NT * 16);
+#pragma unroll
+    for (int j = 0; j < B_CH; j++) load_to_lds16(b_src[j] + k, sb + j * NT * 16);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  // byte offset of this lane's operand chunk inside its row, for each of the four K steps
+  int koff[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; kk++) koff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 7)) * 16;
+  const int a_row = (wm * WTM + l32) * ROWB, b_row = BM * ROWB + (wn * WTN + l32) * ROWB;
+
+  constexpr int MPR = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;       // MFMAs per LDS read
+  constexpr int REST = TM * TN > MPR * (TM + TN) ? TM * TN - MPR * (TM + TN) : 0;
+
+  const int nk = (kend - kbeg) / BK;
+  issue(0, kbeg);
+  wait_vmem_all();
+  __syncthreads();
+  if (nk > 1) issue(1, kbeg + BK);
+  bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(arena + a_row + i * 32 * ROWB + koff[0]);
+#pragma unroll
+  for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(arena + b_row + j * 32 * ROWB + koff[0]);
+
+  int cur = 0;
+  for (int t = 0; t < nk; t++) {
+    const unsigned char* Ac = arena + cur * STAGE + a_row;
+    const unsigned char* Bc = arena + cur * STAGE + b_row;
+    const unsigned char* An = arena + (cur ^ 1) * STAGE + a_row;
+    const unsigned char* Bn = arena + (cur ^ 1) * STAGE + b_row;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < 3; kk++) {
+#pragma unroll
+      for (int i = 0; i < TM; i++) af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * ROWB + koff[kk + 1]);
+#pragma unroll
+      for (int j = 0; j < TN; j++) bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * ROWB + koff[kk + 1]);
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 3; kk++) {
+#pragma unroll
+      for (int x = 0; x < TM + TN; x++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmem_all();
+    __syncthreads();
+    if (t + 2 < nk) issue(cur, kbeg + (t + 2) * BK);
+    __builtin_amdgcn_sched_barrier(0);
+    if (t + 1 < nk) {
+#pragma unroll
+      for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(An + i * 32 * ROWB + koff[0]);
+#pragma unroll
+      for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(Bn + j * 32 * ROWB + koff[0]);
+    }
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int r = 0; r < 16; r++)
+      for (int j = 0; j < TN; j++)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][i], bfr[1][j], acc[i][j], 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < TN; j++) part[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * BN + j * 32] = acc[i][j][r];
-    return;
-  }
-
-  // ---- epilogue
-  const int rbase = m0 + wm * WTM + 4 * lh;
-  const int cbase = n0 + wn * WTN + l32;
-#pragma unroll
-  for (int i = 0; i < TM; i++) {
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
-      if (row >= g.M) continue;
-      if constexpr (EPI == EPI_SWIGLU_BF16) {
-        bf16* out = reinterpret_cast<bf16*>(g.C) + (size_t)row * g.ldc + ((n0 + wn * WTN) >> 1) + l32;
-#pragma unroll
-        for (int j = 0; j < TN; j += 2) {
-          const float gate = acc[i][j][r], up = acc[i][j + 1][r];
-          out[(j >> 1) * 32] = f2bf(gate / (1.f + __expf(-gate)) * up);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < TN; j++) {
-          const size_t idx = (size_t)row * g.ldc + cbase + j * 32;
-          if constexpr (EPI == EPI_BF16) reinterpret_cast<bf16*>(g.C)[idx] = f2bf(acc[i][j][r]);
-          else if constexpr (EPI == EPI_F32)
-            reinterpret_cast<float*>(g.C)[(size_t)blockIdx.y * g.split_stride + idx] = acc[i][j][r];
-          else reinterpret_cast<float*>(g.C)[idx] += acc[i][j][r];
-        }
-      }
+    for (int x = 0; x < TM + TN; x++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
+    if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    cur ^= 1;
   }
+  store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
 
 // Adds the tail pieces of each split tile in piece order and applies the epilogue. One thread per
@@ -269,11 +450,14 @@ void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int*
   *n_full = full; *f = best;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
+template <int BM, int BN, int BK, int WGM, int WGN, int EPI, bool DL = false>
 static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTail* tail) {
   constexpr int NT = WGM * WGN * 64;
-  constexpr size_t lds = 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
-  auto kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
+  static_assert(!DL || BK == 64, "the direct-to-LDS loop is written for BK = 64");
+  constexpr size_t lds = DL ? GEMM_DL_LDS_BASE + 2 * (size_t)(BM + BN) * BK * sizeof(bf16) : 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
+  void (*kern)(GemmArgs);
+  if constexpr (DL) kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI>;
+  else kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -309,13 +493,13 @@ template <int EPI>
 static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int splits, const GemmTail* tail) {
   switch (cfg) {
     case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI>(s, g, splits, tail);
+    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI, true>(s, g, splits, tail);
     case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI>(s, g, splits, tail);
     case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI>(s, g, splits, tail);
     case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits, tail);
     case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI>(s, g, splits, tail);
     case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI>(s, g, splits, tail);
+    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI, true>(s, g, splits, tail);
     default: return hipErrorInvalidValue;
   }
 }
@@ -357,8 +541,8 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
     case EPI_SWIGLU_BF16:
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
         case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
-        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
-        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16, true>(s, g, 1, tail);
+        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16, true>(s, g, 1, tail);
         case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
         case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
         case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
