@@ -31,6 +31,7 @@ from paper_2504_19516_amd import synth  # noqa: E402
 PREFILL_TOKENS, DECODE_BATCH = 2048, 64
 PEAK_BF16 = 2.5e15       # dense MFMA bf16 flop/s, MI355X
 PEAK_HBM = 8.0e12        # bytes/s
+PMC_PROBE_BYTES = 512 << 20   # size of the copy-kernel reference run (--pmc-probe): read 512 MiB, write 512 MiB
 TTFT_SLO_NS, TPOT_SLO_NS, MODEL_LAYERS = 1_000_000_000, 50_000_000, 32
 
 
@@ -149,6 +150,21 @@ def cpu_baseline(desc, ctx):
                       f"(contexts {dctx}); {dt:.1f} s"}
 
 
+def stored_traffic(prefill_cus):
+    """HBM bytes per gate/up launch from the committed rocprofv3 --pmc measurement of this workload
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy kernel; written by
+    paper_2504_19516_amd/pmc_traffic.py), or None when no record matches this split."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2504_19516_amd", "data", "pmc_traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if rec.get("workload") != "config2" or rec.get("prefill_cus") != prefill_cus:
+        return None
+    return rec.get("gateup_hbm_bytes_per_launch")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,6 +172,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split", type=int, default=0, help="fix the prefill CU count instead of sweeping")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="also run the plain copy kernel on %d MiB, as the reference for rocprofv3 --pmc byte counters" % (PMC_PROBE_BYTES >> 20))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -216,9 +234,9 @@ def main():
                    "speedup_vs_time_multiplexed": tm_s / step_s,
                    "slo_per_layer_ms": {"ttft": ttft_budget / 1e6, "tpot": tpot_budget / 1e6},
                    "sweep": sweep},
-        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_kernel, SwiGLU epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4>, SwiGLU epilogue)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16,
-                     "traffic": None, "avg_launch_ms": gu_avg_s * 1e3, "partition_cus": pm,
+                     "traffic": stored_traffic(pm), "avg_launch_ms": gu_avg_s * 1e3, "partition_cus": pm,
                      "frac_of_partition_peak": achieved / (PEAK_BF16 * pm / 256),
                      "prefill_layer_tflops": prefill_flop / (tp * 1e-9) / 1e12,
                      "ms_per_step_with_kernel_events": kt_step_s * 1e3},
@@ -229,6 +247,8 @@ def main():
                             "sum_kernel_ms": dec_kernel_s * 1e3},
         "prefill_kernel_ms": {k: round(v[0] / args.steps / 1e6, 4) for k, v in kp.items()},
     }
+    if args.pmc_probe:
+        eng.probe_copy(0, 256, PMC_PROBE_BYTES, 2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(desc, wl.ctx)
     eng.close()

@@ -63,6 +63,10 @@ struct Phase {
   float* part = nullptr; float* attn_ws = nullptr; bf16* Q = nullptr;
   float* tail_ws = nullptr; size_t tail_ws_bytes = 0;         // prefill GEMM tail pieces
   float* Xlast = nullptr; bf16* Xlast_n = nullptr; float* logits = nullptr; int* next = nullptr;
+  // Per-call metadata (sequence records, block tables, work items, token ids) is packed into one
+  // pinned block and reaches the device in a single copy; the pointers below are views into the
+  // two blocks, laid out afresh by every launch.
+  unsigned char* h_meta = nullptr; unsigned char* d_meta = nullptr; size_t meta_bytes = 0, meta_used = 0;
   int* d_tokens = nullptr; int* d_bt = nullptr; int* d_rows = nullptr;
   PrefillSeq* d_pseq = nullptr; DecodeSeq* d_dseq = nullptr; AttnItem* d_items = nullptr;
   // pinned staging
@@ -114,12 +118,24 @@ int dev_alloc(sts_ctx* c, T** out, size_t count) {
   *out = reinterpret_cast<T*>(p);
   return STS_OK;
 }
+// Next 256-byte aligned view of `count` elements in a phase's metadata blocks.
+template <typename T>
+void meta_take(Phase& ph, T** host, T** dev, size_t count);
+
 template <typename T>
 int host_alloc(T** out, size_t count) {
   void* p = nullptr;
   HIPCK(hipHostMalloc(&p, std::max<size_t>(count, 1) * sizeof(T), hipHostMallocDefault));
   *out = reinterpret_cast<T*>(p);
   return STS_OK;
+}
+
+template <typename T>
+void meta_take(Phase& ph, T** host, T** dev, size_t count) {
+  const size_t off = (ph.meta_used + 255) & ~(size_t)255;
+  *host = reinterpret_cast<T*>(ph.h_meta + off);
+  *dev = reinterpret_cast<T*>(ph.d_meta + off);
+  ph.meta_used = off + count * sizeof(T);
 }
 
 // CU-masked streams are a process-wide pool: one stream per (side, CU count), created on first
@@ -213,7 +229,7 @@ int pick_cfg(int m, int n) {
 int pick_prefill_cfg(int m, int n, int k, int cus, size_t tail_ws_bytes) {
   if (m <= 64) return GEMM_64x128;
   struct Cand { int cfg; double rate; };
-  const Cand cands[2] = {{GEMM_128x128, 3.9}, {GEMM_256x256_W8, 4.5}};
+  const Cand cands[2] = {{GEMM_128x128, 4.0}, {GEMM_256x256_W8, 4.9}};
   int best = GEMM_128x128; double best_cost = 1e300;
   for (const Cand& c : cands) {
     const int tm = gemm_tile_m(c.cfg), tn = gemm_tile_n(c.cfg), per_cu = gemm_wgs_per_cu(c.cfg);
@@ -308,6 +324,13 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
   }
   // ---- stage metadata
   const int mp = c->p.max_pages_per_seq, bq = attn_prefill_tile_q();
+  ph.meta_used = 0;
+  meta_take(ph, &ph.h_pseq, &ph.d_pseq, n_seqs);
+  meta_take(ph, &ph.h_rows, &ph.d_rows, n_seqs);
+  meta_take(ph, &ph.h_items, &ph.d_items, rows / bq + n_seqs);
+  meta_take(ph, &ph.h_tokens, &ph.d_tokens, lb == 0 ? rows : 0);
+  meta_take(ph, &ph.h_bt, &ph.d_bt, (size_t)n_seqs * mp);
+  if (ph.meta_used > ph.meta_bytes) return STS_EINVAL;
   int r0 = 0, n_items = 0;
   for (int i = 0; i < n_seqs; i++) {
     const Seq& s = c->seqs[seqs[i]];
@@ -323,15 +346,9 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
   });
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
-  HIPCK(hipMemcpyAsync(ph.d_pseq, ph.h_pseq, n_seqs * sizeof(PrefillSeq), hipMemcpyHostToDevice, st));
-  HIPCK(hipMemcpyAsync(ph.d_bt, ph.h_bt, (size_t)n_seqs * mp * sizeof(int), hipMemcpyHostToDevice, st));
-  HIPCK(hipMemcpyAsync(ph.d_items, ph.h_items, n_items * sizeof(AttnItem), hipMemcpyHostToDevice, st));
-  HIPCK(hipMemcpyAsync(ph.d_rows, ph.h_rows, n_seqs * sizeof(int), hipMemcpyHostToDevice, st));
-  if (lb == 0) {
-    std::memcpy(ph.h_tokens, tokens, rows * sizeof(int));
-    HIPCK(hipMemcpyAsync(ph.d_tokens, ph.h_tokens, rows * sizeof(int), hipMemcpyHostToDevice, st));
-    KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, rows, d.hidden));
-  }
+  if (lb == 0) std::memcpy(ph.h_tokens, tokens, rows * sizeof(int));
+  HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
+  if (lb == 0) KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, rows, d.hidden));
   const int h = d.hidden;
   for (int l = lb; l < le; l++) {
     const LayerW& w = c->layers[l];
@@ -386,6 +403,11 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   for (int i = 0; i < n; i++) wants.push_back({seqs[i], c->seqs[seqs[i]].len + 1});
   STSCK(reserve_pages(c, wants));
   const int mp = c->p.max_pages_per_seq, pt = c->geo.page_tokens;
+  ph.meta_used = 0;
+  meta_take(ph, &ph.h_dseq, &ph.d_dseq, n);
+  meta_take(ph, &ph.h_tokens, &ph.d_tokens, n);
+  meta_take(ph, &ph.h_bt, &ph.d_bt, (size_t)n * mp);
+  if (ph.meta_used > ph.meta_bytes) return STS_EINVAL;
   int max_pages = 1;
   for (int i = 0; i < n; i++) {
     const Seq& s = c->seqs[seqs[i]];
@@ -408,9 +430,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   const int max_chunks = (max_pages + chunk_pages - 1) / chunk_pages;
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
-  HIPCK(hipMemcpyAsync(ph.d_dseq, ph.h_dseq, n * sizeof(DecodeSeq), hipMemcpyHostToDevice, st));
-  HIPCK(hipMemcpyAsync(ph.d_bt, ph.h_bt, (size_t)n * mp * sizeof(int), hipMemcpyHostToDevice, st));
-  HIPCK(hipMemcpyAsync(ph.d_tokens, ph.h_tokens, n * sizeof(int), hipMemcpyHostToDevice, st));
+  HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
   KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, n, d.hidden));
   const int h = d.hidden;
   KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, c->layers[0].g1, d.rms_eps, n, h));
@@ -480,32 +500,26 @@ int alloc_phase(sts_ctx* c, int side) {
   STSCK(dev_alloc(c, &ph.Xlast_n, nseq * d.hidden));
   STSCK(dev_alloc(c, &ph.logits, nseq * d.vocab));
   STSCK(dev_alloc(c, &ph.next, nseq));
-  STSCK(dev_alloc(c, &ph.d_tokens, rows));
-  STSCK(dev_alloc(c, &ph.d_bt, nseq * mp));
-  STSCK(dev_alloc(c, &ph.d_rows, nseq));
-  STSCK(host_alloc(&ph.h_tokens, rows));
-  STSCK(host_alloc(&ph.h_bt, nseq * mp));
-  STSCK(host_alloc(&ph.h_rows, nseq));
+  {
+    const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
+    ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + sizeof(int)) + items * sizeof(AttnItem) +
+                    rows * sizeof(int) + nseq * mp * sizeof(int) + 8 * 256;
+    STSCK(dev_alloc(c, &ph.d_meta, ph.meta_bytes));
+    STSCK(host_alloc(&ph.h_meta, ph.meta_bytes));
+  }
   STSCK(host_alloc(&ph.h_logits, nseq * d.vocab));
   STSCK(host_alloc(&ph.h_next, nseq));
   if (side == 0) {
-    const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
     STSCK(dev_alloc(c, &ph.QKV, rows * c->qkvn));
-    STSCK(dev_alloc(c, &ph.d_pseq, nseq));
-    STSCK(dev_alloc(c, &ph.d_items, items));
     const size_t tail_floats = (size_t)c->n_cu * 256 * 256;   // one wave of partial tiles at the largest tile on every CU
     STSCK(dev_alloc(c, &ph.tail_ws, tail_floats));
     ph.tail_ws_bytes = tail_floats * sizeof(float);
-    STSCK(host_alloc(&ph.h_pseq, nseq));
-    STSCK(host_alloc(&ph.h_items, items));
   } else {
     const size_t widest = std::max<size_t>(std::max(c->qkvn, 2 * d.mlp), d.hidden);
     const size_t max_chunks = std::min<size_t>(128, (mp + 3) / 4);     // see decode_enqueue: chunks of >= 4 pages, <= 128 chunks
     STSCK(dev_alloc(c, &ph.part, 8 * rows * widest));
     STSCK(dev_alloc(c, &ph.Q, rows * c->qd));
     STSCK(dev_alloc(c, &ph.attn_ws, attn_decode_ws_floats((int)rows, d.n_q_heads, d.head_dim, (int)max_chunks)));
-    STSCK(dev_alloc(c, &ph.d_dseq, nseq));
-    STSCK(host_alloc(&ph.h_dseq, nseq));
   }
   return STS_OK;
 }
@@ -618,7 +632,7 @@ extern "C" int sts_destroy(sts_ctx* c) {
     if (ph.ev0) (void)hipEventDestroy(ph.ev0);
     if (ph.ev1) (void)hipEventDestroy(ph.ev1);
     for (hipEvent_t e : ph.kev) (void)hipEventDestroy(e);
-    void* hosts[] = {ph.h_tokens, ph.h_bt, ph.h_rows, ph.h_pseq, ph.h_dseq, ph.h_items, ph.h_logits, ph.h_next};
+    void* hosts[] = {ph.h_meta, ph.h_logits, ph.h_next};
     for (void* p : hosts) if (p) (void)hipHostFree(p);
   }
   trace("destroy: device memory");

@@ -1,0 +1,81 @@
+"""HBM traffic of the prefill gate/up GEMM from rocprofv3 byte counters.
+
+Takes the counter CSVs of two runs of the benchmark with the copy-kernel reference switched on,
+
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir1> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --pmc-probe
+    rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir2> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --pmc-probe
+
+scales each counter by what it reads for the copy kernel (which moves a known number of bytes
+each way) and prints the per-launch figures. With --json it also writes the record bench.py
+reports as roofline.traffic.
+
+    python -m paper_2504_19516_amd.pmc_traffic <fetch.csv> <write.csv> --prefill-cus 224 [--json]
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import json
+import os
+
+COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
+GATEUP_KERNEL = "gemm_dl_kernel"           # the SwiGLU instantiation is the gate/up GEMM
+COPY_KERNEL = "copy_kernel"
+
+
+def per_kernel(path, counter):
+    rows = collections.defaultdict(list)
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] == counter:
+                rows[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    return rows
+
+
+def pick(rows, needle, also=None):
+    vals = []
+    for name, v in rows.items():
+        if needle in name and (also is None or also in name):
+            vals += v
+    return vals
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("fetch_csv")
+    ap.add_argument("write_csv")
+    ap.add_argument("--prefill-cus", type=int, required=True)
+    ap.add_argument("--json", action="store_true")
+    args = ap.parse_args()
+    out = {}
+    lines = []
+    for counter, path in (("FETCH_SIZE", args.fetch_csv), ("WRITE_SIZE", args.write_csv)):
+        rows = per_kernel(path, counter)
+        copy = pick(rows, COPY_KERNEL)
+        # SwiGLU epilogue = last template argument 3 of the 256x256 8-wave instantiation
+        gate = pick(rows, GATEUP_KERNEL, "ELi3EE") or pick(rows, GATEUP_KERNEL, ", 3>")
+        if not copy or not gate:
+            raise SystemExit(f"{counter}: kernels not found in {path} (copy launches {len(copy)}, gate/up launches {len(gate)})")
+        copy_mean, gate_mean = sum(copy) / len(copy), sum(gate) / len(gate)
+        factor = COPY_BYTES / copy_mean                     # bytes per counter unit
+        out[counter] = dict(copy_counter=copy_mean, factor_bytes_per_unit=factor, gateup_counter=gate_mean,
+                            gateup_bytes=gate_mean * factor, launches=len(gate))
+        lines.append(f"{counter}: copy kernel reads {copy_mean:.1f} per launch for {COPY_BYTES} bytes -> {factor:.2f} bytes per unit; "
+                     f"gate/up GEMM {gate_mean:.1f} per launch over {len(gate)} launches -> {gate_mean * factor / 1e6:.1f} MB")
+    total = out["FETCH_SIZE"]["gateup_bytes"] + out["WRITE_SIZE"]["gateup_bytes"]
+    lines.append(f"gate/up GEMM HBM traffic per launch: {total / 1e6:.1f} MB "
+                 f"(read {out['FETCH_SIZE']['gateup_bytes'] / 1e6:.1f}, written {out['WRITE_SIZE']['gateup_bytes'] / 1e6:.1f})")
+    print("\n".join(lines))
+    if args.json:
+        rec = dict(workload="config2", prefill_cus=args.prefill_cus, gateup_hbm_bytes_per_launch=total,
+                   read_bytes=out["FETCH_SIZE"]["gateup_bytes"], written_bytes=out["WRITE_SIZE"]["gateup_bytes"],
+                   fetch_factor=out["FETCH_SIZE"]["factor_bytes_per_unit"], write_factor=out["WRITE_SIZE"]["factor_bytes_per_unit"])
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data", "pmc_traffic.json")
+        with open(path, "w") as f:
+            json.dump(rec, f, indent=1)
+        print("wrote", path)
+
+
+if __name__ == "__main__":
+    main()
