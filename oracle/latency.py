@@ -63,6 +63,7 @@ class Profile:
     tile_q: int = 128
     wgs_per_cu: int = 1                # b of Section 2.2.1: workgroups resident per CU
     use_waveq: int = 1
+    tail_cut: int = 0                  # > 0: the GEMMs cut the tiles of a partly filled last wave along K, into at most this many pieces
     bw: Grid | None = None             # D_{p,sl}: axes (decode CUs, co-running prefill tokens) -> bytes/ns
     alpha_prefill: Grid = field(default_factory=lambda: Grid([[256], [2048]], [[PPM]]))
     alpha_decode: Grid = field(default_factory=lambda: Grid([[256], [64], [65536]], [[[PPM]]]))
@@ -172,16 +173,56 @@ def _waveq_adjust(t: int, g: int, n_p: int, b: int = 1) -> int:
     return floor_div(t * n_p * w, n_p * w - n_p + tail)
 
 
+GEMM_KERNELS = ("qkv", "o", "gateup", "down")
+PIECE_COST_PPM = 30_000      # start-up and partial-tile store of one K piece, as a share of a tile time
+
+
+def tail_plan(g: int, slots: int, max_cut: int):
+    """The GEMM kernels' remedy for wave quantisation (Section 2.2.1 states the problem): of g
+    tiles on `slots` resident workgroups, full = g // slots waves run whole; the `rest` tiles of
+    the last wave are cut along K into f pieces each, which then take ceil(rest f / slots) rounds
+    of 1/f tile time (plus a fixed cost per piece). f is the cut in 2..max_cut with the smallest
+    such time, used only when it saves at least a tenth of a tile time; otherwise f = 1.
+    Returns (full, rest, f, rounds)."""
+    full = g // slots
+    rest = g - full * slots
+    if rest == 0 or max_cut < 2:
+        return full, rest, 1, 1 if rest else 0
+    best, best_cost = 1, PPM
+    for cut in range(2, max_cut + 1):
+        rounds = _cdiv(rest * cut, slots)
+        cost = rounds * (PPM // cut + PIECE_COST_PPM)
+        if cost < best_cost:
+            best, best_cost = cut, cost
+    if best_cost > 900_000:
+        return full, rest, 1, 1
+    return full, rest, best, _cdiv(rest * best, slots)
+
+
+def _waveq_tail_adjust(t: int, g: int, n_p: int, b: int, max_cut: int) -> int:
+    """As _waveq_adjust, for a kernel that cuts its last wave: the busy-time share g / slots of a
+    wave count becomes full + rounds (1/f + piece cost)."""
+    slots = b * n_p
+    full, rest, f, rounds = tail_plan(g, slots, max_cut)
+    if f == 1:
+        return _waveq_adjust(t, g, n_p, b)
+    waves_ppm = full * PPM + rounds * (PPM // f + PIECE_COST_PPM)
+    return floor_div(t * waves_ppm * slots, g * PPM)
+
+
 def prefill_roofline_ns(s: Shape, hw: Profile, reqs, pm: int, layer_begin: int, n_layers_step: int) -> int:
     """T'_{p,ES}: the sum of T'_k over the kernels of `n_layers_step` layers (and the head
     if the slice ends at the last layer)."""
     with_head = layer_begin + n_layers_step >= s.n_layers
     ks, head = prefill_kernels(s, hw, reqs, with_head)
     per_layer = 0
-    for _, flop, mem, g in ks:
+    for name, flop, mem, g in ks:
         t = srm_ns(flop, mem, pm, hw)
         if hw.use_waveq and g > 0:
-            t = _waveq_adjust(t, g, pm, hw.wgs_per_cu)
+            if hw.tail_cut > 0 and name in GEMM_KERNELS:
+                t = _waveq_tail_adjust(t, g, pm, hw.wgs_per_cu, hw.tail_cut)
+            else:
+                t = _waveq_adjust(t, g, pm, hw.wgs_per_cu)
         per_layer += t
     total = per_layer * n_layers_step
     for _, flop, mem, _ in head:
@@ -245,7 +286,7 @@ def _nest(flat, dims):
 
 def dump_profile(hw: Profile) -> str:
     lines = ["sts-profile 1"]
-    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq"):
+    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut"):
         lines.append(f"{k} {getattr(hw, k)}")
     for name in ("bw", "alpha_prefill", "alpha_decode"):
         g = getattr(hw, name)

@@ -48,7 +48,7 @@ int64_t alpha_at(const Grid& g, const int64_t* x) {
   return std::max<int64_t>(std::max<int64_t>(interp(g, x), g.min_value() / 2), 1);
 }
 
-struct Kern { int64_t flop, mem, g; };
+struct Kern { int64_t flop, mem, g; bool gemm = false; };
 
 static void prefill_kernels(const sts_model_desc& s, const Profile& hw, const int32_t* sl, const int32_t* p, int n,
                             std::vector<Kern>* ks, Kern* head) {
@@ -65,15 +65,15 @@ static void prefill_kernels(const sts_model_desc& s, const Profile& hw, const in
   const int64_t rows = cdiv(t, hw.tile_m), tn = hw.tile_n;
   ks->clear();
   ks->push_back({4 * t * h, 4 * t * h, 0});                                                             // norm1
-  ks->push_back({2 * t * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * cdiv(qkvn, tn)});          // qkv
+  ks->push_back({2 * t * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * cdiv(qkvn, tn), true});    // qkv
   ks->push_back({4 * t * qkvn, 4 * t * qkvn, 0});                                                       // rope
   ks->push_back({att_flop, att_mem, att_g});                                                            // attn
-  ks->push_back({2 * t * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * cdiv(h, tn)});               // o
+  ks->push_back({2 * t * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * cdiv(h, tn), true});         // o
   ks->push_back({4 * t * h, 4 * t * h, 0});                                                             // norm2
-  ks->push_back({4 * t * h * mlp, 2 * (2 * h * mlp + t * h + t * mlp), rows * cdiv(2 * mlp, tn)});      // gate/up
-  ks->push_back({2 * t * mlp * h, 2 * (mlp * h + t * mlp + 2 * t * h), rows * cdiv(h, tn)});            // down
+  ks->push_back({4 * t * h * mlp, 2 * (2 * h * mlp + t * h + t * mlp), rows * cdiv(2 * mlp, tn), true}); // gate/up
+  ks->push_back({2 * t * mlp * h, 2 * (mlp * h + t * mlp + 2 * t * h), rows * cdiv(h, tn), true});      // down
   const int64_t b = n, v = s.vocab;
-  *head = Kern{2 * b * h * v, 2 * (h * v + b * h + b * v), 0};
+  *head = Kern{2 * b * h * v, 2 * (h * v + b * h + b * v), 0, false};
 }
 
 static void decode_kernels(const sts_model_desc& s, const int32_t* cl, int n, std::vector<Kern>* ks, Kern* head) {
@@ -90,7 +90,7 @@ static void decode_kernels(const sts_model_desc& s, const int32_t* cl, int n, st
   ks->push_back({4 * b * h, 4 * b * h, 0});
   ks->push_back({4 * b * h * mlp, 2 * (2 * h * mlp + b * h + b * mlp), 0});
   ks->push_back({2 * b * mlp * h, 2 * (mlp * h + b * mlp + 2 * b * h), 0});
-  *head = Kern{2 * b * h * v, 2 * (h * v + b * h + b * v), 0};
+  *head = Kern{2 * b * h * v, 2 * (h * v + b * h + b * v), 0, false};
 }
 
 // Eq. 1: T' = flop / min(flop/mem * D_p, C_p) = max(flop / C_p, mem / D_p).
@@ -108,6 +108,33 @@ static int64_t waveq_adjust(int64_t t, int64_t g, int64_t n_p, int64_t b) {
   return floor_div((i128)t * n_p * w, n_p * w - n_p + tail);
 }
 
+// The GEMM kernels' remedy for wave quantisation: `full` waves of whole tiles, then the rest
+// tiles cut along K into f pieces that take `rounds` rounds of 1/f tile time plus a fixed cost
+// per piece (3 % of a tile time); f = 1 when no cut in 2..max_cut saves a tenth of a tile time.
+static constexpr int64_t PIECE_COST_PPM = 30000;
+static void tail_plan(int64_t g, int64_t slots, int64_t max_cut, int64_t* full, int64_t* f, int64_t* rounds) {
+  *full = g / slots;
+  const int64_t rest = g - *full * slots;
+  *f = 1; *rounds = rest ? 1 : 0;
+  if (rest == 0 || max_cut < 2) return;
+  int64_t best = 1, best_cost = PPM;
+  for (int64_t cut = 2; cut <= max_cut; cut++) {
+    const int64_t r = (rest * cut + slots - 1) / slots;
+    const int64_t cost = r * (PPM / cut + PIECE_COST_PPM);
+    if (cost < best_cost) { best = cut; best_cost = cost; }
+  }
+  if (best_cost > 900000) return;
+  *f = best; *rounds = (rest * best + slots - 1) / slots;
+}
+static int64_t waveq_tail_adjust(int64_t t, int64_t g, int64_t n_p, int64_t b, int64_t max_cut) {
+  const int64_t slots = b * n_p;
+  int64_t full, f, rounds;
+  tail_plan(g, slots, max_cut, &full, &f, &rounds);
+  if (f == 1) return waveq_adjust(t, g, n_p, b);
+  const int64_t waves_ppm = full * PPM + rounds * (PPM / f + PIECE_COST_PPM);
+  return floor_div((i128)t * waves_ppm * slots, (i128)g * PPM);
+}
+
 int64_t prefill_roofline_ns(const sts_model_desc& s, const Profile& hw, const int32_t* sl, const int32_t* p, int n,
                             int pm, int layer_begin, int n_layers_step) {
   std::vector<Kern> ks; Kern head;
@@ -115,7 +142,8 @@ int64_t prefill_roofline_ns(const sts_model_desc& s, const Profile& hw, const in
   int64_t per_layer = 0;
   for (const Kern& k : ks) {
     int64_t t = srm_ns(k.flop, k.mem, pm, hw, -1);
-    if (hw.use_waveq && k.g > 0) t = waveq_adjust(t, k.g, pm, hw.wgs_per_cu);
+    if (hw.use_waveq && k.g > 0)
+      t = hw.tail_cut > 0 && k.gemm ? waveq_tail_adjust(t, k.g, pm, hw.wgs_per_cu, hw.tail_cut) : waveq_adjust(t, k.g, pm, hw.wgs_per_cu);
     per_layer += t;
   }
   int64_t total = per_layer * n_layers_step;
@@ -205,10 +233,11 @@ bool parse_profile(const std::string& text, Profile* hw) {
     if (key == "n_cu") hw->n_cu = v; else if (key == "granule") hw->granule = v; else if (key == "c_peak") hw->c_peak = v;
     else if (key == "d_peak") hw->d_peak = v; else if (key == "n_d") hw->n_d = v; else if (key == "tile_m") hw->tile_m = v;
     else if (key == "tile_n") hw->tile_n = v; else if (key == "tile_q") hw->tile_q = v; else if (key == "wgs_per_cu") hw->wgs_per_cu = v; else if (key == "use_waveq") hw->use_waveq = v;
+    else if (key == "tail_cut") hw->tail_cut = v;
     else return false;
   }
   return header && hw->n_cu > 0 && hw->granule > 0 && hw->c_peak > 0 && hw->d_peak > 0 && hw->n_d > 0 && hw->tile_m > 0 &&
-         hw->tile_n > 0 && hw->tile_q > 0 && hw->wgs_per_cu > 0;
+         hw->tile_n > 0 && hw->tile_q > 0 && hw->wgs_per_cu > 0 && hw->tail_cut >= 0 && hw->tail_cut <= 64;
 }
 
 static void dump_grid(std::ostringstream& o, const char* name, const Grid& g) {
@@ -221,7 +250,7 @@ std::string dump_profile(const Profile& hw) {
   std::ostringstream o;
   o << "sts-profile 1\n";
   o << "n_cu " << hw.n_cu << "\ngranule " << hw.granule << "\nc_peak " << hw.c_peak << "\nd_peak " << hw.d_peak << "\nn_d " << hw.n_d
-    << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nwgs_per_cu " << hw.wgs_per_cu << "\nuse_waveq " << hw.use_waveq << "\n";
+    << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nwgs_per_cu " << hw.wgs_per_cu << "\nuse_waveq " << hw.use_waveq << "\ntail_cut " << hw.tail_cut << "\n";
   dump_grid(o, "bw", hw.bw);
   dump_grid(o, "alpha_prefill", hw.alpha_prefill);
   dump_grid(o, "alpha_decode", hw.alpha_decode);

@@ -20,6 +20,7 @@ struct Grid {                          // samples on a rectilinear grid, values 
 struct Profile {
   int64_t n_cu = 256, granule = 32, c_peak = 2500000, d_peak = 8000, n_d = 64;
   int64_t tile_m = 256, tile_n = 256, tile_q = 128, wgs_per_cu = 1, use_waveq = 1;
+  int64_t tail_cut = 0;                // > 0: GEMMs cut a partly filled last wave along K into at most this many pieces
   Grid bw;                             // D_{p,sl}; empty = use D_peak min(1, N_p/N_d)
   Grid alpha_prefill{{{256}, {2048}}, {PPM}};
   Grid alpha_decode{{{256}, {64}, {65536}}, {PPM}};

@@ -21,7 +21,7 @@ PPM = 1_000_000
 
 def profile_text(hw: dict, grids: dict) -> str:
     lines = ["sts-profile 1"]
-    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq"):
+    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut"):
         lines.append(f"{k} {int(hw[k])}")
     for name in ("bw", "alpha_prefill", "alpha_decode"):
         if name not in grids:
@@ -43,7 +43,7 @@ class Profiler:
                               max_pages_per_seq=(max_ctx + 128) // 16)
         self.n_cu = self.eng.get_partition()[2]
         self.hw = dict(n_cu=self.n_cu, granule=granule, c_peak=2_500_000, d_peak=8_000, n_d=self.n_cu, tile_m=128, tile_n=128,
-                       tile_q=128, wgs_per_cu=2, use_waveq=1)
+                       tile_q=128, wgs_per_cu=2, use_waveq=1, tail_cut=16)
         self.grids = {}
 
     def close(self):

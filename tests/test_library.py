@@ -76,11 +76,12 @@ def test_profile_text_roundtrip_between_implementations(sts):
     assert e.value.code == sts.EIO
 
 
-@pytest.mark.parametrize("waveq", [0, 1])
-def test_latency_query_bit_exact_vs_oracle(sts, waveq):
+@pytest.mark.parametrize("waveq,tail_cut", [(0, 0), (1, 0), (1, 16), (1, 5)])
+def test_latency_query_bit_exact_vs_oracle(sts, waveq, tail_cut):
     import numpy as np
     hw = sample_profile()
     hw.use_waveq = waveq
+    hw.tail_cut = tail_cut
     p = sts.Profile(text=L.dump_profile(hw))
     rng = np.random.default_rng(5)
     for desc in (synth.llama8b_model(), synth.llama70b_model(), synth.tiny_model()):

@@ -138,8 +138,41 @@ def test_wave_quant_adjustment_uses_workgroups_per_cu():
     assert L._waveq_adjust(1_000_000, 512, 224, 1) == 1_000_000 * 672 // 512
 
 
+def test_tail_cut_plan_and_adjustment_by_hand():
+    """The last, partly filled wave cut along K. Hand cases for 448 slots (224 CUs x 2):
+    512 tiles -> one whole wave, 64 tiles left; 7 pieces each fill the 448 slots once, so the
+    last wave costs 1/7 + 3 % of a tile time. A brute-force search over the cuts confirms the
+    choice; counts that divide evenly, or where no cut saves a tenth of a tile, stay uncut."""
+    assert L.tail_plan(512, 448, 16) == (1, 64, 7, 1)
+    assert L.tail_plan(896, 448, 16) == (2, 0, 1, 0)
+    assert L.tail_plan(512, 320, 16)[:3] == (1, 192, 5)               # 960 pieces = 3 rounds of 1/5
+    assert L.tail_plan(430, 448, 16)[2] == 1                          # 430 of 448 slots busy: nothing to gain
+    assert L.tail_plan(512, 448, 0)[2] == 1
+    for g, slots in [(512, 448), (128, 224), (100, 96), (777, 512), (5, 448)]:
+        full, rest, f, rounds = L.tail_plan(g, slots, 16)
+        costs = {c: -(-rest * c // slots) * (L.PPM // c + L.PIECE_COST_PPM) for c in range(2, 17)}
+        if rest and min(costs.values()) <= 900_000:
+            assert costs[f] == min(costs.values()) and rounds == -(-rest * f // slots)
+        else:
+            assert f == 1
+    t = 1_000_000
+    want = t * (L.PPM + (L.PPM // 7 + 30_000)) * 448 // (512 * L.PPM)
+    assert L._waveq_tail_adjust(t, 512, 224, 2, 16) == want
+    assert 1.02 * t < want < 1.03 * t                                 # against 1.75 t uncut
+    assert L._waveq_tail_adjust(t, 896, 224, 2, 16) == t
+    assert L._waveq_tail_adjust(t, 430, 224, 2, 16) == L._waveq_adjust(t, 430, 224, 2)
+    # whole layer, 2048 tokens of the 8B shape on 224 CUs: the O and down GEMMs (512 tiles each)
+    # lose their 75 % second-wave penalty, gate/up (3584 = 8 x 448) is unchanged
+    s = L.Shape(1, 4096, 32, 8, 128, 14336, 128256)
+    hw0, hw1 = L.Profile(tile_m=128, tile_n=128, wgs_per_cu=2), L.Profile(tile_m=128, tile_n=128, wgs_per_cu=2, tail_cut=16)
+    cut, whole = L.prefill_roofline_ns(s, hw1, [(2048, 0)], 224, 0, 1), L.prefill_roofline_ns(s, hw0, [(2048, 0)], 224, 0, 1)
+    assert 0.8 * whole < cut < 0.9 * whole
+    # 512-tile GEMMs fill 256 CUs x 2 exactly; only qkv (768 tiles) still gains
+    assert L.prefill_roofline_ns(s, hw1, [(2048, 0)], 256, 0, 1) <= L.prefill_roofline_ns(s, hw0, [(2048, 0)], 256, 0, 1)
+
+
 def test_profile_text_roundtrip():
-    hw = L.Profile(n_d=112, c_peak=1_234_567, wgs_per_cu=2)
+    hw = L.Profile(n_d=112, c_peak=1_234_567, wgs_per_cu=2, tail_cut=16)
     hw.bw = L.Grid([[32, 64], [0, 2048, 8192]], [[1600, 1500, 1400], [2700, 2500, 2300]])
     hw.alpha_decode = L.Grid([[32, 256], [8, 64], [1000, 100000]],
                              [[[1, 2], [3, 4]], [[5, 6], [7, 8]]])
