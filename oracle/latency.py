@@ -109,7 +109,7 @@ def _cdiv(a, b):
     return -(-a // b)
 
 
-def prefill_kernels(s: Shape, hw: Profile, reqs, with_head: bool):
+def prefill_kernels(s: Shape, hw: Profile, reqs, with_head: bool, whole_tiles: bool | None = None):
     """One layer of prefill for requests [(sl_i, p_i)]: (name, flop, bytes, workgroups or 0).
     The head entry (final norm + LM head for one row per request) is appended when asked."""
     h, d = s.hidden, s.head_dim
@@ -118,17 +118,22 @@ def prefill_kernels(s: Shape, hw: Profile, reqs, with_head: bool):
     t = sum(sl for sl, _ in reqs)
     tm, tn = hw.tile_m, hw.tile_n
     rows = _cdiv(t, tm)
+    # thread blocks compute whole tiles: with the tile-level (wave quantisation) model on, the GEMM
+    # flop count pads the rows to the tile height; whole_tiles=False asks for the exact counts
+    if whole_tiles is None:
+        whole_tiles = bool(hw.use_waveq)
+    tp = rows * tm if whole_tiles else t
     att_flop = sum(4 * qd * (sl * p + sl * (sl + 1) // 2) for sl, p in reqs)
     att_mem = sum(2 * (2 * sl * qd + 2 * (p + sl) * kvd) for sl, p in reqs)
     att_g = sum(_cdiv(sl, hw.tile_q) * s.n_q_heads for sl, _ in reqs)
     ks = [("norm1", 4 * t * h, 4 * t * h, 0),
-          ("qkv", 2 * t * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * _cdiv(qkvn, tn)),
+          ("qkv", 2 * tp * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * _cdiv(qkvn, tn)),
           ("rope", 4 * t * qkvn, 4 * t * qkvn, 0),
           ("attn", att_flop, att_mem, att_g),
-          ("o", 2 * t * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * _cdiv(h, tn)),
+          ("o", 2 * tp * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * _cdiv(h, tn)),
           ("norm2", 4 * t * h, 4 * t * h, 0),
-          ("gateup", 4 * t * h * s.mlp, 2 * (2 * h * s.mlp + t * h + t * s.mlp), rows * _cdiv(2 * s.mlp, tn)),
-          ("down", 2 * t * s.mlp * h, 2 * (s.mlp * h + t * s.mlp + 2 * t * h), rows * _cdiv(h, tn))]
+          ("gateup", 4 * tp * h * s.mlp, 2 * (2 * h * s.mlp + t * h + t * s.mlp), rows * _cdiv(2 * s.mlp, tn)),
+          ("down", 2 * tp * s.mlp * h, 2 * (s.mlp * h + t * s.mlp + 2 * t * h), rows * _cdiv(h, tn))]
     head = []
     if with_head:
         b = len(reqs)

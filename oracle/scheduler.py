@@ -110,7 +110,7 @@ class Replay:
         return L.predict_decode_ns(self.s, self.hw, [self.reqs[i].in_len + self.reqs[i].n_dec for i in ids], dm, co)
 
     def intensity_below_ridge(self, ids, pm):
-        ks, _ = L.prefill_kernels(self.s, self.hw, [(self.reqs[i].in_len, 0) for i in ids], False)
+        ks, _ = L.prefill_kernels(self.s, self.hw, [(self.reqs[i].in_len, 0) for i in ids], False, whole_tiles=False)
         flop, mem = sum(k[1] for k in ks), sum(k[2] for k in ks)
         hw = self.hw
         return flop * hw.d_peak * min(pm, hw.n_d) * hw.n_cu < mem * hw.c_peak * pm * hw.n_d

@@ -63,15 +63,16 @@ static void prefill_kernels(const sts_model_desc& s, const Profile& hw, const in
     att_g += cdiv(l, hw.tile_q) * s.n_q_heads;
   }
   const int64_t rows = cdiv(t, hw.tile_m), tn = hw.tile_n;
+  const int64_t tp = hw.use_waveq ? rows * hw.tile_m : t;      // thread blocks compute whole tiles
   ks->clear();
   ks->push_back({4 * t * h, 4 * t * h, 0});                                                             // norm1
-  ks->push_back({2 * t * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * cdiv(qkvn, tn), true});    // qkv
+  ks->push_back({2 * tp * h * qkvn, 2 * (h * qkvn + t * h + t * qkvn), rows * cdiv(qkvn, tn), true});    // qkv
   ks->push_back({4 * t * qkvn, 4 * t * qkvn, 0});                                                       // rope
   ks->push_back({att_flop, att_mem, att_g});                                                            // attn
-  ks->push_back({2 * t * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * cdiv(h, tn), true});         // o
+  ks->push_back({2 * tp * qd * h, 2 * (qd * h + t * qd + 2 * t * h), rows * cdiv(h, tn), true});         // o
   ks->push_back({4 * t * h, 4 * t * h, 0});                                                             // norm2
-  ks->push_back({4 * t * h * mlp, 2 * (2 * h * mlp + t * h + t * mlp), rows * cdiv(2 * mlp, tn), true}); // gate/up
-  ks->push_back({2 * t * mlp * h, 2 * (mlp * h + t * mlp + 2 * t * h), rows * cdiv(h, tn), true});      // down
+  ks->push_back({4 * tp * h * mlp, 2 * (2 * h * mlp + t * h + t * mlp), rows * cdiv(2 * mlp, tn), true}); // gate/up
+  ks->push_back({2 * tp * mlp * h, 2 * (mlp * h + t * mlp + 2 * t * h), rows * cdiv(h, tn), true});      // down
   const int64_t b = n, v = s.vocab;
   *head = Kern{2 * b * h * v, 2 * (h * v + b * h + b * v), 0, false};
 }

@@ -147,7 +147,7 @@ class Profiler:
         text = profile_text(self.hw, {k: v for k, v in self.grids.items() if k == "bw"})
         return sts.Profile(text=text).query(self.desc, es, roofline=True)
 
-    def calibrate_prefill(self, pms=(32, 64, 128, 192, 256), tokens=(256, 1024, 2048, 8192), log=print):
+    def calibrate_prefill(self, pms=(32, 64, 96, 128, 160, 192, 224, 256), tokens=(256, 512, 1024, 2048, 4096, 8192), log=print):
         vals = []
         for pm in pms:
             row = []
@@ -191,7 +191,7 @@ def evaluate(prof_text, profiler: Profiler, log=print):
     p = sts.Profile(text=prof_text)
     desc = profiler.desc
     errs_p, errs_d = [], []
-    for pm, t in ((96, 512), (160, 1536), (224, 3000), (256, 6000), (64, 4096), (128, 700)):
+    for pm, t in ((96, 700), (160, 1536), (224, 3000), (256, 6000), (64, 5000), (128, 384), (200, 1300)):
         ns, layers = profiler.prefill_ns(pm, t)
         es = dict(prefill_len=[t], prefill_ctx=[0], prefill_cus=pm, decode_cus=0, layer_begin=0, n_layers_step=layers)
         pred = p.query(desc, es)[0]
