@@ -268,6 +268,22 @@ int pick_splits(int cfg, int m, int n, int k, int cus) {
   return std::max(1, std::min(s, 8));
 }
 
+int64_t now_ns();
+
+// Wait for a stream with a short busy poll before blocking: a layer slice or a decode step lasts
+// around a millisecond, and the wake-up latency of a blocking wait would be a visible share of it.
+hipError_t wait_stream(hipStream_t st) {
+  const int64_t t0 = now_ns();
+  for (;;) {
+    const hipError_t e = hipStreamQuery(st);
+    if (e != hipErrorNotReady) return e;                     // done, or a real error
+    if (now_ns() - t0 > 20000000) return hipStreamSynchronize(st);
+#if defined(__x86_64__)
+    __builtin_ia32_pause();
+#endif
+  }
+}
+
 bool valid_seq(sts_ctx* c, int s) { return s >= 0 && s < (int)c->seqs.size() && c->seqs[s].used; }
 
 // Make `seq` own enough pages for n_tokens; caller holds no lock.
@@ -374,7 +390,7 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
 
 int prefill_finish(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, int le, float* logits) {
   Phase& ph = c->ph[0];
-  HIPCK(hipStreamSynchronize(ph.stream));
+  HIPCK(wait_stream(ph.stream));
   STSCK(k_collect(c, ph));
   c->pf_next_layer = le;
   if (le == c->d.n_layers) {
@@ -472,7 +488,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
 
 int decode_finish(sts_ctx* c, const int32_t* seqs, int n, float* logits, int32_t* next) {
   Phase& ph = c->ph[1];
-  HIPCK(hipStreamSynchronize(ph.stream));
+  HIPCK(wait_stream(ph.stream));
   STSCK(k_collect(c, ph));
   for (int i = 0; i < n; i++) c->seqs[seqs[i]].len += 1;
   if (logits) std::memcpy(logits, ph.h_logits, (size_t)n * c->d.vocab * sizeof(float));
@@ -861,12 +877,17 @@ extern "C" int sts_step_concurrent(sts_ctx* c, int32_t n_pseqs, const int32_t* p
   const int64_t t0 = now_ns();
   c->ph[0].ran = c->ph[1].ran = false;
   if (n_pseqs > 0) STSCK(prefill_enqueue(c, n_pseqs, pseqs, plens, ptokens, lb, le, plogits != nullptr));
+  const int64_t t1 = now_ns();
   int rc = STS_OK;
   if (n_decode > 0) rc = decode_enqueue(c, dseqs, dtokens, n_decode, dlogits != nullptr, dnext != nullptr);
+  const int64_t t2 = now_ns();
   if (n_pseqs > 0) { int r2 = prefill_finish(c, n_pseqs, pseqs, plens, le, plogits); if (rc == STS_OK) rc = r2; else return rc; }
   STSCK(rc);
+  const int64_t t3 = now_ns();
   if (n_decode > 0) STSCK(decode_finish(c, dseqs, n_decode, dlogits, dnext));
   c->last_wall_ns = now_ns() - t0;
+  if (getenv("STS_PROF")) fprintf(stderr, "[sts prof] prefill_enqueue %lld decode_enqueue %lld prefill_wait %lld decode_finish %lld us\n",
+                                  (long long)(t1 - t0) / 1000, (long long)(t2 - t1) / 1000, (long long)(t3 - t2) / 1000, (long long)(now_ns() - t3) / 1000);
   return STS_OK;
 }
 extern "C" int sts_last_timing(sts_ctx* c, int64_t* prefill_ns, int64_t* decode_ns, int64_t* wall_ns) {
