@@ -16,6 +16,9 @@
 
 namespace sts {
 
+#ifndef GEMM_64x128_STAGES
+#define GEMM_64x128_STAGES 3
+#endif
 constexpr int GEMM_DL_LDS_BASE = 1024;   // the direct-to-LDS arena stays clear of LDS address 0
 
 struct GemmArgs {
@@ -245,9 +248,13 @@ __device__ __forceinline__ void load_to_lds16(const void* gsrc, void* lds_dst) {
                                    (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 #endif
 }
-__device__ __forceinline__ void wait_vmem_all() {
+// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in
+// order); the other counters are left alone.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
 #if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0); the other counters are left alone
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 #endif
 }
 
@@ -263,9 +270,10 @@ __device__ __forceinline__ void wait_vmem_all() {
 // already in registers); the loads of the tile after next go out right behind the barrier, a
 // whole iteration ahead of their use; step 3 runs while the first operands of the next tile
 // are read. The LDS arena starts 1 KB above address 0.
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
 __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   constexpr int BK = 64, NT = WGM * WGN * 64;
+  static_assert(NS >= 2 && (NS - 2) * (BM + BN) * 8 / NT < 64, "stages: at least two, outstanding loads within vmcnt's range");
   constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
   constexpr int ROWB = BK * 2;                               // bytes per tile row
   constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;      // 16-byte chunks per thread
@@ -324,23 +332,28 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   constexpr int MPR = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;       // MFMAs per LDS read
   constexpr int REST = TM * TN > MPR * (TM + TN) ? TM * TN - MPR * (TM + TN) : 0;
 
+  // NS LDS stages: tile t lives in stage t % NS; while tile t is consumed, tiles t+1 .. t+NS-1
+  // are landing or on their way.
+  constexpr int LOADS = A_CH + B_CH;                         // loads per thread and tile
   const int nk = (kend - kbeg) / BK;
-  issue(0, kbeg);
-  wait_vmem_all();
+#pragma unroll
+  for (int t = 0; t < NS; t++)
+    if (t < nk) issue(t, kbeg + t * BK);
+  if (nk >= NS) wait_vmem<(NS - 1) * LOADS>(); else wait_vmem<0>();
   __syncthreads();
-  if (nk > 1) issue(1, kbeg + BK);
   bf16x8 af[2][TM], bfr[2][TN];
 #pragma unroll
   for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(arena + a_row + i * 32 * ROWB + koff[0]);
 #pragma unroll
   for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(arena + b_row + j * 32 * ROWB + koff[0]);
 
-  int cur = 0;
+  int cur = 0;                                               // stage of tile t
   for (int t = 0; t < nk; t++) {
+    const int nxt = cur + 1 == NS ? 0 : cur + 1;
     const unsigned char* Ac = arena + cur * STAGE + a_row;
     const unsigned char* Bc = arena + cur * STAGE + b_row;
-    const unsigned char* An = arena + (cur ^ 1) * STAGE + a_row;
-    const unsigned char* Bn = arena + (cur ^ 1) * STAGE + b_row;
+    const unsigned char* An = arena + nxt * STAGE + a_row;
+    const unsigned char* Bn = arena + nxt * STAGE + b_row;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < 3; kk++) {
@@ -364,9 +377,10 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
       if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    wait_vmem_all();
+    // tile t+1 must have landed; the NS-2 tiles issued after it may still be in flight
+    if (t + NS - 1 < nk) wait_vmem<(NS - 2) * LOADS>(); else wait_vmem<0>();
     __syncthreads();
-    if (t + 2 < nk) issue(cur, kbeg + (t + 2) * BK);
+    if (t + NS < nk) issue(cur, kbeg + (t + NS) * BK);
     __builtin_amdgcn_sched_barrier(0);
     if (t + 1 < nk) {
 #pragma unroll
@@ -386,7 +400,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
     }
     if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
     __builtin_amdgcn_sched_barrier(0);
-    cur ^= 1;
+    cur = nxt;
   }
   store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
@@ -450,13 +464,14 @@ void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int*
   *n_full = full; *f = best;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int EPI, bool DL = false>
+// DL = 0: register-staged loop; DL = n >= 2: direct-to-LDS loop with n stages.
+template <int BM, int BN, int BK, int WGM, int WGN, int EPI, int DL = 0>
 static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTail* tail) {
   constexpr int NT = WGM * WGN * 64;
-  static_assert(!DL || BK == 64, "the direct-to-LDS loop is written for BK = 64");
-  constexpr size_t lds = DL ? GEMM_DL_LDS_BASE + 2 * (size_t)(BM + BN) * BK * sizeof(bf16) : 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
+  static_assert(DL == 0 || BK == 64, "the direct-to-LDS loop is written for BK = 64");
+  constexpr size_t lds = DL ? GEMM_DL_LDS_BASE + DL * (size_t)(BM + BN) * BK * sizeof(bf16) : 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
   void (*kern)(GemmArgs);
-  if constexpr (DL) kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI>;
+  if constexpr (DL != 0) kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL>;
   else kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -493,13 +508,13 @@ template <int EPI>
 static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int splits, const GemmTail* tail) {
   switch (cfg) {
     case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI, true>(s, g, splits, tail);
+    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI, 2>(s, g, splits, tail);
     case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI>(s, g, splits, tail);
     case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI>(s, g, splits, tail);
     case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits, tail);
-    case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI>(s, g, splits, tail);
+    case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI, GEMM_64x128_STAGES>(s, g, splits, tail);
     case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI, true>(s, g, splits, tail);
+    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI, 2>(s, g, splits, tail);
     default: return hipErrorInvalidValue;
   }
 }
@@ -541,8 +556,8 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
     case EPI_SWIGLU_BF16:
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
         case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
-        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16, true>(s, g, 1, tail);
-        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16, true>(s, g, 1, tail);
+        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
+        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
         case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
         case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
         case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
