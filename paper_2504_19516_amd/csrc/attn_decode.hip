@@ -7,7 +7,7 @@
 // chunks' (max, sum, weighted V) partials.
 //
 // Inside a workgroup (4 waves):
-//   1. scores: waves take pages in turn, two in flight each; a lane reads a contiguous 1/4 of one token's K row
+//   1. scores: waves take pages in turn, two at a time with the next two already in flight; a lane reads a contiguous 1/4 of one token's K row
 //      (64 bytes for d = 128), so a wave reads one 4 KiB page chunk fully coalesced, and
 //      accumulates q.k with v_dot2_f32_bf16 (no conversions); 4-lane reduction.
 //   2. softmax over the chunk in LDS (exact within the chunk; chunks merge by rescaling).
@@ -48,9 +48,39 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   const int* bt = block_tables + sq.bt_off;
   const size_t head_elems = geo.head_elems();
 
+  // Page ids of the chunk, one per lane (a chunk has at most 32 pages); the loops below fetch
+  // them with a cross-lane read, so no K or V load waits on a block-table load. Indices past the
+  // chunk are clamped to its last page: prefetches beyond the end re-read it and are not used.
+  const int npg = pg1 - pg0;
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const int my_page = bt[pg0 + min(lane, npg - 1)];
+  auto page_base = [&](int i) -> const bf16* {
+    const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(min(i, npg - 1)));
+    return pool + ((size_t)page * geo.n_kv + kvh) * head_elems;
+  };
+  // A wave takes the chunk's pages wv, wv+4 (one pair), wv+8, wv+12 (next pair), ...; the next
+  // pair is in flight while the current one is consumed.
+  const int tok = lane >> 2, seg = lane & 3;
+  auto load_k = [&](int i, u32x4 (&kr)[2][SEGW / 4]) {
+    const u32x4* p0 = reinterpret_cast<const u32x4*>(page_base(i) + (size_t)tok * D + seg * SEG);
+    const u32x4* p1 = reinterpret_cast<const u32x4*>(page_base(i + 4) + (size_t)tok * D + seg * SEG);
+#pragma unroll
+    for (int x = 0; x < SEGW / 4; x++) { kr[0][x] = p0[x]; kr[1][x] = p1[x]; }
+  };
+  auto load_v = [&](int i, u32x4 (&vr)[2][ROWS][2]) {
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+      const bf16* vbase = page_base(i + 4 * u) + (size_t)16 * D;
+#pragma unroll
+      for (int r = 0; r < ROWS; r++) {
+        const u32x4* vp = reinterpret_cast<const u32x4*>(vbase + (size_t)(lane + 64 * r) * 16);
+        vr[u][r][0] = vp[0]; vr[u][r][1] = vp[1];
+      }
+    }
+  };
+
   // ---- 1. scores
   {
-    const int tok = lane >> 2, seg = lane & 3;
     unsigned qr[G][SEGW];
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -58,39 +88,44 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
 #pragma unroll
       for (int i = 0; i < SEGW; i++) qr[g][i] = qp[i];
     }
-    for (int pg = pg0 + wave; pg < pg1; pg += 8) {
-      const bool two = pg + 4 < pg1;                    // wave-uniform
-      const uint4* kp0 = reinterpret_cast<const uint4*>(pool + ((size_t)bt[pg] * geo.n_kv + kvh) * head_elems + (size_t)tok * D + seg * SEG);
-      const uint4* kp1 = reinterpret_cast<const uint4*>(pool + ((size_t)bt[two ? pg + 4 : pg] * geo.n_kv + kvh) * head_elems + (size_t)tok * D + seg * SEG);
-      uint4 kr[2][SEGW / 4];
-#pragma unroll
-      for (int i = 0; i < SEGW / 4; i++) { kr[0][i] = kp0[i]; kr[1][i] = kp1[i]; }
+    auto score = [&](int i, const u32x4 (&kr)[2][SEGW / 4]) {
 #pragma unroll
       for (int u = 0; u < 2; u++) {
-        if (u == 1 && !two) break;
+        if (i + 4 * u >= npg) break;                    // wave-uniform
         float acc[G];
 #pragma unroll
         for (int g = 0; g < G; g++) {
           float a = 0.f;
 #pragma unroll
-          for (int i = 0; i < SEGW / 4; i++) {
-            a = dot2(kr[u][i].x, qr[g][4 * i + 0], a);
-            a = dot2(kr[u][i].y, qr[g][4 * i + 1], a);
-            a = dot2(kr[u][i].z, qr[g][4 * i + 2], a);
-            a = dot2(kr[u][i].w, qr[g][4 * i + 3], a);
+          for (int x = 0; x < SEGW / 4; x++) {
+            a = dot2(kr[u][x][0], qr[g][4 * x + 0], a);
+            a = dot2(kr[u][x][1], qr[g][4 * x + 1], a);
+            a = dot2(kr[u][x][2], qr[g][4 * x + 2], a);
+            a = dot2(kr[u][x][3], qr[g][4 * x + 3], a);
           }
           a += __shfl_xor(a, 1, 64);
           a += __shfl_xor(a, 2, 64);
           acc[g] = a;
         }
         if (seg == 0) {
-          const int t = (pg + 4 * u - pg0) * 16 + tok;
+          const int t = (i + 4 * u) * 16 + tok;
 #pragma unroll
           for (int g = 0; g < G; g++) if (t < nt) S[g][t] = acc[g] * scale_log2e;
         }
       }
+    };
+    u32x4 ka[2][SEGW / 4], kb[2][SEGW / 4];
+    load_k(wv, ka);
+    for (int i = wv; i < npg; i += 16) {
+      load_k(i + 8, kb);
+      score(i, ka);
+      load_k(i + 16, ka);
+      if (i + 8 < npg) score(i + 8, kb);
     }
   }
+  // first V^T pages: in flight during the softmax
+  u32x4 va[2][ROWS][2], vb[2][ROWS][2];
+  load_v(wv, va);
   __syncthreads();
 
   // ---- 2. softmax statistics and probabilities (wave w takes heads w, w+4, ...)
@@ -117,37 +152,32 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   for (int g = 0; g < G; g++)
 #pragma unroll
     for (int r = 0; r < ROWS; r++) acc[g][r] = 0.f;
-  for (int pg = pg0 + wave; pg < pg1; pg += 8) {
-    const bool two = pg + 4 < pg1;
-    uint4 vr[2][ROWS][2];
+  auto pv = [&](int i, const u32x4 (&vr)[2][ROWS][2]) {
 #pragma unroll
     for (int u = 0; u < 2; u++) {
-      const bf16* vbase = pool + ((size_t)bt[(u == 1 && two) ? pg + 4 : pg] * geo.n_kv + kvh) * head_elems + (size_t)16 * D;
-#pragma unroll
-      for (int r = 0; r < ROWS; r++) {
-        const uint4* vp = reinterpret_cast<const uint4*>(vbase + (size_t)(lane + 64 * r) * 16);
-        vr[u][r][0] = vp[0]; vr[u][r][1] = vp[1];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 2; u++) {
-      if (u == 1 && !two) break;
-      const int tb = (pg + 4 * u - pg0) * 16;
+      if (i + 4 * u >= npg) break;                      // wave-uniform
+      const int tb = (i + 4 * u) * 16;
 #pragma unroll
       for (int g = 0; g < G; g++) {
-        const uint4 p0 = *reinterpret_cast<const uint4*>(&P[g][tb]);
-        const uint4 p1 = *reinterpret_cast<const uint4*>(&P[g][tb + 8]);
+        const u32x4 p0 = *reinterpret_cast<const u32x4*>(&P[g][tb]);
+        const u32x4 p1 = *reinterpret_cast<const u32x4*>(&P[g][tb + 8]);
 #pragma unroll
         for (int r = 0; r < ROWS; r++) {
           float a = acc[g][r];
-          a = dot2(vr[u][r][0].x, p0.x, a); a = dot2(vr[u][r][0].y, p0.y, a);
-          a = dot2(vr[u][r][0].z, p0.z, a); a = dot2(vr[u][r][0].w, p0.w, a);
-          a = dot2(vr[u][r][1].x, p1.x, a); a = dot2(vr[u][r][1].y, p1.y, a);
-          a = dot2(vr[u][r][1].z, p1.z, a); a = dot2(vr[u][r][1].w, p1.w, a);
+          a = dot2(vr[u][r][0][0], p0[0], a); a = dot2(vr[u][r][0][1], p0[1], a);
+          a = dot2(vr[u][r][0][2], p0[2], a); a = dot2(vr[u][r][0][3], p0[3], a);
+          a = dot2(vr[u][r][1][0], p1[0], a); a = dot2(vr[u][r][1][1], p1[1], a);
+          a = dot2(vr[u][r][1][2], p1[2], a); a = dot2(vr[u][r][1][3], p1[3], a);
           acc[g][r] = a;
         }
       }
     }
+  };
+  for (int i = wv; i < npg; i += 16) {
+    load_v(i + 8, vb);
+    pv(i, va);
+    load_v(i + 16, va);
+    if (i + 8 < npg) pv(i + 8, vb);
   }
 #pragma unroll
   for (int g = 0; g < G; g++)
