@@ -345,13 +345,16 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
   meta_take(ph, &ph.h_rows, &ph.d_rows, n_seqs);
   meta_take(ph, &ph.h_items, &ph.d_items, rows / bq + n_seqs);
   meta_take(ph, &ph.h_tokens, &ph.d_tokens, lb == 0 ? rows : 0);
-  meta_take(ph, &ph.h_bt, &ph.d_bt, (size_t)n_seqs * mp);
+  size_t bt_entries = 0;                                     // block tables are packed back to back
+  for (int i = 0; i < n_seqs; i++) bt_entries += c->seqs[seqs[i]].pages.size();
+  meta_take(ph, &ph.h_bt, &ph.d_bt, bt_entries);
   if (ph.meta_used > ph.meta_bytes) return STS_EINVAL;
-  int r0 = 0, n_items = 0;
+  int r0 = 0, n_items = 0, bt_off = 0;
   for (int i = 0; i < n_seqs; i++) {
     const Seq& s = c->seqs[seqs[i]];
-    ph.h_pseq[i] = PrefillSeq{r0, lens[i], s.len, i * mp, (int)s.pages.size()};
-    std::memcpy(ph.h_bt + (size_t)i * mp, s.pages.data(), s.pages.size() * sizeof(int));
+    ph.h_pseq[i] = PrefillSeq{r0, lens[i], s.len, bt_off, (int)s.pages.size()};
+    std::memcpy(ph.h_bt + bt_off, s.pages.data(), s.pages.size() * sizeof(int));
+    bt_off += (int)s.pages.size();
     for (int q0 = 0; q0 < lens[i]; q0 += bq) ph.h_items[n_items++] = AttnItem{i, q0};
     ph.h_rows[i] = r0 + lens[i] - 1;
     r0 += lens[i];
@@ -422,14 +425,17 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   ph.meta_used = 0;
   meta_take(ph, &ph.h_dseq, &ph.d_dseq, n);
   meta_take(ph, &ph.h_tokens, &ph.d_tokens, n);
-  meta_take(ph, &ph.h_bt, &ph.d_bt, (size_t)n * mp);
+  size_t bt_entries = 0;                                     // block tables are packed back to back
+  for (int i = 0; i < n; i++) bt_entries += (c->seqs[seqs[i]].len + 1 + pt - 1) / pt;
+  meta_take(ph, &ph.h_bt, &ph.d_bt, bt_entries);
   if (ph.meta_used > ph.meta_bytes) return STS_EINVAL;
-  int max_pages = 1;
+  int max_pages = 1, bt_off = 0;
   for (int i = 0; i < n; i++) {
     const Seq& s = c->seqs[seqs[i]];
     const int np = (s.len + 1 + pt - 1) / pt;
-    ph.h_dseq[i] = DecodeSeq{s.len, i * mp, np};
-    std::memcpy(ph.h_bt + (size_t)i * mp, s.pages.data(), np * sizeof(int));
+    ph.h_dseq[i] = DecodeSeq{s.len, bt_off, np};
+    std::memcpy(ph.h_bt + bt_off, s.pages.data(), np * sizeof(int));
+    bt_off += np;
     max_pages = std::max(max_pages, np);
     ph.h_tokens[i] = in_tokens[i];
   }

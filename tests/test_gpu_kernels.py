@@ -114,7 +114,9 @@ def test_gemm_rejects_bad_shapes(sts):
 
 
 @pytest.mark.parametrize("t,prior,nq,nkv,d", [(128, 0, 4, 4, 64), (300, 0, 8, 2, 128), (70, 45, 4, 1, 128), (1, 0, 4, 4, 64),
-                                              (200, 330, 4, 4, 64), (129, 16, 8, 2, 128)])
+                                              (200, 330, 4, 4, 64), (129, 16, 8, 2, 128),
+                                              (130, 16500, 4, 1, 128),      # context beyond one block-table window (16384 tokens)
+                                              (40, 33000, 4, 1, 64)])       # ... beyond two
 def test_prefill_attention(sts, t, prior, nq, nkv, d):
     q = synth.normal_bf16(11, (t, nq, d))
     k = synth.normal_bf16(12, (prior + t, nkv, d))
