@@ -33,8 +33,15 @@ class Req:
 
 
 class LiveServer:
-    def __init__(self, desc, profile_text, cfg, kv_pool_pages, max_batch_tokens=16384, max_decode_batch=256, max_ctx=10240):
+    def __init__(self, desc, profile_text, cfg, kv_pool_pages, max_batch_tokens=16384, max_decode_batch=256, max_ctx=10240,
+                 sched_slo_ns=None):
+        """cfg carries the SLOs requests are judged by; sched_slo_ns = (ttft, tpot) optionally gives the
+        scheduler tighter targets than those (headroom for estimator error and for the running-mean TPOT,
+        which Algorithm 1 otherwise steers right onto the limit)."""
         self.desc, self.cfg = desc, dict(cfg)
+        self.slo = (cfg["ttft_slo_ns"], cfg["tpot_slo_ns"])
+        if sched_slo_ns:
+            self.cfg.update(ttft_slo_ns=int(sched_slo_ns[0]), tpot_slo_ns=int(sched_slo_ns[1]))
         self.cfg.update(max_batch_tokens=max_batch_tokens, max_decode_batch=max_decode_batch, kv_pool_pages=kv_pool_pages)
         self.profile = sts.Profile(text=profile_text)
         self.eng = sts.Engine(desc, weight_seed=1234, init_weights=True, kv_pool_pages=kv_pool_pages,
@@ -158,7 +165,7 @@ class LiveServer:
                 if log_every and len(timeline) % log_every == 0:
                     timeline.append((now, "decode", eng.get_partition()[1], len(decode_batch)))
         eng.set_partition(n, n)
-        return self.stats(reqs, rejected, cfg), decisions, timeline
+        return self.stats(reqs, rejected, dict(cfg, ttft_slo_ns=self.slo[0], tpot_slo_ns=self.slo[1])), decisions, timeline
 
     @staticmethod
     def stats(reqs, rejected, cfg):
@@ -196,6 +203,8 @@ def main():
     ap.add_argument("--profile", required=True)
     ap.add_argument("--ttft-ms", type=float, default=1000.0)
     ap.add_argument("--tpot-ms", type=float, default=50.0)
+    ap.add_argument("--sched-ttft-ms", type=float, default=0.0, help="TTFT target given to the scheduler (default: the SLO)")
+    ap.add_argument("--sched-tpot-ms", type=float, default=0.0, help="TPOT target given to the scheduler (default: the SLO)")
     ap.add_argument("--layers-per-step", type=int, default=4)
     ap.add_argument("--pool-pages", type=int, default=40000)
     ap.add_argument("--max-ctx", type=int, default=10240)
@@ -204,8 +213,9 @@ def main():
     make = {"8b": synth.llama8b_model, "70b": synth.llama70b_model}.get(args.model)
     desc = (make(args.layers) if args.layers else make()) if make else synth.tiny_model()
     cfg = dict(ttft_slo_ns=int(args.ttft_ms * 1e6), tpot_slo_ns=int(args.tpot_ms * 1e6), layers_per_step=args.layers_per_step)
+    sched = (int((args.sched_ttft_ms or args.ttft_ms) * 1e6), int((args.sched_tpot_ms or args.tpot_ms) * 1e6))
     srv = LiveServer(desc, open(args.profile).read(), cfg, args.pool_pages, max_ctx=args.max_ctx,
-                     max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0))
+                     max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0), sched_slo_ns=sched)
     ind, outd = WORKLOADS[args.workload]
     results = []
     for rate in [float(x) for x in args.rates.split(",")]:
