@@ -227,7 +227,14 @@ typedef struct {
   int32_t max_decode_batch;
   int32_t kv_pool_pages;
   int32_t mode;                       /* 0 concurrent + Algorithm 1; 1 time-multiplexed (full GPU, serialised);
-                                         2 concurrent, fixed split (fixed_prefill_cus / rest) */
+                                         2 concurrent, fixed disjoint split (fixed_prefill_cus / rest);
+                                         ablations of Section 4.5: 3 Naive (both phases on every CU, arrival
+                                         order, decode never delayed), 4 w/Partition (split search only:
+                                         arrival order, decode never suspended), 5 w/Scheduler (reordering
+                                         and delayed decode only, both phases on every CU); 6 Section 4.4:
+                                         prefill on fixed_prefill_cus, decode on every CU. Modes 3, 5, 6
+                                         overlap the two CU sets; the replay's simulated durations ignore
+                                         that contention, so their timing is meaningful on the GPU only */
   int32_t fixed_prefill_cus;
 } sts_sched_config;
 typedef struct {                      /* one scheduling cycle of the prefill scheduler */

@@ -50,7 +50,12 @@ class Config:
     max_batch_tokens: int
     max_decode_batch: int
     kv_pool_pages: int
-    mode: int = 0                 # 0 Algorithm 1; 1 time-multiplexed; 2 fixed split
+    # 0 Algorithm 1; 1 time-multiplexed; 2 fixed disjoint split; the paper's ablations (Section 4.5):
+    # 3 Naive (both phases on every CU, arrival order, no delayed decode), 4 w/Partition (the split
+    # search only: arrival order, decode never suspended), 5 w/Scheduler (reordering and delayed
+    # decode only: both phases on every CU); 6 the sensitivity study's setting (Section 4.4): prefill
+    # on a fixed CU count, decode on every CU
+    mode: int = 0
     fixed_prefill_cus: int = 0
 
 
@@ -135,8 +140,11 @@ class Replay:
             return out
 
         t_fcfs, t_sjf = ttfts(fcfs), ttfts(sjf)
-        hurt = [i for i in fcfs if t_sjf[i] > cfg.ttft_slo_ns >= t_fcfs[i]]
-        self.Q = hurt + [i for i in sjf if i not in hurt]
+        if cfg.mode in (3, 4):                   # ablations without the scheduler keep arrival order
+            self.Q = fcfs
+        else:
+            hurt = [i for i in fcfs if t_sjf[i] > cfg.ttft_slo_ns >= t_fcfs[i]]
+            self.Q = hurt + [i for i in sjf if i not in hurt]
         ttft = ttfts(self.Q)
         for i in self.P:
             ttft[i] = now - reqs[i].arrival + t_p
@@ -184,10 +192,18 @@ class Replay:
 
         grid = list(range(0, self.n, self.g))          # candidate decode CUs
         branch = 0
-        if cfg.mode == 1:
+        if cfg.mode in (1, 3):
             pm, dm = self.n, self.n
         elif cfg.mode == 2:
             pm, dm = cfg.fixed_prefill_cus, self.n - cfg.fixed_prefill_cus
+        elif cfg.mode == 6:
+            pm, dm = cfg.fixed_prefill_cus, self.n
+        elif cfg.mode == 5:
+            pm = self.n
+            if dec and not satisfy and tpot90(0) <= cfg.tpot_slo_ns:
+                branch, dm = 2, 0
+            else:
+                dm = self.n
         else:
             cur_dm = self.dm if (self.pm > 0 and self.dm < self.n) else max(self.g, (self.n // 2) // self.g * self.g)
             tp_now = tpot90(cur_dm)
@@ -203,7 +219,7 @@ class Replay:
 
             def smallest_dm_meeting_tpot():
                 # decode is suspended (dm = 0) only when TTFT is at risk, or when nothing decodes
-                for dm_c in (grid if (not dec or not satisfy) else grid[1:]):
+                for dm_c in (grid if (not dec or (not satisfy and cfg.mode != 4)) else grid[1:]):
                     if tpot90(dm_c) <= cfg.tpot_slo_ns:
                         return dm_c
                 return None

@@ -96,8 +96,13 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
   ttfts(fcfs, t_fcfs); ttfts(sjf, t_sjf);
   std::vector<char> is_hurt(nq, 0);
   std::vector<int> order;
-  for (int i : fcfs) if (t_sjf[i] > cfg.ttft_slo_ns && cfg.ttft_slo_ns >= t_fcfs[i]) { is_hurt[i] = 1; order.push_back(i); }
-  for (int i : sjf) if (!is_hurt[i]) order.push_back(i);
+  const bool reorder = cfg.mode != 3 && cfg.mode != 4;       // the ablations without the scheduler keep arrival order
+  if (reorder) {
+    for (int i : fcfs) if (t_sjf[i] > cfg.ttft_slo_ns && cfg.ttft_slo_ns >= t_fcfs[i]) { is_hurt[i] = 1; order.push_back(i); }
+    for (int i : sjf) if (!is_hurt[i]) order.push_back(i);
+  } else {
+    order = fcfs;
+  }
   ttfts(order, ttft);
 
   bool satisfy;
@@ -150,8 +155,16 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
   for (int x = 0; x < n; x += g) grid.push_back(x);
 
   int branch = 0, pm_new, dm_new;
-  if (cfg.mode == 1) { pm_new = n; dm_new = n; }
+  if (cfg.mode == 1 || cfg.mode == 3) { pm_new = n; dm_new = n; }
   else if (cfg.mode == 2) { pm_new = cfg.fixed_prefill_cus; dm_new = n - cfg.fixed_prefill_cus; }
+  else if (cfg.mode == 6) { pm_new = cfg.fixed_prefill_cus; dm_new = n; }
+  else if (cfg.mode == 5) {
+    // scheduler without partitioning: both phases see every CU; decode is delayed for this slice
+    // when TTFT is at risk and the decoding requests' TPOT can absorb it
+    pm_new = n;
+    if (!dec.empty() && !satisfy && tpot90(0) <= cfg.tpot_slo_ns) { branch = 2; dm_new = 0; }
+    else dm_new = n;
+  }
   else {
     const int cur_dm = (pm > 0 && dm < n) ? dm : half;
     const int64_t tp_now = tpot90(cur_dm);
@@ -166,7 +179,7 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
     };
     auto smallest_dm_meeting_tpot = [&]() -> int {
       // decode is suspended (0 CUs) only when TTFT is at risk, or when nothing decodes
-      for (size_t k = (dec.empty() || !satisfy) ? 0 : 1; k < grid.size(); k++)
+      for (size_t k = (dec.empty() || (!satisfy && cfg.mode != 4)) ? 0 : 1; k < grid.size(); k++)
         if (tpot90(grid[k]) <= cfg.tpot_slo_ns) return grid[k];
       return -1;
     };
@@ -308,9 +321,9 @@ struct Replay {
 
 bool config_ok(const Profile& hw, const sts_sched_config* cfg) {
   if (cfg->layers_per_step < 1 || cfg->max_batch_tokens < 1 || cfg->max_decode_batch < 1 || cfg->kv_pool_pages < 1 ||
-      cfg->mode < 0 || cfg->mode > 2 || cfg->ttft_slo_ns < 1 || cfg->tpot_slo_ns < 1) return false;
+      cfg->mode < 0 || cfg->mode > 6 || cfg->ttft_slo_ns < 1 || cfg->tpot_slo_ns < 1) return false;
   if (hw.n_cu % hw.granule != 0 || hw.n_cu / hw.granule < 2) return false;
-  if (cfg->mode == 2 && (cfg->fixed_prefill_cus < hw.granule || cfg->fixed_prefill_cus >= hw.n_cu || cfg->fixed_prefill_cus % hw.granule)) return false;
+  if ((cfg->mode == 2 || cfg->mode == 6) && (cfg->fixed_prefill_cus < hw.granule || cfg->fixed_prefill_cus >= hw.n_cu || cfg->fixed_prefill_cus % hw.granule)) return false;
   return true;
 }
 

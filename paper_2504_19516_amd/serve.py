@@ -5,7 +5,8 @@ prefill cycle, and hands prefilled requests over to the decode batch without mov
 
 Modes: "concurrent" (Algorithm 1 picks the split), "tm" (time-multiplexed: same kernels, whole
 GPU, prefill slices and decode steps strictly alternate), "fixed:<prefill CUs>" (concurrent with
-a static split). Arrivals follow the trace in real time. Token values are random (weights are
+a static split), the paper's ablations "naive", "wpart", "wsched" (Section 4.5) and
+"fixedall:<prefill CUs>" (Section 4.4: prefill on a fixed CU count, decode on every CU). Arrivals follow the trace in real time. Token values are random (weights are
 random too): output lengths come from the trace, so argmax flips cannot change the workload.
 
     python -m paper_2504_19516_amd.serve --model 8b --rate 8 --window 20 --mode concurrent \
@@ -56,8 +57,9 @@ class LiveServer:
     def run(self, trace, mode="concurrent", seed=0, log_every=0):
         eng, desc, cfg = self.eng, self.desc, dict(self.cfg)
         serial = mode == "tm"
-        cfg["mode"] = 1 if serial else (2 if mode.startswith("fixed") else 0)
-        if mode.startswith("fixed"):
+        name = mode.split(":")[0]
+        cfg["mode"] = MODES[name]
+        if ":" in mode:
             cfg["fixed_prefill_cus"] = int(mode.split(":")[1])
         n = self.n_cu
         rng = np.random.default_rng(seed)
@@ -185,6 +187,11 @@ class LiveServer:
                     tpot_mean_ms=float(tpot.mean()) / 1e6 if len(tpot) else 0.0, tpot_p90_ms=pct(tpot, 90),
                     slo_attainment=ok / max(1, len(reqs)))
 
+
+# scheduler policies: Algorithm 1, time-multiplexed, fixed disjoint split "fixed:<prefill CUs>", the
+# ablations of Section 4.5 (naive, wpart, wsched) and Section 4.4's "fixedall:<prefill CUs>" (prefill
+# on a fixed CU count, decode on every CU)
+MODES = {"concurrent": 0, "tm": 1, "fixed": 2, "naive": 3, "wpart": 4, "wsched": 5, "fixedall": 6}
 
 WORKLOADS = {
     "conversation": (dict(kind="lognormal", median=600, sigma=1.0, cap=8192), dict(kind="lognormal", median=250, sigma=0.9, cap=2048)),

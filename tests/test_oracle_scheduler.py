@@ -84,15 +84,19 @@ def check_invariants(shape, hw, cfg, trace):
         assert slices[0][0] == 0 and slices[-1][1] == shape.n_layers
         assert all(a[1] == b[0] for a, b in zip(slices, slices[1:]))
     for d in dec:
-        if cfg.mode == 1:
+        if cfg.mode in (1, 3):
             assert d[6] == d[7] == hw.n_cu
+        elif cfg.mode == 5:
+            assert d[6] == hw.n_cu and d[7] in (0, hw.n_cu)
+        elif cfg.mode == 6:
+            assert d[6] == cfg.fixed_prefill_cus and d[7] == hw.n_cu
         else:
             assert d[6] + d[7] == hw.n_cu and d[6] >= hw.granule and d[6] % hw.granule == 0
     assert all(a[0] <= b[0] for a, b in zip(dec, dec[1:]))
     return dec, st
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("rate", [2.0, 12.0])
 def test_invariants_on_poisson_trace(mode, rate):
     trace = synth.poisson_trace(7, rate, 8.0, dict(kind="lognormal", median=600, sigma=1.0, cap=8192),
@@ -112,6 +116,24 @@ def test_reorder_does_not_starve_long_request():
     dec2, st2 = check_invariants(SHAPE, hw, config(ttft_slo_ns=400_000_000), trace2)
     start_long = [d[0] for d in dec2 if d[4] == 0 and d[2] <= 1 and d[3] == S.tasks_hash([1])]
     assert start_long and start_long[0] <= 400_000_000
+
+
+def test_ablation_policies_by_inspection():
+    """Section 4.5: Naive and w/Partition keep arrival order; w/Partition never suspends decode while
+    requests decode; w/Scheduler reorders like the full design but never splits the CUs."""
+    hw = profile()
+    # a long request ahead of many short ones: the scheduler policies bring short ones forward
+    trace = [(0, 64, 40)] + [(10, 8000, 40)] + [(20 + i, 64, 40) for i in range(30)]
+
+    for mode, reorders in ((0, True), (3, False), (4, False), (5, True)):
+        dec, st = S.replay(SHAPE, hw, config(mode=mode, max_batch_tokens=8000), [tuple(t) for t in trace])
+        starts = [d for d in dec if d[4] == 0]
+        long_pos = next(k for k, d in enumerate(starts) if d[2] == 1)      # the batch whose lowest id is the long request
+        assert (long_pos > 1) == reorders, (mode, long_pos)       # in arrival order the long one is second
+        if mode == 4:
+            assert all(d[7] > 0 for d in dec if d[9] > 0)          # decode batch present -> decode keeps CUs
+        if mode in (3, 5):
+            assert all(d[6] == hw.n_cu for d in dec)
 
 
 def test_small_pool_serialises_admission_without_deadlock():

@@ -34,7 +34,7 @@ CFG3 = dict(ttft_slo_ns=1_000_000_000, tpot_slo_ns=50_000_000, layers_per_step=4
 
 
 @pytest.mark.parametrize("rate,seed", [(2.0, 1), (8.0, 2), (16.0, 3)])
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4, 5, 6])
 def test_replay_matches_oracle_on_conversational_traces(sts, rate, seed, mode):
     trace = synth.poisson_trace(seed, rate, 6.0, IN3, OUT3)
     cfg = dict(CFG3, mode=mode, fixed_prefill_cus=192)
