@@ -200,6 +200,10 @@ def main():
         sweep[str(pm)] = {"step_ms": round(s * 1e3, 4), "prefill_ms": round(tp / 1e6, 4), "decode_ms": round(td / 1e6, 4), "slo_ok": ok}
         if ok and (best is None or s < best[1]):
             best = (pm, s)
+    # both phases at once on every CU (overlapping masks, no partition): the "Naive" point of the paper's ablation
+    eng.set_partition(256, 256)
+    wl.timed(1)
+    ov_s, ov_tp, ov_td = wl.timed(4)
     if best is None:
         best = (min(sweep, key=lambda k: sweep[k]["step_ms"]), 0)
     pm = int(best[0])
@@ -232,6 +236,8 @@ def main():
                    "time_multiplexed": {"tokens_per_s": tokens_per_step / tm_s, "step_ms": tm_s * 1e3,
                                         "prefill_ms": tm_tp / 1e6, "decode_ms": tm_td / 1e6},
                    "speedup_vs_time_multiplexed": tm_s / step_s,
+                   "unpartitioned_concurrent": {"step_ms": round(ov_s * 1e3, 4), "prefill_ms": round(ov_tp / 1e6, 4),
+                                                "decode_ms": round(ov_td / 1e6, 4)},
                    "slo_per_layer_ms": {"ttft": ttft_budget / 1e6, "tpot": tpot_budget / 1e6},
                    "sweep": sweep},
         "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4>, SwiGLU epilogue)",

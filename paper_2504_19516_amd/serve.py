@@ -47,7 +47,7 @@ class LiveServer:
         self.profile = sts.Profile(text=profile_text)
         self.eng = sts.Engine(desc, weight_seed=1234, init_weights=True, kv_pool_pages=kv_pool_pages,
                               max_prefill_tokens=max_batch_tokens, max_prefill_seqs=64, max_decode_batch=max_decode_batch,
-                              max_seqs=max_decode_batch + 80, max_pages_per_seq=(max_ctx + PAGE - 1) // PAGE)
+                              max_seqs=4096, max_pages_per_seq=(max_ctx + PAGE - 1) // PAGE)
         self.n_cu = self.eng.get_partition()[2]
         self.max_ctx = max_ctx
 
