@@ -6,7 +6,9 @@ prefill cycle, and hands prefilled requests over to the decode batch without mov
 Modes: "concurrent" (Algorithm 1 picks the split), "tm" (time-multiplexed: same kernels, whole
 GPU, prefill slices and decode steps strictly alternate), "fixed:<prefill CUs>" (concurrent with
 a static split), the paper's ablations "naive", "wpart", "wsched" (Section 4.5) and
-"fixedall:<prefill CUs>" (Section 4.4: prefill on a fixed CU count, decode on every CU). Arrivals follow the trace in real time. Token values are random (weights are
+"fixedall:<prefill CUs>" (Section 4.4: prefill on a fixed CU count, decode on every CU), and
+"chunked:<chunk tokens>", the chunked-prefill baseline (whole GPU, one prompt chunk through all
+layers then one decode step, alternating). Arrivals follow the trace in real time. Token values are random (weights are
 random too): output lengths come from the trace, so argmax flips cannot change the workload.
 
     python -m paper_2504_19516_amd.serve --model 8b --rate 8 --window 20 --mode concurrent \
@@ -54,7 +56,78 @@ class LiveServer:
     def close(self):
         self.eng.close()
 
+    def run_chunked(self, trace, chunk_tokens, seed=0):
+        """The chunked-prefill baseline the paper compares against (Sections 2.2.2, 4.1): one engine on the
+        whole GPU; every iteration runs one prompt chunk of at most `chunk_tokens` tokens through ALL
+        layers (appended after the tokens of that prompt already cached, so its attention re-reads
+        them) and then one decode step of the running batch, i.e. the hybrid batch of
+        chunk + decode tokens executed back to back. Prompts are taken in arrival order."""
+        eng, desc = self.eng, self.desc
+        n = self.n_cu
+        rng = np.random.default_rng(seed)
+        reqs = [Req(i, a, il, ol) for i, (a, il, ol) in enumerate(trace)]
+        Q, D = [], []
+        cur, done_tokens = None, 0
+        next_arrival, rejected, chunks = 0, 0, 0
+        eng.set_partition(n, n)
+        max_batch = self.cfg["max_decode_batch"]
+        t0 = time.perf_counter_ns()
+        clock = lambda: time.perf_counter_ns() - t0
+        while True:
+            now = clock()
+            while next_arrival < len(reqs) and reqs[next_arrival].arrival <= now:
+                r = reqs[next_arrival]
+                if r.in_len + r.out_len > self.max_ctx:
+                    rejected += 1
+                else:
+                    Q.append(r)
+                next_arrival += 1
+            if cur is None and Q and len(D) < max_batch and eng.pages_free() >= (Q[0].in_len + Q[0].out_len + PAGE - 1) // PAGE:
+                cur, done_tokens = Q.pop(0), 0
+                cur.seq = eng.seq_create()
+                eng.seq_reserve(cur.seq, cur.in_len + cur.out_len)
+                cur.tokens = rng.integers(0, desc.vocab, cur.in_len, dtype=np.int32)
+            if cur is None and not D:
+                if next_arrival >= len(reqs) and not Q:
+                    break
+                if next_arrival < len(reqs):
+                    wait = reqs[next_arrival].arrival - clock()
+                    if wait > 0:
+                        time.sleep(wait * 1e-9)
+                continue
+            if cur is not None:
+                m = min(chunk_tokens, cur.in_len - done_tokens)
+                eng.prefill_launch([cur.seq], [cur.tokens[done_tokens:done_tokens + m]], 0, desc.n_layers,
+                                   want_logits=(done_tokens + m == cur.in_len))
+                eng.prefill_finish()
+                done_tokens += m
+                chunks += 1
+                if done_tokens == cur.in_len:
+                    now = clock()
+                    cur.first_token = now
+                    if cur.out_len <= 1:
+                        cur.finish = now
+                        eng.seq_free(cur.seq)
+                    else:
+                        D.append(cur)
+                    cur = None
+            if D:
+                batch = list(D)
+                eng.decode_launch([r.seq for r in batch], rng.integers(0, desc.vocab, len(batch), dtype=np.int32), want_next=True)
+                eng.decode_finish(len(batch))
+                now = clock()
+                for r in batch:
+                    r.n_dec += 1
+                    if r.n_dec >= r.out_len - 1:
+                        r.finish = now
+                        eng.seq_free(r.seq)
+                        D.remove(r)
+        cfg = dict(self.cfg, ttft_slo_ns=self.slo[0], tpot_slo_ns=self.slo[1])
+        return self.stats(reqs, rejected, cfg), [(0, 0, 0, 0, 0, n, n, 0, 0, 0)] * chunks, []
+
     def run(self, trace, mode="concurrent", seed=0, log_every=0):
+        if mode.startswith("chunked"):
+            return self.run_chunked(trace, int(mode.split(":")[1]), seed)
         eng, desc, cfg = self.eng, self.desc, dict(self.cfg)
         serial = mode == "tm"
         name = mode.split(":")[0]

@@ -326,7 +326,7 @@ def test_launch_poll_finish_equals_blocking_calls(sts, tiny, eng):
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
 
 
-@pytest.mark.parametrize("mode", ["concurrent", "tm", "fixed:192"])
+@pytest.mark.parametrize("mode", ["concurrent", "tm", "fixed:192", "naive", "wpart", "wsched", "fixedall:128", "chunked:64"])
 def test_live_serving_of_a_short_trace(sts, tiny, mode):
     """The serving loop on the tiny model: every request is prefilled layer slice by layer slice,
     handed over, decoded to its output length, and its pages come back."""
@@ -342,9 +342,17 @@ def test_live_serving_of_a_short_trace(sts, tiny, mode):
     assert st["n_finished"] == len(trace) and st["rejected"] == 0
     assert st["out_tokens"] == int(trace[:, 2].sum())
     assert srv.eng.pages_free() == 600
+    if mode.startswith("chunked"):
+        assert len(dec) >= sum(-(-int(t[1]) // 64) for t in trace)         # every prompt went through in chunks of <= 64 tokens
+        srv.close()
+        return
     assert all(d[3] < d[4] <= desc.n_layers for d in dec)
-    if mode == "tm":
+    if mode in ("tm", "naive"):
         assert all(d[5] == 256 and d[6] == 256 for d in dec)
+    elif mode == "wsched":
+        assert all(d[5] == 256 and d[6] in (0, 256) for d in dec)
+    elif mode.startswith("fixedall"):
+        assert all(d[5] == 128 and d[6] == 256 for d in dec)
     elif mode.startswith("fixed"):
         assert all(d[5] == 192 and d[6] == 64 for d in dec)
     else:
