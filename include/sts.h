@@ -212,6 +212,14 @@ typedef struct {
  * interpolated alpha of Eq. 2. A phase with work but zero CUs gets STS_INF_NS; no work -> 0. */
 int sts_latency_query(const sts_profile* p, const sts_model_desc* desc, const sts_exec_state* es,
                       int64_t* prefill_ns, int64_t* decode_ns);
+/* Online recalibration (Section 3.2.4): feed one measured prefill slice and/or decode step at
+ * execution state es back into the profile. Eq. 2 gives alpha_obs = measured / T' at es; every
+ * alpha sample the interpolation at es reads moves by weight_ppm/1e6 * (alpha_obs /
+ * alpha_predicted - 1) of its value, so the prediction at es moves that share of the way.
+ * A measurement <= 0 skips that phase. Integer arithmetic; not thread-safe against queries on the
+ * same profile. */
+int sts_profile_observe(sts_profile* p, const sts_model_desc* desc, const sts_exec_state* es,
+                        int64_t measured_prefill_ns, int64_t measured_decode_ns, int64_t weight_ppm);
 /* The uncalibrated roofline sums T'_{p,ES} (alpha not applied): what a measurement is divided by
  * to obtain alpha (Eq. 2). */
 int sts_latency_roofline(const sts_profile* p, const sts_model_desc* desc, const sts_exec_state* es,

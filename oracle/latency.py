@@ -277,6 +277,54 @@ def latency_query(s: Shape, hw: Profile, es: dict):
             predict_decode_ns(s, hw, list(es["decode_ctx"]), es["decode_cus"], co))
 
 
+# ------------------------------------------------------------------ online recalibration (Section 3.2.4)
+def _cell_corners(grid: Grid, x):
+    """Index tuples of the samples the interpolation at x reads: per axis both ends of its segment
+    (the single sample of a one-point axis)."""
+    per_axis = []
+    for ax, xv in zip(grid.axes, x):
+        if len(ax) == 1:
+            per_axis.append([0])
+            continue
+        i = 0
+        while i + 2 < len(ax) and xv >= ax[i + 1]:
+            i += 1
+        per_axis.append([i, i + 1])
+    corners = [[]]
+    for choices in per_axis:
+        corners = [c + [k] for c in corners for k in choices]
+    return corners
+
+
+def _blend(grid: Grid, x, t_measured: int, t_roofline: int, weight_ppm: int) -> None:
+    """One observation: Eq. 2 gives alpha_obs = T_measured / T' at x. Every sample the interpolation
+    at x reads moves by weight * (alpha_obs / alpha_predicted - 1) of its own value, so the
+    prediction at x moves by that share toward the measurement; samples stay >= 1."""
+    a_pred = alpha_at(grid, x)
+    a_obs = alpha_from_measurement(t_measured, t_roofline)
+    for idx in _cell_corners(grid, x):
+        node = grid.values
+        for i in idx[:-1]:
+            node = node[i]
+        old = node[idx[-1]]
+        target = floor_div(old * a_obs, a_pred)
+        node[idx[-1]] = max(1, old + floor_div((target - old) * weight_ppm, PPM))
+
+
+def observe(s: Shape, hw: Profile, es: dict, measured_prefill_ns: int, measured_decode_ns: int, weight_ppm: int) -> None:
+    """Recalibrate alpha from one measured slice and/or step at execution state es (a measurement
+    <= 0 is skipped). Mutates hw."""
+    reqs = list(zip(es["prefill_len"], es["prefill_ctx"]))
+    if measured_prefill_ns > 0 and reqs and es["prefill_cus"] > 0:
+        roof = prefill_roofline_ns(s, hw, reqs, es["prefill_cus"], es["layer_begin"], es["n_layers_step"])
+        _blend(hw.alpha_prefill, [es["prefill_cus"], sum(sl for sl, _ in reqs)], measured_prefill_ns, roof, weight_ppm)
+    cls = list(es["decode_ctx"])
+    if measured_decode_ns > 0 and cls and es["decode_cus"] > 0:
+        co = sum(es["prefill_len"]) if es["prefill_cus"] > 0 else 0
+        roof = decode_roofline_ns(s, hw, cls, es["decode_cus"], co)
+        _blend(hw.alpha_decode, [es["decode_cus"], len(cls), sum(cls) // len(cls)], measured_decode_ns, roof, weight_ppm)
+
+
 # ------------------------------------------------------------------ profile file (text)
 def _flatten(v):
     return [y for x in v for y in _flatten(x)] if isinstance(v, list) else [v]

@@ -319,6 +319,53 @@ extern "C" int sts_latency_query(const sts_profile* p, const sts_model_desc* d, 
   if (decode_ns) *decode_ns = predict_decode_ns(*d, p->hw, es->decode_ctx, es->n_decode, es->decode_cus, co);
   return STS_OK;
 }
+// ---- online recalibration (Section 3.2.4): one observation moves every alpha sample that the
+// interpolation at the observed execution state reads by weight * (alpha_obs / alpha_predicted - 1)
+// of its value.
+static void blend(Grid& g, const int64_t* x, int64_t t_measured, int64_t t_roofline, int64_t weight_ppm) {
+  const int64_t a_pred = alpha_at(g, x);
+  const int64_t a_obs = floor_div((i128)t_measured * PPM, std::max<int64_t>(t_roofline, 1));
+  // flat indices of the samples the interpolation at x reads (both ends of each axis's segment)
+  std::vector<size_t> corners{0};
+  size_t stride = g.values.size();
+  for (size_t a = 0; a < g.axes.size(); a++) {
+    const std::vector<int64_t>& ax = g.axes[a];
+    stride /= ax.size();
+    if (ax.size() == 1) continue;
+    size_t i = 0;
+    while (i + 2 < ax.size() && x[a] >= ax[i + 1]) i++;
+    std::vector<size_t> next;
+    for (size_t c : corners) { next.push_back(c + i * stride); next.push_back(c + (i + 1) * stride); }
+    corners.swap(next);
+  }
+  for (size_t c : corners) {
+    const int64_t old = g.values[c];
+    const int64_t target = floor_div((i128)old * a_obs, a_pred);
+    g.values[c] = std::max<int64_t>(1, old + floor_div((i128)(target - old) * weight_ppm, PPM));
+  }
+}
+extern "C" int sts_profile_observe(sts_profile* p, const sts_model_desc* d, const sts_exec_state* es, int64_t measured_prefill_ns,
+                                   int64_t measured_decode_ns, int64_t weight_ppm) {
+  int rc = check_es(p, d, es);
+  if (rc) return rc;
+  if (weight_ppm < 0 || weight_ppm > PPM) return STS_EINVAL;
+  int64_t co = 0;
+  if (es->prefill_cus > 0) for (int i = 0; i < es->n_prefill; i++) co += es->prefill_len[i];
+  if (measured_prefill_ns > 0 && es->n_prefill > 0 && es->prefill_cus > 0) {
+    const int64_t roof = prefill_roofline_ns(*d, p->hw, es->prefill_len, es->prefill_ctx, es->n_prefill, es->prefill_cus, es->layer_begin, es->n_layers_step);
+    const int64_t x[2] = {es->prefill_cus, co};
+    blend(p->hw.alpha_prefill, x, measured_prefill_ns, roof, weight_ppm);
+  }
+  if (measured_decode_ns > 0 && es->n_decode > 0 && es->decode_cus > 0) {
+    const int64_t roof = decode_roofline_ns(*d, p->hw, es->decode_ctx, es->n_decode, es->decode_cus, co);
+    int64_t ctx = 0;
+    for (int i = 0; i < es->n_decode; i++) ctx += es->decode_ctx[i];
+    const int64_t x[3] = {es->decode_cus, es->n_decode, ctx / es->n_decode};
+    blend(p->hw.alpha_decode, x, measured_decode_ns, roof, weight_ppm);
+  }
+  return STS_OK;
+}
+
 extern "C" int sts_latency_roofline(const sts_profile* p, const sts_model_desc* d, const sts_exec_state* es, int64_t* prefill_ns, int64_t* decode_ns) {
   int rc = check_es(p, d, es);
   if (rc) return rc;

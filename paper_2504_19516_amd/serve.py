@@ -37,12 +37,13 @@ class Req:
 
 class LiveServer:
     def __init__(self, desc, profile_text, cfg, kv_pool_pages, max_batch_tokens=16384, max_decode_batch=256, max_ctx=10240,
-                 sched_slo_ns=None):
+                 sched_slo_ns=None, recalibrate_ppm=0):
         """cfg carries the SLOs requests are judged by; sched_slo_ns = (ttft, tpot) optionally gives the
         scheduler tighter targets than those (headroom for estimator error and for the running-mean TPOT,
         which Algorithm 1 otherwise steers right onto the limit)."""
         self.desc, self.cfg = desc, dict(cfg)
         self.slo = (cfg["ttft_slo_ns"], cfg["tpot_slo_ns"])
+        self.recalibrate_ppm = int(recalibrate_ppm)      # > 0: feed every finished slice and step back into alpha (Section 3.2.4)
         if sched_slo_ns:
             self.cfg.update(ttft_slo_ns=int(sched_slo_ns[0]), tpot_slo_ns=int(sched_slo_ns[1]))
         self.cfg.update(max_batch_tokens=max_batch_tokens, max_decode_batch=max_decode_batch, kv_pool_pages=kv_pool_pages)
@@ -143,6 +144,7 @@ class LiveServer:
         decode_batch, cur_slice = [], None
         next_arrival, rejected = 0, 0
         timeline, decisions = [], []
+        err_p, err_d = [], []                  # |predicted - measured| / measured of every slice and step (host clock)
         eng.set_partition(n, n)
         t0 = time.perf_counter_ns()
         clock = lambda: time.perf_counter_ns() - t0
@@ -182,6 +184,8 @@ class LiveServer:
                     lb, le = ch["layer_begin"], ch["layer_end"]
                     eng.prefill_launch([r.seq for r in P], [r.tokens for r in P], lb, le, want_logits=(le == desc.n_layers))
                     prefill_busy, cur_slice = True, (now, lb, le, ch["predicted_ns"])
+                    slice_es = dict(prefill_len=[r.in_len for r in P], prefill_ctx=[0] * len(P), decode_ctx=[], prefill_cus=pm,
+                                    decode_cus=0, layer_begin=lb, n_layers_step=le - lb)
                     decisions.append((now, len(P), sum(r.in_len for r in P), lb, le, pm, dm, ch["branch"], len(D) + len(H), len(Q)))
             # ---- decode engine: merge hand-offs, one step on the CUs left to it
             if not decode_busy and not (serial and prefill_busy):
@@ -193,6 +197,11 @@ class LiveServer:
                         if not serial:
                             eng.set_partition(-1, dm_eff)
                         decode_batch = list(D)
+                        co = [sum(r.in_len for r in P)] if (prefill_busy and not serial and P) else []
+                        step_es = dict(prefill_len=co, prefill_ctx=[0] * len(co), decode_ctx=[r.in_len + r.n_dec for r in D],
+                                       prefill_cus=pm if co else 0, decode_cus=dm_eff, layer_begin=0, n_layers_step=1)
+                        step_pred = self.profile.query(desc, step_es)[1]
+                        step_t0 = clock()
                         eng.decode_launch([r.seq for r in D], rng.integers(0, desc.vocab, len(D), dtype=np.int32), want_next=True)
                         decode_busy = True
             # ---- wait for the next event
@@ -221,6 +230,9 @@ class LiveServer:
                 prefill_busy, turn_decode = False, True
                 l_exe = cur_slice[2]
                 timeline.append((now, "prefill", pm, sum(r.in_len for r in P), cur_slice[1], cur_slice[2], now - cur_slice[0], cur_slice[3]))
+                err_p.append(abs(cur_slice[3] - (now - cur_slice[0])) / max(1, now - cur_slice[0]))
+                if self.recalibrate_ppm:
+                    self.profile.observe(desc, slice_es, now - cur_slice[0], 0, self.recalibrate_ppm)
                 if l_exe == desc.n_layers:
                     for r in P:
                         r.first_token = now
@@ -232,6 +244,9 @@ class LiveServer:
             if ddone:
                 eng.decode_finish(len(decode_batch))
                 decode_busy, turn_decode = False, False
+                err_d.append(abs(step_pred - (now - step_t0)) / max(1, now - step_t0))
+                if self.recalibrate_ppm:
+                    self.profile.observe(desc, step_es, 0, now - step_t0, self.recalibrate_ppm)
                 for r in decode_batch:
                     r.n_dec += 1
                     if r.n_dec >= r.out_len - 1:
@@ -240,7 +255,10 @@ class LiveServer:
                 if log_every and len(timeline) % log_every == 0:
                     timeline.append((now, "decode", eng.get_partition()[1], len(decode_batch)))
         eng.set_partition(n, n)
-        return self.stats(reqs, rejected, dict(cfg, ttft_slo_ns=self.slo[0], tpot_slo_ns=self.slo[1])), decisions, timeline
+        st = self.stats(reqs, rejected, dict(cfg, ttft_slo_ns=self.slo[0], tpot_slo_ns=self.slo[1]))
+        st["estimator_mape_prefill"] = float(np.mean(err_p)) if err_p else 0.0
+        st["estimator_mape_decode"] = float(np.mean(err_d)) if err_d else 0.0
+        return st, decisions, timeline
 
     @staticmethod
     def stats(reqs, rejected, cfg):
@@ -286,6 +304,8 @@ def main():
     ap.add_argument("--sched-ttft-ms", type=float, default=0.0, help="TTFT target given to the scheduler (default: the SLO)")
     ap.add_argument("--sched-tpot-ms", type=float, default=0.0, help="TPOT target given to the scheduler (default: the SLO)")
     ap.add_argument("--layers-per-step", type=int, default=4)
+    ap.add_argument("--recalibrate-ppm", type=int, default=0,
+                    help="online alpha recalibration weight (parts per million per observation; 0 = off)")
     ap.add_argument("--pool-pages", type=int, default=40000)
     ap.add_argument("--max-ctx", type=int, default=10240)
     ap.add_argument("--out", default=None)
@@ -295,7 +315,8 @@ def main():
     cfg = dict(ttft_slo_ns=int(args.ttft_ms * 1e6), tpot_slo_ns=int(args.tpot_ms * 1e6), layers_per_step=args.layers_per_step)
     sched = (int((args.sched_ttft_ms or args.ttft_ms) * 1e6), int((args.sched_tpot_ms or args.tpot_ms) * 1e6))
     srv = LiveServer(desc, open(args.profile).read(), cfg, args.pool_pages, max_ctx=args.max_ctx,
-                     max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0), sched_slo_ns=sched)
+                     max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0), sched_slo_ns=sched,
+                     recalibrate_ppm=args.recalibrate_ppm)
     ind, outd = WORKLOADS[args.workload]
     results = []
     for rate in [float(x) for x in args.rates.split(",")]:

@@ -90,7 +90,7 @@ EXPORTS = [
     "sts_prefill_append", "sts_prefill_launch", "sts_decode_launch", "sts_phase_done", "sts_prefill_finish",
     "sts_decode_finish", "sts_prefill_abort", "sts_decode_step", "sts_step_concurrent", "sts_last_timing", "sts_read_hidden",
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
-    "sts_probe_copy", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
+    "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
     "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay",
 ]
@@ -385,6 +385,13 @@ class Profile:
         fn = lib().sts_latency_roofline if roofline else lib().sts_latency_query
         _ck(fn(self._p, C.byref(d), C.byref(st), C.byref(a), C.byref(b)), "sts_latency_query")
         return a.value, b.value
+
+    def observe(self, desc, es, measured_prefill_ns=0, measured_decode_ns=0, weight_ppm=100_000):
+        """Online recalibration: blend one measured slice / step at execution state es into alpha."""
+        st, keep = self._es(es)
+        d = model_desc(desc)
+        _ck(lib().sts_profile_observe(self._p, C.byref(d), C.byref(st), C.c_int64(int(measured_prefill_ns)),
+                                      C.c_int64(int(measured_decode_ns)), C.c_int64(int(weight_ppm))), "sts_profile_observe")
 
     @staticmethod
     def _sched_config(cfg):

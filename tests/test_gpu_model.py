@@ -358,3 +358,26 @@ def test_live_serving_of_a_short_trace(sts, tiny, mode):
     else:
         assert all(d[5] + d[6] == 256 for d in dec)
     srv.close()
+
+
+def test_live_serving_with_online_recalibration(sts, tiny):
+    """Section 3.2.4: every finished slice and step is fed back into alpha while serving. The trace
+    is served to the end, the profile's alpha samples move, and the server reports the estimator's
+    error over the run (its size on the tiny model is launch-overhead noise, so only its presence
+    is checked here; the 8B-shape figures are in the live-serving report)."""
+    from oracle import latency as L
+    from paper_2504_19516_amd import serve
+    desc, _ = tiny
+    hw = L.Profile(n_cu=256, granule=32, c_peak=200_000, d_peak=2_000, n_d=128, tile_m=128, tile_n=128, wgs_per_cu=2)
+    cfg = dict(ttft_slo_ns=200_000_000, tpot_slo_ns=20_000_000, layers_per_step=1)
+    trace = synth.poisson_trace(5, 80.0, 0.6, dict(kind="lognormal", median=100, sigma=0.6, cap=400),
+                                dict(kind="lognormal", median=20, sigma=0.5, cap=100))
+    rows = [tuple(int(x) for x in r) for r in trace]
+    srv = serve.LiveServer(desc, L.dump_profile(hw), cfg, kv_pool_pages=600, max_batch_tokens=512, max_decode_batch=16, max_ctx=640,
+                           recalibrate_ppm=300_000)
+    before = srv.profile.dump()
+    st, _, _ = srv.run(rows, "concurrent")
+    assert st["n_finished"] == len(rows) and srv.eng.pages_free() == 600
+    assert srv.profile.dump() != before
+    assert st["estimator_mape_prefill"] > 0 and st["estimator_mape_decode"] > 0
+    srv.close()

@@ -104,3 +104,32 @@ def test_latency_query_rejects_bad_state(sts):
     p = sts.Profile(text=L.dump_profile(sample_profile()))
     with pytest.raises(sts.StsError):
         p.query(synth.tiny_model(), dict(prefill_len=[0], prefill_ctx=[0], prefill_cus=32))
+
+
+def test_online_recalibration_bit_exact_vs_oracle_and_converges(sts):
+    """A stream of observations (Eq. 2 applied online, Section 3.2.4) leaves the library's profile and
+    the oracle's identical, text for text; and repeated observations of one state pull its
+    prediction onto the measurement."""
+    import numpy as np
+    hw = sample_profile()
+    hw.tail_cut = 16
+    p = sts.Profile(text=L.dump_profile(hw))
+    desc = synth.llama8b_model()
+    shape = L.Shape(desc.n_layers, desc.hidden, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.mlp, desc.vocab)
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        npre, ndec = int(rng.integers(0, 4)), int(rng.integers(0, 30))
+        es = dict(prefill_len=[int(x) for x in rng.integers(1, 12000, npre)], prefill_ctx=[int(x) for x in rng.integers(0, 3000, npre)],
+                  decode_ctx=[int(x) for x in rng.integers(0, 20000, ndec)], prefill_cus=int(rng.choice([0, 32, 96, 224, 256])),
+                  decode_cus=int(rng.choice([0, 32, 160, 256])), layer_begin=int(rng.integers(0, 28)), n_layers_step=4)
+        mp, md = int(rng.integers(0, 50_000_000)), int(rng.integers(0, 50_000_000))
+        w = int(rng.choice([0, 50_000, 300_000, 1_000_000]))
+        p.observe(desc, es, mp, md, w)
+        L.observe(shape, hw, es, mp, md, w)
+    assert L.parse_profile(p.dump()) == hw
+    es = dict(prefill_len=[3000], prefill_ctx=[0], decode_ctx=[1500] * 40, prefill_cus=192, decode_cus=64, layer_begin=0, n_layers_step=4)
+    target_p, target_d = 7_000_000, 9_000_000
+    for _ in range(60):
+        p.observe(desc, es, target_p, target_d, 300_000)
+    got = p.query(desc, es)
+    assert abs(got[0] - target_p) <= 0.02 * target_p and abs(got[1] - target_d) <= 0.02 * target_d
