@@ -25,6 +25,7 @@ __device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
 
 template <int D, int G>
 __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict__ q, const DecodeSeq* __restrict__ seqs,
+                                                          const AttnItem* __restrict__ items,
                                                           const int* __restrict__ block_tables, const bf16* __restrict__ pool,
                                                           KvGeom geo, int n_q, int chunk_pages, int max_chunks,
                                                           float* __restrict__ ws, float scale_log2e) {
@@ -36,7 +37,8 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   __shared__ float red[4][G][D];
   __shared__ float stat_m[G], stat_l[G];
 
-  const int chunk = blockIdx.x, kvh = blockIdx.y, req = blockIdx.z;
+  const AttnItem item = items[blockIdx.x];          // (request, chunk): only chunks that exist are launched
+  const int chunk = item.q0, kvh = blockIdx.y, req = item.seq;
   const DecodeSeq sq = seqs[req];
   const int len = sq.cl + 1;
   const int n_pages = (len + 15) >> 4;
@@ -216,26 +218,27 @@ int attn_decode_max_chunk_tokens() { return MAX_CHUNK_TOKENS; }
 size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks) { return (size_t)n * n_q * chunks * (d + 2); }
 
 template <int D, int G>
-static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const int* bt, const bf16* pool,
-                          KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
-  hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(max_chunks, geo.n_kv, n), dim3(256), 0, s, q, seqs, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const AttnItem* items, int n_items,
+                          const int* bt, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
+  hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), 0, s, q, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
   hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
 }
 
 // q, out: [n, n_q * d] bf16 (q already rotated). A context is cut into chunks of `chunk_pages`
 // pages (1..32: at most attn_decode_max_chunk_tokens() tokens); `max_chunks` must be at least
-// the chunk count of the longest context. ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
-hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const int* block_tables,
-                       const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws) {
-  if (n == 0) return hipSuccess;
+// the chunk count of the longest context. items: one (request, chunk index) record per chunk
+// that exists, n_items of them (device memory). ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
+hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const AttnItem* items, int n_items,
+                       const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws) {
+  if (n == 0 || n_items == 0) return hipSuccess;
   if (geo.page_tokens != 16 || n_q % geo.n_kv != 0 || chunk_pages < 1 || chunk_pages * 16 > MAX_CHUNK_TOKENS || max_chunks < 1) return hipErrorInvalidValue;
   const int G = n_q / geo.n_kv;
   const float sc = 1.4426950408889634f / sqrtf((float)geo.d);
-  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
