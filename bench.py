@@ -240,7 +240,7 @@ def main():
                                                 "decode_ms": round(ov_td / 1e6, 4)},
                    "slo_per_layer_ms": {"ttft": ttft_budget / 1e6, "tpot": tpot_budget / 1e6},
                    "sweep": sweep},
-        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4>, SwiGLU epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4,SwiGLU,2 stages>)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16,
                      "traffic": stored_traffic(pm), "avg_launch_ms": gu_avg_s * 1e3, "partition_cus": pm,
                      "frac_of_partition_peak": achieved / (PEAK_BF16 * pm / 256),
