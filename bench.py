@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-Workload (BASELINE configuration 2): one Llama-3-8B-shaped layer in bf16; one step = a
+Workload (benchmark configuration 2): one Llama-3-8B-shaped layer in bf16; one step = a
 2048-token prefill chunk concurrent with a decode batch of 64 requests whose contexts are
 lognormal (median 1024, sigma 0.8, cap 8192), KV pages of 16 in a randomly permuted pool.
 The CU split is swept over 32..224 of 256 CUs (untimed, part of warm-up); the timed region
