@@ -229,7 +229,7 @@ int pick_cfg(int m, int n) {
 int pick_prefill_cfg(int m, int n, int k, int cus, size_t tail_ws_bytes) {
   if (m <= 64) return GEMM_64x128;
   struct Cand { int cfg; double rate; };
-  const Cand cands[2] = {{GEMM_128x128, 4.0}, {GEMM_256x256_W8, 4.9}};
+  const Cand cands[2] = {{GEMM_128x128, 3.5}, {GEMM_256x256_W8, 4.8}};
   int best = GEMM_128x128; double best_cost = 1e300;
   for (const Cand& c : cands) {
     const int tm = gemm_tile_m(c.cfg), tn = gemm_tile_n(c.cfg), per_cu = gemm_wgs_per_cu(c.cfg);
