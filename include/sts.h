@@ -244,6 +244,11 @@ typedef struct {
                                          overlap the two CU sets; the replay's simulated durations ignore
                                          that contention, so their timing is meaningful on the GPU only */
   int32_t fixed_prefill_cus;
+  int32_t decode_boost_cus;           /* end-of-prefill boost (Section 3.3.1): while the final slice of a prefill
+                                         batch runs, decode gets this many extra CUs (a multiple of the granule,
+                                         0 = off; modes 0, 2, 4, only when decode runs). The prefill set is kept,
+                                         so the two CU sets intersect for that slice; the simulated durations
+                                         ignore the contention */
 } sts_sched_config;
 typedef struct {                      /* one scheduling cycle of the prefill scheduler */
   int64_t t_ns;                       /* simulated time of the decision */

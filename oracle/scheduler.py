@@ -57,6 +57,9 @@ class Config:
     # on a fixed CU count, decode on every CU
     mode: int = 0
     fixed_prefill_cus: int = 0
+    # end-of-prefill boost (Section 3.3.1): extra decode CUs while the final slice of a prefill batch
+    # runs; the prefill set is kept, so the two sets intersect for that slice. 0 = off
+    decode_boost_cus: int = 0
 
 
 @dataclass
@@ -238,6 +241,8 @@ class Replay:
                     ok = [dm_c for dm_c in grid if ttft_max(self.n - dm_c) <= cfg.ttft_slo_ns]
                     dm = ok[-1] if ok else balanced()
             pm = self.n - dm
+        if cfg.decode_boost_cus > 0 and cfg.mode in (0, 2, 4) and dec and dm > 0 and self.l_exe + l_eff == n_layers:
+            dm = min(self.n, dm + cfg.decode_boost_cus)
         self.pm, self.dm = pm, dm
         dur = self.t_prefill(next_tasks, pm, self.l_exe, l_eff)
         self.decisions.append((now, len(next_tasks), min(next_tasks), tasks_hash(next_tasks), self.l_exe, self.l_exe + l_eff,

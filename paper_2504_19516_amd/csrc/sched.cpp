@@ -196,6 +196,12 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
     }
     pm_new = n - dm_new;
   }
+  // End-of-prefill boost (Section 3.3.1): while the batch's final slice runs, decode gets extra CUs
+  // so the hand-over to decode-only is smooth. The prefill set stays, so the two sets intersect for
+  // that slice instead of the phases synchronising.
+  if (cfg.decode_boost_cus > 0 && (cfg.mode == 0 || cfg.mode == 2 || cfg.mode == 4) && !dec.empty() && dm_new > 0 &&
+      l_exe + l_eff == n_layers)
+    dm_new = std::min(n, dm_new + cfg.decode_boost_cus);
   for (const QReq& r : next_tasks) out.tasks.push_back(r.id);
   out.layer_begin = l_exe; out.layer_end = l_exe + l_eff; out.pm = pm_new; out.dm = dm_new; out.branch = branch;
   out.predicted_ns = c.t_prefill(next_tasks, pm_new, l_exe, l_eff);
@@ -323,6 +329,7 @@ bool config_ok(const Profile& hw, const sts_sched_config* cfg) {
   if (cfg->layers_per_step < 1 || cfg->max_batch_tokens < 1 || cfg->max_decode_batch < 1 || cfg->kv_pool_pages < 1 ||
       cfg->mode < 0 || cfg->mode > 6 || cfg->ttft_slo_ns < 1 || cfg->tpot_slo_ns < 1) return false;
   if (hw.n_cu % hw.granule != 0 || hw.n_cu / hw.granule < 2) return false;
+  if (cfg->decode_boost_cus < 0 || cfg->decode_boost_cus % hw.granule) return false;
   if ((cfg->mode == 2 || cfg->mode == 6) && (cfg->fixed_prefill_cus < hw.granule || cfg->fixed_prefill_cus >= hw.n_cu || cfg->fixed_prefill_cus % hw.granule)) return false;
   return true;
 }

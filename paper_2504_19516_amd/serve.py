@@ -133,7 +133,9 @@ class LiveServer:
         serial = mode == "tm"
         name = mode.split(":")[0]
         cfg["mode"] = MODES[name]
-        if ":" in mode:
+        if name == "boost":
+            cfg["decode_boost_cus"] = int(mode.split(":")[1])
+        elif ":" in mode:
             cfg["fixed_prefill_cus"] = int(mode.split(":")[1])
         n = self.n_cu
         rng = np.random.default_rng(seed)
@@ -281,8 +283,9 @@ class LiveServer:
 
 # scheduler policies: Algorithm 1, time-multiplexed, fixed disjoint split "fixed:<prefill CUs>", the
 # ablations of Section 4.5 (naive, wpart, wsched) and Section 4.4's "fixedall:<prefill CUs>" (prefill
-# on a fixed CU count, decode on every CU)
-MODES = {"concurrent": 0, "tm": 1, "fixed": 2, "naive": 3, "wpart": 4, "wsched": 5, "fixedall": 6}
+# on a fixed CU count, decode on every CU); "boost:<extra decode CUs>" is Algorithm 1 with the end-of-prefill
+# decode boost of Section 3.3.1 (the two CU sets intersect during a batch's final slice)
+MODES = {"concurrent": 0, "tm": 1, "fixed": 2, "naive": 3, "wpart": 4, "wsched": 5, "fixedall": 6, "boost": 0}
 
 WORKLOADS = {
     "conversation": (dict(kind="lognormal", median=600, sigma=1.0, cap=8192), dict(kind="lognormal", median=250, sigma=0.9, cap=2048)),

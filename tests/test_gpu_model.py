@@ -178,11 +178,12 @@ def test_serial_calls_equal_concurrent_call(sts, tiny):
 def test_split_and_neighbour_independence(sts, tiny, eng):
     """Prefill output does not depend on the CU split or on what runs beside it (bitwise: its
     grids and reduction orders are fixed); decode's split-K width follows its CU count, so
-    decode is compared within the fp32-accumulation tolerance."""
+    decode is compared within the fp32-accumulation tolerance. CU sets that intersect (the
+    end-of-prefill boost, repartitioning without a synchronisation) change timing only."""
     desc, w = tiny
     _, ctx_tokens, dec_tokens, pre_tokens = build_case(desc, w)
     outs = []
-    for mode in ("serial_full", "concurrent_96_160", "concurrent_160_96"):
+    for mode in ("serial_full", "concurrent_96_160", "concurrent_160_96", "concurrent_224_96"):     # the last: 64 CUs shared
         dseqs = gpu_contexts(eng, ctx_tokens)
         pseq = eng.seq_create()
         if mode == "serial_full":
@@ -326,7 +327,7 @@ def test_launch_poll_finish_equals_blocking_calls(sts, tiny, eng):
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
 
 
-@pytest.mark.parametrize("mode", ["concurrent", "tm", "fixed:192", "naive", "wpart", "wsched", "fixedall:128", "chunked:64"])
+@pytest.mark.parametrize("mode", ["concurrent", "tm", "fixed:192", "naive", "wpart", "wsched", "fixedall:128", "chunked:64", "boost:64"])
 def test_live_serving_of_a_short_trace(sts, tiny, mode):
     """The serving loop on the tiny model: every request is prefilled layer slice by layer slice,
     handed over, decoded to its output length, and its pages come back."""
@@ -355,6 +356,10 @@ def test_live_serving_of_a_short_trace(sts, tiny, mode):
         assert all(d[5] == 128 and d[6] == 256 for d in dec)
     elif mode.startswith("fixed"):
         assert all(d[5] == 192 and d[6] == 64 for d in dec)
+    elif mode.startswith("boost"):
+        for d in dec:                                                      # extra decode CUs only beside a batch's final slice
+            boosted = d[4] == desc.n_layers and d[8] > 0 and d[6] > 0
+            assert (256 < d[5] + d[6] <= 320) if boosted else (d[5] + d[6] == 256)
     else:
         assert all(d[5] + d[6] == 256 for d in dec)
     srv.close()

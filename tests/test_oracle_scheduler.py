@@ -56,6 +56,29 @@ def test_decode_is_given_the_minimum_that_meets_tpot():
     assert st["n_finished"] == 2 and st["n_slo_ok"] == 2
 
 
+def test_end_of_prefill_boost_by_inspection():
+    """Section 3.3.1: while the final slice of a prefill runs, decode gets extra CUs and the prefill
+    set is kept (the sets intersect); every other slice, and every decision without the boost, is
+    unchanged because the simulated durations ignore the shared CUs."""
+    hw = profile()
+    trace = [(0, 512, 200), (100_000_000, 4096, 4)]
+    base = S.replay(SHAPE, hw, config(), trace)[0]
+    boost = S.replay(SHAPE, hw, config(decode_boost_cus=64), trace)[0]
+    assert len(base) == len(boost)
+    n_boosted = 0
+    for a, b in zip(base, boost):
+        assert a[:7] == b[:7] and a[8:] == b[8:]                 # same batch, slice, prefill CUs, branch, duration
+        last_with_decode = a[5] == SHAPE.n_layers and a[9] > 0 and a[7] > 0
+        assert b[7] == (min(hw.n_cu, a[7] + 64) if last_with_decode else a[7])
+        n_boosted += last_with_decode
+    assert n_boosted == 1                                        # the second request's last slice, beside request 0's decode
+    last = [d for d in boost if d[2] == 1][-1]
+    assert (last[6], last[7]) == (224, 96)                       # 224 + 96 > 256: 64 CUs are shared for that slice
+    # nothing decodes -> nothing to boost
+    solo = S.replay(SHAPE, hw, config(decode_boost_cus=64), [(0, 2048, 1)])[0]
+    assert all(d[7] == 0 for d in solo)
+
+
 def test_tight_tpot_pushes_cus_to_decode_and_overload_balances():
     hw = profile()
     trace = [(0, 256, 400)] * 48 + [(400_000_000 + i, 8000, 8) for i in range(12)]
@@ -90,6 +113,8 @@ def check_invariants(shape, hw, cfg, trace):
             assert d[6] == hw.n_cu and d[7] in (0, hw.n_cu)
         elif cfg.mode == 6:
             assert d[6] == cfg.fixed_prefill_cus and d[7] == hw.n_cu
+        elif cfg.decode_boost_cus and d[5] == shape.n_layers and d[9] > 0 and d[7] > 0:
+            assert hw.n_cu < d[6] + d[7] <= hw.n_cu + cfg.decode_boost_cus and d[7] <= hw.n_cu
         else:
             assert d[6] + d[7] == hw.n_cu and d[6] >= hw.granule and d[6] % hw.granule == 0
     assert all(a[0] <= b[0] for a, b in zip(dec, dec[1:]))
@@ -103,6 +128,15 @@ def test_invariants_on_poisson_trace(mode, rate):
                                 dict(kind="lognormal", median=250, sigma=0.9, cap=2048))
     cfg = config(mode=mode, fixed_prefill_cus=160)
     check_invariants(SHAPE, profile(), cfg, [tuple(int(x) for x in r) for r in trace])
+
+
+def test_invariants_with_end_of_prefill_boost():
+    trace = synth.poisson_trace(7, 12.0, 8.0, dict(kind="lognormal", median=600, sigma=1.0, cap=8192),
+                                dict(kind="lognormal", median=250, sigma=0.9, cap=2048))
+    for mode in (0, 2, 4):
+        dec, _ = check_invariants(SHAPE, profile(), config(mode=mode, fixed_prefill_cus=160, decode_boost_cus=64),
+                                  [tuple(int(x) for x in r) for r in trace])
+        assert any(d[6] + d[7] > 256 for d in dec)
 
 
 def test_reorder_does_not_starve_long_request():

@@ -42,6 +42,16 @@ def test_replay_matches_oracle_on_conversational_traces(sts, rate, seed, mode):
     assert st["n_finished"] == len(trace)
 
 
+@pytest.mark.parametrize("mode", [0, 2, 4])
+def test_replay_matches_oracle_with_end_of_prefill_boost(sts, mode):
+    trace = synth.poisson_trace(8, 12.0, 6.0, IN3, OUT3)
+    cfg = dict(CFG3, mode=mode, fixed_prefill_cus=192, decode_boost_cus=64)
+    dec, st = run_both(sts, synth.llama8b_model(), sample_profile(), cfg, trace)
+    assert any(d[6] + d[7] > 256 for d in dec)
+    with pytest.raises(Exception):
+        sts.Profile(text=L.dump_profile(sample_profile())).replay(synth.llama8b_model(), dict(cfg, decode_boost_cus=20), trace)
+
+
 def test_replay_matches_oracle_on_long_prompts_and_70b(sts):
     trace = synth.poisson_trace(4, 1.0, 10.0, IN4, OUT4)
     cfg = dict(CFG3, max_batch_tokens=65536, kv_pool_pages=30000)
