@@ -62,6 +62,16 @@ class Config:
     decode_boost_cus: int = 0
 
 
+def chunked_prefill_iterations(sl, cs, ds):
+    """Chunked-prefill accounting (Section 2.2.2): with a token budget cs per hybrid batch of which
+    ds go to the running decode requests, a prompt of sl tokens needs N = ceil(sl / (cs - ds))
+    iterations, and chunk i (1-based) attends over the i chunks cached so far, N(N+1)/2 chunk
+    loads of KV cache in all. Returns (N, N(N+1)/2)."""
+    assert cs > ds >= 0 and sl >= 1
+    n = -(-sl // (cs - ds))
+    return n, n * (n + 1) // 2
+
+
 @dataclass
 class Req:
     rid: int

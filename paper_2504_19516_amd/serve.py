@@ -62,7 +62,9 @@ class LiveServer:
         whole GPU; every iteration runs one prompt chunk of at most `chunk_tokens` tokens through ALL
         layers (appended after the tokens of that prompt already cached, so its attention re-reads
         them) and then one decode step of the running batch, i.e. the hybrid batch of
-        chunk + decode tokens executed back to back. Prompts are taken in arrival order."""
+        chunk + decode tokens executed back to back. The token budget is shared as in Section 2.2.2:
+        the ds running decode requests come first, the prompt gets the remaining cs - ds tokens (at
+        least one). Prompts are taken in arrival order."""
         eng, desc = self.eng, self.desc
         n = self.n_cu
         rng = np.random.default_rng(seed)
@@ -97,7 +99,7 @@ class LiveServer:
                         time.sleep(wait * 1e-9)
                 continue
             if cur is not None:
-                m = min(chunk_tokens, cur.in_len - done_tokens)
+                m = min(max(1, chunk_tokens - len(D)), cur.in_len - done_tokens)
                 eng.prefill_launch([cur.seq], [cur.tokens[done_tokens:done_tokens + m]], 0, desc.n_layers,
                                    want_logits=(done_tokens + m == cur.in_len))
                 eng.prefill_finish()

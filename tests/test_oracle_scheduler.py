@@ -25,6 +25,18 @@ def config(**kw):
     return S.Config(**c)
 
 
+def test_chunked_prefill_accounting_by_brute_force():
+    """Section 2.2.2: count the iterations and the KV chunk loads by running the lock-step loop."""
+    for sl, cs, ds in ((16384, 1024, 0), (16384, 2048, 0), (1000, 512, 12), (513, 512, 0), (5, 512, 500), (4096, 256, 255)):
+        left, iters, loads = sl, 0, 0
+        while left > 0:
+            left -= min(cs - ds, left)
+            iters += 1
+            loads += iters                      # this chunk's attention reads every chunk cached so far, itself included
+        assert S.chunked_prefill_iterations(sl, cs, ds) == (iters, loads)
+    assert S.chunked_prefill_iterations(16384, 1024, 0) == (16, 136)
+
+
 def test_p90_is_nearest_rank():
     assert S.p90([]) == 0 and S.p90([5]) == 5
     assert S.p90(list(range(1, 11))) == 9                 # ceil(0.9 * 10) = 9th smallest
