@@ -186,29 +186,84 @@ class Profiler:
         return profile_text(self.hw, self.grids)
 
 
-def evaluate(prof_text, profiler: Profiler, log=print):
-    """MAPE of the profile's predictions on execution states outside the calibration grid."""
-    p = sts.Profile(text=prof_text)
-    desc = profiler.desc
-    errs_p, errs_d = [], []
-    for pm, t in ((96, 700), (160, 1536), (224, 3000), (256, 6000), (64, 5000), (128, 384), (200, 1300)):
+def measure_heldout(profiler: Profiler, n_prefill=24, n_decode=12, seed=11, step=None, log=print):
+    """Measured latencies of seeded execution states that are not calibration samples: a list of
+    (phase, execution state, measured ns). CU counts are multiples of `step` (default: the
+    scheduler's granule, the only counts Algorithm 1 can choose)."""
+    rng = np.random.default_rng(seed)
+    desc, n = profiler.desc, profiler.n_cu
+    step = step or profiler.granule
+    out = []
+    on_grid = step % profiler.granule == 0
+    fixed_p = [(96, 700), (160, 1536), (224, 3000), (256, 6000), (64, 5000), (128, 384), (192, 1300)] if on_grid else []
+    rand_p = [(int(rng.integers(32 // step, n // step + 1)) * step, int(rng.integers(200, 8000))) for _ in range(max(0, n_prefill - len(fixed_p)))]
+    for pm, t in fixed_p + rand_p:
         ns, layers = profiler.prefill_ns(pm, t)
         es = dict(prefill_len=[t], prefill_ctx=[0], prefill_cus=pm, decode_cus=0, layer_begin=0, n_layers_step=layers)
-        pred = p.query(desc, es)[0]
-        errs_p.append(abs(pred - ns) / ns)
-        log(f"prefill pm={pm} tokens={t}: measured {ns / 1e6:.3f} ms predicted {pred / 1e6:.3f} ms")
-    for dm, b, mc in ((96, 32, 1024), (160, 16, 512), (224, 48, 1500), (64, 64, 700), (256, 24, 3000)):
-        rng = np.random.default_rng(b)
-        ctxs = np.clip(rng.normal(mc, mc / 4, b), 16, 8000).astype(int)
+        out.append(("prefill", es, ns))
+        log(f"held-out prefill pm={pm} tokens={t}: measured {ns / 1e6:.3f} ms")
+    fixed_d = [(96, 32, 1024), (160, 16, 512), (224, 48, 1500), (64, 64, 700), (256, 24, 3000)] if on_grid else []
+    rand_d = [(int(rng.integers(32 // step, n // step + 1)) * step, int(rng.integers(4, 65)), int(rng.integers(200, 3000)))
+              for _ in range(max(0, n_decode - len(fixed_d)))]
+    for dm, b, mc in fixed_d + rand_d:
+        r2 = np.random.default_rng(b)
+        ctxs = np.clip(r2.normal(mc, mc / 4, b), 16, 8000).astype(int)
         seqs = profiler.make_decode_batch(ctxs)
         ns = profiler.decode_ns(dm, seqs)
         es = dict(decode_ctx=[profiler.eng.seq_length(s) for s in seqs], decode_cus=dm, prefill_cus=0)
-        pred = p.query(desc, es)[1]
-        errs_d.append(abs(pred - ns) / ns)
-        log(f"decode dm={dm} batch={b} mean ctx={mc}: measured {ns / 1e6:.3f} ms predicted {pred / 1e6:.3f} ms")
+        out.append(("decode", es, ns))
+        log(f"held-out decode dm={dm} batch={b} mean ctx={mc}: measured {ns / 1e6:.3f} ms")
         for s in seqs:
             profiler.eng.seq_free(s)
-    return float(np.mean(errs_p)), float(np.mean(errs_d))
+    return out
+
+
+def score(prof_text, desc, heldout, log=None):
+    """MAPE of a profile's predictions on the held-out states: (prefill, decode)."""
+    p = sts.Profile(text=prof_text)
+    errs = {"prefill": [], "decode": []}
+    for phase, es, ns in heldout:
+        pred = p.query(desc, es)[0 if phase == "prefill" else 1]
+        errs[phase].append(abs(pred - ns) / ns)
+        if log:
+            log(f"{phase} {({k: v for k, v in es.items() if k in ('prefill_len', 'prefill_cus', 'decode_cus')})}"
+                f"{' batch ' + str(len(es['decode_ctx'])) if phase == 'decode' else ''}: measured {ns / 1e6:.3f} ms predicted {pred / 1e6:.3f} ms")
+    return float(np.mean(errs["prefill"])) if errs["prefill"] else 0.0, float(np.mean(errs["decode"])) if errs["decode"] else 0.0
+
+
+def subsample(grid, keep):
+    """A calibration grid restricted to the axis positions in keep (one index list per axis)."""
+    axes, values = grid
+    v = np.asarray(values)
+    for ax, idx in enumerate(keep):
+        v = np.take(v, idx, axis=ax)
+    return [[axes[a][i] for i in idx] for a, idx in enumerate(keep)], v.tolist()
+
+
+def sample_count_study(profiler: Profiler, heldout, log=print):
+    """Accuracy against the number of calibration samples (the experiment of Table 2): profiles built
+    from subsets of the measured alpha grids, scored on the same held-out states; the small subsets
+    leave the larger held-out states outside their range (extrapolation)."""
+    gp, gd = profiler.grids["alpha_prefill"], profiler.grids["alpha_decode"]
+    npm, nt = len(gp[0][0]), len(gp[0][1])
+    ndm = len(gd[0][0])
+    every = lambda n, k: sorted(set(list(range(0, n, k)) + [n - 1]))
+    p_sets = [("ends of the CU axis, tokens <= %d" % gp[0][1][min(2, nt - 1)], [[0, npm - 1], list(range(min(3, nt)))]),
+              ("every other CU count, tokens <= %d" % gp[0][1][min(3, nt - 1)], [every(npm, 2), list(range(min(4, nt)))]),
+              ("full grid", [list(range(npm)), list(range(nt))])]
+    d_sets = [("ends of the CU axis", [[0, ndm - 1], [0, 1], [0, 1]]), ("full grid", [list(range(ndm)), [0, 1], [0, 1]])]
+    rows = []
+    for name, keep in p_sets:
+        grids = dict(profiler.grids, alpha_prefill=subsample(gp, keep))
+        mp, _ = score(profile_text(profiler.hw, grids), profiler.desc, heldout)
+        rows.append(("prefill", int(np.prod([len(k) for k in keep])), name, mp))
+    for name, keep in d_sets:
+        grids = dict(profiler.grids, alpha_decode=subsample(gd, keep))
+        _, md = score(profile_text(profiler.hw, grids), profiler.desc, heldout)
+        rows.append(("decode", int(np.prod([len(k) for k in keep])), name, md))
+    for phase, cnt, name, m in rows:
+        log(f"sample-count study: {phase} {cnt} samples ({name}): MAPE {100 * m:.1f} %")
+    return rows
 
 
 def main():
@@ -235,8 +290,17 @@ def main():
     text = pr.text()
     with open(args.out, "w") as f:
         f.write(text)
-    mp, md = evaluate(text, pr, log)
-    log(f"MAPE on held-out execution states: prefill {100 * mp:.1f} %, decode {100 * md:.1f} %")
+    heldout = measure_heldout(pr, log=log)
+    mp, md = score(text, desc, heldout, log)
+    log(f"MAPE on {len(heldout)} held-out execution states: prefill {100 * mp:.1f} %, decode {100 * md:.1f} %")
+    sample_count_study(pr, heldout, log)
+    # CU counts between the scheduler's grid points: the hardware deals workgroups to the shader engines of an
+    # XCD, not to its enabled CUs, so a count that leaves the engines unequal runs the one-workgroup-per-CU
+    # GEMMs in two rounds; Algorithm 1 never chooses such a count, the figure is reported for reference
+    off = [h for h in measure_heldout(pr, n_prefill=10, n_decode=6, seed=12, step=8, log=log)
+           if (h[1]["prefill_cus"] or h[1]["decode_cus"]) % pr.granule]
+    mpo, mdo = score(text, desc, off, log)
+    log(f"MAPE on {len(off)} execution states whose CU count is off the scheduler's grid: prefill {100 * mpo:.1f} %, decode {100 * mdo:.1f} %")
     if args.report:
         with open(args.report, "w") as f:
             f.write("\n".join(lines) + "\n")
