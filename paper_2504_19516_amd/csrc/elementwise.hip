@@ -312,29 +312,47 @@ hipError_t reduce_f32(hipStream_t s, float* out, const float* partials, int spli
 }
 
 // ------------------------------------------------------------------ greedy sampling
-__global__ void __launch_bounds__(256) argmax_kernel(int* out, const float* logits, int vocab) {
-  __shared__ float bv[256];
-  __shared__ int bi[256];
+// One workgroup of 1024 threads per row; 16-byte loads, four in flight per thread. The first
+// maximum wins: a thread scans its indices in ascending order and the tree keeps the lower index
+// on equal values.
+__global__ void __launch_bounds__(1024) argmax_kernel(int* out, const float* logits, int vocab) {
+  __shared__ float bv[1024];
+  __shared__ int bi[1024];
   const float* l = logits + (size_t)blockIdx.x * vocab;
   float best = -INFINITY; int idx = 0x7FFFFFFF;
-  for (int c = threadIdx.x; c < vocab; c += 256) {
-    const float v = l[c];
-    if (v > best) { best = v; idx = c; }           // ascending c: first maximum wins
+  auto take = [&](float v, int c) { if (v > best) { best = v; idx = c; } };
+  if ((vocab & 3) == 0) {
+    const float4* l4 = reinterpret_cast<const float4*>(l);
+    const int n4 = vocab >> 2;
+    int q = threadIdx.x;
+    for (; q + 3 * 1024 < n4; q += 4 * 1024) {
+      const float4 a = l4[q], b = l4[q + 1024], c = l4[q + 2048], d = l4[q + 3072];
+      take(a.x, 4 * q); take(a.y, 4 * q + 1); take(a.z, 4 * q + 2); take(a.w, 4 * q + 3);
+      take(b.x, 4 * q + 4096); take(b.y, 4 * q + 4097); take(b.z, 4 * q + 4098); take(b.w, 4 * q + 4099);
+      take(c.x, 4 * q + 8192); take(c.y, 4 * q + 8193); take(c.z, 4 * q + 8194); take(c.w, 4 * q + 8195);
+      take(d.x, 4 * q + 12288); take(d.y, 4 * q + 12289); take(d.z, 4 * q + 12290); take(d.w, 4 * q + 12291);
+    }
+    for (; q < n4; q += 1024) {
+      const float4 a = l4[q];
+      take(a.x, 4 * q); take(a.y, 4 * q + 1); take(a.z, 4 * q + 2); take(a.w, 4 * q + 3);
+    }
+  } else {
+    for (int c = threadIdx.x; c < vocab; c += 1024) take(l[c], c);
   }
   bv[threadIdx.x] = best; bi[threadIdx.x] = idx;
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (int o = 512; o > 0; o >>= 1) {
     if (threadIdx.x < o) {
       const float v = bv[threadIdx.x + o]; const int i = bi[threadIdx.x + o];
       if (v > bv[threadIdx.x] || (v == bv[threadIdx.x] && i < bi[threadIdx.x])) { bv[threadIdx.x] = v; bi[threadIdx.x] = i; }
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[blockIdx.x] = bi[0];
+  if (threadIdx.x == 0) out[blockIdx.x] = bi[0] == 0x7FFFFFFF ? 0 : bi[0];     // a row without any value above -inf
 }
 hipError_t argmax_rows(hipStream_t s, int* out, const float* logits, int n, int vocab) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(256), 0, s, out, logits, vocab);
+  hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(1024), 0, s, out, logits, vocab);
   return hipGetLastError();
 }
 

@@ -213,13 +213,16 @@ int k_collect(sts_ctx* c, Phase& ph) {
     STSCK(k_end(c, ph));                  \
   } while (0)
 
-int pick_cfg(int m, int n) {
+int pick_cfg(int m, int n, int k, int cus) {
   // decode batches: 64x128 tiles keep two workgroups (8 waves) per CU streaming weights, which
   // measured faster than 64x256 / 32x256 (one workgroup per CU) at every partition size
   if (m <= 64) return GEMM_64x128;
-  // 128x128 tiles leave room for two workgroups per CU (two waves per SIMD), which hides LDS
-  // and global latency better than one 256x256 workgroup; measured faster on every layer shape
-  return GEMM_128x128;
+  // up to 128 rows: one row of 128x128 tiles, two workgroups per CU. Above that both shapes compute
+  // 256 rows and the 256x256 tile's larger wave tiles run the MFMAs faster; a large decode batch
+  // on a small partition is compute-bound (Section 2.1). One 256x256 workgroup fills a CU, so the
+  // shape is taken only when its tiles times the deepest split-K still cover the partition.
+  const bool covers = (long long)(n / 256) * std::min(8, std::max(1, k / 512)) >= cus;
+  return (m <= 128 || n % 256 != 0 || !covers) ? GEMM_128x128 : GEMM_256x256_W8;
 }
 // Prefill GEMM tile choice for a partition of `cus` CUs: the candidate with the smallest
 // estimated time, which is where wave quantisation (paper Section 2.2.1) enters -- complete
@@ -263,7 +266,7 @@ hipError_t prefill_gemm(Phase& ph, int epi, const bf16* A, int lda, const bf16* 
 }
 int pick_splits(int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
-  int s = (2 * std::max(cus, 8) + tiles - 1) / tiles;          // two workgroups per CU of the partition
+  int s = (gemm_wgs_per_cu(cfg) * std::max(cus, 8) + tiles - 1) / tiles;      // fill the partition's workgroup slots
   s = std::min(s, std::max(1, k / 512));                        // at least 8 K-steps per slice
   return std::max(1, std::min(s, 8));
 }
@@ -383,7 +386,7 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
   if (le == d.n_layers && want_logits) {
     KL(ph, STS_K_HEAD, gather_rows_f32(st, ph.Xlast, ph.X, ph.d_rows, n_seqs, h));
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xlast_n, ph.Xlast, c->gf, d.rms_eps, n_seqs, h));
-    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n_seqs, d.vocab), EPI_F32, ph.Xlast_n, h, c->lm, h, ph.logits, d.vocab, n_seqs, d.vocab, h, 1, 0));
+    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n_seqs, d.vocab, h, ph.cus), EPI_F32, ph.Xlast_n, h, c->lm, h, ph.logits, d.vocab, n_seqs, d.vocab, h, 1, 0));
     HIPCK(hipMemcpyAsync(ph.h_logits, ph.logits, (size_t)n_seqs * d.vocab * sizeof(float), hipMemcpyDeviceToHost, st));
   }
   HIPCK(hipEventRecord(ph.ev1, st));
@@ -467,7 +470,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   auto skinny = [&](int kind, const bf16* A, int lda, const bf16* W, int N, int K, int* splits_out, long long* stride_out) -> int {
     const long long stride = (long long)n * N;
     *stride_out = stride;
-    const int cfg = pick_cfg(n, N);
+    const int cfg = pick_cfg(n, N, K, ph.cus);
     const int splits = pick_splits(cfg, n, N, K, ph.cus);
     *splits_out = splits;
     KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
@@ -488,7 +491,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, next_gain, d.rms_eps, n, h));
   }
   if (want_logits || want_next) {
-    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n, d.vocab), EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
+    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n, d.vocab, h, ph.cus), EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
     if (want_next) {
       KL(ph, STS_K_SAMPLE, argmax_rows(st, ph.next, ph.logits, n, d.vocab));
       HIPCK(hipMemcpyAsync(ph.h_next, ph.next, n * sizeof(int), hipMemcpyDeviceToHost, st));
