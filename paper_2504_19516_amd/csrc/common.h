@@ -30,6 +30,25 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave writes at
+// lds_dst + 16 * l (lds_dst must be wave-uniform); completion is counted by vmcnt. Buffers filled
+// this way are kept 1 KB above LDS address 0.
+__device__ __forceinline__ void load_to_lds16(const void* gsrc, void* lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+#endif
+}
+// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in
+// order); the other counters are left alone.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+#endif
+}
+
 // Workgroup id -> work item so that the workgroups resident on one XCD (hardware hands
 // consecutive ids to the 8 XCDs in turn) get a contiguous range of items and share its L2.
 __device__ __forceinline__ int xcd_contiguous(int bid, int per_xcd) { return (bid & 7) * per_xcd + (bid >> 3); }

@@ -442,10 +442,11 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     max_pages = std::max(max_pages, np);
     ph.h_tokens[i] = in_tokens[i];
   }
-  // Context chunks of a fixed page count: the largest of 32/16/8/4 pages that still yields about
-  // four workgroups per CU of the partition, never more than 128 chunks for the longest context.
+  // Context chunks of a fixed page count: the largest of 32/16/8 pages that still yields about
+  // four workgroups per CU of the partition (8 pages keep the four waves of a workgroup busy with
+  // one two-page block each), never more than 128 chunks for the longest context.
   int chunk_pages = attn_decode_max_chunk_tokens() / pt;
-  const int floor_pages = std::max(4, (max_pages + 127) / 128);
+  const int floor_pages = std::max(8, (max_pages + 127) / 128);
   while (chunk_pages / 2 >= floor_pages) {
     long long wgs = 0;
     for (int i = 0; i < n; i++) wgs += (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages;

@@ -240,24 +240,6 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
 }
 
 // ---- direct-to-LDS main loop ---------------------------------------------------------------
-// 16 bytes per lane from global memory straight into LDS: lane l of the wave writes at
-// lds_dst + 16 * l (lds_dst must be wave-uniform); completion is counted by vmcnt.
-__device__ __forceinline__ void load_to_lds16(const void* gsrc, void* lds_dst) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                   (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
-#endif
-}
-// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in
-// order); the other counters are left alone.
-template <int N>
-__device__ __forceinline__ void wait_vmem() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-#endif
-}
-
 // Tiles go global -> LDS without passing through registers (no staging VGPRs, no LDS store
 // instructions). A tile row is 128 bytes (BK = 64) and unpadded; the 16-byte K-chunk c of row r
 // is stored at slot c ^ ((r >> 1) & 7), which keeps the 16-byte operand reads bank-conflict

@@ -133,7 +133,9 @@ def test_prefill_attention(sts, t, prior, nq, nkv, d):
 
 @pytest.mark.parametrize("nq,nkv,d,ctx,chunks", [(4, 4, 64, [32, 256, 1, 17, 100], 32), (4, 4, 64, [250, 33], 4),
                                                  (32, 8, 128, [1000, 40, 513, 16], 8), (8, 1, 128, [700], 5),
-                                                 (32, 8, 128, [2048, 100], 16), (4, 4, 64, [129, 3], 1)])
+                                                 (32, 8, 128, [2048, 100], 16), (4, 4, 64, [129, 3], 1),
+                                                 (32, 8, 128, [3000, 1025, 64], 64), (8, 1, 128, [1500], 33),
+                                                 (16, 2, 128, [600, 31], 8), (4, 1, 64, [1100, 15], 64)])
 def test_decode_attention(sts, nq, nkv, d, ctx, chunks):
     """`chunks` = pages per context chunk."""
     n = len(ctx)
