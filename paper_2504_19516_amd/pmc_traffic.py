@@ -18,6 +18,7 @@ import collections
 import csv
 import json
 import os
+import re
 
 COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
 GATEUP_KERNEL = "gemm_dl_kernel"           # the SwiGLU instantiation is the gate/up GEMM
@@ -33,10 +34,10 @@ def per_kernel(path, counter):
     return rows
 
 
-def pick(rows, needle, also=None):
+def pick(rows, needle, pattern=None):
     vals = []
     for name, v in rows.items():
-        if needle in name and (also is None or also in name):
+        if needle in name and (pattern is None or re.search(pattern, name)):
             vals += v
     return vals
 
@@ -53,8 +54,8 @@ def main():
     for counter, path in (("FETCH_SIZE", args.fetch_csv), ("WRITE_SIZE", args.write_csv)):
         rows = per_kernel(path, counter)
         copy = pick(rows, COPY_KERNEL)
-        # SwiGLU epilogue = last template argument 3 of the 256x256 8-wave instantiation
-        gate = pick(rows, GATEUP_KERNEL, "ELi3EE") or pick(rows, GATEUP_KERNEL, ", 3>")
+        # SwiGLU epilogue = fifth template argument 3 (the sixth is the stage count), demangled or mangled name
+        gate = pick(rows, GATEUP_KERNEL, r"<\d+, \d+, \d+, \d+, 3, \d+>|ELi3ELi\d+EE")
         if not copy or not gate:
             raise SystemExit(f"{counter}: kernels not found in {path} (copy launches {len(copy)}, gate/up launches {len(gate)})")
         copy_mean, gate_mean = sum(copy) / len(copy), sum(gate) / len(gate)
