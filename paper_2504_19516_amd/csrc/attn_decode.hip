@@ -21,6 +21,15 @@ namespace sts {
 
 constexpr int MAX_CHUNK_TOKENS = 512;     // tokens per (request, kv head, chunk) workgroup
 
+// A context of n_pages is cut into ceil(n_pages / chunk_pages) chunks of EQUAL size (the last may be
+// shorter by less than the chunk count) instead of full chunks and a remainder: a workgroup with a
+// page or two is bound by the latency of its few dependent loads, and while it waits it holds one
+// of the two workgroup slots of its CU.
+__device__ __forceinline__ int balanced_chunk_pages(int n_pages, int chunk_pages) {
+  const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
+  return (n_pages + chunks - 1) / chunks;
+}
+
 __device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }
@@ -44,7 +53,8 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   const DecodeSeq sq = seqs[req];
   const int len = sq.cl + 1;
   const int n_pages = (len + 15) >> 4;
-  const int pg0 = chunk * chunk_pages, pg1 = min(n_pages, pg0 + chunk_pages);
+  const int cp = balanced_chunk_pages(n_pages, chunk_pages);
+  const int pg0 = chunk * cp, pg1 = min(n_pages, pg0 + cp);
   if (pg0 >= pg1) return;                 // this request has fewer chunks (the merge knows)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* wout = ws + (((size_t)req * geo.n_kv + kvh) * max_chunks + chunk) * G * (D + 2);
@@ -247,7 +257,8 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
   const DecodeSeq sq = seqs[req];
   const int len = sq.cl + 1;
   const int n_pages = (len + 15) >> 4;
-  const int pg0 = chunk * chunk_pages, pg1 = min(n_pages, pg0 + chunk_pages);
+  const int cp = balanced_chunk_pages(n_pages, chunk_pages);
+  const int pg0 = chunk * cp, pg1 = min(n_pages, pg0 + cp);
   if (pg0 >= pg1) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
   float* wout = ws + (((size_t)req * geo.n_kv + kvh) * max_chunks + chunk) * G * (D + 2);
