@@ -36,7 +36,7 @@ __device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
 
 template <int D, int G>
 __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict__ q, const DecodeSeq* __restrict__ seqs,
-                                                          const AttnItem* __restrict__ items,
+                                                          const DecodeItem* __restrict__ items,
                                                           const int* __restrict__ block_tables, const bf16* __restrict__ pool,
                                                           KvGeom geo, int n_q, int chunk_pages, int max_chunks,
                                                           float* __restrict__ ws, float scale_log2e) {
@@ -48,10 +48,9 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   __shared__ float red[4][G][D];
   __shared__ float stat_m[G], stat_l[G];
 
-  const AttnItem item = items[blockIdx.x];          // (request, chunk): only chunks that exist are launched
-  const int chunk = item.q0, kvh = blockIdx.y, req = item.seq;
-  const DecodeSeq sq = seqs[req];
-  const int len = sq.cl + 1;
+  const DecodeItem item = items[blockIdx.x];        // (request, chunk): only chunks that exist are launched
+  const int chunk = item.chunk, kvh = blockIdx.y, req = item.seq;
+  const int len = item.cl + 1;
   const int n_pages = (len + 15) >> 4;
   const int cp = balanced_chunk_pages(n_pages, chunk_pages);
   const int pg0 = chunk * cp, pg1 = min(n_pages, pg0 + cp);
@@ -59,7 +58,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* wout = ws + (((size_t)req * geo.n_kv + kvh) * max_chunks + chunk) * G * (D + 2);
   const int t0 = pg0 * 16, nt = min(len, pg1 * 16) - t0;
-  const int* bt = block_tables + sq.bt_off;
+  const int* bt = block_tables + item.bt_off;
   const size_t head_elems = geo.head_elems();
 
   // Page ids of the chunk, one per lane (a chunk has at most 32 pages); the loops below fetch
@@ -237,7 +236,7 @@ constexpr int attn_decode_mfma_lds() { return MFMA_LDS_BASE + 4 * 2 * 2 * 16 * D
 
 template <int D, int G>
 __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __restrict__ q, const DecodeSeq* __restrict__ seqs,
-                                                               const AttnItem* __restrict__ items,
+                                                               const DecodeItem* __restrict__ items,
                                                                const int* __restrict__ block_tables, const bf16* __restrict__ pool,
                                                                KvGeom geo, int n_q, int chunk_pages, int max_chunks,
                                                                float* __restrict__ ws, float scale_log2e) {
@@ -252,10 +251,9 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
   constexpr int LOADS = 2 * IPP + 2 * DB;            // vector-memory loads a wave issues per block (K to LDS + V^T to registers)
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const AttnItem item = items[blockIdx.x];
-  const int chunk = item.q0, kvh = blockIdx.y, req = item.seq;
-  const DecodeSeq sq = seqs[req];
-  const int len = sq.cl + 1;
+  const DecodeItem item = items[blockIdx.x];
+  const int chunk = item.chunk, kvh = blockIdx.y, req = item.seq;
+  const int len = item.cl + 1;
   const int n_pages = (len + 15) >> 4;
   const int cp = balanced_chunk_pages(n_pages, chunk_pages);
   const int pg0 = chunk * cp, pg1 = min(n_pages, pg0 + cp);
@@ -263,7 +261,7 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
   float* wout = ws + (((size_t)req * geo.n_kv + kvh) * max_chunks + chunk) * G * (D + 2);
   const int nt = min(len, pg1 * 16) - pg0 * 16;      // tokens of the chunk
-  const int* bt = block_tables + sq.bt_off;
+  const int* bt = block_tables + item.bt_off;
   const size_t head_elems = geo.head_elems();
   const int npg = pg1 - pg0, nblk = (npg + 1) >> 1;
   const int wv = __builtin_amdgcn_readfirstlane(wave);
@@ -471,7 +469,7 @@ constexpr int MAX_CHUNK_TOKENS_MFMA = 1024;
 int attn_decode_max_chunk_tokens() { return use_mfma_decode() ? MAX_CHUNK_TOKENS_MFMA : MAX_CHUNK_TOKENS; }
 
 template <int D, int G>
-static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const AttnItem* items, int n_items,
+static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
                           const int* bt, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
   if (use_mfma_decode()) {
     constexpr int lds = attn_decode_mfma_lds<D>();
@@ -487,7 +485,7 @@ static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeS
 // pages (at most attn_decode_max_chunk_tokens() tokens); `max_chunks` must be at least
 // the chunk count of the longest context. items: one (request, chunk index) record per chunk
 // that exists, n_items of them (device memory). ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
-hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const AttnItem* items, int n_items,
+hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
                        const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws) {
   if (n == 0 || n_items == 0) return hipSuccess;
   if (geo.page_tokens != 16 || n_q % geo.n_kv != 0 || chunk_pages < 1 || chunk_pages * 16 > attn_decode_max_chunk_tokens() || max_chunks < 1) return hipErrorInvalidValue;

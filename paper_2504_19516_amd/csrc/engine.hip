@@ -68,10 +68,10 @@ struct Phase {
   // two blocks, laid out afresh by every launch.
   unsigned char* h_meta = nullptr; unsigned char* d_meta = nullptr; size_t meta_bytes = 0, meta_used = 0;
   int* d_tokens = nullptr; int* d_bt = nullptr; int* d_rows = nullptr;
-  PrefillSeq* d_pseq = nullptr; DecodeSeq* d_dseq = nullptr; AttnItem* d_items = nullptr;
+  PrefillSeq* d_pseq = nullptr; DecodeSeq* d_dseq = nullptr; AttnItem* d_items = nullptr; DecodeItem* d_ditems = nullptr;
   // pinned staging
   int* h_tokens = nullptr; int* h_bt = nullptr; int* h_rows = nullptr;
-  PrefillSeq* h_pseq = nullptr; DecodeSeq* h_dseq = nullptr; AttnItem* h_items = nullptr;
+  PrefillSeq* h_pseq = nullptr; DecodeSeq* h_dseq = nullptr; AttnItem* h_items = nullptr; DecodeItem* h_ditems = nullptr;
   float* h_logits = nullptr; int* h_next = nullptr;
   int rows = 0;                               // rows of the last call
   // per-kernel timing
@@ -457,11 +457,11 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   // one attention workgroup row per context chunk that exists
   int n_items = 0;
   for (int i = 0; i < n; i++) n_items += (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages;
-  meta_take(ph, &ph.h_items, &ph.d_items, n_items);
+  meta_take(ph, &ph.h_ditems, &ph.d_ditems, n_items);
   if (ph.meta_used > ph.meta_bytes) return STS_EINVAL;
   n_items = 0;
   for (int i = 0; i < n; i++)
-    for (int ch = 0; ch < (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages; ch++) ph.h_items[n_items++] = AttnItem{i, ch};
+    for (int ch = 0; ch < (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages; ch++) ph.h_ditems[n_items++] = DecodeItem{i, ch, ph.h_dseq[i].cl, ph.h_dseq[i].bt_off};
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
   HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
@@ -482,7 +482,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     int sp; long long ss;
     STSCK(skinny(STS_K_QKV, ph.Xn, h, w.wqkv, c->qkvn, h, &sp, &ss));
     KL(ph, STS_K_ROPE, decode_qkv_finish(st, ph.part, sp, ss, c->qkvn, ph.d_dseq, ph.d_bt, c->inv_freq, ph.Q, layer_pool(c, l), c->geo, n, d.n_q_heads));
-    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_items, n_items, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
+    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_ditems, n_items, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
     STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
     STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
@@ -538,7 +538,7 @@ int alloc_phase(sts_ctx* c, int side) {
     const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
     // decode attention items: a context has at most 128 chunks, and never more than one per 4 pages
     const size_t dec_items = side == 1 ? nseq * std::min<size_t>(128, (mp + 3) / 4) : 0;
-    ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + sizeof(int)) + (items + dec_items) * sizeof(AttnItem) +
+    ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + sizeof(int)) + items * sizeof(AttnItem) + dec_items * sizeof(DecodeItem) +
                     rows * sizeof(int) + nseq * mp * sizeof(int) + 8 * 256;
     STSCK(dev_alloc(c, &ph.d_meta, ph.meta_bytes));
     STSCK(host_alloc(&ph.h_meta, ph.meta_bytes));

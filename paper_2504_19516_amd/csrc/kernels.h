@@ -44,6 +44,10 @@ struct DecodeSeq {
   int n_pages;     // pages covering positions 0..cl
 };
 
+// One context chunk of one decode request, with what its workgroup needs to start: a single
+// 16-byte load instead of a chain through the per-request record.
+struct DecodeItem { int seq; int chunk; int cl; int bt_off; };
+
 // ---- element-wise / small kernels ---------------------------------------------------------
 hipError_t init_weight(hipStream_t s, bf16* dst, int ld, uint64_t seed, uint64_t tensor_id, int rows, int cols,
                        int row_offset, int interleave_block, int interleave_phase);
@@ -81,7 +85,7 @@ hipError_t attn_prefill(hipStream_t s, const bf16* qkv, int ld, bf16* out, int l
                         KvGeom geo, int n_q);
 int attn_prefill_tile_q();
 size_t attn_decode_ws_floats(int n, int n_q, int d, int max_chunks);
-hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const AttnItem* items, int n_items,
+hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
                        const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws);
 int attn_decode_max_chunk_tokens();
 

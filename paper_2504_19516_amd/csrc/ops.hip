@@ -189,11 +189,11 @@ extern "C" int sts_op_attn_decode(const float* q, const float* k, const float* v
     if (kv_write_tokens(nullptr, pool, geo, d_bt + (size_t)i * max_pages, 0, ctx[i], dk + off * n_kv * d, dv + off * n_kv * d) != hipSuccess) return STS_EHIP;
     off += ctx[i];
   }
-  std::vector<AttnItem> items;
+  std::vector<DecodeItem> items;
   for (int i = 0; i < n; i++)
-    for (int ch = 0; ch < (seqs[i].n_pages + chunk_pages - 1) / chunk_pages; ch++) items.push_back(AttnItem{i, ch});
-  AttnItem* d_items = b.get<AttnItem>(items.size());
-  if (!d_items || hipMemcpy(d_items, items.data(), items.size() * sizeof(AttnItem), hipMemcpyHostToDevice) != hipSuccess) return STS_EHIP;
+    for (int ch = 0; ch < (seqs[i].n_pages + chunk_pages - 1) / chunk_pages; ch++) items.push_back(DecodeItem{i, ch, seqs[i].cl, seqs[i].bt_off});
+  DecodeItem* d_items = b.get<DecodeItem>(items.size());
+  if (!d_items || hipMemcpy(d_items, items.data(), items.size() * sizeof(DecodeItem), hipMemcpyHostToDevice) != hipSuccess) return STS_EHIP;
   hipError_t e = attn_decode(nullptr, dq, dout, d_seq, d_items, (int)items.size(), d_bt, pool, geo, n, n_q, chunk_pages, max_chunks, ws);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
   int rc = download_bf16(b, out, dout, (size_t)n * n_q * d);
