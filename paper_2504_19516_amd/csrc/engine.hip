@@ -266,9 +266,23 @@ hipError_t prefill_gemm(Phase& ph, int epi, const bf16* A, int lda, const bf16* 
 }
 int pick_splits(int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
-  int s = (gemm_wgs_per_cu(cfg) * std::max(cus, 8) + tiles - 1) / tiles;      // fill the partition's workgroup slots
-  s = std::min(s, std::max(1, k / 512));                        // at least 8 K-steps per slice
-  return std::max(1, std::min(s, 8));
+  const int slots = gemm_wgs_per_cu(cfg) * std::max(cus, 8);
+  const int s_max = std::min(8, std::max(1, k / 512));            // at least 8 K-steps per slice
+  if (gemm_wgs_per_cu(cfg) == 1) {
+    // one workgroup owns a CU, so rounds of workgroups are strict: estimated time of s slices =
+    // ceil(tiles * s / slots) rounds of a 1/s tile at 4.8 TFLOP/s per CU, plus the fp32 partial
+    // sums written and read back (about 20 GB/s per CU); the cheapest s wins
+    const double tile_s = 2.0 * gemm_tile_m(cfg) * gemm_tile_n(cfg) * k / 4.8e12;
+    const double part_s = 8.0 * m * n / (std::max(cus, 8) * 20e9);
+    int best = 1; double best_t = 1e300;
+    for (int s = 1; s <= s_max; s++) {
+      const double t = (double)(((long long)tiles * s + slots - 1) / slots) * tile_s / s + s * part_s;
+      if (t < best_t - 1e-9) { best_t = t; best = s; }
+    }
+    return best;
+  }
+  const int s = (slots + tiles - 1) / tiles;                        // fill the partition's workgroup slots
+  return std::max(1, std::min(s, s_max));
 }
 
 int64_t now_ns();

@@ -201,6 +201,35 @@ def test_split_and_neighbour_independence(sts, tiny, eng):
         assert rel(o[1], outs[0][1]) <= 1e-3
 
 
+@pytest.mark.parametrize("dm", [8, 256])
+def test_large_decode_batch_matches_oracle(sts, tiny, dm):
+    """160 decode requests in one step (more than 128 rows: on 8 CUs the gate/up projection takes
+    the 256x256 tiles, on 256 CUs the 128x128 ones) against the oracle, request by request."""
+    desc, w = tiny
+    n = 160
+    ctx = synth.uniform_lengths(7, n, 5, 60)
+    ctx_tokens = [synth.tokens(300 + i, int(c), desc.vocab) for i, c in enumerate(ctx)]
+    dec_tokens = synth.tokens(299, n, desc.vocab)
+    eng = new_engine(sts, desc, kv_pool_pages=1000, max_decode_batch=n, max_seqs=n + 4)
+    seqs = gpu_contexts(eng, ctx_tokens)
+    eng.set_partition(256, dm)
+    got, nxt = eng.decode_step(seqs, dec_tokens)
+    eng.close()
+    orc = T.Oracle(desc, w, 1000)
+    page = 0
+    for i, c in enumerate(ctx):
+        k = (int(c) + 1 + 15) // 16
+        orc.kv.add_sequence(i, list(range(page, page + k)))
+        page += k
+        orc.prefill_append(i, ctx_tokens[i])
+    ref = orc.decode_step(list(range(n)), dec_tokens)
+    assert rel(got, ref) <= TOL
+    # greedy sampling: the chosen token's reference logit is within the tolerance of the reference maximum
+    for i in range(n):
+        assert ref[i, nxt[i]] >= ref[i].max() - TOL * np.abs(ref).max()
+        assert nxt[i] == int(np.argmax(got[i]))
+
+
 def test_decode_equals_row_of_full_recompute(sts, tiny, eng):
     desc, _ = tiny
     toks = synth.tokens(31, 77, desc.vocab)
