@@ -268,7 +268,7 @@ int pick_splits(int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
   const int slots = gemm_wgs_per_cu(cfg) * std::max(cus, 8);
   const int s_max = std::min(8, std::max(1, k / 512));            // at least 8 K-steps per slice
-  if (gemm_wgs_per_cu(cfg) == 1) {
+  if (gemm_wgs_per_cu(cfg) == 1 && gemm_tile_m(cfg) >= 256) {
     // one workgroup owns a CU, so rounds of workgroups are strict: estimated time of s slices =
     // ceil(tiles * s / slots) rounds of a 1/s tile at 4.8 TFLOP/s per CU, plus the fp32 partial
     // sums written and read back (about 20 GB/s per CU); the cheapest s wins
@@ -283,6 +283,21 @@ int pick_splits(int cfg, int m, int n, int k, int cus) {
   }
   const int s = (slots + tiles - 1) / tiles;                        // fill the partition's workgroup slots
   return std::max(1, std::min(s, s_max));
+}
+
+// Tile shape and split-K of one decode GEMM. Up to 64 rows the choice is between 64x128 tiles (two
+// workgroups per CU) and 64x256 tiles (one 8-wave workgroup per CU): the wide tile re-reads the
+// activation rows half as often, which measured 13 % faster per weight byte, but its rounds are
+// strict where two narrow workgroups per CU balance in half rounds.
+void pick_decode_gemm(int m, int n, int k, int cus, bool may_split, int* cfg, int* splits) {
+  *cfg = pick_cfg(m, n, k, cus);
+  *splits = may_split ? pick_splits(*cfg, m, n, k, cus) : 1;
+  if (*cfg != GEMM_64x128 || m <= 32 || n % 256 != 0) return;
+  const int c = std::max(cus, 8);
+  const int sw = may_split ? pick_splits(GEMM_64x256, m, n, k, cus) : 1;
+  const double t_narrow = 0.5 * (((long long)(n / 128) * *splits + c - 1) / c) / *splits;
+  const double t_wide = 0.87 * (((long long)(n / 256) * sw + c - 1) / c) / sw;
+  if (t_wide < t_narrow) { *cfg = GEMM_64x256; *splits = sw; }
 }
 
 int64_t now_ns();
@@ -485,8 +500,8 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   auto skinny = [&](int kind, const bf16* A, int lda, const bf16* W, int N, int K, int* splits_out, long long* stride_out) -> int {
     const long long stride = (long long)n * N;
     *stride_out = stride;
-    const int cfg = pick_cfg(n, N, K, ph.cus);
-    const int splits = pick_splits(cfg, n, N, K, ph.cus);
+    int cfg, splits;
+    pick_decode_gemm(n, N, K, ph.cus, true, &cfg, &splits);
     *splits_out = splits;
     KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
     return STS_OK;
@@ -506,7 +521,9 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, next_gain, d.rms_eps, n, h));
   }
   if (want_logits || want_next) {
-    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n, d.vocab, h, ph.cus), EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
+    int head_cfg, head_splits;
+    pick_decode_gemm(n, d.vocab, h, ph.cus, false, &head_cfg, &head_splits);
+    KL(ph, STS_K_HEAD, gemm_bf16(st, head_cfg, EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
     if (want_next) {
       KL(ph, STS_K_SAMPLE, argmax_rows(st, ph.next, ph.logits, n, d.vocab));
       HIPCK(hipMemcpyAsync(ph.h_next, ph.next, n * sizeof(int), hipMemcpyDeviceToHost, st));

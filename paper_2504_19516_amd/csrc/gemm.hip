@@ -492,7 +492,7 @@ static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int spli
     case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI>(s, g, splits, tail);
     case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI, 2>(s, g, splits, tail);
     case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI>(s, g, splits, tail);
+    case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 8, EPI, 3>(s, g, splits, tail);
     case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits, tail);
     case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI, GEMM_64x128_STAGES>(s, g, splits, tail);
     case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits, tail);
@@ -521,7 +521,7 @@ int gemm_tile_m(int cfg) {
 // K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1.
 // With splits > 1 (EPI_F32 only) partial sums go to C + z * split_stride. With `tail` (splits == 1)
 // the tiles of the last, partly filled wave of workgroups are cut along K (see GemmArgs).
-int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_256x256_W8 || cfg == GEMM_256x128 ? 1 : 2; }
+int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_256x256_W8 || cfg == GEMM_256x128 || cfg == GEMM_64x256 ? 1 : 2; }
 
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
                      void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail) {
