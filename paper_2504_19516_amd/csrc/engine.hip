@@ -297,7 +297,7 @@ void pick_decode_gemm(int m, int n, int k, int cus, bool may_split, int* cfg, in
   const int sw = may_split ? pick_splits(GEMM_64x256, m, n, k, cus) : 1;
   const double t_narrow = 0.5 * (((long long)(n / 128) * *splits + c - 1) / c) / *splits;
   const double t_wide = 0.87 * (((long long)(n / 256) * sw + c - 1) / c) / sw;
-  if (t_wide < t_narrow) { *cfg = GEMM_64x256; *splits = sw; }
+  if (t_wide < 0.95 * t_narrow) { *cfg = GEMM_64x256; *splits = sw; }     // a near tie goes to the tiles that balance
 }
 
 int64_t now_ns();
