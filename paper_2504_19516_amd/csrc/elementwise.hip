@@ -114,27 +114,85 @@ __device__ __forceinline__ float block_sum(float v, float* red) {   // red: one 
   return t;
 }
 
-__global__ void __launch_bounds__(256) rmsnorm_kernel(bf16* out, const float* X, const float* gain, float eps, int h) {
-  __shared__ float red[16];
-  const float* x = X + (size_t)blockIdx.x * h;
-  float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < h; c += 1024) {
-    f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
-    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-  }
-  const float inv = rsqrtf(block_sum(ss, red) / (float)h + eps);
-  for (int c = threadIdx.x * 4; c < h; c += 1024) {
-    f32x4 v = *reinterpret_cast<const f32x4*>(x + c);
-    f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
-    bf16x4 o;
+// A workgroup normalises R rows at once: all their loads are issued before the first reduction, so
+// the launch is one round of latency-bound workgroups instead of two. Rows of up to 4096 * PER / 4
+// elements stay in registers between the sum of squares and the scaling (PER 16-byte loads per
+// thread and row); longer rows are read a second time.
+template <int R, int PER>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(bf16* out, const float* X, const float* gain, float eps, int h, int n) {
+  __shared__ float red[R][16];
+  const int row0 = blockIdx.x * R;
+  const bool in_regs = h <= 1024 * PER;
+  f32x4 v[R][PER];
+  float ss[R];
 #pragma unroll
-    for (int j = 0; j < 4; j++) o[j] = f2bf(v[j] * inv * g[j]);
-    *reinterpret_cast<bf16x4*>(out + (size_t)blockIdx.x * h + c) = o;
+  for (int r = 0; r < R; r++) {
+    ss[r] = 0.f;
+    const float* x = X + (size_t)min(row0 + r, n - 1) * h;
+    if (in_regs) {
+#pragma unroll
+      for (int i = 0; i < PER; i++) {
+        const int c = threadIdx.x * 4 + i * 1024;
+        v[r][i] = c < h ? *reinterpret_cast<const f32x4*>(x + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    if (in_regs) {
+#pragma unroll
+      for (int i = 0; i < PER; i++) ss[r] += v[r][i][0] * v[r][i][0] + v[r][i][1] * v[r][i][1] + v[r][i][2] * v[r][i][2] + v[r][i][3] * v[r][i][3];
+    } else {
+      const float* x = X + (size_t)min(row0 + r, n - 1) * h;
+      for (int c = threadIdx.x * 4; c < h; c += 1024) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(x + c);
+        ss[r] += t[0] * t[0] + t[1] * t[1] + t[2] * t[2] + t[3] * t[3];
+      }
+    }
+  }
+  // block sums of the R rows with one pair of barriers
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    const float w = wave_sum(ss[r]);
+    if (lane == 0) red[r][wave] = w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    if (row0 + r >= n) break;
+    const float tot = red[r][0] + red[r][1] + red[r][2] + red[r][3];
+    const float inv = rsqrtf(tot / (float)h + eps);
+    const float* x = X + (size_t)(row0 + r) * h;
+    bf16* o_row = out + (size_t)(row0 + r) * h;
+    if (in_regs) {
+#pragma unroll
+      for (int i = 0; i < PER; i++) {
+        const int c = threadIdx.x * 4 + i * 1024;
+        if (c < h) {
+          const f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; j++) o[j] = f2bf(v[r][i][j] * inv * g[j]);
+          *reinterpret_cast<bf16x4*>(o_row + c) = o;
+        }
+      }
+    } else {
+      for (int c = threadIdx.x * 4; c < h; c += 1024) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(x + c);
+        const f32x4 g = *reinterpret_cast<const f32x4*>(gain + c);
+        bf16x4 o;
+#pragma unroll
+        for (int j = 0; j < 4; j++) o[j] = f2bf(t[j] * inv * g[j]);
+        *reinterpret_cast<bf16x4*>(o_row + c) = o;
+      }
+    }
   }
 }
 hipError_t rmsnorm_rows(hipStream_t s, bf16* out, const float* X, const float* gain, float eps, int n, int h) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3(n), dim3(256), 0, s, out, X, gain, eps, h);
+  if (n >= 1024) hipLaunchKernelGGL((rmsnorm_kernel<2, 4>), dim3((n + 1) / 2), dim3(256), 0, s, out, X, gain, eps, h, n);
+  else hipLaunchKernelGGL((rmsnorm_kernel<1, 8>), dim3(n), dim3(256), 0, s, out, X, gain, eps, h, n);
   return hipGetLastError();
 }
 
