@@ -217,17 +217,22 @@ __global__ void __launch_bounds__(256) rope_kv_prefill_kernel(bf16* qkv, int ld,
   __syncthreads();
   const int page = block_tables[sq.bt_off + pos / geo.page_tokens], slot = pos % geo.page_tokens;
   bf16* r = qkv + (size_t)row * ld;
-  const int n_rot = (n_q + geo.n_kv) * half;
+  // eight rotation pairs (two 16-byte loads, two 16-byte stores) per work item
+  const int per_head = half >> 3, n_rot = (n_q + geo.n_kv) * per_head;
   for (int t = threadIdx.x; t < n_rot; t += blockDim.x) {
-    const int hd = t / half, i = t % half;
-    const float a = bf2f(r[hd * d + i]), b = bf2f(r[hd * d + i + half]);
-    const bf16 ya = f2bf(a * cs[i] - b * sn[i]), yb = f2bf(a * sn[i] + b * cs[i]);
-    if (hd < n_q) {
-      r[hd * d + i] = ya; r[hd * d + i + half] = yb;
-    } else {
-      bf16* k = pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
-      k[i] = ya; k[i + half] = yb;
+    const int hd = t / per_head, i0 = (t % per_head) * 8;
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(r + hd * d + i0);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(r + hd * d + i0 + half);
+    bf16x8 ya, yb;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float fa = bf2f(a[e]), fb = bf2f(b[e]);
+      ya[e] = f2bf(fa * cs[i0 + e] - fb * sn[i0 + e]);
+      yb[e] = f2bf(fa * sn[i0 + e] + fb * cs[i0 + e]);
     }
+    bf16* dst = hd < n_q ? r + hd * d : pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
+    *reinterpret_cast<bf16x8*>(dst + i0) = ya;
+    *reinterpret_cast<bf16x8*>(dst + i0 + half) = yb;
   }
   const bf16* vsrc = r + (n_q + geo.n_kv) * d;
   for (int t = threadIdx.x; t < geo.n_kv * d; t += blockDim.x) {
