@@ -346,18 +346,25 @@ hipError_t reduce_resid_norm(hipStream_t s, float* X, const float* partials, int
 }
 
 // H[row][j] = silu(sum gate_j) * sum up_j; gate/up columns are interleaved in blocks of 32.
-__global__ void reduce_swiglu_kernel(bf16* H, const float* partials, int splits, long long split_stride, int mlp) {
+__global__ void __launch_bounds__(256) reduce_swiglu_kernel(bf16* H, const float* partials, int splits, long long split_stride, int mlp) {
   const int row = blockIdx.y;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;         // four consecutive outputs, inside one block of 32
   if (j >= mlp) return;
   const float* p = partials + (size_t)row * 2 * mlp + (j >> 5) * 64 + (j & 31);
-  float g = 0.f, u = 0.f;
-  for (int z = 0; z < splits; z++) { g += p[z * split_stride]; u += p[z * split_stride + 32]; }
-  H[(size_t)row * mlp + j] = f2bf(g / (1.f + __expf(-g)) * u);
+  f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < splits; z++) {
+    g += *reinterpret_cast<const f32x4*>(p + z * split_stride);
+    u += *reinterpret_cast<const f32x4*>(p + z * split_stride + 32);
+  }
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; e++) o[e] = f2bf(g[e] / (1.f + __expf(-g[e])) * u[e]);
+  *reinterpret_cast<bf16x4*>(H + (size_t)row * mlp + j) = o;
 }
 hipError_t reduce_swiglu(hipStream_t s, bf16* H, const float* partials, int splits, long long split_stride, int n, int mlp) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((mlp + 255) / 256, n), dim3(256), 0, s, H, partials, splits, split_stride, mlp);
+  if (mlp % 32 != 0 || split_stride % 4 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((mlp / 4 + 255) / 256, n), dim3(256), 0, s, H, partials, splits, split_stride, mlp);
   return hipGetLastError();
 }
 
