@@ -273,29 +273,39 @@ __global__ void __launch_bounds__(256) decode_qkv_finish_kernel(const float* par
   __syncthreads();
   const int page = block_tables[sq.bt_off + pos / geo.page_tokens], slot = pos % geo.page_tokens;
   const float* pr = partials + (size_t)row * ld;
-  for (int t = threadIdx.x; t < (slot1 - slot0) * half; t += blockDim.x) {
-    const int hd = slot0 + t / half, i = t % half;
-    if (hd < n_q + geo.n_kv) {
-      float a = 0.f, b = 0.f;
-      for (int z = 0; z < splits; z++) { a += pr[z * split_stride + hd * d + i]; b += pr[z * split_stride + hd * d + i + half]; }
-      // the projection's result is rounded to bf16 before the rotation, as in the prefill path
-      a = bf2f(f2bf(a)); b = bf2f(f2bf(b));
-      const bf16 ya = f2bf(a * cs[i] - b * sn[i]), yb = f2bf(a * sn[i] + b * cs[i]);
-      if (hd < n_q) {
-        q_out[(size_t)row * n_q * d + hd * d + i] = ya; q_out[(size_t)row * n_q * d + hd * d + i + half] = yb;
-      } else {
-        bf16* k = pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
-        k[i] = ya; k[i + half] = yb;
+  // a work item is four consecutive rotation pairs of a Q or K head, or four consecutive elements of a V head
+  const int per_rot = half >> 2, per_v = d >> 2;
+  const int n_rot_slots = max(0, min(slot1, n_q + geo.n_kv) - slot0), n_v_slots = (slot1 - slot0) - n_rot_slots;
+  const int n_items = n_rot_slots * per_rot + n_v_slots * per_v;
+  for (int t = threadIdx.x; t < n_items; t += blockDim.x) {
+    if (t < n_rot_slots * per_rot) {
+      const int hd = slot0 + t / per_rot, i0 = (t % per_rot) * 4;
+      f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+      for (int z = 0; z < splits; z++) {
+        a += *reinterpret_cast<const f32x4*>(pr + z * split_stride + hd * d + i0);
+        b += *reinterpret_cast<const f32x4*>(pr + z * split_stride + hd * d + i0 + half);
       }
-    } else {                                   // a V head: two elements per work item, no rotation
+      bf16x4 ya, yb;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        // the projection's result is rounded to bf16 before the rotation, as in the prefill path
+        const float fa = bf2f(f2bf(a[e])), fb = bf2f(f2bf(b[e]));
+        ya[e] = f2bf(fa * cs[i0 + e] - fb * sn[i0 + e]);
+        yb[e] = f2bf(fa * sn[i0 + e] + fb * cs[i0 + e]);
+      }
+      bf16* dst = hd < n_q ? q_out + (size_t)row * n_q * d + hd * d
+                           : pool + ((size_t)page * geo.n_kv + (hd - n_q)) * geo.head_elems() + (size_t)slot * d;
+      *reinterpret_cast<bf16x4*>(dst + i0) = ya;
+      *reinterpret_cast<bf16x4*>(dst + i0 + half) = yb;
+    } else {
+      const int tv = t - n_rot_slots * per_rot;
+      const int hd = slot0 + n_rot_slots + tv / per_v, dd0 = (tv % per_v) * 4;
       const int vh = hd - n_q - geo.n_kv;
+      f32x4 a = {0.f, 0.f, 0.f, 0.f};
+      for (int z = 0; z < splits; z++) a += *reinterpret_cast<const f32x4*>(pr + z * split_stride + hd * d + dd0);
       bf16* v = pool + ((size_t)page * geo.n_kv + vh) * geo.head_elems() + (size_t)geo.page_tokens * d;
-      for (int e = 0; e < 2; e++) {
-        const int dd = i + e * half;
-        float a = 0.f;
-        for (int z = 0; z < splits; z++) a += pr[z * split_stride + hd * d + dd];
-        v[(size_t)dd * geo.page_tokens + slot] = f2bf(a);
-      }
+#pragma unroll
+      for (int e = 0; e < 4; e++) v[(size_t)(dd0 + e) * geo.page_tokens + slot] = f2bf(a[e]);
     }
   }
 }
