@@ -434,27 +434,31 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
   }
 }
 
-// Merge the chunks of one (request, query head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
+// Merge the chunks of one (request, KV head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m) for
+// each of the G query heads of the group. One workgroup per (request, KV head): a few fat workgroups
+// instead of one per query head, whose count made the launch latency-bound on a small partition.
 template <int D>
-__global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
-                                         int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
-  const int head = blockIdx.x, req = blockIdx.y, dd = threadIdx.x;
-  const int kvh = head / G, g = head % G;
+__global__ void __launch_bounds__(256) attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
+                                                                int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
+  const int kvh = blockIdx.x, req = blockIdx.y;
   const int n_pages = (seqs[req].cl + 1 + 15) >> 4;
   const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
-  const float* base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * G * (D + 2) + g * (D + 2);
   const size_t cstride = (size_t)G * (D + 2);
-  float m = -INFINITY;
-  for (int c = 0; c < chunks; c++) m = fmaxf(m, base[c * cstride + D]);
-  float l = 0.f, o = 0.f;
-  for (int c = 0; c < chunks; c++) {
-    const float w = __builtin_amdgcn_exp2f(base[c * cstride + D] - m);
-    l += base[c * cstride + D + 1] * w;
-    o += base[c * cstride + dd] * w;
+  const float* kv_base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * cstride;
+  for (int i = threadIdx.x; i < G * D; i += 256) {
+    const int g = i / D, dd = i % D;
+    const float* base = kv_base + g * (D + 2);
+    float m = -INFINITY;
+    for (int c = 0; c < chunks; c++) m = fmaxf(m, base[c * cstride + D]);
+    float l = 0.f, o = 0.f;
+    for (int c = 0; c < chunks; c++) {
+      const float w = __builtin_amdgcn_exp2f(base[c * cstride + D] - m);
+      l += base[c * cstride + D + 1] * w;
+      o += base[c * cstride + dd] * w;
+    }
+    out[((size_t)req * n_q + kvh * G + g) * D + dd] = f2bf(o / l);
   }
-  out[((size_t)req * n_q + head) * D + dd] = f2bf(o / l);
 }
-
 
 size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks) { return (size_t)n * n_q * chunks * (d + 2); }
 
@@ -478,7 +482,7 @@ static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeS
     hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
   } else
     hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), 0, s, q, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
+  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(geo.n_kv, n), dim3(256), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
 }
 
 // q, out: [n, n_q * d] bf16 (q already rotated). A context is cut into chunks of `chunk_pages`
