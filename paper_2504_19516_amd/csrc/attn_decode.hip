@@ -235,7 +235,7 @@ template <int D>
 constexpr int attn_decode_mfma_lds() { return MFMA_LDS_BASE + 4 * 2 * 2 * 16 * D * 2; }   // 4 waves x 2 stages x 2 pages of K
 
 template <int D, int G>
-__global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __restrict__ q, const DecodeSeq* __restrict__ seqs,
+__global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, const DecodeSeq* __restrict__ seqs,
                                                                const DecodeItem* __restrict__ items,
                                                                const int* __restrict__ block_tables, const bf16* __restrict__ pool,
                                                                KvGeom geo, int n_q, int chunk_pages, int max_chunks,
@@ -420,11 +420,22 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
       for (int r = 0; r < 16; r++) red[(wv * G + l32) * D + bb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)] = o[bb][r] * f;
   }
   __syncthreads();
+  // a context that fits one chunk needs no merge: normalise and store the attention output itself
+  const bool single = n_pages <= chunk_pages;
   for (int i = tid; i < G * D; i += 256) {
     const int g = i / D;
-    wout[g * (D + 2) + i % D] = red[i] + red[G * D + i] + red[2 * G * D + i] + red[3 * G * D + i];
+    const float o_sum = red[i] + red[G * D + i] + red[2 * G * D + i] + red[3 * G * D + i];
+    if (single) {
+      const float mall = fmaxf(fmaxf(sm[g], sm[G + g]), fmaxf(sm[2 * G + g], sm[3 * G + g]));
+      float l = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; w++) l += (sm[w * G + g] == -INFINITY) ? 0.f : sl[w * G + g] * __builtin_amdgcn_exp2f(sm[w * G + g] - mall);
+      out[((size_t)req * n_q + kvh * G + g) * D + i % D] = f2bf(o_sum / l);
+    } else {
+      wout[g * (D + 2) + i % D] = o_sum;
+    }
   }
-  if (tid < G) {
+  if (!single && tid < G) {
     const float mall = fmaxf(fmaxf(sm[tid], sm[G + tid]), fmaxf(sm[2 * G + tid], sm[3 * G + tid]));
     float l = 0.f;
 #pragma unroll
@@ -434,31 +445,28 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
   }
 }
 
-// Merge the chunks of one (request, KV head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m) for
-// each of the G query heads of the group. One workgroup per (request, KV head): a few fat workgroups
-// instead of one per query head, whose count made the launch latency-bound on a small partition.
+// Merge the chunks of one (request, query head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 template <int D>
-__global__ void __launch_bounds__(256) attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
-                                                                int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
-  const int kvh = blockIdx.x, req = blockIdx.y;
+__global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
+                                         int n_q, int n_kv, int G, int chunk_pages, int max_chunks, int skip_single) {
+  const int head = blockIdx.x, req = blockIdx.y, dd = threadIdx.x;
+  const int kvh = head / G, g = head % G;
   const int n_pages = (seqs[req].cl + 1 + 15) >> 4;
   const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
+  if (skip_single && chunks == 1) return;          // the attention kernel stored this request's output itself
+  const float* base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * G * (D + 2) + g * (D + 2);
   const size_t cstride = (size_t)G * (D + 2);
-  const float* kv_base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * cstride;
-  for (int i = threadIdx.x; i < G * D; i += 256) {
-    const int g = i / D, dd = i % D;
-    const float* base = kv_base + g * (D + 2);
-    float m = -INFINITY;
-    for (int c = 0; c < chunks; c++) m = fmaxf(m, base[c * cstride + D]);
-    float l = 0.f, o = 0.f;
-    for (int c = 0; c < chunks; c++) {
-      const float w = __builtin_amdgcn_exp2f(base[c * cstride + D] - m);
-      l += base[c * cstride + D + 1] * w;
-      o += base[c * cstride + dd] * w;
-    }
-    out[((size_t)req * n_q + kvh * G + g) * D + dd] = f2bf(o / l);
+  float m = -INFINITY;
+  for (int c = 0; c < chunks; c++) m = fmaxf(m, base[c * cstride + D]);
+  float l = 0.f, o = 0.f;
+  for (int c = 0; c < chunks; c++) {
+    const float w = __builtin_amdgcn_exp2f(base[c * cstride + D] - m);
+    l += base[c * cstride + D + 1] * w;
+    o += base[c * cstride + dd] * w;
   }
+  out[((size_t)req * n_q + head) * D + dd] = f2bf(o / l);
 }
+
 
 size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks) { return (size_t)n * n_q * chunks * (d + 2); }
 
@@ -479,10 +487,10 @@ static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeS
     constexpr int lds = attn_decode_mfma_lds<D>();
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_mfma_kernel<D, G>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     (void)attr;
-    hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+    hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, out, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
   } else
     hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), 0, s, q, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(geo.n_kv, n), dim3(256), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
+  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks, use_mfma_decode() ? 1 : 0);
 }
 
 // q, out: [n, n_q * d] bf16 (q already rotated). A context is cut into chunks of `chunk_pages`
