@@ -6,6 +6,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cmath>
 #include <cstdio>
@@ -93,6 +94,7 @@ struct sts_ctx {
   double* inv_freq = nullptr;
   std::mutex alloc_mu;                         // serialises page allocation / release
   std::mutex state_mu;                         // guards the in-flight prefill batch description
+  std::mutex part_mu;                          // serialises repartitioning (one control thread per phase may call it)
   std::vector<int> free_pages; std::vector<char> page_used;
   std::vector<Seq> seqs;
   Phase ph[2];
@@ -102,7 +104,7 @@ struct sts_ctx {
   bool pf_active = false; int pf_next_layer = 0; std::vector<int> pf_seqs, pf_lens;
   int64_t last_wall_ns = 0;
   // launches whose finish call is still due (non-blocking API)
-  bool pend_prefill = false, pend_decode = false;
+  std::atomic<bool> pend_prefill{false}, pend_decode{false};    // a launch of that phase is in flight (each set by its own control thread)
   std::vector<int> pend_pseqs, pend_plens, pend_dseqs; int pend_le = 0;
   void* probe_src = nullptr; void* probe_dst = nullptr; size_t probe_bytes = 0;
   std::vector<void*> allocs;
@@ -964,16 +966,27 @@ extern "C" int sts_read_hidden(sts_ctx* c, int32_t phase, float* out, int32_t ro
 // ---- partition
 extern "C" int sts_set_partition(sts_ctx* c, int32_t prefill_cus, int32_t decode_cus) {
   if (!c) return STS_EINVAL;
+  std::lock_guard<std::mutex> g(c->part_mu);
   const int old[2] = {c->part_cus[0], c->part_cus[1]};
   if (prefill_cus == -1) prefill_cus = old[0];
   if (decode_cus == -1) decode_cus = old[1];
   const int v[2] = {prefill_cus, decode_cus};
   for (int x : v) if (x != 0 && (x < 8 || x > c->n_cu || x % 8 != 0)) return STS_EINVAL;
-  if ((c->pend_prefill && prefill_cus != old[0]) || (c->pend_decode && decode_cus != old[1])) return STS_ESTATE;
-  c->part_cus[0] = prefill_cus; c->part_cus[1] = decode_cus;
-  const int rc = select_streams(c);
-  if (rc != STS_OK) { c->part_cus[0] = old[0]; c->part_cus[1] = old[1]; (void)select_streams(c); }
-  return rc;
+  if ((prefill_cus != old[0] && c->pend_prefill) || (decode_cus != old[1] && c->pend_decode)) return STS_ESTATE;
+  // only a side whose CU count changes is touched: the other side's control thread may be queuing
+  // a step on its stream at this moment
+  hipStream_t st[2] = {c->ph[0].stream, c->ph[1].stream};
+  for (int side = 0; side < 2; side++) {
+    if (v[side] == old[side]) continue;
+    if (v[side] == 0) { st[side] = nullptr; continue; }
+    const int rc = get_stream(c, side, v[side], &st[side]);
+    if (rc != STS_OK) return rc;                  // nothing was changed yet
+  }
+  for (int side = 0; side < 2; side++) {
+    if (v[side] == old[side]) continue;
+    c->part_cus[side] = v[side]; c->ph[side].stream = st[side]; c->ph[side].cus = v[side];
+  }
+  return STS_OK;
 }
 extern "C" int sts_get_partition(sts_ctx* c, int32_t* prefill_cus, int32_t* decode_cus, int32_t* total_cus) {
   if (!c) return STS_EINVAL;

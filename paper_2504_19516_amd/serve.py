@@ -18,6 +18,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import threading
 import time
 
 import numpy as np
@@ -37,13 +38,15 @@ class Req:
 
 class LiveServer:
     def __init__(self, desc, profile_text, cfg, kv_pool_pages, max_batch_tokens=16384, max_decode_batch=256, max_ctx=10240,
-                 sched_slo_ns=None, recalibrate_ppm=0):
+                 sched_slo_ns=None, recalibrate_ppm=0, control_threads=1):
         """cfg carries the SLOs requests are judged by; sched_slo_ns = (ttft, tpot) optionally gives the
         scheduler tighter targets than those (headroom for estimator error and for the running-mean TPOT,
         which Algorithm 1 otherwise steers right onto the limit)."""
         self.desc, self.cfg = desc, dict(cfg)
         self.slo = (cfg["ttft_slo_ns"], cfg["tpot_slo_ns"])
         self.recalibrate_ppm = int(recalibrate_ppm)      # > 0: feed every finished slice and step back into alpha (Section 3.2.4)
+        self.control_threads = int(control_threads)      # 2: one control thread per phase, as the paper's two engines (Section 3.5);
+                                                         # measured no faster than 1 here (the Python parts of the two loops share the GIL)
         if sched_slo_ns:
             self.cfg.update(ttft_slo_ns=int(sched_slo_ns[0]), tpot_slo_ns=int(sched_slo_ns[1]))
         self.cfg.update(max_batch_tokens=max_batch_tokens, max_decode_batch=max_decode_batch, kv_pool_pages=kv_pool_pages)
@@ -139,6 +142,8 @@ class LiveServer:
             cfg["decode_boost_cus"] = int(mode.split(":")[1])
         elif ":" in mode:
             cfg["fixed_prefill_cus"] = int(mode.split(":")[1])
+        if not serial and self.control_threads == 2:
+            return self.run_two_threads(trace, cfg, seed)
         n = self.n_cu
         rng = np.random.default_rng(seed)
         reqs = [Req(i, a, il, ol) for i, (a, il, ol) in enumerate(trace)]
@@ -264,6 +269,175 @@ class LiveServer:
         st["estimator_mape_decode"] = float(np.mean(err_d)) if err_d else 0.0
         return st, decisions, timeline
 
+    def run_two_threads(self, trace, cfg, seed=0):
+        """The concurrent modes with one control thread per phase (Section 3.5: two engines that run
+        autonomously and meet only in shared metadata): the prefill thread admits arrivals, runs
+        Algorithm 1 and launches layer slices; the decode thread merges the requests handed over and
+        launches decode steps on the CUs the last decision left to it. They share the hand-over list,
+        the split in force and the decode status under one lock; the library allows one caller per
+        phase. Queuing a decode step (about 1 ms of host time) then does not hold back the next prefill
+        slice; measured on the 8B shape the two loops serve no better than the single one."""
+        eng, desc, n = self.eng, self.desc, self.n_cu
+        reqs = [Req(i, a, il, ol) for i, (a, il, ol) in enumerate(trace)]
+        lock, prof_lock = threading.Lock(), threading.Lock()
+        sh = dict(H=[], D=[], prefill_busy=False, pm=0, dm=n, co=0, prefill_over=False, error=None)
+        decisions, timeline, err_p, err_d = [], [], [], []
+        rejected = [0]
+        eng.set_partition(n, n)
+        t0 = time.perf_counter_ns()
+        clock = lambda: time.perf_counter_ns() - t0
+        recal = self.recalibrate_ppm
+
+        def prof_call(fn, *a):
+            if not recal:
+                return fn(*a)
+            with prof_lock:                     # observe() rewrites alpha samples that queries read
+                return fn(*a)
+
+        def prefill_loop():
+            rng = np.random.default_rng(seed)
+            Q, P = [], []
+            l_exe, pm, dm, nxt = 0, 0, n, 0
+            while True:
+                now = clock()
+                while nxt < len(reqs) and reqs[nxt].arrival <= now:
+                    r = reqs[nxt]
+                    total = r.in_len + r.out_len
+                    if (total + PAGE - 1) // PAGE > cfg["kv_pool_pages"] or r.in_len > cfg["max_batch_tokens"] or total > self.max_ctx:
+                        rejected[0] += 1
+                    else:
+                        Q.append(r)
+                    nxt += 1
+                launched = False
+                if P or Q:
+                    with lock:
+                        dec = [(r.first_token, r.n_dec, r.in_len) for r in sh["D"] + sh["H"]]
+                    ch = prof_call(self.profile.decide, desc, cfg, now, [(r.rid, r.arrival, r.in_len, r.out_len) for r in Q],
+                                   [(r.rid, r.arrival, r.in_len, r.out_len) for r in P], l_exe, dec, eng.pages_free(), pm, dm)
+                    by_id = {r.rid: r for r in Q}
+                    Q = [by_id[i] for i in ch["queue"]]
+                    if ch["tasks"]:
+                        if ch["admitted"]:
+                            P = [by_id[i] for i in ch["tasks"]]
+                            l_exe = 0
+                            for r in P:
+                                r.seq = eng.seq_create()
+                                eng.seq_reserve(r.seq, r.in_len + r.out_len)
+                                r.tokens = rng.integers(0, desc.vocab, r.in_len, dtype=np.int32)
+                        pm, dm = ch["prefill_cus"], ch["decode_cus"]
+                        eng.set_partition(pm, -1)
+                        lb, le = ch["layer_begin"], ch["layer_end"]
+                        with lock:
+                            sh.update(prefill_busy=True, pm=pm, dm=dm, co=sum(r.in_len for r in P))
+                        eng.prefill_launch([r.seq for r in P], [r.tokens for r in P], lb, le, want_logits=(le == desc.n_layers))
+                        launched = True
+                        slice_es = dict(prefill_len=[r.in_len for r in P], prefill_ctx=[0] * len(P), decode_ctx=[], prefill_cus=pm,
+                                        decode_cus=0, layer_begin=lb, n_layers_step=le - lb)
+                        decisions.append((now, len(P), sum(r.in_len for r in P), lb, le, pm, dm, ch["branch"], len(dec), len(Q)))
+                        while not eng.phase_done(0):
+                            time.sleep(20e-6)
+                        eng.prefill_finish()
+                        done = clock()
+                        l_exe = le
+                        timeline.append((done, "prefill", pm, sum(r.in_len for r in P), lb, le, done - now, ch["predicted_ns"]))
+                        err_p.append(abs(ch["predicted_ns"] - (done - now)) / max(1, done - now))
+                        if recal:
+                            prof_call(self.profile.observe, desc, slice_es, done - now, 0, recal)
+                        if l_exe == desc.n_layers:
+                            hand = []
+                            for r in P:
+                                r.first_token = done
+                                if r.out_len <= 1:
+                                    r.finish = done
+                                    eng.seq_free(r.seq)
+                                else:
+                                    hand.append(r)
+                            with lock:
+                                sh["H"].extend(hand)
+                            P, l_exe = [], 0
+                if not launched:
+                    # nothing to run (or the KV pool is full): decode gets the whole GPU until the next slice. The flag
+                    # stays set between the slices of a batch, so the split of the last decision holds across them.
+                    with lock:
+                        sh["prefill_busy"] = False
+                    if nxt >= len(reqs) and not (P or Q):
+                        break
+                    wait = (reqs[nxt].arrival - clock()) if (nxt < len(reqs) and not (P or Q)) else 200_000   # KV pool full: retry shortly
+                    if wait > 0:
+                        time.sleep(min(wait, 2_000_000) * 1e-9)
+
+        def decode_loop():
+            rng = np.random.default_rng(seed + 1)
+            while True:
+                with lock:
+                    while sh["H"] and len(sh["D"]) < cfg["max_decode_batch"]:
+                        sh["D"].append(sh["H"].pop(0))
+                    batch = list(sh["D"])
+                    busy, pm, dm, co_tok = sh["prefill_busy"], sh["pm"], sh["dm"], sh["co"]
+                    over = sh["prefill_over"] and not sh["H"]
+                if not batch:
+                    if over:
+                        break
+                    time.sleep(50e-6)
+                    continue
+                dm_eff = dm if busy else n
+                if dm_eff <= 0:                  # decode is suspended for this slice
+                    time.sleep(50e-6)
+                    continue
+                eng.set_partition(-1, dm_eff)
+                co = [co_tok] if busy else []
+                step_es = dict(prefill_len=co, prefill_ctx=[0] * len(co), decode_ctx=[r.in_len + r.n_dec for r in batch],
+                               prefill_cus=pm if co else 0, decode_cus=dm_eff, layer_begin=0, n_layers_step=1)
+                pred = prof_call(self.profile.query, desc, step_es)[1]
+                t_start = clock()
+                eng.decode_launch([r.seq for r in batch], rng.integers(0, desc.vocab, len(batch), dtype=np.int32), want_next=True)
+                while not eng.phase_done(1):
+                    time.sleep(20e-6)
+                eng.decode_finish(len(batch))
+                now = clock()
+                err_d.append(abs(pred - (now - t_start)) / max(1, now - t_start))
+                if recal:
+                    prof_call(self.profile.observe, desc, step_es, 0, now - t_start, recal)
+                gone = []
+                for r in batch:
+                    r.n_dec += 1
+                    if r.n_dec >= r.out_len - 1:
+                        r.finish = now
+                        eng.seq_free(r.seq)
+                        gone.append(r)
+                if gone:
+                    with lock:
+                        for r in gone:
+                            sh["D"].remove(r)
+
+        def guarded(fn):
+            def run():
+                try:
+                    fn()
+                except BaseException as e:      # surfaces in the caller; the other thread is told to stop
+                    sh["error"] = e
+                finally:
+                    if fn is prefill_loop:
+                        with lock:
+                            sh["prefill_over"] = True
+            return run
+
+        tp = threading.Thread(target=guarded(prefill_loop))
+        td = threading.Thread(target=guarded(decode_loop))
+        tp.start(); td.start()
+        tp.join()
+        if sh["error"] is not None:             # the decode thread leaves once nothing is handed over any more
+            with lock:
+                sh["H"].clear(); sh["D"].clear()
+        td.join()
+        if sh["error"] is not None:
+            raise sh["error"]
+        eng.set_partition(n, n)
+        st = self.stats(reqs, rejected[0], dict(cfg, ttft_slo_ns=self.slo[0], tpot_slo_ns=self.slo[1]))
+        st["estimator_mape_prefill"] = float(np.mean(err_p)) if err_p else 0.0
+        st["estimator_mape_decode"] = float(np.mean(err_d)) if err_d else 0.0
+        return st, decisions, timeline
+
     @staticmethod
     def stats(reqs, rejected, cfg):
         done = [r for r in reqs if r.finish >= 0]
@@ -311,6 +485,8 @@ def main():
     ap.add_argument("--layers-per-step", type=int, default=4)
     ap.add_argument("--recalibrate-ppm", type=int, default=0,
                     help="online alpha recalibration weight (parts per million per observation; 0 = off)")
+    ap.add_argument("--control-threads", type=int, default=1, choices=[1, 2],
+                    help="1: a single loop drives both phases; 2: one control thread per phase in the concurrent modes")
     ap.add_argument("--pool-pages", type=int, default=40000)
     ap.add_argument("--max-ctx", type=int, default=10240)
     ap.add_argument("--out", default=None)
@@ -321,7 +497,7 @@ def main():
     sched = (int((args.sched_ttft_ms or args.ttft_ms) * 1e6), int((args.sched_tpot_ms or args.tpot_ms) * 1e6))
     srv = LiveServer(desc, open(args.profile).read(), cfg, args.pool_pages, max_ctx=args.max_ctx,
                      max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0), sched_slo_ns=sched,
-                     recalibrate_ppm=args.recalibrate_ppm)
+                     recalibrate_ppm=args.recalibrate_ppm, control_threads=args.control_threads)
     ind, outd = WORKLOADS[args.workload]
     results = []
     for rate in [float(x) for x in args.rates.split(",")]:

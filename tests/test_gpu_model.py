@@ -356,16 +356,20 @@ def test_launch_poll_finish_equals_blocking_calls(sts, tiny, eng):
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
 
 
-@pytest.mark.parametrize("mode", ["concurrent", "tm", "fixed:192", "naive", "wpart", "wsched", "fixedall:128", "chunked:64", "boost:64"])
+@pytest.mark.parametrize("mode", ["concurrent", "concurrent/2", "tm", "fixed:192", "naive", "wpart", "wsched", "fixedall:128", "chunked:64",
+                                  "boost:64", "boost:64/2", "wsched/2"])
 def test_live_serving_of_a_short_trace(sts, tiny, mode):
     """The serving loop on the tiny model: every request is prefilled layer slice by layer slice,
-    handed over, decoded to its output length, and its pages come back."""
+    handed over, decoded to its output length, and its pages come back. "/2" runs a concurrent
+    mode with one control thread per phase instead of a single loop."""
+    mode, _, threads = mode.partition("/")
     from oracle import latency as L
     from paper_2504_19516_amd import serve
     desc, _ = tiny
     hw = L.Profile(n_cu=256, granule=32, c_peak=200_000, d_peak=2_000, n_d=128, tile_m=128, tile_n=128, wgs_per_cu=2)
     cfg = dict(ttft_slo_ns=200_000_000, tpot_slo_ns=20_000_000, layers_per_step=1)
-    srv = serve.LiveServer(desc, L.dump_profile(hw), cfg, kv_pool_pages=600, max_batch_tokens=512, max_decode_batch=16, max_ctx=640)
+    srv = serve.LiveServer(desc, L.dump_profile(hw), cfg, kv_pool_pages=600, max_batch_tokens=512, max_decode_batch=16, max_ctx=640,
+                           control_threads=int(threads or 1))
     trace = synth.poisson_trace(3, 60.0, 0.5, dict(kind="lognormal", median=100, sigma=0.6, cap=400),
                                 dict(kind="lognormal", median=20, sigma=0.5, cap=100))
     st, dec, tl = srv.run([tuple(int(x) for x in r) for r in trace], mode)
