@@ -192,8 +192,10 @@ int sts_wave_quant(int64_t g, int64_t n, int64_t b, int64_t* waves, int64_t* tai
 
 /* Profile = hardware constants (C_peak flop/ns, D_peak bytes/ns, inflection N_d, tile sizes)
  * plus sample grids: bw (D_{p,sl}: decode CUs x co-running prefill tokens -> bytes/ns),
- * alpha_prefill (CUs x tokens -> alpha ppm), alpha_decode (CUs x batch x mean context per request -> ppm).
- * Text format: see sts_profile_dump. */
+ * alpha_prefill (CUs x tokens -> alpha ppm), alpha_decode (CUs x batch x mean context per request -> ppm),
+ * and optionally prefill_corun (decode CUs beside the slice -> slowdown ppm of a prefill slice that shares
+ * the memory system with a decode step on a disjoint CU set; Section 3.2.3 treats this direction of the
+ * contention as small, a measured table keeps it where it is not). Text format: see sts_profile_dump. */
 int sts_profile_parse(const char* text, sts_profile** out);
 int sts_profile_load(const char* path, sts_profile** out);
 int sts_profile_dump(const sts_profile* p, char* buf, size_t cap, size_t* needed);
@@ -209,7 +211,9 @@ typedef struct {
 } sts_exec_state;
 #define STS_INF_NS ((int64_t)1 << 60)
 /* Eq. 1 summed over the kernels of the slice (prefill) / the whole step (decode), times the
- * interpolated alpha of Eq. 2. A phase with work but zero CUs gets STS_INF_NS; no work -> 0. */
+ * interpolated alpha of Eq. 2. A phase with work but zero CUs gets STS_INF_NS; no work -> 0.
+ * When es holds a decode batch on CUs disjoint from the prefill CUs (prefill_cus + decode_cus within
+ * the CU count), the prefill figure also carries the profile's prefill_corun factor at decode_cus. */
 int sts_latency_query(const sts_profile* p, const sts_model_desc* desc, const sts_exec_state* es,
                       int64_t* prefill_ns, int64_t* decode_ns);
 /* Online recalibration (Section 3.2.4): feed one measured prefill slice and/or decode step at

@@ -65,6 +65,10 @@ class Profile:
     use_waveq: int = 1
     tail_cut: int = 0                  # > 0: the GEMMs cut the tiles of a partly filled last wave along K, into at most this many pieces
     bw: Grid | None = None             # D_{p,sl}: axes (decode CUs, co-running prefill tokens) -> bytes/ns
+    # slowdown (ppm) of a prefill slice beside a decode step, over the decode CUs it shares the GPU
+    # with; None = none. Section 3.2.3 measures this direction of the contention as small and
+    # drops it; kept here as a measured table because it is not small on every part
+    prefill_corun: Grid | None = None
     alpha_prefill: Grid = field(default_factory=lambda: Grid([[256], [2048]], [[PPM]]))
     alpha_decode: Grid = field(default_factory=lambda: Grid([[256], [64], [65536]], [[[PPM]]]))
 
@@ -250,12 +254,27 @@ def alpha_from_measurement(t_measured_ns: int, t_roofline_ns: int) -> int:
     return floor_div(t_measured_ns * PPM, max(t_roofline_ns, 1))
 
 
-def predict_prefill_ns(s: Shape, hw: Profile, reqs, pm: int, layer_begin: int, n_layers_step: int) -> int:
+def prefill_corun_ppm(hw: Profile, co_decode_cus: int) -> int:
+    """Slowdown of a prefill slice that runs beside a decode step on co_decode_cus other CUs."""
+    if co_decode_cus <= 0 or hw.prefill_corun is None:
+        return PPM
+    return alpha_at(hw.prefill_corun, [co_decode_cus])
+
+
+def predict_prefill_ns(s: Shape, hw: Profile, reqs, pm: int, layer_begin: int, n_layers_step: int, co_decode_cus: int = 0) -> int:
     if pm <= 0 or not reqs:
         return INF_NS if reqs else 0
     t = prefill_roofline_ns(s, hw, reqs, pm, layer_begin, n_layers_step)
     a = alpha_at(hw.alpha_prefill, [pm, sum(sl for sl, _ in reqs)])
-    return floor_div(t * a, PPM)
+    alone = floor_div(t * a, PPM)
+    return floor_div(alone * prefill_corun_ppm(hw, co_decode_cus), PPM)
+
+
+def co_decode_cus(hw: Profile, es: dict) -> int:
+    """The decode CUs a prefill slice of execution state es shares the GPU with: a decode batch on a
+    disjoint CU set; 0 when nothing decodes or the two sets overlap."""
+    dm = es["decode_cus"]
+    return dm if (len(es["decode_ctx"]) > 0 and dm > 0 and es["prefill_cus"] + dm <= hw.n_cu) else 0
 
 
 def predict_decode_ns(s: Shape, hw: Profile, cls, dm: int, co_prefill_tokens: int) -> int:
@@ -273,7 +292,7 @@ def latency_query(s: Shape, hw: Profile, es: dict):
     n_layers_step. Returns (prefill_ns for the slice, decode_ns for one step)."""
     reqs = list(zip(es["prefill_len"], es["prefill_ctx"]))
     co = sum(es["prefill_len"]) if es["prefill_cus"] > 0 else 0
-    return (predict_prefill_ns(s, hw, reqs, es["prefill_cus"], es["layer_begin"], es["n_layers_step"]),
+    return (predict_prefill_ns(s, hw, reqs, es["prefill_cus"], es["layer_begin"], es["n_layers_step"], co_decode_cus(hw, es)),
             predict_decode_ns(s, hw, list(es["decode_ctx"]), es["decode_cus"], co))
 
 
@@ -317,6 +336,7 @@ def observe(s: Shape, hw: Profile, es: dict, measured_prefill_ns: int, measured_
     reqs = list(zip(es["prefill_len"], es["prefill_ctx"]))
     if measured_prefill_ns > 0 and reqs and es["prefill_cus"] > 0:
         roof = prefill_roofline_ns(s, hw, reqs, es["prefill_cus"], es["layer_begin"], es["n_layers_step"])
+        roof = floor_div(roof * prefill_corun_ppm(hw, co_decode_cus(hw, es)), PPM)      # alpha stays the stand-alone factor
         _blend(hw.alpha_prefill, [es["prefill_cus"], sum(sl for sl, _ in reqs)], measured_prefill_ns, roof, weight_ppm)
     cls = list(es["decode_ctx"])
     if measured_decode_ns > 0 and cls and es["decode_cus"] > 0:
@@ -341,7 +361,7 @@ def dump_profile(hw: Profile) -> str:
     lines = ["sts-profile 1"]
     for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut"):
         lines.append(f"{k} {getattr(hw, k)}")
-    for name in ("bw", "alpha_prefill", "alpha_decode"):
+    for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         g = getattr(hw, name)
         if g is None:
             continue

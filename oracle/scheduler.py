@@ -121,8 +121,9 @@ class Replay:
         self.n_rejected = 0
 
     # ---------------------------------------------------------------- estimator shorthands
-    def t_prefill(self, ids, pm, l0, nl):
-        return L.predict_prefill_ns(self.s, self.hw, [(self.reqs[i].in_len, 0) for i in ids], pm, l0, nl)
+    def t_prefill(self, ids, pm, l0, nl, co_dm):
+        """co_dm: CUs of a decode step running beside the slice on the other CUs (0 = prefill alone)."""
+        return L.predict_prefill_ns(self.s, self.hw, [(self.reqs[i].in_len, 0) for i in ids], pm, l0, nl, co_dm)
 
     def t_decode(self, ids, dm, co):
         return L.predict_decode_ns(self.s, self.hw, [self.reqs[i].in_len + self.reqs[i].n_dec for i in ids], dm, co)
@@ -139,8 +140,11 @@ class Replay:
         n_layers = self.s.n_layers
         pm_cur = self.pm if self.pm > 0 else self.n
         # line 2: estimate latencies of P u Q under the current execution state
-        t_p = self.t_prefill(self.P, pm_cur, self.l_exe, n_layers - self.l_exe) if self.P else 0
-        est = {i: self.t_prefill([i], pm_cur, 0, n_layers) for i in self.Q}
+        # while requests decode, a prefill slice on pm < n CUs has a decode step on the other n - pm beside it
+        # (dec is built below from D and H; the same test is used here)
+        co_dm = lambda pm_c: 0 if (not (self.D or self.H) or pm_c >= self.n) else self.n - pm_c
+        t_p = self.t_prefill(self.P, pm_cur, self.l_exe, n_layers - self.l_exe, co_dm(pm_cur)) if self.P else 0
+        est = {i: self.t_prefill([i], pm_cur, 0, n_layers, co_dm(pm_cur)) for i in self.Q}
         # line 5: sort by least estimated latency, guarded against new SLO violations
         fcfs = list(self.Q)
         sjf = sorted(self.Q, key=lambda i: (est[i], reqs[i].arrival, i))
@@ -196,11 +200,11 @@ class Replay:
                 extra = self.t_decode(dec, dm, co)
             else:
                 half = max(self.g, (self.n // 2) // self.g * self.g)
-                extra = self.t_prefill(next_tasks, self.n, self.l_exe, l_eff) + self.t_decode(dec, half, co)
+                extra = self.t_prefill(next_tasks, self.n, self.l_exe, l_eff, 0) + self.t_decode(dec, half, co)
             return p90([(now - reqs[i].first_token + extra) // (reqs[i].n_dec + 1) for i in dec])
 
         def ttft_max(pm):
-            t = self.t_prefill(next_tasks, pm, self.l_exe, n_layers - self.l_exe)
+            t = self.t_prefill(next_tasks, pm, self.l_exe, n_layers - self.l_exe, co_dm(pm))
             return max(now - reqs[i].arrival + t for i in next_tasks)
 
         grid = list(range(0, self.n, self.g))          # candidate decode CUs
@@ -254,7 +258,7 @@ class Replay:
         if cfg.decode_boost_cus > 0 and cfg.mode in (0, 2, 4) and dec and dm > 0 and self.l_exe + l_eff == n_layers:
             dm = min(self.n, dm + cfg.decode_boost_cus)
         self.pm, self.dm = pm, dm
-        dur = self.t_prefill(next_tasks, pm, self.l_exe, l_eff)
+        dur = self.t_prefill(next_tasks, pm, self.l_exe, l_eff, co_dm(pm) if dm > 0 else 0)
         self.decisions.append((now, len(next_tasks), min(next_tasks), tasks_hash(next_tasks), self.l_exe, self.l_exe + l_eff,
                                pm, dm, branch, len(dec), dur))
         return dur

@@ -165,15 +165,24 @@ int64_t decode_roofline_ns(const sts_model_desc& s, const Profile& hw, const int
   return per_layer * s.n_layers + srm_ns(head.flop, head.mem, dm, hw, d_meas);
 }
 
+// Slowdown of a prefill slice beside a decode step that runs on co_decode_cus other CUs (1.0 = PPM
+// when nothing decodes beside it or no table was measured).
+int64_t prefill_corun_ppm(const Profile& hw, int co_decode_cus) {
+  if (co_decode_cus <= 0 || hw.prefill_corun.values.empty()) return PPM;
+  const int64_t x[1] = {co_decode_cus};
+  return alpha_at(hw.prefill_corun, x);
+}
+
 int64_t predict_prefill_ns(const sts_model_desc& s, const Profile& hw, const int32_t* sl, const int32_t* p, int n,
-                           int pm, int layer_begin, int n_layers_step) {
+                           int pm, int layer_begin, int n_layers_step, int co_decode_cus) {
   if (n <= 0) return 0;
   if (pm <= 0) return INF_NS;
   const int64_t t = prefill_roofline_ns(s, hw, sl, p, n, pm, layer_begin, n_layers_step);
   int64_t tok = 0;
   for (int i = 0; i < n; i++) tok += sl[i];
   const int64_t x[2] = {pm, tok};
-  return floor_div((i128)t * alpha_at(hw.alpha_prefill, x), PPM);
+  const int64_t alone = floor_div((i128)t * alpha_at(hw.alpha_prefill, x), PPM);
+  return floor_div((i128)alone * prefill_corun_ppm(hw, co_decode_cus), PPM);
 }
 
 int64_t predict_decode_ns(const sts_model_desc& s, const Profile& hw, const int32_t* cl, int n, int dm, int64_t co_tokens) {
@@ -224,8 +233,9 @@ bool parse_profile(const std::string& text, Profile* hw) {
     if (key == "grid") {
       std::string name; int nd = 0;
       if (!(ls >> name >> nd) || nd < 1 || nd > 3) return false;
-      Grid* g = name == "bw" ? &hw->bw : name == "alpha_prefill" ? &hw->alpha_prefill : name == "alpha_decode" ? &hw->alpha_decode : nullptr;
-      const int want = name == "alpha_decode" ? 3 : 2;
+      Grid* g = name == "bw" ? &hw->bw : name == "alpha_prefill" ? &hw->alpha_prefill : name == "alpha_decode" ? &hw->alpha_decode :
+                name == "prefill_corun" ? &hw->prefill_corun : nullptr;
+      const int want = name == "alpha_decode" ? 3 : name == "prefill_corun" ? 1 : 2;
       if (!g || nd != want || !parse_grid(in, nd, g)) return false;
       continue;
     }
@@ -253,6 +263,7 @@ std::string dump_profile(const Profile& hw) {
   o << "n_cu " << hw.n_cu << "\ngranule " << hw.granule << "\nc_peak " << hw.c_peak << "\nd_peak " << hw.d_peak << "\nn_d " << hw.n_d
     << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nwgs_per_cu " << hw.wgs_per_cu << "\nuse_waveq " << hw.use_waveq << "\ntail_cut " << hw.tail_cut << "\n";
   dump_grid(o, "bw", hw.bw);
+  dump_grid(o, "prefill_corun", hw.prefill_corun);
   dump_grid(o, "alpha_prefill", hw.alpha_prefill);
   dump_grid(o, "alpha_decode", hw.alpha_decode);
   return o.str();
@@ -310,12 +321,18 @@ static int check_es(const sts_profile* p, const sts_model_desc* d, const sts_exe
   for (int i = 0; i < es->n_decode; i++) if (es->decode_ctx[i] < 0) return STS_EINVAL;
   return STS_OK;
 }
+// The decode CUs a prefill slice of this execution state shares the GPU with: a decode batch on a
+// disjoint CU set; 0 when nothing decodes or the two sets overlap.
+static int co_decode_cus(const Profile& hw, const sts_exec_state* es) {
+  return (es->n_decode > 0 && es->decode_cus > 0 && (int64_t)es->prefill_cus + es->decode_cus <= hw.n_cu) ? es->decode_cus : 0;
+}
 extern "C" int sts_latency_query(const sts_profile* p, const sts_model_desc* d, const sts_exec_state* es, int64_t* prefill_ns, int64_t* decode_ns) {
   int rc = check_es(p, d, es);
   if (rc) return rc;
   int64_t co = 0;
   if (es->prefill_cus > 0) for (int i = 0; i < es->n_prefill; i++) co += es->prefill_len[i];
-  if (prefill_ns) *prefill_ns = predict_prefill_ns(*d, p->hw, es->prefill_len, es->prefill_ctx, es->n_prefill, es->prefill_cus, es->layer_begin, es->n_layers_step);
+  if (prefill_ns) *prefill_ns = predict_prefill_ns(*d, p->hw, es->prefill_len, es->prefill_ctx, es->n_prefill, es->prefill_cus, es->layer_begin,
+                                                   es->n_layers_step, co_decode_cus(p->hw, es));
   if (decode_ns) *decode_ns = predict_decode_ns(*d, p->hw, es->decode_ctx, es->n_decode, es->decode_cus, co);
   return STS_OK;
 }
@@ -352,7 +369,8 @@ extern "C" int sts_profile_observe(sts_profile* p, const sts_model_desc* d, cons
   int64_t co = 0;
   if (es->prefill_cus > 0) for (int i = 0; i < es->n_prefill; i++) co += es->prefill_len[i];
   if (measured_prefill_ns > 0 && es->n_prefill > 0 && es->prefill_cus > 0) {
-    const int64_t roof = prefill_roofline_ns(*d, p->hw, es->prefill_len, es->prefill_ctx, es->n_prefill, es->prefill_cus, es->layer_begin, es->n_layers_step);
+    int64_t roof = prefill_roofline_ns(*d, p->hw, es->prefill_len, es->prefill_ctx, es->n_prefill, es->prefill_cus, es->layer_begin, es->n_layers_step);
+    roof = floor_div((i128)roof * prefill_corun_ppm(p->hw, co_decode_cus(p->hw, es)), PPM);      // alpha stays the stand-alone factor
     const int64_t x[2] = {es->prefill_cus, co};
     blend(p->hw.alpha_prefill, x, measured_prefill_ns, roof, weight_ppm);
   }

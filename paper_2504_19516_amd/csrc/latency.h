@@ -22,6 +22,9 @@ struct Profile {
   int64_t tile_m = 256, tile_n = 256, tile_q = 128, wgs_per_cu = 1, use_waveq = 1;
   int64_t tail_cut = 0;                // > 0: GEMMs cut a partly filled last wave along K into at most this many pieces
   Grid bw;                             // D_{p,sl}; empty = use D_peak min(1, N_p/N_d)
+  Grid prefill_corun;                  // slowdown (ppm, over the decode CUs beside it) of a prefill slice that shares HBM with a
+                                       // running decode step; empty = none. Section 3.2.3 measures this side of the contention as
+                                       // small and drops it; on this part it reaches 1.1x-1.4x and is kept as a measured table
   Grid alpha_prefill{{{256}, {2048}}, {PPM}};
   Grid alpha_decode{{{256}, {64}, {65536}}, {PPM}};
 };
@@ -35,7 +38,8 @@ int64_t prefill_roofline_ns(const sts_model_desc& s, const Profile& hw, const in
                             int pm, int layer_begin, int n_layers_step);
 int64_t decode_roofline_ns(const sts_model_desc& s, const Profile& hw, const int32_t* cl, int n, int dm, int64_t co_tokens);
 int64_t predict_prefill_ns(const sts_model_desc& s, const Profile& hw, const int32_t* sl, const int32_t* p, int n,
-                           int pm, int layer_begin, int n_layers_step);
+                           int pm, int layer_begin, int n_layers_step, int co_decode_cus = 0);
+int64_t prefill_corun_ppm(const Profile& hw, int co_decode_cus);
 int64_t predict_decode_ns(const sts_model_desc& s, const Profile& hw, const int32_t* cl, int n, int dm, int64_t co_tokens);
 bool parse_profile(const std::string& text, Profile* hw);
 std::string dump_profile(const Profile& hw);

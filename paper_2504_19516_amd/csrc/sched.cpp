@@ -42,10 +42,11 @@ int64_t p90(std::vector<int64_t> v) {
 struct Ctx {
   const sts_model_desc& s; const Profile& hw; const sts_sched_config& cfg;
   int n, g;
-  int64_t t_prefill(const std::vector<QReq>& rs, int pm_, int l0, int nl) const {
+  // co_dm: CUs of a decode step running beside the slice on the other CUs (0 = prefill runs alone)
+  int64_t t_prefill(const std::vector<QReq>& rs, int pm_, int l0, int nl, int co_dm) const {
     std::vector<int32_t> sl(rs.size()), p(rs.size(), 0);
     for (size_t i = 0; i < rs.size(); i++) sl[i] = rs[i].in_len;
-    return predict_prefill_ns(s, hw, sl.data(), p.data(), (int)rs.size(), pm_, l0, nl);
+    return predict_prefill_ns(s, hw, sl.data(), p.data(), (int)rs.size(), pm_, l0, nl, co_dm);
   }
   int64_t t_decode(const std::vector<DReq>& rs, int dm_, int64_t co) const {
     std::vector<int32_t> cl(rs.size());
@@ -77,10 +78,12 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
   const int n = c.n, g = c.g, n_layers = c.s.n_layers;
   Decision out;
   const int pm_cur = pm > 0 ? pm : n;
-  const int64_t t_p = P.empty() ? 0 : c.t_prefill(P, pm_cur, l_exe, n_layers - l_exe);
+  // while requests decode, a prefill slice on pm_c < n CUs has a decode step on the other n - pm_c beside it
+  auto co_dm = [&](int pm_c) { return (dec.empty() || pm_c >= n) ? 0 : n - pm_c; };
+  const int64_t t_p = P.empty() ? 0 : c.t_prefill(P, pm_cur, l_exe, n_layers - l_exe, co_dm(pm_cur));
   const size_t nq = Q.size();
   std::vector<int64_t> est(nq);
-  for (size_t i = 0; i < nq; i++) est[i] = c.t_prefill(std::vector<QReq>{Q[i]}, pm_cur, 0, n_layers);
+  for (size_t i = 0; i < nq; i++) est[i] = c.t_prefill(std::vector<QReq>{Q[i]}, pm_cur, 0, n_layers, co_dm(pm_cur));
   std::vector<int> fcfs(nq), sjf(nq);
   for (size_t i = 0; i < nq; i++) fcfs[i] = sjf[i] = (int)i;
   std::sort(sjf.begin(), sjf.end(), [&](int a, int b) {
@@ -140,13 +143,13 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
     if (dec.empty()) return 0;
     int64_t extra;
     if (dm_c > 0) extra = c.t_decode(dec, dm_c, co);
-    else extra = c.t_prefill(next_tasks, n, l_exe, l_eff) + c.t_decode(dec, half, co);
+    else extra = c.t_prefill(next_tasks, n, l_exe, l_eff, 0) + c.t_decode(dec, half, co);
     std::vector<int64_t> v;
     for (const DReq& r : dec) v.push_back((now - r.first_token + extra) / (r.n_dec + 1));
     return p90(v);
   };
   auto ttft_max = [&](int pm_c) -> int64_t {
-    const int64_t t = c.t_prefill(next_tasks, pm_c, l_exe, n_layers - l_exe);
+    const int64_t t = c.t_prefill(next_tasks, pm_c, l_exe, n_layers - l_exe, co_dm(pm_c));
     int64_t m = INT64_MIN;
     for (const QReq& r : next_tasks) m = std::max(m, now - r.arrival + t);
     return m;
@@ -204,7 +207,7 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
     dm_new = std::min(n, dm_new + cfg.decode_boost_cus);
   for (const QReq& r : next_tasks) out.tasks.push_back(r.id);
   out.layer_begin = l_exe; out.layer_end = l_exe + l_eff; out.pm = pm_new; out.dm = dm_new; out.branch = branch;
-  out.predicted_ns = c.t_prefill(next_tasks, pm_new, l_exe, l_eff);
+  out.predicted_ns = c.t_prefill(next_tasks, pm_new, l_exe, l_eff, dm_new > 0 ? co_dm(pm_new) : 0);
   return out;
 }
 

@@ -23,7 +23,7 @@ def profile_text(hw: dict, grids: dict) -> str:
     lines = ["sts-profile 1"]
     for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut"):
         lines.append(f"{k} {int(hw[k])}")
-    for name in ("bw", "alpha_prefill", "alpha_decode"):
+    for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         if name not in grids:
             continue
         axes, values = grids[name]
@@ -142,6 +142,54 @@ class Profiler:
         vals.append([full] * len(sls))
         self.grids["bw"] = ([dms, list(sls)], vals)
         log(f"D_p,sl bytes/ns (rows: decode CUs {dms}, cols: co-running prefill tokens {list(sls)}): {vals}")
+
+    def prefill_host_ns(self, tokens, layers=4, reps=3):
+        """Host-clock time of a prefill slice on the prefill CUs in force (usable while decode runs)."""
+        eng = self.eng
+        toks = synth.tokens(3, tokens, self.desc.vocab)
+        best = None
+        for _ in range(reps + 1):
+            s = eng.seq_create()
+            t0 = time.perf_counter_ns()
+            eng.prefill_launch([s], [toks], 0, layers, want_logits=False)
+            while not eng.phase_done(0):
+                time.sleep(10e-6)
+            eng.prefill_finish()
+            t = time.perf_counter_ns() - t0
+            if layers < self.desc.n_layers:
+                eng.prefill_abort()
+            eng.seq_free(s)
+            best = t if best is None else min(best, t)
+        return best
+
+    def sweep_prefill_corun(self, dms=(32, 64, 128, 192), tokens=2048, batch=64, ctx=1024, log=print):
+        """Slowdown of a prefill slice on n - dm CUs while decode steps of a resident batch run back to
+        back on the other dm CUs, against the same slice alone (both on the host clock)."""
+        eng, n = self.eng, self.n_cu
+        vals = [PPM]
+        for dm in dms:
+            eng.set_partition(n - dm, dm)
+            alone = self.prefill_host_ns(tokens)
+            seqs = self.make_decode_batch([ctx] * batch)
+            dtoks = synth.tokens(4, batch, self.desc.vocab)
+            stop = [False]
+
+            def decode_loop():
+                while not stop[0]:
+                    eng.decode_step(seqs, dtoks, want_logits=False, want_next=True)
+            th = threading.Thread(target=decode_loop)
+            th.start()
+            time.sleep(0.03)
+            beside = self.prefill_host_ns(tokens)
+            stop[0] = True
+            th.join()
+            for s in seqs:
+                eng.seq_free(s)
+            vals.append(max(PPM, beside * PPM // max(alone, 1)))
+            log(f"prefill slice ({tokens} tokens, 4 layers) on {n - dm} CUs: alone {alone / 1e6:.3f} ms, beside decode on {dm} CUs {beside / 1e6:.3f} ms "
+                f"-> x{vals[-1] / PPM:.3f}")
+        eng.set_partition(n, n)
+        self.grids["prefill_corun"] = ([[0] + list(dms)], vals)
 
     def _roofline(self, es):
         text = profile_text(self.hw, {k: v for k, v in self.grids.items() if k == "bw"})
@@ -285,6 +333,7 @@ def main():
     pr = Profiler(desc)
     pr.sweep_hardware(log)
     pr.sweep_contention(log=log)
+    pr.sweep_prefill_corun(log=log)
     pr.calibrate_prefill(log=log)
     pr.calibrate_decode(log=log)
     text = pr.text()

@@ -193,8 +193,10 @@ class LiveServer:
                     lb, le = ch["layer_begin"], ch["layer_end"]
                     eng.prefill_launch([r.seq for r in P], [r.tokens for r in P], lb, le, want_logits=(le == desc.n_layers))
                     prefill_busy, cur_slice = True, (now, lb, le, ch["predicted_ns"])
-                    slice_es = dict(prefill_len=[r.in_len for r in P], prefill_ctx=[0] * len(P), decode_ctx=[], prefill_cus=pm,
-                                    decode_cus=0, layer_begin=lb, n_layers_step=le - lb)
+                    # the decode batch beside the slice (the estimator's co-run slowdown applies when one runs on other CUs)
+                    slice_es = dict(prefill_len=[r.in_len for r in P], prefill_ctx=[0] * len(P),
+                                    decode_ctx=[r.in_len + r.n_dec for r in D + H] if dm > 0 else [], prefill_cus=pm,
+                                    decode_cus=dm, layer_begin=lb, n_layers_step=le - lb)
                     decisions.append((now, len(P), sum(r.in_len for r in P), lb, le, pm, dm, ch["branch"], len(D) + len(H), len(Q)))
             # ---- decode engine: merge hand-offs, one step on the CUs left to it
             if not decode_busy and not (serial and prefill_busy):
@@ -331,8 +333,9 @@ class LiveServer:
                             sh.update(prefill_busy=True, pm=pm, dm=dm, co=sum(r.in_len for r in P))
                         eng.prefill_launch([r.seq for r in P], [r.tokens for r in P], lb, le, want_logits=(le == desc.n_layers))
                         launched = True
-                        slice_es = dict(prefill_len=[r.in_len for r in P], prefill_ctx=[0] * len(P), decode_ctx=[], prefill_cus=pm,
-                                        decode_cus=0, layer_begin=lb, n_layers_step=le - lb)
+                        slice_es = dict(prefill_len=[r.in_len for r in P], prefill_ctx=[0] * len(P),
+                                        decode_ctx=[in_len + n_dec for _, n_dec, in_len in dec] if dm > 0 else [], prefill_cus=pm,
+                                        decode_cus=dm, layer_begin=lb, n_layers_step=le - lb)
                         decisions.append((now, len(P), sum(r.in_len for r in P), lb, le, pm, dm, ch["branch"], len(dec), len(Q)))
                         while not eng.phase_done(0):
                             time.sleep(20e-6)

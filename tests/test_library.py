@@ -58,6 +58,7 @@ def sample_profile():
     hw = L.Profile(n_cu=256, granule=32, c_peak=1_000_000, d_peak=5_000, n_d=112, tile_m=128, tile_n=128, tile_q=128, wgs_per_cu=2, use_waveq=1)
     hw.bw = L.Grid([[32, 64, 128, 256], [0, 2048, 8192]],
                    [[1500, 1300, 1200], [2600, 2300, 2100], [4500, 4000, 3700], [5200, 4800, 4400]])
+    hw.prefill_corun = L.Grid([[0, 32, 64, 128, 192]], [1_000_000, 1_110_000, 1_190_000, 1_370_000, 1_480_000])
     hw.alpha_prefill = L.Grid([[32, 128, 256], [256, 2048, 16384]],
                               [[2_400_000, 1_900_000, 1_700_000], [2_300_000, 1_800_000, 1_650_000], [2_500_000, 2_000_000, 1_800_000]])
     hw.alpha_decode = L.Grid([[32, 256], [8, 64, 256], [4096, 262144]],

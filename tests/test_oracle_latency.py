@@ -130,6 +130,27 @@ def test_contention_table_replaces_d_p_for_decode():
     assert abs(solo - sum(k[2] for k in ks + head) / 3000) < len(ks) + 2
 
 
+def test_prefill_corun_table_by_hand():
+    """The measured slowdown of a prefill slice beside a decode step multiplies the stand-alone
+    prediction: exact at the samples, linear between and beyond them, absent when nothing decodes
+    beside the slice or when the two CU sets overlap."""
+    s = L.Shape(32, 4096, 32, 8, 128, 14336, 128256)
+    hw = L.Profile(use_waveq=0)
+    hw.prefill_corun = L.Grid([[0, 32, 64, 128]], [1_000_000, 1_100_000, 1_200_000, 1_400_000])
+    alone = L.predict_prefill_ns(s, hw, [(2048, 0)], 224, 0, 4)
+    assert L.predict_prefill_ns(s, hw, [(2048, 0)], 224, 0, 4, 0) == alone
+    assert L.predict_prefill_ns(s, hw, [(2048, 0)], 224, 0, 4, 32) == alone * 1_100_000 // 1_000_000
+    assert L.predict_prefill_ns(s, hw, [(2048, 0)], 192, 0, 4, 48) == L.predict_prefill_ns(s, hw, [(2048, 0)], 192, 0, 4) * 1_150_000 // 1_000_000
+    assert L.prefill_corun_ppm(hw, 192) == 1_600_000                  # extrapolated along the last segment
+    es = dict(prefill_len=[2048], prefill_ctx=[0], decode_ctx=[1000] * 8, prefill_cus=224, decode_cus=32, layer_begin=0, n_layers_step=4)
+    assert L.latency_query(s, hw, es)[0] == alone * 1_100_000 // 1_000_000
+    assert L.latency_query(s, hw, dict(es, decode_ctx=[]))[0] == alone                       # nothing decodes
+    assert L.latency_query(s, hw, dict(es, decode_cus=64))[0] == alone                       # 224 + 64 > 256: overlapping sets
+    hw.prefill_corun = None
+    assert L.latency_query(s, hw, es)[0] == alone
+    assert L.parse_profile(L.dump_profile(hw)) == hw
+
+
 def test_wave_quant_adjustment_uses_workgroups_per_cu():
     """224 CUs x 2 resident workgroups: 512 tiles need 2 waves of 448 slots, the second one
     running on 64/2 = 32 CUs -> 1 - idle = (224*2 - 224 + 32) / (224*2)."""
