@@ -253,6 +253,14 @@ def main():
                             "sum_kernel_ms": dec_kernel_s * 1e3},
         "prefill_kernel_ms": {k: round(v[0] / args.steps / 1e6, 4) for k, v in kp.items()},
     }
+    # what a plain copy kernel moves (read + write) on the decode partition alone: the practical ceiling of that partition
+    dm = 256 - pm
+    if dm >= 8:
+        copy_bytes, copy_iters = 1 << 28, 4        # 512 MiB touched per pass: beyond the 256 MB memory-side cache
+        eng.probe_copy(1, dm, copy_bytes, 1)
+        copy_gbps = 2 * copy_bytes * copy_iters / eng.probe_copy(1, dm, copy_bytes, copy_iters)
+        out["roofline_decode"]["partition_copy_gbps"] = copy_gbps
+        out["roofline_decode"]["frac_of_partition_copy"] = out["roofline_decode"]["achieved"] / copy_gbps
     if args.pmc_probe:
         eng.probe_copy(0, 256, PMC_PROBE_BYTES, 2)
     if not args.no_cpu_baseline:
