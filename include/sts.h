@@ -181,8 +181,10 @@ int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32
 int sts_op_attn_prefill(const float* q, const float* k, const float* v, float* out, int32_t t, int32_t prior,
                         int32_t n_q, int32_t n_kv, int32_t d, const int32_t* pages, int32_t n_pool_pages);
 /* Decode attention: q [n, n_q, d]; request r has ctx[r] cached tokens given in k,v (concatenated
- * over requests, [sum ctx, n_kv, d]) and attends to all of them. A context is processed in chunks
- * of chunk_pages pages (1..32) whose partial results are merged. out [n, n_q, d]. */
+ * over requests, [sum ctx, n_kv, d]) and attends to all of them. A context is cut into
+ * ceil(pages / chunk_pages) equal chunks (chunk_pages 1..64) whose partial results are merged; a
+ * context of one chunk is finished by the attention kernel itself. out [n, n_q, d].
+ * STS_EINVAL for a chunk size out of range. */
 int sts_op_attn_decode(const float* q, const float* k, const float* v, float* out, int32_t n, const int32_t* ctx,
                        int32_t n_q, int32_t n_kv, int32_t d, int32_t chunk_pages);
 
