@@ -419,3 +419,13 @@ def test_live_serving_with_online_recalibration(sts, tiny):
     assert srv.profile.dump() != before
     assert st["estimator_mape_prefill"] > 0 and st["estimator_mape_decode"] > 0
     srv.close()
+
+
+def test_chunk_study_tool_on_the_small_model(sts, capsys, monkeypatch):
+    """The chunked-prefill experiment of Section 2.2.2 runs end to end (small model, 512-token prompt)."""
+    import sys
+    from paper_2504_19516_amd import chunk_study
+    monkeypatch.setattr(sys, "argv", ["chunk_study", "--model", "tiny", "--tokens", "512", "--chunks", "128,256"])
+    chunk_study.main()
+    out = capsys.readouterr().out
+    assert "| 128 | 4 |" in out and "| 256 | 2 |" in out and "(unchunked) | 1 |" in out

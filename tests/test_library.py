@@ -134,3 +134,15 @@ def test_online_recalibration_bit_exact_vs_oracle_and_converges(sts):
         p.observe(desc, es, target_p, target_d, 300_000)
     got = p.query(desc, es)
     assert abs(got[0] - target_p) <= 0.02 * target_p and abs(got[1] - target_d) <= 0.02 * target_d
+
+
+def test_host_overheads_tool_runs_without_a_gpu(sts, capsys, monkeypatch):
+    """The control-path timing tool (latency query, Algorithm 1 cycle, replay) needs no GPU."""
+    import os
+    import sys
+    from paper_2504_19516_amd import host_overheads
+    prof = os.path.join(os.path.dirname(host_overheads.__file__), "data", "mi355x_llama8b.profile")
+    monkeypatch.setattr(sys, "argv", ["host_overheads", "--profile", prof])
+    host_overheads.main()
+    out = capsys.readouterr().out
+    assert "sts_latency_query" in out and out.count("sts_sched_decide") == 3 and "sts_sched_replay" in out
