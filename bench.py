@@ -253,7 +253,25 @@ def main():
                             "sum_kernel_ms": dec_kernel_s * 1e3},
         "prefill_kernel_ms": {k: round(v[0] / args.steps / 1e6, 4) for k, v in kp.items()},
     }
-    # what a plain copy kernel moves (read + write) on the decode partition alone: the practical ceiling of that partition
+    # the prefill GEMMs one by one: rate against the partition's share of the MFMA peak, and against that share
+    # less the idle ratio of wave quantisation (paper Section 2.2.1) for the tile grid the latency model assumes
+    # (128 x 128 tiles, two workgroups per CU), which separates quantisation loss from kernel inefficiency
+    h, mlp = desc.hidden, desc.mlp
+    qd, kvd = desc.n_q_heads * desc.head_dim, desc.n_kv_heads * desc.head_dim
+    part_peak = PEAK_BF16 * pm / 256
+    gemms = {}
+    for name, n_out, k_in in (("qkv", qd + 2 * kvd, h), ("o", h, qd), ("gateup", 2 * mlp, h), ("down", h, mlp)):
+        ns, cnt = kp[name]
+        rate = 2 * PREFILL_TOKENS * n_out * k_in / (ns / cnt * 1e-9)
+        tiles = -(-PREFILL_TOKENS // 128) * -(-n_out // 128)
+        _, _, idle_num, idle_den = sts.wave_quant(tiles, pm, 2)
+        idle = idle_num / idle_den
+        gemms[name] = {"tflops": round(rate / 1e12, 1), "frac_of_partition_peak": round(rate / part_peak, 4),
+                       "tiles_128x128": tiles, "idle_ratio": round(idle, 4),
+                       "frac_of_partition_peak_less_idle": round(rate / (part_peak * (1 - idle)), 4)}
+    out["prefill_gemms"] = gemms
+    # what a plain copy kernel moves (read + write) on the decode partition, alone and beside a prefill slice of
+    # this workload (D_p and D_{p,sl} of the paper's Section 3.2): the practical ceiling of that partition
     dm = 256 - pm
     if dm >= 8:
         copy_bytes, copy_iters = 1 << 28, 4        # 512 MiB touched per pass: beyond the 256 MB memory-side cache
@@ -261,6 +279,12 @@ def main():
         copy_gbps = 2 * copy_bytes * copy_iters / eng.probe_copy(1, dm, copy_bytes, copy_iters)
         out["roofline_decode"]["partition_copy_gbps"] = copy_gbps
         out["roofline_decode"]["frac_of_partition_copy"] = out["roofline_decode"]["achieved"] / copy_gbps
+        pseq = eng.seq_create()                    # two timed passes (0.7 ms) inside the 1 ms prefill slice
+        eng.prefill_launch([pseq], [wl.ptokens], 0, 1)
+        co_ns = eng.probe_copy(1, dm, copy_bytes, 2)
+        eng.prefill_finish()
+        eng.seq_free(pseq)
+        out["roofline_decode"]["partition_copy_gbps_beside_prefill"] = 2 * copy_bytes * 2 / co_ns
     if args.pmc_probe:
         eng.probe_copy(0, 256, PMC_PROBE_BYTES, 2)
     if not args.no_cpu_baseline:
