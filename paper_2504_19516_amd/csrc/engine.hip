@@ -22,7 +22,7 @@
 
 using namespace sts;
 
-static int g_hip_err = 0;
+static std::atomic<int> g_hip_err{0};   // either phase's control thread may record an error
 #define HIPCK(x)                                                 \
   do {                                                           \
     hipError_t e_ = (x);                                         \
@@ -41,7 +41,7 @@ extern "C" const char* sts_strerror(int code) {
     default: return "unknown error";
   }
 }
-extern "C" int sts_last_hip_error(void) { return g_hip_err; }
+extern "C" int sts_last_hip_error(void) { return g_hip_err.load(); }
 
 static const char* kKernelNames[STS_K_COUNT] = {"embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup",
                                                 "swiglu", "down", "reduce", "head", "sample"};
@@ -1023,17 +1023,19 @@ extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t byte
     HIPCK(hipDeviceSynchronize());
     c->probe_bytes = bytes;
   }
-  hipEvent_t e0, e1;
-  HIPCK(hipEventCreate(&e0)); HIPCK(hipEventCreate(&e1));
+  struct Events {                                                   // destroyed on every return path
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ~Events() { if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); }
+  } ev;
+  HIPCK(hipEventCreate(&ev.e0)); HIPCK(hipEventCreate(&ev.e1));
   const int grid = cus * 8;
   HIPCK(copy_probe(st, c->probe_dst, c->probe_src, bytes, grid));   // warm-up
-  HIPCK(hipEventRecord(e0, st));
+  HIPCK(hipEventRecord(ev.e0, st));
   for (int i = 0; i < iters; i++) HIPCK(copy_probe(st, c->probe_dst, c->probe_src, bytes, grid));
-  HIPCK(hipEventRecord(e1, st));
-  HIPCK(hipEventSynchronize(e1));
+  HIPCK(hipEventRecord(ev.e1, st));
+  HIPCK(hipEventSynchronize(ev.e1));
   float ms = 0.f;
-  HIPCK(hipEventElapsedTime(&ms, e0, e1));
-  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  HIPCK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
   *ns_out = (int64_t)((double)ms * 1e6);
   return STS_OK;
 }

@@ -12,6 +12,8 @@
 //
 // Lane layout of the 32x32 accumulator block (register r of lane l):
 //   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
+#include <atomic>
+
 #include "kernels.h"
 
 namespace sts {
@@ -455,11 +457,11 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   void (*kern)(GemmArgs);
   if constexpr (DL != 0) kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL>;
   else kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
+  if (!attr_set.load()) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.store(true);
   }
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = g.N / BN;
