@@ -150,10 +150,10 @@ def cpu_baseline(desc, ctx, n_pre=PREFILL_TOKENS, n_dec=DECODE_BATCH):
                       f"(contexts {min(dctx)}..{max(dctx)}, {sum(dctx)} cached tokens in all), the whole step of this workload; {dt:.1f} s"}
 
 
-def stored_traffic(prefill_cus):
-    """HBM bytes per gate/up launch from the committed rocprofv3 --pmc measurement of this workload
-    (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy kernel; written by
-    paper_2504_19516_amd/pmc_traffic.py), or None when no record matches this split."""
+def stored_traffic(prefill_cus, key="gateup_hbm_bytes_per_launch"):
+    """HBM bytes per gate/up launch (or, with key "decode_hbm_bytes_per_step", per decode layer-step) from
+    the committed rocprofv3 --pmc measurement of this workload (FETCH_SIZE and WRITE_SIZE runs, scaled by
+    the copy kernel; written by paper_2504_19516_amd/pmc_traffic.py), or None when no record matches this split."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2504_19516_amd", "data", "pmc_traffic.json")
     try:
         with open(path) as f:
@@ -162,7 +162,7 @@ def stored_traffic(prefill_cus):
         return None
     if rec.get("workload") != "config2" or rec.get("prefill_cus") != prefill_cus:
         return None
-    return rec.get("gateup_hbm_bytes_per_launch")
+    return rec.get(key)
 
 
 def main():
@@ -248,7 +248,8 @@ def main():
                      "ms_per_step_with_kernel_events": kt_step_s * 1e3},
         "roofline_decode": {"bound": "hbm", "phase": "decode layer-step (all its kernels)", "achieved": decode_bytes / (td * 1e-9) / 1e9,
                             "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": decode_bytes / (td * 1e-9) / PEAK_HBM,
-                            "algorithmic_bytes": decode_bytes, "partition_cus": 256 - pm,
+                            "algorithmic_bytes": decode_bytes, "traffic": stored_traffic(pm, "decode_hbm_bytes_per_step"),
+                            "partition_cus": 256 - pm,
                             "kernel_ms": {k: round(v[0] / args.steps / 1e6, 4) for k, v in kd.items()},
                             "sum_kernel_ms": dec_kernel_s * 1e3},
         "prefill_kernel_ms": {k: round(v[0] / args.steps / 1e6, 4) for k, v in kp.items()},

@@ -216,8 +216,8 @@ int k_collect(sts_ctx* c, Phase& ph) {
   } while (0)
 
 int pick_cfg(int m, int n, int k, int cus) {
-  // decode batches: 64x128 tiles keep two workgroups (8 waves) per CU streaming weights, which
-  // measured faster than 64x256 / 32x256 (one workgroup per CU) at every partition size
+  // decode batches: 64x128 tiles, two workgroups (8 waves) per CU streaming weights
+  // (pick_decode_gemm may widen them to 64x256)
   if (m <= 64) return GEMM_64x128;
   // up to 128 rows: one row of 128x128 tiles, two workgroups per CU. Above that both shapes compute
   // 256 rows and the 256x256 tile's larger wave tiles run the MFMAs faster; a large decode batch
@@ -473,7 +473,7 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     max_pages = std::max(max_pages, np);
     ph.h_tokens[i] = in_tokens[i];
   }
-  // Context chunks of a fixed page count: the largest of 32/16/8 pages that still yields about
+  // Context chunks of at most chunk_pages pages: the largest of 64/32/16/8 that still yields about
   // four workgroups per CU of the partition (8 pages keep the four waves of a workgroup busy with
   // one two-page block each), never more than 128 chunks for the longest context.
   int chunk_pages = attn_decode_max_chunk_tokens() / pt;
@@ -569,7 +569,7 @@ int alloc_phase(sts_ctx* c, int side) {
   STSCK(dev_alloc(c, &ph.next, nseq));
   {
     const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
-    // decode attention items: a context has at most 128 chunks, and never more than one per 4 pages
+    // decode attention items: a context has at most 128 chunks, and fewer than one per 4 pages (chunks hold >= 8)
     const size_t dec_items = side == 1 ? nseq * std::min<size_t>(128, (mp + 3) / 4) : 0;
     ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + sizeof(int)) + items * sizeof(AttnItem) + dec_items * sizeof(DecodeItem) +
                     rows * sizeof(int) + nseq * mp * sizeof(int) + 8 * 256;
@@ -585,7 +585,7 @@ int alloc_phase(sts_ctx* c, int side) {
     ph.tail_ws_bytes = tail_floats * sizeof(float);
   } else {
     const size_t widest = std::max<size_t>(std::max(c->qkvn, 2 * d.mlp), d.hidden);
-    const size_t max_chunks = std::min<size_t>(128, (mp + 3) / 4);     // see decode_enqueue: chunks of >= 4 pages, <= 128 chunks
+    const size_t max_chunks = std::min<size_t>(128, (mp + 3) / 4);     // see decode_enqueue: chunks of >= 8 pages, <= 128 chunks
     STSCK(dev_alloc(c, &ph.part, 8 * rows * widest));
     STSCK(dev_alloc(c, &ph.Q, rows * c->qd));
     STSCK(dev_alloc(c, &ph.attn_ws, attn_decode_ws_floats((int)rows, d.n_q_heads, d.head_dim, (int)max_chunks)));

@@ -1,4 +1,4 @@
-"""HBM traffic of the prefill gate/up GEMM from rocprofv3 byte counters.
+"""HBM traffic of the prefill gate/up GEMM and of the decode layer-step from rocprofv3 byte counters.
 
 Takes the counter CSVs of two runs of the benchmark with the copy-kernel reference switched on,
 
@@ -6,8 +6,9 @@ Takes the counter CSVs of two runs of the benchmark with the copy-kernel referen
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir2> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --pmc-probe
 
 scales each counter by what it reads for the copy kernel (which moves a known number of bytes
-each way) and prints the per-launch figures. With --json it also writes the record bench.py
-reports as roofline.traffic.
+each way) and prints the per-launch figures of the gate/up GEMM and the per-step sum over the
+decode phase's kernels. With --json it also writes the record bench.py reports as
+roofline.traffic and roofline_decode.traffic.
 
     python -m paper_2504_19516_amd.pmc_traffic <fetch.csv> <write.csv> --prefill-cus 224 [--json]
 """
@@ -23,6 +24,12 @@ import re
 COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
 GATEUP_KERNEL = "gemm_dl_kernel"           # the SwiGLU instantiation is the gate/up GEMM
 COPY_KERNEL = "copy_kernel"
+# kernels that only the decode phase launches; one attn_decode_mfma launch = one decode layer-step.
+# (Its embedding and first RMSNorm launches share kernels with the prefill phase and are left out:
+# 64 rows, under 2 MB per step.)
+DECODE_STEP_KERNEL = "attn_decode_mfma_kernel"
+DECODE_KERNELS = (r"attn_decode_mfma_kernel", r"attn_decode_merge_kernel", r"decode_qkv_finish_kernel", r"reduce_resid_norm_kernel",
+                  r"reduce_swiglu_kernel", r"gemm_dl_kernel<64, |gemm_dl_kernelILi64E")
 
 
 def per_kernel(path, counter):
@@ -48,29 +55,50 @@ def main():
     ap.add_argument("write_csv")
     ap.add_argument("--prefill-cus", type=int, required=True)
     ap.add_argument("--json", action="store_true")
+    ap.add_argument("--list", action="store_true", help="also print every kernel's mean bytes per launch")
     args = ap.parse_args()
     out = {}
     lines = []
     for counter, path in (("FETCH_SIZE", args.fetch_csv), ("WRITE_SIZE", args.write_csv)):
         rows = per_kernel(path, counter)
         copy = pick(rows, COPY_KERNEL)
+        # the benchmark also runs the copy kernel on smaller buffers (its bandwidth probes of the decode
+        # partition); the reference launches are the largest ones
+        copy = [v for v in copy if v >= 0.75 * max(copy)] if copy else copy
         # SwiGLU epilogue = fifth template argument 3 (the sixth is the stage count), demangled or mangled name
         gate = pick(rows, GATEUP_KERNEL, r"<\d+, \d+, \d+, \d+, 3, \d+>|ELi3ELi\d+EE")
         if not copy or not gate:
             raise SystemExit(f"{counter}: kernels not found in {path} (copy launches {len(copy)}, gate/up launches {len(gate)})")
         copy_mean, gate_mean = sum(copy) / len(copy), sum(gate) / len(gate)
         factor = COPY_BYTES / copy_mean                     # bytes per counter unit
+        steps = len(pick(rows, DECODE_STEP_KERNEL))
+        dec_units = sum(sum(v) for name, v in rows.items() if any(re.search(pat, name) for pat in DECODE_KERNELS))
+        if not steps:
+            raise SystemExit(f"{counter}: no decode step found in {path}")
         out[counter] = dict(copy_counter=copy_mean, factor_bytes_per_unit=factor, gateup_counter=gate_mean,
-                            gateup_bytes=gate_mean * factor, launches=len(gate))
+                            gateup_bytes=gate_mean * factor, launches=len(gate), decode_bytes=dec_units / steps * factor, decode_steps=steps)
         lines.append(f"{counter}: copy kernel reads {copy_mean:.1f} per launch for {COPY_BYTES} bytes -> {factor:.2f} bytes per unit; "
                      f"gate/up GEMM {gate_mean:.1f} per launch over {len(gate)} launches -> {gate_mean * factor / 1e6:.1f} MB")
     total = out["FETCH_SIZE"]["gateup_bytes"] + out["WRITE_SIZE"]["gateup_bytes"]
     lines.append(f"gate/up GEMM HBM traffic per launch: {total / 1e6:.1f} MB "
                  f"(read {out['FETCH_SIZE']['gateup_bytes'] / 1e6:.1f}, written {out['WRITE_SIZE']['gateup_bytes'] / 1e6:.1f})")
+    if args.list:
+        for counter, path in (("FETCH_SIZE", args.fetch_csv), ("WRITE_SIZE", args.write_csv)):
+            rows = per_kernel(path, counter)
+            f = out[counter]["factor_bytes_per_unit"]
+            lines.append(f"{counter}, mean per launch:")
+            for name, v in sorted(rows.items(), key=lambda kv: -sum(kv[1]) / len(kv[1])):
+                if sum(v) / len(v) * f >= 1e5:
+                    lines.append(f"  {sum(v) / len(v) * f / 1e6:10.1f} MB  x {len(v):4d}  {name[:90]}")
+    dec_total = out["FETCH_SIZE"]["decode_bytes"] + out["WRITE_SIZE"]["decode_bytes"]
+    lines.append(f"decode layer-step HBM traffic (its own kernels, mean of {out['FETCH_SIZE']['decode_steps']} steps): {dec_total / 1e6:.1f} MB "
+                 f"(read {out['FETCH_SIZE']['decode_bytes'] / 1e6:.1f}, written {out['WRITE_SIZE']['decode_bytes'] / 1e6:.1f})")
     print("\n".join(lines))
     if args.json:
         rec = dict(workload="config2", prefill_cus=args.prefill_cus, gateup_hbm_bytes_per_launch=total,
                    read_bytes=out["FETCH_SIZE"]["gateup_bytes"], written_bytes=out["WRITE_SIZE"]["gateup_bytes"],
+                   decode_hbm_bytes_per_step=dec_total, decode_read_bytes=out["FETCH_SIZE"]["decode_bytes"],
+                   decode_written_bytes=out["WRITE_SIZE"]["decode_bytes"],
                    fetch_factor=out["FETCH_SIZE"]["factor_bytes_per_unit"], write_factor=out["WRITE_SIZE"]["factor_bytes_per_unit"])
         path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data", "pmc_traffic.json")
         with open(path, "w") as f:
