@@ -18,6 +18,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import sys
 import threading
 import time
 
@@ -157,6 +158,7 @@ class LiveServer:
         eng.set_partition(n, n)
         t0 = time.perf_counter_ns()
         clock = lambda: time.perf_counter_ns() - t0
+        next_report = 30_000_000_000
 
         def finish(r, now):
             r.finish = now
@@ -263,6 +265,10 @@ class LiveServer:
                     if r.n_dec >= r.out_len - 1:
                         finish(r, now)
                         D.remove(r)
+                if now >= next_report:             # a long run says where it is every 30 s
+                    next_report = now + 30_000_000_000
+                    print(f"[serve] {mode}: t = {now / 1e9:.0f} s, {sum(r.finish >= 0 for r in reqs)}/{len(reqs)} finished, "
+                          f"{len(Q)} queued, {len(D)} decoding", file=sys.stderr, flush=True)
                 if log_every and len(timeline) % log_every == 0:
                     timeline.append((now, "decode", eng.get_partition()[1], len(decode_batch)))
         eng.set_partition(n, n)
