@@ -35,9 +35,10 @@ def profile_text(hw: dict, grids: dict) -> str:
 
 
 class Profiler:
-    def __init__(self, desc, max_tokens=8192, max_batch=64, max_ctx=8192, granule=32):
+    def __init__(self, desc, max_tokens=8192, max_batch=224, max_ctx=8192, granule=32):
         self.desc, self.granule = desc, granule
-        pages = (max_batch * (max_ctx + 64) + 2 * max_tokens) // 16 + 64
+        # room for the largest decode samples: 64 requests at max_ctx, or max_batch requests at 2048 tokens
+        pages = (max(64 * (max_ctx + 64), max_batch * (2048 + 64)) + 2 * max_tokens) // 16 + 64
         self.eng = sts.Engine(desc, weight_seed=1, init_weights=True, kv_pool_pages=pages, max_prefill_tokens=max_tokens,
                               max_prefill_seqs=4, max_decode_batch=max_batch, max_seqs=max_batch + 8,
                               max_pages_per_seq=(max_ctx + 128) // 16)
@@ -211,7 +212,7 @@ class Profiler:
             log(f"alpha_prefill pm={pm}: {[round(v / PPM, 3) for v in row]}")
         self.grids["alpha_prefill"] = ([list(pms), list(tokens)], vals)
 
-    def calibrate_decode(self, dms=(32, 64, 128, 256), batches=(8, 64), mean_ctx=(256, 2048), log=print):
+    def calibrate_decode(self, dms=(32, 64, 128, 256), batches=(8, 64, 224), mean_ctx=(256, 2048), log=print):
         vals = np.zeros((len(dms), len(batches), len(mean_ctx)), dtype=np.int64)
         ctx_axis = None
         for bi, b in enumerate(batches):
@@ -234,7 +235,7 @@ class Profiler:
         return profile_text(self.hw, self.grids)
 
 
-def measure_heldout(profiler: Profiler, n_prefill=24, n_decode=12, seed=11, step=None, log=print):
+def measure_heldout(profiler: Profiler, n_prefill=24, n_decode=16, seed=11, step=None, log=print):
     """Measured latencies of seeded execution states that are not calibration samples: a list of
     (phase, execution state, measured ns). CU counts are multiples of `step` (default: the
     scheduler's granule, the only counts Algorithm 1 can choose)."""
@@ -250,7 +251,8 @@ def measure_heldout(profiler: Profiler, n_prefill=24, n_decode=12, seed=11, step
         es = dict(prefill_len=[t], prefill_ctx=[0], prefill_cus=pm, decode_cus=0, layer_begin=0, n_layers_step=layers)
         out.append(("prefill", es, ns))
         log(f"held-out prefill pm={pm} tokens={t}: measured {ns / 1e6:.3f} ms")
-    fixed_d = [(96, 32, 1024), (160, 16, 512), (224, 48, 1500), (64, 64, 700), (256, 24, 3000)] if on_grid else []
+    fixed_d = [(96, 32, 1024), (160, 16, 512), (224, 48, 1500), (64, 64, 700), (256, 24, 3000), (32, 150, 900), (64, 200, 600),
+               (128, 120, 1200)] if on_grid else []
     rand_d = [(int(rng.integers(32 // step, n // step + 1)) * step, int(rng.integers(4, 65)), int(rng.integers(200, 3000)))
               for _ in range(max(0, n_decode - len(fixed_d)))]
     for dm, b, mc in fixed_d + rand_d:
@@ -294,12 +296,13 @@ def sample_count_study(profiler: Profiler, heldout, log=print):
     leave the larger held-out states outside their range (extrapolation)."""
     gp, gd = profiler.grids["alpha_prefill"], profiler.grids["alpha_decode"]
     npm, nt = len(gp[0][0]), len(gp[0][1])
-    ndm = len(gd[0][0])
+    ndm, nb, nc = len(gd[0][0]), len(gd[0][1]), len(gd[0][2])
     every = lambda n, k: sorted(set(list(range(0, n, k)) + [n - 1]))
     p_sets = [("ends of the CU axis, tokens <= %d" % gp[0][1][min(2, nt - 1)], [[0, npm - 1], list(range(min(3, nt)))]),
               ("every other CU count, tokens <= %d" % gp[0][1][min(3, nt - 1)], [every(npm, 2), list(range(min(4, nt)))]),
               ("full grid", [list(range(npm)), list(range(nt))])]
-    d_sets = [("ends of the CU axis", [[0, ndm - 1], [0, 1], [0, 1]]), ("full grid", [list(range(ndm)), [0, 1], [0, 1]])]
+    d_sets = [("ends of the CU and batch axes", [[0, ndm - 1], sorted({0, nb - 1}), list(range(nc))]),
+              ("full grid", [list(range(ndm)), list(range(nb)), list(range(nc))])]
     rows = []
     for name, keep in p_sets:
         grids = dict(profiler.grids, alpha_prefill=subsample(gp, keep))
