@@ -147,6 +147,7 @@ class Profiler:
     def prefill_host_ns(self, tokens, layers=4, reps=3):
         """Host-clock time of a prefill slice on the prefill CUs in force (usable while decode runs)."""
         eng = self.eng
+        layers = min(layers, self.desc.n_layers)
         toks = synth.tokens(3, tokens, self.desc.vocab)
         best = None
         for _ in range(reps + 1):

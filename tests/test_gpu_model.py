@@ -429,3 +429,32 @@ def test_chunk_study_tool_on_the_small_model(sts, capsys, monkeypatch):
     chunk_study.main()
     out = capsys.readouterr().out
     assert "| 128 | 4 |" in out and "| 256 | 2 |" in out and "(unchunked) | 1 |" in out
+
+
+def test_profiler_builds_a_profile_the_estimator_loads(sts):
+    """The offline sweep of Section 3.2.4 on the small model with a reduced grid: the profile it writes
+    parses, carries every table the estimator reads, and reproduces a calibration sample (a prefill
+    slice and a decode step measured again land near the prediction; small-model times are
+    launch-bound and noisy, hence the wide band)."""
+    from paper_2504_19516_amd import profiler
+    desc = synth.tiny_model()
+    quiet = lambda msg: None
+    pr = profiler.Profiler(desc, max_tokens=4096, max_batch=16, max_ctx=4096)    # the compute-peak probe prefills 4096 tokens
+    pr.sweep_hardware(log=quiet)
+    pr.sweep_contention(dms=(64, 192), sls=(0, 1024), log=quiet)
+    pr.sweep_prefill_corun(dms=(64,), tokens=512, batch=8, ctx=256, log=quiet)
+    pr.calibrate_prefill(pms=(64, 256), tokens=(256, 1024), log=quiet)
+    pr.calibrate_decode(dms=(64, 256), batches=(4, 16), mean_ctx=(64, 512), log=quiet)
+    text = pr.text()
+    for table in ("grid bw 2", "grid prefill_corun 1", "grid alpha_prefill 2", "grid alpha_decode 3"):
+        assert table in text
+    prof = sts.Profile(text=text)
+    assert prof.dump() == text
+    ns, layers = pr.prefill_ns(256, 1024)
+    pred = prof.query(desc, dict(prefill_len=[1024], prefill_ctx=[0], prefill_cus=256, decode_cus=0, layer_begin=0, n_layers_step=layers))[0]
+    assert 0.6 < pred / ns < 1.6
+    seqs = pr.make_decode_batch([512] * 16)
+    dns = pr.decode_ns(256, seqs)
+    dpred = prof.query(desc, dict(decode_ctx=[pr.eng.seq_length(s) for s in seqs], decode_cus=256, prefill_cus=0))[1]
+    assert 0.6 < dpred / dns < 1.6
+    pr.close()
