@@ -146,3 +146,34 @@ def test_host_overheads_tool_runs_without_a_gpu(sts, capsys, monkeypatch):
     host_overheads.main()
     out = capsys.readouterr().out
     assert "sts_latency_query" in out and out.count("sts_sched_decide") == 3 and "sts_sched_replay" in out
+
+
+def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, monkeypatch):
+    """The counter arithmetic on hand-made rocprofv3 CSVs: the unit of each counter comes from the largest
+    copy-kernel launches (512 MiB each way; smaller probe launches are ignored), the gate/up GEMM is the
+    SwiGLU instantiation, and the decode step sums the decode-only kernels per attention launch."""
+    import sys
+    from paper_2504_19516_amd import pmc_traffic
+    gateup = "void sts::gemm_dl_kernel<256, 256, 2, 4, 3, 2>(sts::GemmArgs)"
+    other = "void sts::gemm_dl_kernel<256, 256, 2, 4, 0, 2>(sts::GemmArgs)"
+    skinny = "void sts::gemm_dl_kernel<64, 128, 1, 4, 1, 3>(sts::GemmArgs)"
+    attn = "void sts::attn_decode_mfma_kernel<128, 4>(args)"
+    copy = "sts::copy_kernel(a, b, c)"
+
+    def write(name, counter, unit):
+        rows = [(copy, (512 << 20) // unit)] * 3 + [(copy, (256 << 20) // unit)] * 5           # reference launches, then probes
+        rows += [(gateup, 800_000_000 // unit), (gateup, 780_000_000 // unit), (other, 123)]
+        rows += [(attn, 300_000_000 // unit)] * 2 + [(skinny, 100_000_000 // unit)] * 8         # two decode steps
+        path = tmp_path / name
+        with open(path, "w") as f:
+            f.write("Counter_Name,Kernel_Name,Counter_Value\n")
+            for k, v in rows:
+                f.write(f'{counter},"{k}",{v}\n')
+        return str(path)
+    fetch, wr = write("fetch.csv", "FETCH_SIZE", 2048), write("write.csv", "WRITE_SIZE", 1024)
+    monkeypatch.setattr(sys, "argv", ["pmc_traffic", fetch, wr, "--prefill-cus", "224"])
+    pmc_traffic.main()
+    out = capsys.readouterr().out
+    assert "2048.00 bytes per unit" in out and "1024.00 bytes per unit" in out
+    assert "gate/up GEMM HBM traffic per launch: 1580.0 MB (read 790.0, written 790.0)" in out
+    assert "decode layer-step HBM traffic (its own kernels, mean of 2 steps): 1400.0 MB (read 700.0, written 700.0)" in out
