@@ -273,6 +273,36 @@ def test_chunked_and_layer_sliced_prefill(sts, tiny, eng, oracle_case):
     free_all(eng, [whole, sliced, chunked])
 
 
+def test_kv_pages_after_prefill_chunks_and_decode_match_oracle(sts, tiny, eng):
+    """What the path leaves in the paged cache (rotated K, V; Section 3.5.1's shared KV pool): two prompt
+    chunks that meet in the middle of a page, a batched second sequence, then three decode steps; every
+    layer's K and V of every position against the oracle's cache."""
+    desc, w = tiny
+    toks = synth.tokens(SEED_TOK + 40, 131, desc.vocab)
+    toks_b = synth.tokens(SEED_TOK + 41, 37, desc.vocab)
+    dec = synth.tokens(SEED_TOK + 42, 6, desc.vocab).reshape(3, 2)
+    orc = T.Oracle(desc, w, 16)
+    orc.kv.add_sequence(0, list(range(0, 9)))
+    orc.kv.add_sequence(1, list(range(9, 12)))
+    orc.prefill_append(0, toks[:50]); orc.prefill_append(0, toks[50:]); orc.prefill_append(1, toks_b)
+    a, b = eng.seq_create(), eng.seq_create()
+    eng.prefill_append(a, toks[:50], want_logits=False)
+    eng.prefill_batch([a, b], [toks[50:], toks_b], want_logits=False)
+    for step in range(3):
+        orc.decode_step([0, 1], dec[step])
+        eng.decode_step([a, b], dec[step], want_logits=False, want_next=False)
+    for seq, gseq, n in ((0, a, 134), (1, b, 40)):
+        assert eng.seq_length(gseq) == n
+        for l in range(desc.n_layers):
+            k_ref, v_ref = orc.kv.gather(l, seq, n)
+            k, v = eng.kv_read(l, gseq, 0, n)
+            assert rel(k, k_ref) <= TOL and rel(v, v_ref) <= TOL, (seq, l)
+            # position by position, so that a token written to the wrong slot cannot hide in the maximum
+            assert np.all(np.abs(k - k_ref).max(axis=(1, 2)) <= TOL * np.abs(k_ref).max())
+            assert np.all(np.abs(v - v_ref).max(axis=(1, 2)) <= TOL * np.abs(v_ref).max())
+    free_all(eng, [a, b])
+
+
 def test_batched_prefill_equals_separate(sts, tiny, eng):
     desc, _ = tiny
     t1, t2, t3 = synth.tokens(41, 37, desc.vocab), synth.tokens(42, 150, desc.vocab), synth.tokens(43, 1, desc.vocab)
