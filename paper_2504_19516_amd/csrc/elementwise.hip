@@ -199,7 +199,7 @@ hipError_t rmsnorm_rows(hipStream_t s, bf16* out, const float* X, const float* g
 // ------------------------------------------------------------------ rotary + KV page write (prefill)
 // One workgroup per token row. cos/sin of the row's position are computed once (in double:
 // positions reach tens of thousands of radians) and applied to every head. Q is rotated in
-// place; K is rotated and scattered to its page; V is scattered transposed.
+// place; K is rotated and scattered to its page; V is scattered transposed (page_tokens = 16).
 __global__ void __launch_bounds__(256) rope_kv_prefill_kernel(bf16* qkv, int ld, const PrefillSeq* seqs, int n_seqs,
                                                               const int* block_tables, const double* inv_freq,
                                                               bf16* pool, KvGeom geo, int n_q) {
@@ -234,7 +234,25 @@ __global__ void __launch_bounds__(256) rope_kv_prefill_kernel(bf16* qkv, int ld,
     *reinterpret_cast<bf16x8*>(dst + i0) = ya;
     *reinterpret_cast<bf16x8*>(dst + i0 + half) = yb;
   }
+  // V^T: a page row holds 16 tokens of one (head, dd). Where the chunk covers a whole group of 8
+  // tokens, the workgroup of the group's first row writes all 8 at once (one 16-byte store per
+  // (head, dd), the 8 values gathered from the 8 rows with lane-contiguous loads) and the other
+  // seven rows write nothing; a group the chunk covers only partly is written element by element.
   const bf16* vsrc = r + (n_q + geo.n_kv) * d;
+  const int g0 = pos & ~7;                                  // first position of this row's group of 8
+  const bool whole_group = g0 >= sq.p && g0 + 8 <= sq.p + sq.sl;
+  if (whole_group) {
+    if (pos != g0) return;
+    for (int t = threadIdx.x; t < geo.n_kv * d; t += blockDim.x) {
+      const int hd = t / d, dd = t % d;
+      bf16x8 pack;
+#pragma unroll
+      for (int e = 0; e < 8; e++) pack[e] = vsrc[(size_t)e * ld + t];
+      bf16* v = pool + ((size_t)page * geo.n_kv + hd) * geo.head_elems() + (size_t)geo.page_tokens * d;
+      *reinterpret_cast<bf16x8*>(v + (size_t)dd * geo.page_tokens + slot) = pack;
+    }
+    return;
+  }
   for (int t = threadIdx.x; t < geo.n_kv * d; t += blockDim.x) {
     const int hd = t / d, dd = t % d;
     bf16* v = pool + ((size_t)page * geo.n_kv + hd) * geo.head_elems() + (size_t)geo.page_tokens * d;
