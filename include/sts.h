@@ -131,7 +131,8 @@ int sts_step_concurrent(sts_ctx* ctx,
                         const int32_t* dseqs, const int32_t* dtokens, int32_t n_decode,
                         float* dlogits, int32_t* dnext);
 /* Device time of the last call's prefill part and decode part (HIP events on their own
- * streams), and the wall-clock span of the call. A part that did not run reports 0. */
+ * streams), and the wall-clock span of the call. A part that did not run, or whose launch is
+ * still in flight (sts_*_launch without its finish), reports 0. */
 int sts_last_timing(sts_ctx* ctx, int64_t* prefill_ns, int64_t* decode_ns, int64_t* wall_ns);
 /* Test hook: hidden state (residual stream) after the last call of a phase, fp32 [rows, hidden];
  * phase 0 = prefill batch rows, 1 = decode rows. */

@@ -949,7 +949,9 @@ extern "C" int sts_last_timing(sts_ctx* c, int64_t* prefill_ns, int64_t* decode_
   for (int side = 0; side < 2; side++) {
     if (!c->ph[side].ran) continue;
     float ms = 0.f;
-    HIPCK(hipEventElapsedTime(&ms, c->ph[side].ev0, c->ph[side].ev1));
+    const hipError_t e = hipEventElapsedTime(&ms, c->ph[side].ev0, c->ph[side].ev1);
+    if (e == hipErrorNotReady) { (void)hipGetLastError(); continue; }   // that phase has a launch in flight: reported as 0
+    HIPCK(e);
     t[side] = (int64_t)((double)ms * 1e6);
   }
   if (prefill_ns) *prefill_ns = t[0];

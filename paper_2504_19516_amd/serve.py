@@ -154,7 +154,10 @@ class LiveServer:
         decode_batch, cur_slice = [], None
         next_arrival, rejected = 0, 0
         timeline, decisions = [], []
-        err_p, err_d = [], []                  # |predicted - measured| / measured of every slice and step (host clock)
+        # |predicted - measured| / measured of every slice and step, measured on the device (HIP events around
+        # the phase's kernels, what the estimator was calibrated on); the host clock, which also sees how late
+        # this loop noticed the end of a phase while it was queuing the other one, is kept beside it
+        err_p, err_d, err_p_host, err_d_host = [], [], [], []
         eng.set_partition(n, n)
         t0 = time.perf_counter_ns()
         clock = lambda: time.perf_counter_ns() - t0
@@ -243,9 +246,11 @@ class LiveServer:
                 prefill_busy, turn_decode = False, True
                 l_exe = cur_slice[2]
                 timeline.append((now, "prefill", pm, sum(r.in_len for r in P), cur_slice[1], cur_slice[2], now - cur_slice[0], cur_slice[3]))
-                err_p.append(abs(cur_slice[3] - (now - cur_slice[0])) / max(1, now - cur_slice[0]))
+                dev_ns = eng.last_timing()[0] or now - cur_slice[0]
+                err_p.append(abs(cur_slice[3] - dev_ns) / max(1, dev_ns))
+                err_p_host.append(abs(cur_slice[3] - (now - cur_slice[0])) / max(1, now - cur_slice[0]))
                 if self.recalibrate_ppm:
-                    self.profile.observe(desc, slice_es, now - cur_slice[0], 0, self.recalibrate_ppm)
+                    self.profile.observe(desc, slice_es, dev_ns, 0, self.recalibrate_ppm)
                 if l_exe == desc.n_layers:
                     for r in P:
                         r.first_token = now
@@ -257,9 +262,11 @@ class LiveServer:
             if ddone:
                 eng.decode_finish(len(decode_batch))
                 decode_busy, turn_decode = False, False
-                err_d.append(abs(step_pred - (now - step_t0)) / max(1, now - step_t0))
+                dev_ns = eng.last_timing()[1] or now - step_t0
+                err_d.append(abs(step_pred - dev_ns) / max(1, dev_ns))
+                err_d_host.append(abs(step_pred - (now - step_t0)) / max(1, now - step_t0))
                 if self.recalibrate_ppm:
-                    self.profile.observe(desc, step_es, 0, now - step_t0, self.recalibrate_ppm)
+                    self.profile.observe(desc, step_es, 0, dev_ns, self.recalibrate_ppm)
                 for r in decode_batch:
                     r.n_dec += 1
                     if r.n_dec >= r.out_len - 1:
@@ -275,6 +282,8 @@ class LiveServer:
         st = self.stats(reqs, rejected, dict(cfg, ttft_slo_ns=self.slo[0], tpot_slo_ns=self.slo[1]))
         st["estimator_mape_prefill"] = float(np.mean(err_p)) if err_p else 0.0
         st["estimator_mape_decode"] = float(np.mean(err_d)) if err_d else 0.0
+        st["estimator_mape_prefill_host_clock"] = float(np.mean(err_p_host)) if err_p_host else 0.0
+        st["estimator_mape_decode_host_clock"] = float(np.mean(err_d_host)) if err_d_host else 0.0
         return st, decisions, timeline
 
     def run_two_threads(self, trace, cfg, seed=0):
