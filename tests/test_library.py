@@ -177,3 +177,26 @@ def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, m
     assert "2048.00 bytes per unit" in out and "1024.00 bytes per unit" in out
     assert "gate/up GEMM HBM traffic per launch: 1580.0 MB (read 790.0, written 790.0)" in out
     assert "decode layer-step HBM traffic (its own kernels, mean of 2 steps): 1400.0 MB (read 700.0, written 700.0)" in out
+
+
+def test_live_serving_statistics_by_inspection():
+    """SLO attainment counts a request only when its TTFT and its mean TPOT are both inside their limits
+    (the definition of the paper's Section 4.1); unfinished requests count against it; throughput is over
+    the makespan. Four hand-made requests, one per case."""
+    from paper_2504_19516_amd import serve
+    ms = 1_000_000
+
+    def req(rid, arrival, first, n_dec, finish, in_len=100, out_len=11):
+        r = serve.Req(rid, arrival, in_len, out_len)
+        r.first_token, r.n_dec, r.finish = first, n_dec, finish
+        return r
+    reqs = [req(0, 0, 500 * ms, 10, 900 * ms),                 # TTFT 0.5 s, TPOT 40 ms: inside both
+            req(1, 100 * ms, 1200 * ms, 10, 1500 * ms),        # TTFT 1.1 s: late first token
+            req(2, 200 * ms, 300 * ms, 10, 900 * ms),          # TPOT 60 ms: slow decode
+            req(3, 300 * ms, -1, 0, -1)]                       # never finished
+    st = serve.LiveServer.stats(reqs, 0, dict(ttft_slo_ns=1000 * ms, tpot_slo_ns=50 * ms))
+    assert st["n_requests"] == 4 and st["n_finished"] == 3
+    assert st["slo_attainment"] == 0.25
+    assert st["makespan_s"] == 1.5 and st["out_tokens"] == 33 and st["in_tokens"] == 300
+    assert abs(st["out_tokens_per_s"] - 22.0) < 1e-9 and abs(st["total_tokens_per_s"] - 222.0) < 1e-9
+    assert abs(st["ttft_mean_ms"] - (500 + 1100 + 100) / 3) < 1e-9 and abs(st["tpot_mean_ms"] - (40 + 30 + 60) / 3) < 1e-9
