@@ -245,8 +245,9 @@ class LiveServer:
                 eng.prefill_finish()
                 prefill_busy, turn_decode = False, True
                 l_exe = cur_slice[2]
-                timeline.append((now, "prefill", pm, sum(r.in_len for r in P), cur_slice[1], cur_slice[2], now - cur_slice[0], cur_slice[3]))
                 dev_ns = eng.last_timing()[0] or now - cur_slice[0]
+                timeline.append((now, "prefill", pm, sum(r.in_len for r in P), cur_slice[1], cur_slice[2], now - cur_slice[0], cur_slice[3],
+                                 dev_ns, len(P), len(D) if decode_busy else 0))
                 err_p.append(abs(cur_slice[3] - dev_ns) / max(1, dev_ns))
                 err_p_host.append(abs(cur_slice[3] - (now - cur_slice[0])) / max(1, now - cur_slice[0]))
                 if self.recalibrate_ppm:
