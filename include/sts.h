@@ -256,6 +256,9 @@ typedef struct {
                                          0 = off; modes 0, 2, 4, only when decode runs). The prefill set is kept,
                                          so the two CU sets intersect for that slice; the simulated durations
                                          ignore the contention */
+  int32_t min_batch_tokens;           /* batching floor, not in the paper: a new prefill batch keeps taking queued
+                                         requests until it holds this many tokens, also past the roofline ridge at
+                                         which Algorithm 1 stops batching (0 = the paper's rule alone) */
 } sts_sched_config;
 typedef struct {                      /* one scheduling cycle of the prefill scheduler */
   int64_t t_ns;                       /* simulated time of the decision */

@@ -60,6 +60,10 @@ class Config:
     # end-of-prefill boost (Section 3.3.1): extra decode CUs while the final slice of a prefill batch
     # runs; the prefill set is kept, so the two sets intersect for that slice. 0 = off
     decode_boost_cus: int = 0
+    # batching floor: keep adding queued requests to a new prefill batch until it holds this many tokens,
+    # even past the roofline ridge where Algorithm 1 stops (a batch at the ridge is still small enough
+    # for wave quantisation and launch overheads to cost 10-60 %). 0 = the paper's rule alone
+    min_batch_tokens: int = 0
 
 
 def chunked_prefill_iterations(sl, cs, ds):
@@ -172,7 +176,7 @@ class Replay:
         else:
             satisfy = p90([ttft[i] for i in self.Q]) <= cfg.ttft_slo_ns
             next_tasks, tokens = [], 0
-            while self.Q and (not next_tasks or self.intensity_below_ridge(next_tasks, pm_cur)):
+            while self.Q and (not next_tasks or self.intensity_below_ridge(next_tasks, pm_cur) or tokens < cfg.min_batch_tokens):
                 i = self.Q[0]
                 need = (reqs[i].in_len + reqs[i].out_len + PAGE - 1) // PAGE
                 if next_tasks and tokens + reqs[i].in_len > cfg.max_batch_tokens:

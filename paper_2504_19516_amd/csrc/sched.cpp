@@ -120,7 +120,7 @@ Decision decide(const Ctx& c, int64_t now, const std::vector<QReq>& Q, const std
     for (int i : order) qt.push_back(ttft[i]);
     satisfy = p90(qt) <= cfg.ttft_slo_ns;
     int64_t tokens = 0;
-    while (taken < order.size() && (next_tasks.empty() || c.intensity_below_ridge(next_tasks, pm_cur))) {
+    while (taken < order.size() && (next_tasks.empty() || c.intensity_below_ridge(next_tasks, pm_cur) || tokens < cfg.min_batch_tokens)) {
       const QReq& r = Q[order[taken]];
       const int64_t need = ((int64_t)r.in_len + r.out_len + PAGE - 1) / PAGE;
       if (!next_tasks.empty() && tokens + r.in_len > cfg.max_batch_tokens) break;
@@ -333,6 +333,7 @@ bool config_ok(const Profile& hw, const sts_sched_config* cfg) {
       cfg->mode < 0 || cfg->mode > 6 || cfg->ttft_slo_ns < 1 || cfg->tpot_slo_ns < 1) return false;
   if (hw.n_cu % hw.granule != 0 || hw.n_cu / hw.granule < 2) return false;
   if (cfg->decode_boost_cus < 0 || cfg->decode_boost_cus % hw.granule) return false;
+  if (cfg->min_batch_tokens < 0) return false;
   if ((cfg->mode == 2 || cfg->mode == 6) && (cfg->fixed_prefill_cus < hw.granule || cfg->fixed_prefill_cus >= hw.n_cu || cfg->fixed_prefill_cus % hw.granule)) return false;
   return true;
 }

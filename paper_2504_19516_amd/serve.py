@@ -502,6 +502,8 @@ def main():
     ap.add_argument("--sched-ttft-ms", type=float, default=0.0, help="TTFT target given to the scheduler (default: the SLO)")
     ap.add_argument("--sched-tpot-ms", type=float, default=0.0, help="TPOT target given to the scheduler (default: the SLO)")
     ap.add_argument("--layers-per-step", type=int, default=4)
+    ap.add_argument("--min-batch-tokens", type=int, default=0,
+                    help="batching floor: a new prefill batch keeps taking queued requests until it holds this many tokens (0: Algorithm 1's rule alone)")
     ap.add_argument("--recalibrate-ppm", type=int, default=0,
                     help="online alpha recalibration weight (parts per million per observation; 0 = off)")
     ap.add_argument("--control-threads", type=int, default=1, choices=[1, 2],
@@ -512,7 +514,8 @@ def main():
     args = ap.parse_args()
     make = {"8b": synth.llama8b_model, "70b": synth.llama70b_model}.get(args.model)
     desc = (make(args.layers) if args.layers else make()) if make else synth.tiny_model()
-    cfg = dict(ttft_slo_ns=int(args.ttft_ms * 1e6), tpot_slo_ns=int(args.tpot_ms * 1e6), layers_per_step=args.layers_per_step)
+    cfg = dict(ttft_slo_ns=int(args.ttft_ms * 1e6), tpot_slo_ns=int(args.tpot_ms * 1e6), layers_per_step=args.layers_per_step,
+               min_batch_tokens=args.min_batch_tokens)
     sched = (int((args.sched_ttft_ms or args.ttft_ms) * 1e6), int((args.sched_tpot_ms or args.tpot_ms) * 1e6))
     srv = LiveServer(desc, open(args.profile).read(), cfg, args.pool_pages, max_ctx=args.max_ctx,
                      max_batch_tokens=max(16384, args.max_ctx if args.workload == "long" else 0), sched_slo_ns=sched,

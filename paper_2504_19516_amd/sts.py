@@ -47,7 +47,7 @@ class ExecState(C.Structure):
 
 class SchedConfig(C.Structure):
     _fields_ = [("ttft_slo_ns", C.c_int64), ("tpot_slo_ns", C.c_int64)] + [(n, C.c_int32) for n in (
-        "layers_per_step", "max_batch_tokens", "max_decode_batch", "kv_pool_pages", "mode", "fixed_prefill_cus", "decode_boost_cus")]
+        "layers_per_step", "max_batch_tokens", "max_decode_batch", "kv_pool_pages", "mode", "fixed_prefill_cus", "decode_boost_cus", "min_batch_tokens")]
 
 
 class SchedReq(C.Structure):
@@ -397,7 +397,7 @@ class Profile:
     def _sched_config(cfg):
         return SchedConfig(cfg["ttft_slo_ns"], cfg["tpot_slo_ns"], cfg["layers_per_step"], cfg["max_batch_tokens"],
                            cfg["max_decode_batch"], cfg["kv_pool_pages"], cfg.get("mode", 0), cfg.get("fixed_prefill_cus", 0),
-                           cfg.get("decode_boost_cus", 0))
+                           cfg.get("decode_boost_cus", 0), cfg.get("min_batch_tokens", 0))
 
     def decide(self, desc, cfg: dict, now_ns, queue, inflight, layers_done, decode, pages_free, cur_pm, cur_dm):
         """One cycle of Algorithm 1. queue / inflight: lists of (id, arrival_ns, in_len, out_len);

@@ -196,3 +196,19 @@ def test_time_multiplexed_is_slower_under_load():
     b = S.replay(SHAPE, profile(), config(mode=1), tr)[1]
     assert a["n_finished"] == b["n_finished"] == len(tr)
     assert a["ttft_sum_ns"] < b["ttft_sum_ns"]
+
+
+def test_batching_floor_by_inspection():
+    """Three 700-token prompts queued at time 0. A 700-token batch is already past the roofline ridge of this
+    profile, so Algorithm 1's rule starts one prompt alone; with min_batch_tokens = 1500 the first batch
+    keeps taking queued prompts until it holds at least 1500 tokens (three prompts: 700, 1400, 2100), and
+    with a floor that a single prompt already meets nothing changes."""
+    trace = [(0, 700, 1)] * 3
+    first = lambda cfg: S.replay(SHAPE, profile(), cfg, trace)[0][0]
+    assert first(config())[1] == 1
+    assert first(config(min_batch_tokens=1500))[1] == 3
+    assert first(config(min_batch_tokens=1400))[1] == 2
+    assert first(config(min_batch_tokens=700))[1] == 1
+    # never more than the queue holds, and max_batch_tokens still caps the batch
+    assert first(config(min_batch_tokens=100000))[1] == 3
+    assert first(config(min_batch_tokens=100000, max_batch_tokens=1400))[1] == 2

@@ -119,3 +119,16 @@ def test_single_cycle_decide_matches_oracle_on_built_states(sts):
         assert got["tasks"] == r.P and got["admitted"] == (not had_p)
         assert (got["layer_begin"], got["layer_end"], got["prefill_cus"], got["decode_cus"], got["branch"], got["predicted_ns"]) == \
                (d[4], d[5], d[6], d[7], d[8], d[10]), case
+
+
+@pytest.mark.parametrize("mode", [0, 1, 5])
+def test_replay_matches_oracle_with_a_batching_floor(sts, mode):
+    """min_batch_tokens keeps a new batch taking queued requests past the roofline ridge; the library's
+    replay stays equal to the oracle's, and batches do grow."""
+    trace = synth.poisson_trace(9, 24.0, 6.0, IN3, OUT3)
+    plain, _ = run_both(sts, synth.llama8b_model(), sample_profile(), dict(CFG3, mode=mode), trace)
+    floor, st = run_both(sts, synth.llama8b_model(), sample_profile(), dict(CFG3, mode=mode, min_batch_tokens=2048), trace)
+    assert st["n_finished"] == len(trace)
+    assert max(d[1] for d in floor) > max(d[1] for d in plain)
+    with pytest.raises(Exception):
+        sts.Profile(text=L.dump_profile(sample_profile())).replay(synth.llama8b_model(), dict(CFG3, min_batch_tokens=-1), trace)
