@@ -32,6 +32,10 @@ Readings where the paper is silent (listed in the design document):
     SLO under that order but not under arrival order goes to the front (no starvation)
   * when prefill has no work decode runs on all CUs
   * the first output token comes from the prefill; a request decodes out_len - 1 more
+
+Outside the paper, off by default: Config.min_batch_tokens keeps the batching loop of Algorithm 1
+going past the ridge until the batch holds that many tokens (queued requests only). With 0 the
+loop is the paper's rule exactly.
 """
 from __future__ import annotations
 
