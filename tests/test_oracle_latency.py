@@ -15,15 +15,20 @@ def read_table1():
     for line in open(os.path.join(GOLD, "wave_quant_table1.txt")):
         if line.strip() and not line.startswith("#"):
             seq, kern, g, pct = line.split()
-            rows.append((int(seq), kern, int(g), pct))
+            rows.append((int(seq), kern, [int(x) for x in g.split("+")], pct))
     return rows
 
 
 def test_wave_quant_reproduces_paper_table1():
-    """Table 1 (108 SMs, one block per SM): idle percentages as printed."""
-    for seq, kern, g, pct in read_table1():
-        _, _, idle = L.wave_quant(g, 108, 1)
-        assert f"{float(idle) * 100:.1f}" == pct, (seq, kern, g, float(idle))
+    """Table 1 (108 SMs, one block per SM): idle percentages as printed. An MLP cell lists the block
+    counts of its two GEMMs (gate/up, down) and is their flop-weighted (2 : 1) mean."""
+    rows = read_table1()
+    assert sorted({k for _, k, _, _ in rows}) == ["Attn", "MLP", "O", "QKV"] and len(rows) == 16
+    for seq, kern, gs, pct in rows:
+        idles = [L.wave_quant(g, 108, 1)[2] for g in gs]
+        assert len(gs) == (2 if kern == "MLP" else 1)
+        idle = (2 * idles[0] + idles[1]) / 3 if kern == "MLP" else idles[0]
+        assert f"{float(idle) * 100:.1f}" == pct, (seq, kern, gs, float(idle))
 
 
 def test_wave_quant_definitions():
@@ -199,3 +204,51 @@ def test_profile_text_roundtrip():
                              [[[1, 2], [3, 4]], [[5, 6], [7, 8]]])
     hw2 = L.parse_profile(L.dump_profile(hw))
     assert hw2 == hw
+
+
+def test_online_recalibration_by_hand():
+    """Section 3.2.4 / Eq. 2 on a 2 x 2 alpha grid, every number worked out on paper. Samples over
+    (CUs, tokens) = (64 | 192) x (1000 | 3000): 1.0, 1.2 / 1.4, 1.6. The execution state (128 CUs,
+    2000 tokens) is the centre of the cell, so the interpolation reads all four and predicts their
+    mean, alpha = 1.3. A slice measured at 1.56 times its roofline time gives alpha_obs = 1.56
+    (Eq. 2), 1.2 times the prediction. With weight 0.5 every sample the interpolation read moves by
+    0.5 x (1.2 - 1) = +10 % of its own value: 1.1, 1.32 / 1.54, 1.76; the prediction at the state
+    moves from 1.3 to 1.43, half of the way to 1.56."""
+    g = L.Grid([[64, 192], [1000, 3000]], [[1_000_000, 1_200_000], [1_400_000, 1_600_000]])
+    assert L.alpha_at(g, [128, 2000]) == 1_300_000
+    L._blend(g, [128, 2000], 1_560_000, 1_000_000, 500_000)
+    assert g.values == [[1_100_000, 1_320_000], [1_540_000, 1_760_000]]
+    assert L.alpha_at(g, [128, 2000]) == 1_430_000
+    # weight 1: the prediction at the state lands on the measurement; a state on a grid line reads
+    # (and moves) only the two samples of that line
+    g = L.Grid([[64, 192], [1000, 3000]], [[1_000_000, 1_200_000], [1_400_000, 1_600_000]])
+    L._blend(g, [64, 2000], 2_200_000, 1_000_000, 1_000_000)          # predicted 1.1, observed 2.2: samples double
+    assert g.values[0] == [2_000_000, 2_400_000]
+    assert L.alpha_at(g, [64, 2000]) == 2_200_000
+    # through observe(): the roofline time comes from the model (pinned by the tests above), the
+    # measurement is 1.56 times it; only the prefill grid moves, the decode grid is untouched
+    s = L.Shape(32, 4096, 32, 8, 128, 14336, 128256)
+    hw = L.Profile(use_waveq=0)
+    hw.alpha_prefill = L.Grid([[64, 192], [1000, 3000]], [[1_000_000, 1_200_000], [1_400_000, 1_600_000]])
+    hw.alpha_decode = L.Grid([[64, 192], [8, 64], [512, 4096]], [[[1_000_000, 1_100_000], [1_200_000, 1_300_000]], [[900_000, 950_000], [1_000_000, 1_050_000]]])
+    before_decode = [[list(r) for r in p] for p in hw.alpha_decode.values]
+    roof = L.prefill_roofline_ns(s, hw, [(2000, 0)], 128, 4, 4)
+    es = dict(prefill_len=[2000], prefill_ctx=[0], decode_ctx=[], prefill_cus=128, decode_cus=0, layer_begin=4, n_layers_step=4)
+    L.observe(s, hw, es, roof * 156 // 100, 0, 500_000)
+    want = [[1_100_000, 1_320_000], [1_540_000, 1_760_000]]
+    for row, wrow in zip(hw.alpha_prefill.values, want):
+        for v, wv in zip(row, wrow):
+            assert abs(v - wv) <= 2                                     # floor of roof * 1.56 costs at most a ppm or two
+    assert hw.alpha_decode.values == before_decode
+    # a decode measurement moves the eight samples around (128 CUs, batch 36, mean context 2304) and no prefill sample
+    hw.alpha_prefill = L.Grid([[64, 192], [1000, 3000]], [[1_000_000, 1_200_000], [1_400_000, 1_600_000]])
+    cls = [2304] * 36
+    es = dict(prefill_len=[], prefill_ctx=[], decode_ctx=cls, prefill_cus=0, decode_cus=128, layer_begin=0, n_layers_step=0)
+    a_pred = L.alpha_at(hw.alpha_decode, [128, 36, 2304])
+    assert a_pred == (1_000_000 + 1_100_000 + 1_200_000 + 1_300_000 + 900_000 + 950_000 + 1_000_000 + 1_050_000) // 8
+    droof = L.decode_roofline_ns(s, hw, cls, 128, 0)
+    L.observe(s, hw, es, 0, droof * a_pred // 1_000_000 * 2, 1_000_000)     # measured twice the prediction, weight 1
+    flat = [v for p in hw.alpha_decode.values for r in p for v in r]
+    for v, old in zip(flat, [1_000_000, 1_100_000, 1_200_000, 1_300_000, 900_000, 950_000, 1_000_000, 1_050_000]):
+        assert abs(v - 2 * old) <= 4
+    assert hw.alpha_prefill.values == [[1_000_000, 1_200_000], [1_400_000, 1_600_000]]

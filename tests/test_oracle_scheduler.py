@@ -212,3 +212,123 @@ def test_batching_floor_by_inspection():
     # never more than the queue holds, and max_batch_tokens still caps the batch
     assert first(config(min_batch_tokens=100000))[1] == 3
     assert first(config(min_batch_tokens=100000, max_batch_tokens=1400))[1] == 2
+
+
+# ---------------------------------------------------------------------------------------------
+# Algorithm 1, lines 14-20, and the reorder guard of Section 3.3.2 on hand-built states. The
+# estimator is replaced by literal tables (milliseconds per layer over the prefill CUs, per step
+# over the decode CUs), so every number in the expected decision can be worked out on paper and
+# none of it passes through the latency model or the library.
+MS = 1_000_000
+PREFILL_MS_PER_LAYER = {256: 8, 224: 10, 192: 12, 160: 15, 128: 20, 96: 30, 64: 45, 32: 90}
+
+
+class TableReplay(S.Replay):
+    """Replay whose estimator is two literal tables; the batching loop stops after one request."""
+
+    def __init__(self, cfg, trace, decode_ms, prefill_ms=None):
+        super().__init__(SHAPE, profile(), cfg, trace)
+        self.decode_ms = decode_ms
+        self.prefill_ms = prefill_ms            # per request id: ms for the whole prefill, whatever the CUs
+
+    def t_prefill(self, ids, pm, l0, nl, co_dm):
+        if self.prefill_ms is not None:
+            return sum(self.prefill_ms[i] for i in ids) * MS * nl // SHAPE.n_layers
+        return PREFILL_MS_PER_LAYER[pm] * MS * nl
+
+    def t_decode(self, ids, dm, co):
+        return self.decode_ms[dm] * MS
+
+    def intensity_below_ridge(self, ids, pm):
+        return False
+
+
+def inflight_state(decode_ms):
+    """Request 0 decodes (first token just now, none generated yet, so its predicted TPOT is the
+    next step's latency); request 1 arrived 100 ms ago and has 4 of 32 prefill layers done; the
+    split in force is 224 prefill / 32 decode CUs."""
+    r = TableReplay(config(), [(0, 512, 200), (0, 4096, 4)], decode_ms)
+    r.now = 100 * MS
+    r.reqs[0].first_token = r.now
+    r.D = [0]
+    r.P, r.l_exe = [1], 4
+    r.pm, r.dm = 224, 32
+    return r
+
+
+def test_reduce_prefill_sm_takes_smallest_decode_share_that_meets_tpot():
+    """In-flight TTFT: 100 ms waited + 28 layers x 10 ms = 380 ms <= 1 s, so `satisfy` holds; TPOT on
+    the current 32 decode CUs is 80 ms > 50 ms: neither SetBalancedSM (needs `not satisfy`) nor
+    ReduceDecodeSM (needs TPOT within its SLO) applies, Algorithm 1 takes its third branch. Walking
+    the decode share upwards, 32 -> 80 ms, 64 -> 60 ms, 96 -> 40 ms: 96 CUs is the first that meets
+    50 ms, prefill keeps the other 160; the slice is 4 layers x 15 ms."""
+    r = inflight_state({32: 80, 64: 60, 96: 40, 128: 30, 160: 25, 192: 22, 224: 20})
+    dur = r.schedule()
+    now, n_tasks, first, _, l0, l1, pm, dm, branch, n_dec, pred = r.decisions[-1]
+    assert (n_tasks, first, l0, l1) == (1, 1, 4, 8)
+    assert (pm, dm, branch, n_dec) == (160, 96, 3, 1)
+    assert dur == pred == 4 * 15 * MS
+
+
+def test_reduce_prefill_sm_falls_back_to_largest_decode_share_that_keeps_ttft():
+    """No decode share meets the 50 ms TPOT (the best, 224 CUs, still needs 55 ms). The fallback gives
+    decode as much as the in-flight request's TTFT allows: 100 ms waited + 28 layers x t(pm) <= 1000 ms
+    needs t <= 32.1 ms per layer, i.e. at least 96 prefill CUs (30 ms; 64 CUs take 45 ms), so decode
+    gets 256 - 96 = 160 CUs. The slice is 4 layers x 30 ms."""
+    r = inflight_state({32: 90, 64: 85, 96: 80, 128: 75, 160: 70, 192: 60, 224: 55})
+    dur = r.schedule()
+    _, _, _, _, l0, l1, pm, dm, branch, _, pred = r.decisions[-1]
+    assert (l0, l1, pm, dm, branch) == (4, 8, 96, 160, 3)
+    assert dur == pred == 4 * 30 * MS
+
+
+def test_reduce_prefill_sm_without_any_admissible_share_balances():
+    """As above, but the in-flight request has already waited 990 ms: no split keeps its TTFT (the
+    28 layers left need 224 ms even on every CU) -- yet on the current 224 CUs its estimate is
+    990 + 280 = 1270 ms > 1 s, so `satisfy` fails and with TPOT over its SLO Algorithm 1 takes the
+    first branch, SetBalancedSM: minimise max(TTFT / 1000 ms, TPOT / 50 ms) over the decode shares
+    32..224 (decode is not suspended while a request decodes).
+      dm   pm   TTFT = 990 + 28 t(pm)   /1000    TPOT  /50     max
+      32   224  1270                    1.270    90    1.80    1.80
+      64   192  1326                    1.326    85    1.70    1.70
+      96   160  1410                    1.410    80    1.60    1.60
+      128  128  1550                    1.550    75    1.50    1.55   <- smallest
+      160  96   1830                    1.830    70    1.40    1.83
+    so decode gets 128 CUs and the slice is 4 layers x 20 ms."""
+    r = inflight_state({32: 90, 64: 85, 96: 80, 128: 75, 160: 70, 192: 60, 224: 55})
+    r.now = 990 * MS
+    r.reqs[0].first_token = r.now
+    dur = r.schedule()
+    _, _, _, _, _, _, pm, dm, branch, _, pred = r.decisions[-1]
+    assert (pm, dm, branch) == (128, 128, 1)
+    assert dur == pred == 4 * 20 * MS
+
+
+def test_reorder_guard_moves_exactly_the_request_it_would_hurt():
+    """Queue in arrival order A, B, C, D (ids 0..3) with whole-prefill estimates 600, 300, 100, 200 ms;
+    A has waited 200 ms, the others 50 ms; TTFT SLO 1000 ms; nothing is in flight.
+      arrival order:            A 200+600 = 800, B 50+900 = 950, C 50+1000 = 1050, D 50+1200 = 1250
+      least-latency order C, D, B, A:  C 50+100 = 150, D 50+300 = 350, B 50+600 = 650, A 200+1200 = 1400
+    Only A meets its SLO in arrival order and misses it after the reordering, so only A is moved to
+    the front; the rest keep the least-latency order: A, C, D, B. The batching loop (stubbed to stop
+    after one request) then starts A and leaves C, D, B queued in that order."""
+    cfg = config()
+    trace = [(150 * MS, 4000, 2), (300 * MS, 2000, 2), (300 * MS, 700, 2), (300 * MS, 1400, 2)]
+    r = TableReplay(cfg, trace, {}, prefill_ms={0: 600, 1: 300, 2: 100, 3: 200})
+    r.now = 350 * MS
+    r.Q = [0, 1, 2, 3]
+    r.schedule()
+    assert r.P == [0] and r.Q == [2, 3, 1]
+    assert r.decisions[-1][1:4] == (1, 0, S.tasks_hash([0]))
+    # without a request that the reordering would push over its SLO the order is least-latency first
+    r2 = TableReplay(config(ttft_slo_ns=2000 * MS), trace, {}, prefill_ms={0: 600, 1: 300, 2: 100, 3: 200})
+    r2.now = 350 * MS
+    r2.Q = [0, 1, 2, 3]
+    r2.schedule()
+    assert r2.P == [2] and r2.Q == [3, 1, 0]
+    # a request that misses its SLO either way is not protected (A has waited 700 ms: 1300 and 1900 ms)
+    r3 = TableReplay(cfg, [(-350 * MS, 4000, 2)] + trace[1:], {}, prefill_ms={0: 600, 1: 300, 2: 100, 3: 200})
+    r3.now = 350 * MS
+    r3.Q = [0, 1, 2, 3]
+    r3.schedule()
+    assert r3.P == [2] and r3.Q == [3, 1, 0]
