@@ -55,13 +55,25 @@ typedef struct {
   int32_t max_prefill_seqs;    /* sequences per prefill batch */
   int32_t max_decode_batch;    /* requests per decode step */
   int32_t max_seqs;            /* live sequences */
-  int32_t max_pages_per_seq;   /* block-table length */
+  int32_t max_pages_per_seq;   /* block-table length; at most sts_max_pages_per_seq_limit(page_tokens) */
 } sts_init_params;
 
 /* ---- lifetime (Section 3.5.1: weights and the KV pool are allocated once, before serving,
  *      and shared by both phases) */
 int sts_init(const sts_model_desc* desc, const sts_init_params* params, sts_ctx** out);
+/* Waits for everything the ctx queued (on every partition's stream it ever selected and on the
+ * null stream), then releases its memory. The CU-masked streams themselves belong to the process
+ * and stay. */
 int sts_destroy(sts_ctx* ctx);
+/* Longest block table sts_init accepts: decode attention cuts a context into at most 128 chunks of
+ * at most 64 pages (Section 3.5.1's pool is shared, a sequence's share of it is bounded by this). */
+int sts_max_pages_per_seq_limit(int32_t page_tokens);
+/* Host only, no GPU state: how a decode step over contexts of n_pages[i] pages is cut into chunks on
+ * a partition of `cus` CUs (pages per chunk, chunks of the longest context), next to the chunk count
+ * the engine allocates its merge workspace and work list for when max_pages_per_seq is the bound.
+ * max_chunks <= allocated_chunks holds for every input sts_init accepts. */
+int sts_decode_chunk_plan(const int32_t* n_pages, int32_t n, int32_t n_kv_heads, int32_t cus, int32_t page_tokens,
+                          int32_t max_pages_per_seq, int32_t* chunk_pages, int32_t* max_chunks, int32_t* allocated_chunks);
 
 /* Weights. `name`: "emb", "lm" (layer ignored), "wq","wk","wv","wo","wg","wu","wd" (matrices,
  * row-major [out_features, in_features] fp32, rounded to bf16 on upload) or "g1","g2","gf"
@@ -72,7 +84,8 @@ int sts_read_weights(sts_ctx* ctx, int32_t layer, const char* name, float* host,
 /* ---- sequences and the paged KV cache (Section 3.5.1). Token t of a sequence lives in page
  *      block_table[t / page_tokens], slot t % page_tokens, in every layer. */
 int sts_seq_create(sts_ctx* ctx, int32_t* seq_out);
-int sts_seq_free(sts_ctx* ctx, int32_t seq);                       /* pages return to the pool */
+int sts_seq_free(sts_ctx* ctx, int32_t seq);                       /* pages return to the pool; STS_ESTATE while the sequence is part of
+                                                                      a layer-sliced prefill batch or of a launch whose finish is due */
 int sts_seq_length(sts_ctx* ctx, int32_t seq, int32_t* len_out);
 int sts_seq_reserve(sts_ctx* ctx, int32_t seq, int32_t n_tokens);  /* make pages cover n_tokens; STS_ENOMEM leaves state unchanged */
 int sts_pages_free(sts_ctx* ctx, int32_t* n_out);
@@ -124,7 +137,9 @@ int sts_decode_step(sts_ctx* ctx, const int32_t* seqs, const int32_t* in_tokens,
 /* Both at once: the prefill slice on the prefill partition's stream and the decode step on the
  * decode partition's stream, launched back to back with no synchronisation between them, one
  * join at the end (Section 3.3.1). The two must touch disjoint sequences. Either side may be
- * empty (n == 0). */
+ * empty (n == 0). Both sides are validated and the pages of both are reserved before anything is
+ * queued: STS_EINVAL, STS_ESTATE or STS_ENOMEM from either side leaves every sequence unchanged
+ * and nothing launched. */
 int sts_step_concurrent(sts_ctx* ctx,
                         int32_t n_pseqs, const int32_t* pseqs, const int32_t* plens, const int32_t* ptokens,
                         int32_t layer_begin, int32_t layer_end, float* plogits,

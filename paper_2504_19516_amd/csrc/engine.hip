@@ -108,6 +108,7 @@ struct sts_ctx {
   std::vector<int> pend_pseqs, pend_plens, pend_dseqs; int pend_le = 0;
   void* probe_src = nullptr; void* probe_dst = nullptr; size_t probe_bytes = 0;
   std::vector<void*> allocs;
+  std::vector<hipStream_t> used_streams;       // every pooled stream this ctx ever selected (guarded by part_mu)
 };
 
 namespace {
@@ -171,11 +172,17 @@ int get_stream(sts_ctx* c, int side, int cus, hipStream_t* out) {
   return STS_OK;
 }
 
+// Caller holds part_mu (or is the only user of the ctx).
+void remember_stream(sts_ctx* c, hipStream_t s) {
+  if (s && std::find(c->used_streams.begin(), c->used_streams.end(), s) == c->used_streams.end()) c->used_streams.push_back(s);
+}
+
 int select_streams(sts_ctx* c) {
   for (int side = 0; side < 2; side++) {
     Phase& ph = c->ph[side];
     if (c->part_cus[side] == 0) { ph.stream = nullptr; ph.cus = 0; continue; }
     STSCK(get_stream(c, side, c->part_cus[side], &ph.stream));
+    remember_stream(c, ph.stream);
     ph.cus = c->part_cus[side];
   }
   return STS_OK;
@@ -344,8 +351,10 @@ int reserve_pages(sts_ctx* c, const std::vector<std::pair<int, int>>& wants) {  
 bf16* layer_pool(sts_ctx* c, int l) { return c->pool + (size_t)l * c->pool_layer_elems; }
 
 // ------------------------------------------------------------------------------------ prefill
-int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
-                    int lb, int le, bool want_logits) {
+// Checks of a prefill slice that touch no state: arguments, the order of layer slices, and the
+// pages the batch will need (appended to `wants` for slice 0). Nothing is launched or reserved.
+int prefill_validate(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens, int lb, int le,
+                     std::vector<std::pair<int, int>>* wants) {
   Phase& ph = c->ph[0];
   const sts_model_desc& d = c->d;
   if (n_seqs < 1 || n_seqs > c->p.max_prefill_seqs || !seqs || !lens) return STS_EINVAL;
@@ -356,22 +365,63 @@ int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* 
     if (!valid_seq(c, seqs[i]) || lens[i] < 1) return STS_EINVAL;
     for (int j = 0; j < i; j++) if (seqs[j] == seqs[i]) return STS_EINVAL;
     rows += lens[i];
+    if (rows > c->p.max_prefill_tokens) return STS_EINVAL;
   }
-  if (rows > c->p.max_prefill_tokens) return STS_EINVAL;
+  std::lock_guard<std::mutex> g(c->state_mu);
+  for (int i = 0; i < n_seqs; i++) for (int s : c->pend_dseqs) if (s == seqs[i]) return STS_EINVAL;   // a request is in one phase only
   if (lb == 0) {
     if (!tokens) return STS_EINVAL;
     for (int i = 0; i < rows; i++) if (tokens[i] < 0 || tokens[i] >= d.vocab) return STS_EINVAL;
     if (c->pf_active) return STS_ESTATE;
-    std::vector<std::pair<int, int>> wants;
-    for (int i = 0; i < n_seqs; i++) wants.push_back({seqs[i], c->seqs[seqs[i]].len + lens[i]});
-    STSCK(reserve_pages(c, wants));
-    std::lock_guard<std::mutex> g(c->state_mu);
-    c->pf_active = true; c->pf_next_layer = 0;
-    c->pf_seqs.assign(seqs, seqs + n_seqs); c->pf_lens.assign(lens, lens + n_seqs);
+    for (int i = 0; i < n_seqs; i++) {
+      const int total = c->seqs[seqs[i]].len + lens[i];
+      if ((total + c->geo.page_tokens - 1) / c->geo.page_tokens > c->p.max_pages_per_seq) return STS_EINVAL;
+      wants->push_back({seqs[i], total});
+    }
   } else {
     if (!c->pf_active || lb != c->pf_next_layer || (int)c->pf_seqs.size() != n_seqs) return STS_ESTATE;
     for (int i = 0; i < n_seqs; i++) if (c->pf_seqs[i] != seqs[i] || c->pf_lens[i] != lens[i]) return STS_ESTATE;
   }
+  return STS_OK;
+}
+
+// Queues a validated slice whose pages are reserved. A failure in here (a HIP error) leaves the
+// batch description as it was before the call.
+int prefill_launch_checked(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                           int lb, int le, bool want_logits);
+
+int prefill_enqueue(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                    int lb, int le, bool want_logits) {
+  std::vector<std::pair<int, int>> wants;
+  STSCK(prefill_validate(c, n_seqs, seqs, lens, tokens, lb, le, &wants));
+  STSCK(reserve_pages(c, wants));
+  return prefill_launch_checked(c, n_seqs, seqs, lens, tokens, lb, le, want_logits);
+}
+
+int prefill_launch_body(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                        int lb, int le, bool want_logits);
+
+int prefill_launch_checked(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                           int lb, int le, bool want_logits) {
+  if (lb == 0) {
+    std::lock_guard<std::mutex> g(c->state_mu);
+    c->pf_active = true; c->pf_next_layer = 0;
+    c->pf_seqs.assign(seqs, seqs + n_seqs); c->pf_lens.assign(lens, lens + n_seqs);
+  }
+  const int rc = prefill_launch_body(c, n_seqs, seqs, lens, tokens, lb, le, want_logits);
+  if (rc != STS_OK && lb == 0) {                             // the batch never started: later prefills are not blocked
+    std::lock_guard<std::mutex> g(c->state_mu);
+    c->pf_active = false; c->pf_seqs.clear(); c->pf_lens.clear();
+  }
+  return rc;
+}
+
+int prefill_launch_body(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* lens, const int32_t* tokens,
+                        int lb, int le, bool want_logits) {
+  Phase& ph = c->ph[0];
+  const sts_model_desc& d = c->d;
+  int rows = 0;
+  for (int i = 0; i < n_seqs; i++) rows += lens[i];
   // ---- stage metadata
   const int mp = c->p.max_pages_per_seq, bq = attn_prefill_tile_q();
   ph.meta_used = 0;
@@ -439,7 +489,30 @@ int prefill_finish(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32_t* l
 }
 
 // ------------------------------------------------------------------------------------ decode
-int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int n, bool want_logits, bool want_next) {
+// Context chunks of at most chunk_pages pages: the largest of 64/32/16/8 that still yields about
+// four workgroups per CU of the partition (8 pages keep the four waves of a workgroup busy with
+// one two-page block each), never more than 128 chunks for the longest context.
+void decode_chunk_plan(const int* n_pages, int n, int n_kv, int cus, int page_tokens, int* chunk_pages_out, int* max_chunks_out) {
+  int max_pages = 1;
+  for (int i = 0; i < n; i++) max_pages = std::max(max_pages, n_pages[i]);
+  int chunk_pages = attn_decode_max_chunk_tokens() / page_tokens;
+  const int floor_pages = std::max(8, (max_pages + 127) / 128);
+  while (chunk_pages / 2 >= floor_pages) {
+    long long wgs = 0;
+    for (int i = 0; i < n; i++) wgs += (n_pages[i] + chunk_pages - 1) / chunk_pages;
+    if (wgs * n_kv >= 4LL * cus) break;
+    chunk_pages /= 2;
+  }
+  *chunk_pages_out = chunk_pages;
+  *max_chunks_out = (max_pages + chunk_pages - 1) / chunk_pages;
+}
+// Chunks per context the merge workspace and the work list are allocated for: chunks hold at least
+// 8 pages (fewer than one chunk per 4 pages), and never more than 128 per context.
+int decode_max_chunks(int max_pages_per_seq) { return (int)std::min<size_t>(128, ((size_t)max_pages_per_seq + 3) / 4); }
+
+// Checks of a decode step that touch no state; the page each request needs for its new token is
+// appended to `wants`.
+int decode_validate(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int n, std::vector<std::pair<int, int>>* wants) {
   Phase& ph = c->ph[1];
   const sts_model_desc& d = c->d;
   if (n < 1 || n > c->p.max_decode_batch || !seqs || !in_tokens) return STS_EINVAL;
@@ -447,14 +520,28 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
   for (int i = 0; i < n; i++) {
     if (!valid_seq(c, seqs[i]) || in_tokens[i] < 0 || in_tokens[i] >= d.vocab) return STS_EINVAL;
     for (int j = 0; j < i; j++) if (seqs[j] == seqs[i]) return STS_EINVAL;
+    if ((c->seqs[seqs[i]].len + 1 + c->geo.page_tokens - 1) / c->geo.page_tokens > c->p.max_pages_per_seq) return STS_EINVAL;
   }
   {
     std::lock_guard<std::mutex> g(c->state_mu);                                        // a request is in one phase only
     if (c->pf_active) for (int i = 0; i < n; i++) for (int s : c->pf_seqs) if (s == seqs[i]) return STS_EINVAL;
   }
+  for (int i = 0; i < n; i++) wants->push_back({seqs[i], c->seqs[seqs[i]].len + 1});
+  return STS_OK;
+}
+
+int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int n, bool want_logits, bool want_next);
+
+int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int n, bool want_logits, bool want_next) {
   std::vector<std::pair<int, int>> wants;
-  for (int i = 0; i < n; i++) wants.push_back({seqs[i], c->seqs[seqs[i]].len + 1});
+  STSCK(decode_validate(c, seqs, in_tokens, n, &wants));
   STSCK(reserve_pages(c, wants));
+  return decode_launch_checked(c, seqs, in_tokens, n, want_logits, want_next);
+}
+
+int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int n, bool want_logits, bool want_next) {
+  Phase& ph = c->ph[1];
+  const sts_model_desc& d = c->d;
   const int mp = c->p.max_pages_per_seq, pt = c->geo.page_tokens;
   ph.meta_used = 0;
   meta_take(ph, &ph.h_dseq, &ph.d_dseq, n);
@@ -473,18 +560,11 @@ int decode_enqueue(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, in
     max_pages = std::max(max_pages, np);
     ph.h_tokens[i] = in_tokens[i];
   }
-  // Context chunks of at most chunk_pages pages: the largest of 64/32/16/8 that still yields about
-  // four workgroups per CU of the partition (8 pages keep the four waves of a workgroup busy with
-  // one two-page block each), never more than 128 chunks for the longest context.
-  int chunk_pages = attn_decode_max_chunk_tokens() / pt;
-  const int floor_pages = std::max(8, (max_pages + 127) / 128);
-  while (chunk_pages / 2 >= floor_pages) {
-    long long wgs = 0;
-    for (int i = 0; i < n; i++) wgs += (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages;
-    if (wgs * d.n_kv_heads >= 4LL * ph.cus) break;
-    chunk_pages /= 2;
-  }
-  const int max_chunks = (max_pages + chunk_pages - 1) / chunk_pages;
+  std::vector<int> np_list(n);
+  for (int i = 0; i < n; i++) np_list[i] = ph.h_dseq[i].n_pages;
+  int chunk_pages, max_chunks;
+  decode_chunk_plan(np_list.data(), n, d.n_kv_heads, ph.cus, pt, &chunk_pages, &max_chunks);
+  if (max_chunks > decode_max_chunks(mp)) return STS_EINVAL;   // cannot happen within sts_init's bound on max_pages_per_seq
   // one attention workgroup row per context chunk that exists
   int n_items = 0;
   for (int i = 0; i < n; i++) n_items += (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages;
@@ -570,7 +650,7 @@ int alloc_phase(sts_ctx* c, int side) {
   {
     const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
     // decode attention items: a context has at most 128 chunks, and fewer than one per 4 pages (chunks hold >= 8)
-    const size_t dec_items = side == 1 ? nseq * std::min<size_t>(128, (mp + 3) / 4) : 0;
+    const size_t dec_items = side == 1 ? nseq * (size_t)decode_max_chunks((int)mp) : 0;
     ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + sizeof(int)) + items * sizeof(AttnItem) + dec_items * sizeof(DecodeItem) +
                     rows * sizeof(int) + nseq * mp * sizeof(int) + 8 * 256;
     STSCK(dev_alloc(c, &ph.d_meta, ph.meta_bytes));
@@ -585,7 +665,7 @@ int alloc_phase(sts_ctx* c, int side) {
     ph.tail_ws_bytes = tail_floats * sizeof(float);
   } else {
     const size_t widest = std::max<size_t>(std::max(c->qkvn, 2 * d.mlp), d.hidden);
-    const size_t max_chunks = std::min<size_t>(128, (mp + 3) / 4);     // see decode_enqueue: chunks of >= 8 pages, <= 128 chunks
+    const size_t max_chunks = decode_max_chunks((int)mp);
     STSCK(dev_alloc(c, &ph.part, 8 * rows * widest));
     STSCK(dev_alloc(c, &ph.Q, rows * c->qd));
     STSCK(dev_alloc(c, &ph.attn_ws, attn_decode_ws_floats((int)rows, d.n_q_heads, d.head_dim, (int)max_chunks)));
@@ -630,6 +710,8 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
   if (((d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim) % 128 || (d.n_q_heads * d.head_dim) % 64 || d.mlp % 32) return STS_EINVAL;
   if (params->kv_pool_pages < 1 || params->max_prefill_tokens < 1 || params->max_prefill_seqs < 1 ||
       params->max_decode_batch < 1 || params->max_seqs < 1 || params->max_pages_per_seq < 1) return STS_EINVAL;
+  // decode attention cuts a context into at most 128 chunks (the merge workspace and the work list are sized for that)
+  if (params->max_pages_per_seq > sts_max_pages_per_seq_limit(d.page_tokens)) return STS_EINVAL;
   int ndev = 0;
   HIPCK(hipGetDeviceCount(&ndev));
   if (ndev < 1) { g_hip_err = (int)hipErrorNoDevice; return STS_EHIP; }
@@ -691,10 +773,26 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
   return STS_OK;
 }
 
+extern "C" int sts_max_pages_per_seq_limit(int32_t page_tokens) {
+  return page_tokens > 0 ? 128 * (attn_decode_max_chunk_tokens() / page_tokens) : 0;
+}
+extern "C" int sts_decode_chunk_plan(const int32_t* n_pages, int32_t n, int32_t n_kv_heads, int32_t cus, int32_t page_tokens,
+                                     int32_t max_pages_per_seq, int32_t* chunk_pages, int32_t* max_chunks, int32_t* allocated_chunks) {
+  if (!n_pages || n < 1 || n_kv_heads < 1 || cus < 1 || page_tokens < 1 || !chunk_pages || !max_chunks || !allocated_chunks) return STS_EINVAL;
+  for (int i = 0; i < n; i++) if (n_pages[i] < 1 || n_pages[i] > max_pages_per_seq) return STS_EINVAL;
+  decode_chunk_plan(n_pages, n, n_kv_heads, cus, page_tokens, chunk_pages, max_chunks);
+  *allocated_chunks = decode_max_chunks(max_pages_per_seq);
+  return STS_OK;
+}
+
 extern "C" int sts_destroy(sts_ctx* c) {
   if (!c) return STS_EINVAL;
-  trace("destroy: sync phase streams");
-  for (int side = 0; side < 2; side++) if (c->ph[side].stream) (void)hipStreamSynchronize(c->ph[side].stream);
+  // Everything this ctx ever queued must have drained before its buffers go: the pooled streams of
+  // every partition it selected (they outlive the ctx), and the null stream used by the weight
+  // loaders and the KV test hooks.
+  trace("destroy: sync every stream this ctx used");
+  for (hipStream_t s : c->used_streams) (void)hipStreamSynchronize(s);
+  (void)hipStreamSynchronize(nullptr);
   trace("destroy: events and pinned buffers");
   for (int side = 0; side < 2; side++) {
     Phase& ph = c->ph[side];
@@ -755,8 +853,12 @@ extern "C" int sts_seq_create(sts_ctx* c, int32_t* seq_out) {
 extern "C" int sts_seq_free(sts_ctx* c, int32_t seq) {
   if (!c || !valid_seq(c, seq)) return STS_EINVAL;
   {
+    // a sequence of the layer-sliced batch or of a launch still in flight keeps its pages: kernels
+    // may be reading and writing them
     std::lock_guard<std::mutex> g(c->state_mu);
     if (c->pf_active) for (int s : c->pf_seqs) if (s == seq) return STS_ESTATE;
+    for (int s : c->pend_pseqs) if (s == seq) return STS_ESTATE;
+    for (int s : c->pend_dseqs) if (s == seq) return STS_ESTATE;
   }
   std::lock_guard<std::mutex> g(c->alloc_mu);
   for (int pg : c->seqs[seq].pages) { c->page_used[pg] = 0; c->free_pages.push_back(pg); }
@@ -874,6 +976,7 @@ extern "C" int sts_prefill_launch(sts_ctx* c, int32_t n_seqs, const int32_t* seq
   if (!c) return STS_EINVAL;
   if (c->pend_prefill) return STS_ESTATE;
   STSCK(prefill_enqueue(c, n_seqs, seqs, lens, tokens, lb, le, want_logits != 0));
+  std::lock_guard<std::mutex> g(c->state_mu);
   c->pend_prefill = true; c->pend_le = le;
   c->pend_pseqs.assign(seqs, seqs + n_seqs); c->pend_plens.assign(lens, lens + n_seqs);
   return STS_OK;
@@ -881,8 +984,15 @@ extern "C" int sts_prefill_launch(sts_ctx* c, int32_t n_seqs, const int32_t* seq
 extern "C" int sts_decode_launch(sts_ctx* c, const int32_t* seqs, const int32_t* in_tokens, int32_t n, int32_t want_logits, int32_t want_next) {
   if (!c) return STS_EINVAL;
   if (c->pend_decode) return STS_ESTATE;
-  STSCK(decode_enqueue(c, seqs, in_tokens, n, want_logits != 0, want_next != 0));
-  c->pend_decode = true; c->pend_dseqs.assign(seqs, seqs + n);
+  {
+    // the batch is listed before anything is queued, so that from this moment neither a prefill of
+    // one of its sequences nor sts_seq_free gets through
+    std::lock_guard<std::mutex> g(c->state_mu);
+    c->pend_dseqs.assign(seqs, seqs + std::max(n, 0));
+  }
+  const int rc = decode_enqueue(c, seqs, in_tokens, n, want_logits != 0, want_next != 0);
+  if (rc != STS_OK) { std::lock_guard<std::mutex> g(c->state_mu); c->pend_dseqs.clear(); return rc; }
+  c->pend_decode = true;
   return STS_OK;
 }
 extern "C" int sts_phase_done(sts_ctx* c, int32_t phase, int32_t* done) {
@@ -897,14 +1007,20 @@ extern "C" int sts_phase_done(sts_ctx* c, int32_t phase, int32_t* done) {
 extern "C" int sts_prefill_finish(sts_ctx* c, float* logits) {
   if (!c) return STS_EINVAL;
   if (!c->pend_prefill) return STS_ESTATE;
-  c->pend_prefill = false;
-  return prefill_finish(c, (int)c->pend_pseqs.size(), c->pend_pseqs.data(), c->pend_plens.data(), c->pend_le, logits);
+  const std::vector<int> seqs = c->pend_pseqs, lens = c->pend_plens;
+  const int rc = prefill_finish(c, (int)seqs.size(), seqs.data(), lens.data(), c->pend_le, logits);
+  std::lock_guard<std::mutex> g(c->state_mu);
+  c->pend_prefill = false; c->pend_pseqs.clear(); c->pend_plens.clear();
+  return rc;
 }
 extern "C" int sts_decode_finish(sts_ctx* c, float* logits, int32_t* next) {
   if (!c) return STS_EINVAL;
   if (!c->pend_decode) return STS_ESTATE;
-  c->pend_decode = false;
-  return decode_finish(c, c->pend_dseqs.data(), (int)c->pend_dseqs.size(), logits, next);
+  const std::vector<int> seqs = c->pend_dseqs;
+  const int rc = decode_finish(c, seqs.data(), (int)seqs.size(), logits, next);
+  std::lock_guard<std::mutex> g(c->state_mu);
+  c->pend_decode = false; c->pend_dseqs.clear();
+  return rc;
 }
 extern "C" int sts_prefill_abort(sts_ctx* c) {
   if (!c) return STS_EINVAL;
@@ -929,13 +1045,23 @@ extern "C" int sts_step_concurrent(sts_ctx* c, int32_t n_pseqs, const int32_t* p
   for (int i = 0; i < n_pseqs; i++) for (int j = 0; j < n_decode; j++) if (pseqs && dseqs && pseqs[i] == dseqs[j]) return STS_EINVAL;
   const int64_t t0 = now_ns();
   c->ph[0].ran = c->ph[1].ran = false;
-  if (n_pseqs > 0) STSCK(prefill_enqueue(c, n_pseqs, pseqs, plens, ptokens, lb, le, plogits != nullptr));
+  // Both sides are checked and the pages of both are reserved in one step before anything is
+  // queued: an invalid argument or an exhausted pool on either side leaves every sequence as it was.
+  std::vector<std::pair<int, int>> wants;
+  if (n_pseqs > 0) STSCK(prefill_validate(c, n_pseqs, pseqs, plens, ptokens, lb, le, &wants));
+  if (n_decode > 0) STSCK(decode_validate(c, dseqs, dtokens, n_decode, &wants));
+  STSCK(reserve_pages(c, wants));
+  if (n_pseqs > 0) STSCK(prefill_launch_checked(c, n_pseqs, pseqs, plens, ptokens, lb, le, plogits != nullptr));
   const int64_t t1 = now_ns();
   int rc = STS_OK;
-  if (n_decode > 0) rc = decode_enqueue(c, dseqs, dtokens, n_decode, dlogits != nullptr, dnext != nullptr);
+  if (n_decode > 0) rc = decode_launch_checked(c, dseqs, dtokens, n_decode, dlogits != nullptr, dnext != nullptr);
   const int64_t t2 = now_ns();
-  if (n_pseqs > 0) { int r2 = prefill_finish(c, n_pseqs, pseqs, plens, le, plogits); if (rc == STS_OK) rc = r2; else return rc; }
-  STSCK(rc);
+  if (rc != STS_OK) {
+    // only a HIP failure can get here; the prefill slice already queued is waited for and dropped
+    if (n_pseqs > 0) { (void)wait_stream(c->ph[0].stream); (void)k_collect(c, c->ph[0]); (void)sts_prefill_abort(c); }
+    return rc;
+  }
+  if (n_pseqs > 0) STSCK(prefill_finish(c, n_pseqs, pseqs, plens, le, plogits));
   const int64_t t3 = now_ns();
   if (n_decode > 0) STSCK(decode_finish(c, dseqs, n_decode, dlogits, dnext));
   c->last_wall_ns = now_ns() - t0;
@@ -987,6 +1113,7 @@ extern "C" int sts_set_partition(sts_ctx* c, int32_t prefill_cus, int32_t decode
   for (int side = 0; side < 2; side++) {
     if (v[side] == old[side]) continue;
     c->part_cus[side] = v[side]; c->ph[side].stream = st[side]; c->ph[side].cus = v[side];
+    remember_stream(c, st[side]);
   }
   return STS_OK;
 }
@@ -1018,6 +1145,7 @@ extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t byte
   if (!c || side < 0 || side > 1 || bytes < 4096 || bytes % 16 || iters < 1 || !ns_out) return STS_EINVAL;
   hipStream_t st;
   STSCK(get_stream(c, side, cus, &st));
+  { std::lock_guard<std::mutex> g(c->part_mu); remember_stream(c, st); }
   if (c->probe_bytes < bytes) {
     if (c->probe_src) { (void)hipFree(c->probe_src); (void)hipFree(c->probe_dst); c->probe_src = c->probe_dst = nullptr; c->probe_bytes = 0; }
     HIPCK(hipMalloc(&c->probe_src, bytes)); HIPCK(hipMalloc(&c->probe_dst, bytes));

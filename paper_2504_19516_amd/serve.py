@@ -57,6 +57,19 @@ class LiveServer:
                               max_seqs=4096, max_pages_per_seq=(max_ctx + PAGE - 1) // PAGE)
         self.n_cu = self.eng.get_partition()[2]
         self.max_ctx = max_ctx
+        # Live-mode replay (Algorithm 1's decisions must be reproducible from a per-cycle log): when this is a
+        # list, every scheduling cycle appends the exact state handed to sts_sched_decide, the scheduler
+        # configuration and the choice that came back, so that a second implementation can re-decide it.
+        self.state_log = None
+
+    def decide(self, cfg, now, queue, inflight, layers_done, decode, pages_free, pm, dm):
+        ch = self.profile.decide(self.desc, cfg, now, queue, inflight, layers_done, decode, pages_free, pm, dm)
+        if self.state_log is not None:
+            self.state_log.append(dict(cfg=dict(cfg), now_ns=int(now), queue=[tuple(map(int, q)) for q in queue],
+                                       inflight=[tuple(map(int, q)) for q in inflight], layers_done=int(layers_done),
+                                       decode=[tuple(map(int, d)) for d in decode], pages_free=int(pages_free),
+                                       cur_prefill_cus=int(pm), cur_decode_cus=int(dm), choice=dict(ch)))
+        return ch
 
     def close(self):
         self.eng.close()
@@ -179,9 +192,9 @@ class LiveServer:
                 next_arrival += 1
             # ---- prefill engine: one scheduling cycle of Algorithm 1
             if not prefill_busy and (P or Q) and not (serial and (decode_busy or (turn_decode and (D or H)))):
-                ch = self.profile.decide(desc, cfg, now, [(r.rid, r.arrival, r.in_len, r.out_len) for r in Q],
-                                         [(r.rid, r.arrival, r.in_len, r.out_len) for r in P], l_exe,
-                                         [(r.first_token, r.n_dec, r.in_len) for r in D + H], eng.pages_free(), pm, dm)
+                ch = self.decide(cfg, now, [(r.rid, r.arrival, r.in_len, r.out_len) for r in Q],
+                                 [(r.rid, r.arrival, r.in_len, r.out_len) for r in P], l_exe,
+                                 [(r.first_token, r.n_dec, r.in_len) for r in D + H], eng.pages_free(), pm, dm)
                 by_id = {r.rid: r for r in Q}
                 Q = [by_id[i] for i in ch["queue"]]
                 if ch["tasks"]:
@@ -330,7 +343,7 @@ class LiveServer:
                 if P or Q:
                     with lock:
                         dec = [(r.first_token, r.n_dec, r.in_len) for r in sh["D"] + sh["H"]]
-                    ch = prof_call(self.profile.decide, desc, cfg, now, [(r.rid, r.arrival, r.in_len, r.out_len) for r in Q],
+                    ch = prof_call(self.decide, cfg, now, [(r.rid, r.arrival, r.in_len, r.out_len) for r in Q],
                                    [(r.rid, r.arrival, r.in_len, r.out_len) for r in P], l_exe, dec, eng.pages_free(), pm, dm)
                     by_id = {r.rid: r for r in Q}
                     Q = [by_id[i] for i in ch["queue"]]

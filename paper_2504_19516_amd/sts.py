@@ -92,7 +92,7 @@ EXPORTS = [
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan",
 ]
 
 
@@ -343,6 +343,19 @@ def op_attn_decode(q, k, v, ctx, chunk_pages):
     _ck(lib().sts_op_attn_decode(_p(q, C.c_float), _p(k, C.c_float), _p(v, C.c_float), _p(out, C.c_float), n, _p(ctx),
                                  n_q, k.shape[1], d, chunk_pages), "sts_op_attn_decode")
     return out
+
+
+def max_pages_per_seq_limit(page_tokens=16):
+    return lib().sts_max_pages_per_seq_limit(page_tokens)
+
+
+def decode_chunk_plan(n_pages, n_kv_heads, cus, page_tokens, max_pages_per_seq):
+    """(pages per chunk, chunks of the longest context, chunks per context the engine allocates for)."""
+    a = _i32(n_pages)
+    cp, mc, ac = C.c_int32(), C.c_int32(), C.c_int32()
+    _ck(lib().sts_decode_chunk_plan(_p(a), a.size, n_kv_heads, cus, page_tokens, max_pages_per_seq, C.byref(cp), C.byref(mc), C.byref(ac)),
+        "sts_decode_chunk_plan")
+    return cp.value, mc.value, ac.value
 
 
 # ---- performance estimator and scheduler (host only)

@@ -159,6 +159,37 @@ def make_weights(desc: ModelDesc, seed: int, layers: range | None = None) -> dic
     return w
 
 
+def normal_weights(desc: ModelDesc, seed: int, emb_block_rows: int | None = None) -> dict:
+    """Weights for tests that LOAD them into the library instead of having the device generate
+    them: numpy's N(0, 0.02) deviates (much faster on the host than the counter-based recipe above),
+    rounded to bf16 when the model says so. With emb_block_rows the embedding table repeats one
+    random block of that many rows (token t reads block row t mod emb_block_rows): tests that look
+    up a few tokens need not draw a whole vocabulary of rows."""
+    bf = desc.dtype == "bf16"
+    rng = np.random.default_rng([seed, 17])
+
+    def draw(shape):
+        x = rng.standard_normal(size=shape, dtype=np.float32)
+        x *= np.float32(0.02)
+        return to_bf16(x) if bf else x
+
+    w: dict = {}
+    if emb_block_rows:
+        block = draw((emb_block_rows, desc.hidden))
+        w["emb"] = np.tile(block, (-(-desc.vocab // emb_block_rows), 1))[:desc.vocab]
+    else:
+        w["emb"] = draw(desc.shape("emb"))
+    w["lm"] = draw(desc.shape("lm"))
+    w["gf"] = np.ones(desc.hidden, dtype=np.float32)
+    w["layers"] = []
+    for _ in range(desc.n_layers):
+        lw = {name: draw(desc.shape(name)) for name in SLOT}
+        lw["g1"] = np.ones(desc.hidden, dtype=np.float32)
+        lw["g2"] = np.ones(desc.hidden, dtype=np.float32)
+        w["layers"].append(lw)
+    return w
+
+
 # ------------------------------------------------------------------- request-level inputs
 def tokens(seed: int, n: int, vocab: int) -> np.ndarray:
     return np.random.default_rng([seed, 11]).integers(0, vocab, size=n, dtype=np.int32)

@@ -351,6 +351,50 @@ def test_error_paths_leave_state_unchanged(sts, tiny):
     eng.close()
 
 
+def test_failed_concurrent_step_commits_nothing(sts, tiny):
+    """A concurrent step whose decode side cannot get its page (or is invalid) fails before anything
+    is queued: the prefill side has not run, no length moved, no page was taken, and the same
+    prefill can be issued again; a sequence in a launch whose finish is due cannot be freed."""
+    desc, _ = tiny
+    eng = new_engine(sts, desc, kv_pool_pages=7, max_pages_per_seq=8)
+    d = eng.seq_create()
+    eng.prefill_append(d, synth.tokens(52, 32, desc.vocab), want_logits=False)     # 2 pages, both full
+    p = eng.seq_create()
+    toks = synth.tokens(53, 80, desc.vocab)                                         # 5 pages: the pool is then exhausted
+    assert eng.pages_free() == 5
+    with pytest.raises(sts.StsError) as e:
+        eng.step_concurrent([p], [toks], 0, desc.n_layers, [d], [3])              # decode needs a sixth page
+    assert e.value.code == sts.ENOMEM
+    assert eng.pages_free() == 5 and eng.seq_length(p) == 0 and eng.seq_length(d) == 32
+    with pytest.raises(sts.StsError) as e:
+        eng.step_concurrent([p], [toks], 0, desc.n_layers, [d], [desc.vocab])     # token id out of range on the decode side
+    assert e.value.code == sts.EINVAL and eng.pages_free() == 5 and eng.seq_length(p) == 0
+    # nothing is left half-started: the prefill alone goes through, in two slices
+    eng.prefill_append(p, toks, 0, 1, want_logits=False)
+    with pytest.raises(sts.StsError) as e:
+        eng.seq_free(p)                                                            # part of a layer-sliced batch
+    assert e.value.code == sts.ESTATE
+    eng.prefill_append(p, toks, 1, desc.n_layers, want_logits=False)
+    assert eng.seq_length(p) == 80 and eng.pages_free() == 0
+    eng.seq_free(p)
+    # launch without finish: the batch's sequences are pinned until the finish call
+    eng.decode_launch([d], [3])
+    with pytest.raises(sts.StsError) as e:
+        eng.seq_free(d)
+    assert e.value.code == sts.ESTATE
+    with pytest.raises(sts.StsError) as e:
+        eng.prefill_append(d, toks[:4], want_logits=False)                         # a request is in one phase only
+    assert e.value.code == sts.EINVAL
+    eng.decode_finish(1)
+    assert eng.seq_length(d) == 33
+    eng.seq_free(d)
+    assert eng.pages_free() == 7
+    with pytest.raises(sts.StsError) as e:
+        new_engine(sts, desc, max_pages_per_seq=sts.max_pages_per_seq_limit(16) + 1)
+    assert e.value.code == sts.EINVAL
+    eng.close()
+
+
 def test_launch_poll_finish_equals_blocking_calls(sts, tiny, eng):
     desc, w = tiny
     _, ctx_tokens, dec_tokens, pre_tokens = build_case(desc, w)
@@ -386,6 +430,40 @@ def test_launch_poll_finish_equals_blocking_calls(sts, tiny, eng):
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
 
 
+def redecide_log_with_oracle(desc, hw, log):
+    """Feeds each logged scheduling cycle (the state a live run handed to sts_sched_decide) to the
+    oracle's Algorithm 1 and demands the identical choice."""
+    from oracle import latency as L
+    from oracle import scheduler as S
+    shape = L.Shape(desc.n_layers, desc.hidden, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.mlp, desc.vocab)
+    keys = ("ttft_slo_ns", "tpot_slo_ns", "layers_per_step", "max_batch_tokens", "max_decode_batch", "kv_pool_pages", "mode",
+            "fixed_prefill_cus", "decode_boost_cus", "min_batch_tokens")
+    for n_cycle, e in enumerate(log):
+        cfg = S.Config(**{k: e["cfg"].get(k, 0) for k in keys})
+        # requests by id: queue and in-flight carry (id, arrival, in_len, out_len); decoding ones are given fresh ids
+        rows = {i: (a, il, ol) for i, a, il, ol in e["queue"] + e["inflight"]}
+        top = max(rows, default=-1) + 1
+        dec_ids = list(range(top, top + len(e["decode"])))
+        r = S.Replay(shape, hw, cfg, [rows.get(i, (0, 1, 1)) for i in range(top)] + [(0, il, 1 << 20) for _, _, il in e["decode"]])
+        r.now = e["now_ns"]
+        r.Q, r.P, r.l_exe = [q[0] for q in e["queue"]], [q[0] for q in e["inflight"]], e["layers_done"]
+        r.D, r.H = dec_ids, []
+        for i, (ft, nd, _) in zip(dec_ids, e["decode"]):
+            r.reqs[i].first_token, r.reqs[i].n_dec = ft, nd
+        r.pages_free, r.pm, r.dm = e["pages_free"], e["cur_prefill_cus"], e["cur_decode_cus"]
+        had_p = bool(r.P)
+        dur = r.schedule()
+        got = e["choice"]
+        assert got["queue"] == r.Q, n_cycle
+        if dur is None:
+            assert got["tasks"] == [] and got["predicted_ns"] == -1, n_cycle
+            continue
+        d = r.decisions[-1]
+        assert got["tasks"] == r.P and got["admitted"] == (not had_p), n_cycle
+        assert (got["layer_begin"], got["layer_end"], got["prefill_cus"], got["decode_cus"], got["branch"], got["predicted_ns"]) == \
+               (d[4], d[5], d[6], d[7], d[8], d[10]), n_cycle
+
+
 @pytest.mark.parametrize("mode", ["concurrent", "concurrent/2", "tm", "fixed:192", "naive", "wpart", "wsched", "fixedall:128", "chunked:64",
                                   "boost:64", "boost:64/2", "wsched/2"])
 def test_live_serving_of_a_short_trace(sts, tiny, mode):
@@ -402,8 +480,14 @@ def test_live_serving_of_a_short_trace(sts, tiny, mode):
                            control_threads=int(threads or 1))
     trace = synth.poisson_trace(3, 60.0, 0.5, dict(kind="lognormal", median=100, sigma=0.6, cap=400),
                                 dict(kind="lognormal", median=20, sigma=0.5, cap=100))
+    srv.state_log = []
     st, dec, tl = srv.run([tuple(int(x) for x in r) for r in trace], mode)
     assert st["n_finished"] == len(trace) and st["rejected"] == 0
+    if not mode.startswith("chunked"):
+        # live-mode replay: every scheduling cycle of the run, re-decided by the CPU oracle from the logged
+        # state, gives the same tasks, queue order, layer slice, split, branch and predicted duration
+        assert len(srv.state_log) >= len(dec) > 0
+        redecide_log_with_oracle(desc, hw, srv.state_log)
     assert st["out_tokens"] == int(trace[:, 2].sum())
     assert srv.eng.pages_free() == 600
     if mode.startswith("chunked"):

@@ -200,3 +200,26 @@ def test_live_serving_statistics_by_inspection():
     assert st["makespan_s"] == 1.5 and st["out_tokens"] == 33 and st["in_tokens"] == 300
     assert abs(st["out_tokens_per_s"] - 22.0) < 1e-9 and abs(st["total_tokens_per_s"] - 222.0) < 1e-9
     assert abs(st["ttft_mean_ms"] - (500 + 1100 + 100) / 3) < 1e-9 and abs(st["tpot_mean_ms"] - (40 + 30 + 60) / 3) < 1e-9
+
+
+def test_decode_chunk_sizing_stays_within_what_the_engine_allocates(sts):
+    """Host arithmetic of the decode attention work list: for every block-table bound that sts_init
+    accepts and any mix of context lengths and partition sizes, a context is cut into at most as
+    many chunks as the merge workspace and the work list are allocated for (at most 128), chunks
+    hold 8..64 pages, and the bound itself is 128 chunks of 64 pages."""
+    import numpy as np
+    limit = sts.max_pages_per_seq_limit(16)
+    assert limit == 128 * 64
+    rng = np.random.default_rng(5)
+    for mp in (1, 3, 8, 64, 513, 520, 2048, 4097, limit):
+        for cus in (8, 32, 128, 256):
+            for _ in range(6):
+                n = int(rng.integers(1, 65))
+                pages = rng.integers(1, mp + 1, size=n)
+                pages[0] = mp                                     # the longest context the bound allows
+                cp, mc, alloc = sts.decode_chunk_plan(pages, 8, cus, 16, mp)
+                assert cp in (8, 16, 32, 64)
+                assert mc == -(-mp // cp)
+                assert mc <= alloc <= 128, (mp, cus, cp, mc, alloc)
+    with pytest.raises(sts.StsError):
+        sts.decode_chunk_plan([limit + 1], 8, 32, 16, limit)       # a context longer than the block table
