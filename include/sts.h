@@ -191,6 +191,22 @@ enum { STS_GEMM_256x256 = 0, STS_GEMM_128x128, STS_GEMM_256x128, STS_GEMM_64x256
        STS_GEMM_256x256_W8 /* 256x256 tile, 8 waves */ };
 int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                 int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots);
+/* sts_op_gemm's fp32-store form (epilogue 1) for callers that cannot allocate -- code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc. a_dev [m, k] and w_dev [n, k]
+ * are DEVICE pointers to bf16 (row-major, K contiguous), c_dev [m, n] a DEVICE pointer to fp32; all
+ * three are the caller's and must stay valid until the work has run. The kernels are queued on
+ * `stream` (a hipStream_t, NULL = the null stream) and the call returns without waiting for them.
+ * The split-K partial sums (split_k > 1) or the partial tiles of a cut last wave (tail_slots > 0,
+ * needs split_k == 1) go to a fixed device array of STS_NOALLOC_SCRATCH_BYTES that every GPU running
+ * this library holds until the process ends; a call whose scratch need (split_k * m * n floats, or
+ * tail_slots tiles of the configuration's size) exceeds it returns STS_EINVAL, as do k % 64 != 0 and
+ * n not a multiple of the tile width. Nothing in the array has to start at zero (every element read
+ * was written by the same call), and its contents after the call are unspecified. All calls on one
+ * GPU share the array: calls that may overlap on one GPU (different streams, or different threads)
+ * race and must be serialised by the caller. No hipMalloc, hipFree or other allocating routine runs. */
+#define STS_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+int sts_op_gemm_noalloc(const void* a_dev, const void* w_dev, float* c_dev, int32_t m, int32_t n, int32_t k,
+                        int32_t tile_cfg, int32_t split_k, int32_t tail_slots, void* stream);
 /* Causal attention of a chunk: q [t, n_q, d], k and v [prior + t, n_kv, d]; query i sits at
  * position prior + i. K,V go through a paged pool with the given page order (pages[] of
  * ceil((prior+t)/16) distinct ids < n_pool_pages). out [t, n_q, d]. */

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsts.so")
-SOURCES = ["gemm.hip", "attn_prefill.hip", "attn_decode.hip", "elementwise.hip", "engine.hip", "ops.hip",
+SOURCES = ["gemm.hip", "attn_prefill.hip", "attn_decode.hip", "elementwise.hip", "engine.hip", "ops.hip", "noalloc.hip",
            "latency.cpp", "sched.cpp"]
 # packed fp32 VALU instructions are switched off: some of their forms have produced wrong results
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-result",

@@ -92,7 +92,7 @@ EXPORTS = [
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_op_gemm_noalloc",
 ]
 
 
@@ -325,6 +325,13 @@ def op_gemm(a, w, tile_cfg="128x128", epilogue=1, split_k=1, c_in=None, tail_slo
     c = _f32(c_in).copy() if c_in is not None else np.zeros((m, n), np.float32)
     _ck(lib().sts_op_gemm(_p(a, C.c_float), _p(w, C.c_float), _p(c, C.c_float), m, n, k, GEMM_CFGS[tile_cfg], epilogue, split_k, tail_slots), "sts_op_gemm")
     return c
+
+
+def op_gemm_noalloc(a_dev, w_dev, c_dev, m, n, k, tile_cfg="64x128", split_k=1, tail_slots=0, stream=None):
+    """a_dev, w_dev (bf16) and c_dev (fp32) are device addresses (ints) of the caller's buffers; the
+    kernels are queued on `stream` (a hipStream_t value, None = the null stream) and not waited for."""
+    _ck(lib().sts_op_gemm_noalloc(C.c_void_p(a_dev), C.c_void_p(w_dev), C.c_void_p(c_dev), m, n, k, GEMM_CFGS[tile_cfg], split_k,
+                                  tail_slots, C.c_void_p(stream)), "sts_op_gemm_noalloc")
 
 
 def op_attn_prefill(q, k, v, prior, pages, n_pool_pages):
