@@ -10,8 +10,11 @@ runs the split with the highest tokens/s among those meeting the per-layer share
 
 One JSON line on stdout: tokens/s of the concurrent step (inputs resident in HBM), the
 time-multiplexed comparison (same kernels, whole GPU, serialised), the roofline of the
-dominant kernel (prefill gate/up GEMM: MFMA bf16) and of the decode phase (HBM), and the CPU
-oracle timed on a bounded sample of the same workload.
+dominant kernel (prefill gate/up GEMM: MFMA bf16) and of the decode phase (HBM), the CPU
+oracle timed on a bounded sample of the same workload, and `serving`: a short live run of
+configuration 3 (the full 32-layer 8B-shaped model serving a seeded Poisson trace, Algorithm 1
+choosing batch, layer slice and CU split) beside the time-multiplexed loop on the same trace --
+output tokens/s, SLO attainment, TTFT / TPOT and the estimator's error (paper Section 4.2).
 """
 from __future__ import annotations
 
@@ -150,6 +153,38 @@ def cpu_baseline(desc, ctx, n_pre=PREFILL_TOKENS, n_dec=DECODE_BATCH):
                       f"(contexts {min(dctx)}..{max(dctx)}, {sum(dctx)} cached tokens in all), the whole step of this workload; {dt:.1f} s"}
 
 
+def serving_leg(rate, window_s):
+    """Configuration 3 for a bounded window: Poisson arrivals at `rate` req/s for `window_s` seconds (then
+    drained), input lengths lognormal(median 600, sigma 1.0, cap 8192), output lengths lognormal(median 250,
+    sigma 0.9, cap 2048), SLOs TTFT <= 1 s and TPOT <= 50 ms, L_step = 4 layers, on the full 32-layer
+    8B-shaped model with the estimator profile measured on this part. The concurrent design (Algorithm 1) and
+    the time-multiplexed loop (same kernels, whole GPU, slices and steps alternating) serve the same trace."""
+    from paper_2504_19516_amd import serve
+    desc = synth.llama8b_model()
+    prof = os.path.join(ROOT, "paper_2504_19516_amd", "data", "mi355x_llama8b.profile")
+    cfg = dict(ttft_slo_ns=TTFT_SLO_NS, tpot_slo_ns=TPOT_SLO_NS, layers_per_step=4, min_batch_tokens=0)
+    ind, outd = serve.WORKLOADS["conversation"]
+    seed = int(rate * 10) + 1
+    trace = [tuple(int(x) for x in r) for r in synth.poisson_trace(seed, rate, window_s, ind, outd)]
+    srv = serve.LiveServer(desc, open(prof).read(), cfg, 40000, max_ctx=10240)
+    keep = ("n_requests", "n_finished", "makespan_s", "out_tokens_per_s", "total_tokens_per_s", "slo_attainment", "ttft_mean_ms",
+            "ttft_p90_ms", "tpot_mean_ms", "tpot_p90_ms", "estimator_mape_prefill", "estimator_mape_decode")
+    out = {"workload": "config 3: 32-layer Llama-3-8B-shaped model, Poisson arrivals, inputs lognormal(600, 1.0, cap 8192), outputs "
+                       "lognormal(250, 0.9, cap 2048), SLO TTFT <= 1 s and TPOT <= 50 ms, L_step 4",
+           "rate_req_per_s": rate, "window_s": window_s, "trace_seed": seed, "profile": os.path.relpath(prof, ROOT)}
+    for mode, key in (("concurrent", "concurrent"), ("tm", "time_multiplexed")):
+        st, dec, _ = srv.run(trace, mode)
+        row = {k: (round(st[k], 4) if isinstance(st[k], float) else st[k]) for k in keep}
+        splits = {}
+        for d in dec:
+            splits[str(d[5])] = splits.get(str(d[5]), 0) + 1
+        row["prefill_cus_chosen"] = splits
+        out[key] = row
+    srv.close()
+    out["out_tokens_per_s_ratio"] = round(out["concurrent"]["out_tokens_per_s"] / max(out["time_multiplexed"]["out_tokens_per_s"], 1e-9), 4)
+    return out
+
+
 def stored_traffic(prefill_cus, key="gateup_hbm_bytes_per_launch"):
     """HBM bytes per gate/up launch (or, with key "decode_hbm_bytes_per_step", per decode layer-step) from
     the committed rocprofv3 --pmc measurement of this workload (FETCH_SIZE and WRITE_SIZE runs, scaled by
@@ -172,6 +207,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split", type=int, default=0, help="fix the prefill CU count instead of sweeping")
+    ap.add_argument("--no-serving", action="store_true", help="skip the live configuration-3 leg")
+    ap.add_argument("--serve-rate", type=float, default=24.0, help="request rate of the configuration-3 leg (req/s)")
+    ap.add_argument("--serve-window", type=float, default=15.0, help="arrival window of the configuration-3 leg (s); the run then drains")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="also run the plain copy kernel on %d MiB, as the reference for rocprofv3 --pmc byte counters" % (PMC_PROBE_BYTES >> 20))
     args = ap.parse_args()
@@ -194,12 +232,23 @@ def main():
     best = None
     for pm in ([args.split] if args.split else range(32, 225, 32)):
         eng.set_partition(pm, 256 - pm)
-        wl.timed(1)
-        s, tp, td = wl.timed(4)
+        wl.timed(3)                                 # the clocks and the tile choice settle on the new partition
+        s, tp, td = wl.timed(12)
         ok = tp <= ttft_budget and td <= tpot_budget
         sweep[str(pm)] = {"step_ms": round(s * 1e3, 4), "prefill_ms": round(tp / 1e6, 4), "decode_ms": round(td / 1e6, 4), "slo_ok": ok}
         if ok and (best is None or s < best[1]):
             best = (pm, s)
+    # the two fastest admissible splits are timed again, back to back, before one is chosen
+    top = sorted((k for k in sweep if sweep[k]["slo_ok"]), key=lambda k: sweep[k]["step_ms"])[:2]
+    if len(top) == 2:
+        again = {}
+        for k in top:
+            eng.set_partition(int(k), 256 - int(k))
+            wl.timed(3)
+            again[k] = wl.timed(12)[0]
+            sweep[k]["step_ms_again"] = round(again[k] * 1e3, 4)
+        k = min(again, key=again.get)
+        best = (int(k), again[k])
     # both phases at once on every CU (overlapping masks, no partition): the "Naive" point of the paper's ablation
     eng.set_partition(256, 256)
     wl.timed(1)
@@ -291,6 +340,11 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(desc, wl.ctx)
     eng.close()
+    if not args.no_serving:
+        out["serving"] = serving_leg(args.serve_rate, args.serve_window)
+    if os.environ.get("STS_DUMP_MAPS"):          # for symbolising a crash in an exit handler: where every library was mapped
+        with open("/proc/self/maps") as f, open(os.environ["STS_DUMP_MAPS"], "w") as g:
+            g.write(f.read())
     print(json.dumps(out))
 
 

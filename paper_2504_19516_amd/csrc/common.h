@@ -39,6 +39,17 @@ __device__ __forceinline__ void load_to_lds16(const void* gsrc, void* lds_dst) {
                                    (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 #endif
 }
+// The same transfer with the address given as a wave-uniform base plus a 32-bit byte offset per lane
+// (the scalar-base form of the instruction: 4 address bytes per lane travel to the memory pipeline
+// instead of 8, and advancing along K is scalar arithmetic). lds_dst must be wave-uniform. The
+// compiler does not see this load: the caller orders it against LDS reads with wait_vmem and a
+// barrier, as for load_to_lds16.
+__device__ __forceinline__ void lds_dma16(const void* base, unsigned lane_off, void* lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const unsigned m = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_dst;
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(m) : "memory");
+#endif
+}
 // Wait until at most N of this wave's vector-memory loads are outstanding (they complete in
 // order); the other counters are left alone.
 template <int N>

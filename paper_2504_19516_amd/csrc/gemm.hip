@@ -254,7 +254,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
 // already in registers); the loads of the tile after next go out right behind the barrier, a
 // whole iteration ahead of their use; step 3 runs while the first operands of the next tile
 // are read. The LDS arena starts 1 KB above address 0.
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS, bool SPLIT = false>
 __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   constexpr int BK = 64, NT = WGM * WGN * 64;
   static_assert(NS >= 2 && (NS - 2) * (BM + BN) * 8 / NT < 64, "stages: at least two, outstanding loads within vmcnt's range");
@@ -277,27 +277,37 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   const int l32 = lane & 31, lh = lane >> 5;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // slot q = j * NT + tid of a tile: row q / 8, holds K-chunk (q % 8) ^ ((row >> 1) & 7)
-  const bf16* a_src[A_CH];
-  const bf16* b_src[B_CH];
+  // slot q = j * NT + tid of a tile: row q / 8, holds K-chunk (q % 8) ^ ((row >> 1) & 7). A lane keeps
+  // the 32-bit byte offset of its chunk from the tile's first row; the tile bases are wave-uniform
+  // and advance along K in scalar registers, and so do the LDS destinations (the wave index is read
+  // into a scalar once): queuing a load takes no vector ALU work and sends 4 address bytes per lane.
+  const int swave = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.A + (size_t)m0 * g.lda);
+  const unsigned char* b_base = reinterpret_cast<const unsigned char*>(g.W + (size_t)n0 * g.ldw);
+  unsigned a_off[A_CH], b_off[B_CH];
 #pragma unroll
   for (int j = 0; j < A_CH; j++) {
     const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
-    a_src[j] = g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + ch * 8;
+    a_off[j] = (unsigned)(min(m0 + row, g.M - 1) - m0) * (unsigned)g.lda * 2u + ch * 16;
   }
 #pragma unroll
   for (int j = 0; j < B_CH; j++) {
     const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
-    b_src[j] = g.W + (size_t)(n0 + row) * g.ldw + ch * 8;
+    b_off[j] = (unsigned)row * (unsigned)g.ldw * 2u + ch * 16;
   }
-  auto issue = [&](int stage, int k) {
-    unsigned char* sa = arena + stage * STAGE + wave * 1024;
-    unsigned char* sb = sa + BM * ROWB;
+  auto issue_a = [&](int stage, int k) {
+    unsigned char* sa = arena + stage * STAGE + swave * 1024;
+    const unsigned char* ak = a_base + (size_t)k * 2;
 #pragma unroll
-    for (int j = 0; j < A_CH; j++) load_to_lds16(a_src[j] + k, sa + j * NT * 16);
-#pragma unroll
-    for (int j = 0; j < B_CH; j++) load_to_lds16(b_src[j] + k, sb + j * NT * 16);
+    for (int j = 0; j < A_CH; j++) lds_dma16(ak, a_off[j], sa + j * NT * 16);
   };
+  auto issue_b = [&](int stage, int k) {
+    unsigned char* sb = arena + stage * STAGE + swave * 1024 + BM * ROWB;
+    const unsigned char* bk = b_base + (size_t)k * 2;
+#pragma unroll
+    for (int j = 0; j < B_CH; j++) lds_dma16(bk, b_off[j], sb + j * NT * 16);
+  };
+  auto issue = [&](int stage, int k) { issue_a(stage, k); issue_b(stage, k); };
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -364,7 +374,10 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
     // tile t+1 must have landed; the NS-2 tiles issued after it may still be in flight
     if (t + NS - 1 < nk) wait_vmem<(NS - 2) * LOADS>(); else wait_vmem<0>();
     __syncthreads();
-    if (t + NS < nk) issue(cur, kbeg + (t + NS) * BK);
+    // The tile after the ones in flight goes into the stage just retired: in one burst right here, or
+    // (SPLIT) the A half here and the W half behind the last step's MFMAs. The burst is the better
+    // form when every CU of the partition is busy, the split one when the launch leaves CUs idle.
+    if (t + NS < nk) { if constexpr (SPLIT) issue_a(cur, kbeg + (t + NS) * BK); else issue(cur, kbeg + (t + NS) * BK); }
     __builtin_amdgcn_sched_barrier(0);
     if (t + 1 < nk) {
 #pragma unroll
@@ -384,6 +397,10 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
     }
     if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (SPLIT) {
+      if (t + NS < nk) issue_b(cur, kbeg + (t + NS) * BK);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     cur = nxt;
   }
   store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
@@ -455,11 +472,17 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   static_assert(DL == 0 || BK == 64, "the direct-to-LDS loop is written for BK = 64");
   constexpr size_t lds = DL ? GEMM_DL_LDS_BASE + DL * (size_t)(BM + BN) * BK * sizeof(bf16) : 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
   void (*kern)(GemmArgs);
-  if constexpr (DL != 0) kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL>;
-  else kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
+  void (*kern_split)(GemmArgs) = nullptr;          // the large prefill tile also exists with its tile loads issued in two halves
+  if constexpr (DL != 0) {
+    kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL>;
+    if constexpr (BM == 256 && BN == 256) kern_split = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL, true>;
+  } else {
+    kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
+  }
   static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
   if (!attr_set.load()) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess && kern_split) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set.store(true);
   }
@@ -482,6 +505,9 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   const int per = (ksteps + splits - 1) / splits;
   g.k_per_split = per * BK;
   const int ny = (ksteps + per - 1) / per;
+  // fewer than two full waves of workgroups on the partition: CUs idle for part of the launch
+  const long long n_wg = (long long)(g.n_full + g.n_pieces) * ny;
+  if (kern_split && tail && tail->slots > 0 && n_wg < 2LL * tail->slots) kern = kern_split;
   hipLaunchKernelGGL(kern, dim3((g.full_per_xcd + g.piece_per_xcd) * 8, ny), dim3(NT), lds, s, g);
   if (g.n_pieces > 0)
     hipLaunchKernelGGL((gemm_tail_fixup<BM, BN, EPI>), dim3(tiles - g.n_full, BM * BN / 1024), dim3(256), 0, s, g);
