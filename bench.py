@@ -36,6 +36,7 @@ PEAK_BF16 = 2.5e15       # dense MFMA bf16 flop/s, MI355X
 PEAK_HBM = 8.0e12        # bytes/s
 PMC_PROBE_BYTES = 512 << 20   # size of the copy-kernel reference run (--pmc-probe): read 512 MiB, write 512 MiB
 TTFT_SLO_NS, TPOT_SLO_NS, MODEL_LAYERS = 1_000_000_000, 50_000_000, 32
+PROFILE_8B = os.path.join(ROOT, "paper_2504_19516_amd", "data", "mi355x_llama8b.profile")
 
 
 def layer_desc():
@@ -55,6 +56,8 @@ class Workload:
         self.eng = sts.Engine(self.desc, weight_seed=1234, init_weights=True, kv_pool_pages=pages_needed + 256,
                               max_prefill_tokens=PREFILL_TOKENS, max_prefill_seqs=1, max_decode_batch=DECODE_BATCH,
                               max_seqs=DECODE_BATCH + 4, max_pages_per_seq=(8192 + 128) // 16)
+        # the GEMM tile choice reads the rates the offline profiler measured on this part
+        self.eng.set_tile_model(*sts.Profile(path=PROFILE_8B).tile_model())
         perm = synth.page_permutation(3, pages_needed + 256)
         off = 0
         self.dseqs = []
@@ -161,7 +164,7 @@ def serving_leg(rate, window_s):
     the time-multiplexed loop (same kernels, whole GPU, slices and steps alternating) serve the same trace."""
     from paper_2504_19516_amd import serve
     desc = synth.llama8b_model()
-    prof = os.path.join(ROOT, "paper_2504_19516_amd", "data", "mi355x_llama8b.profile")
+    prof = PROFILE_8B
     cfg = dict(ttft_slo_ns=TTFT_SLO_NS, tpot_slo_ns=TPOT_SLO_NS, layers_per_step=4, min_batch_tokens=0)
     ind, outd = serve.WORKLOADS["conversation"]
     seed = int(rate * 10) + 1

@@ -1,214 +1,15 @@
 // Decode attention over the paged KV cache (one new query token per request), gfx950.
 //
-// HBM-bound: every K and V byte of a request's context is read exactly once per KV head —
-// the G query heads that share a KV head are processed together. Work is split over
-// (request, kv head, context chunk of a fixed number of pages) so that a few long contexts
-// still fill the CUs while short ones cost few workgroups; a small second kernel merges the
-// chunks' (max, sum, weighted V) partials.
+// HBM-bound: every K and V byte of a request's context is read exactly once per KV head -- the G
+// query heads that share a KV head are processed together. Work is split over (request, KV head,
+// context chunk of up to 64 pages) so that a few long contexts still fill the CUs while short ones
+// cost few workgroups; a small second kernel merges the chunks' (max, sum, weighted V) partials,
+// and a context of a single chunk is finished by the attention kernel itself.
 //
-// Inside a workgroup (4 waves):
-//   1. scores: waves take pages in turn, two at a time with the next two already in flight; a lane reads a contiguous 1/4 of one token's K row
-//      (64 bytes for d = 128), so a wave reads one 4 KiB page chunk fully coalesced, and
-//      accumulates q.k with v_dot2_f32_bf16 (no conversions); 4-lane reduction.
-//   2. softmax over the chunk in LDS (exact within the chunk; chunks merge by rescaling).
-//   3. P.V: V is stored transposed in a page (d rows of 16 tokens), so a lane owns d rows,
-//      reads 32 contiguous bytes per row and dots them with the 16 probabilities.
-#include <cstdlib>
-
-#include "kernels.h"
-
-namespace sts {
-
-constexpr int MAX_CHUNK_TOKENS = 512;     // tokens per (request, kv head, chunk) workgroup
-
-// A context of n_pages is cut into ceil(n_pages / chunk_pages) chunks of EQUAL size (the last may be
-// shorter by less than the chunk count) instead of full chunks and a remainder: a workgroup with a
-// page or two is bound by the latency of its few dependent loads, and while it waits it holds one
-// of the two workgroup slots of its CU.
-__device__ __forceinline__ int balanced_chunk_pages(int n_pages, int chunk_pages) {
-  const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
-  return (n_pages + chunks - 1) / chunks;
-}
-
-__device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
-}
-
-template <int D, int G>
-__global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict__ q, const DecodeSeq* __restrict__ seqs,
-                                                          const DecodeItem* __restrict__ items,
-                                                          const int* __restrict__ block_tables, const bf16* __restrict__ pool,
-                                                          KvGeom geo, int n_q, int chunk_pages, int max_chunks,
-                                                          float* __restrict__ ws, float scale_log2e) {
-  constexpr int SEG = D / 4;              // K elements per lane (a token's row is split over 4 lanes)
-  constexpr int SEGW = SEG / 2;           // ... as packed bf16 pairs
-  constexpr int ROWS = D / 64;            // V^T rows per lane
-  __shared__ float S[G][MAX_CHUNK_TOKENS];
-  __shared__ __align__(16) bf16 P[G][MAX_CHUNK_TOKENS];
-  __shared__ float red[4][G][D];
-  __shared__ float stat_m[G], stat_l[G];
-
-  const DecodeItem item = items[blockIdx.x];        // (request, chunk): only chunks that exist are launched
-  const int chunk = item.chunk, kvh = blockIdx.y, req = item.seq;
-  const int len = item.cl + 1;
-  const int n_pages = (len + 15) >> 4;
-  const int cp = balanced_chunk_pages(n_pages, chunk_pages);
-  const int pg0 = chunk * cp, pg1 = min(n_pages, pg0 + cp);
-  if (pg0 >= pg1) return;                 // this request has fewer chunks (the merge knows)
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  float* wout = ws + (((size_t)req * geo.n_kv + kvh) * max_chunks + chunk) * G * (D + 2);
-  const int t0 = pg0 * 16, nt = min(len, pg1 * 16) - t0;
-  const int* bt = block_tables + item.bt_off;
-  const size_t head_elems = geo.head_elems();
-
-  // Page ids of the chunk, one per lane (a chunk has at most 32 pages); the loops below fetch
-  // them with a cross-lane read, so no K or V load waits on a block-table load. Indices past the
-  // chunk are clamped to its last page: prefetches beyond the end re-read it and are not used.
-  const int npg = pg1 - pg0;
-  const int wv = __builtin_amdgcn_readfirstlane(wave);
-  const int my_page = bt[pg0 + min(lane, npg - 1)];
-  auto page_base = [&](int i) -> const bf16* {
-    const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(min(i, npg - 1)));
-    return pool + ((size_t)page * geo.n_kv + kvh) * head_elems;
-  };
-  // A wave takes the chunk's pages wv, wv+4 (one pair), wv+8, wv+12 (next pair), ...; the next
-  // pair is in flight while the current one is consumed.
-  const int tok = lane >> 2, seg = lane & 3;
-  auto load_k = [&](int i, u32x4 (&kr)[2][SEGW / 4]) {
-    const u32x4* p0 = reinterpret_cast<const u32x4*>(page_base(i) + (size_t)tok * D + seg * SEG);
-    const u32x4* p1 = reinterpret_cast<const u32x4*>(page_base(i + 4) + (size_t)tok * D + seg * SEG);
-#pragma unroll
-    for (int x = 0; x < SEGW / 4; x++) { kr[0][x] = p0[x]; kr[1][x] = p1[x]; }
-  };
-  auto load_v = [&](int i, u32x4 (&vr)[2][ROWS][2]) {
-#pragma unroll
-    for (int u = 0; u < 2; u++) {
-      const bf16* vbase = page_base(i + 4 * u) + (size_t)16 * D;
-#pragma unroll
-      for (int r = 0; r < ROWS; r++) {
-        const u32x4* vp = reinterpret_cast<const u32x4*>(vbase + (size_t)(lane + 64 * r) * 16);
-        vr[u][r][0] = vp[0]; vr[u][r][1] = vp[1];
-      }
-    }
-  };
-
-  // ---- 1. scores
-  {
-    unsigned qr[G][SEGW];
-#pragma unroll
-    for (int g = 0; g < G; g++) {
-      const unsigned* qp = reinterpret_cast<const unsigned*>(q + ((size_t)req * n_q + kvh * G + g) * D + seg * SEG);
-#pragma unroll
-      for (int i = 0; i < SEGW; i++) qr[g][i] = qp[i];
-    }
-    auto score = [&](int i, const u32x4 (&kr)[2][SEGW / 4]) {
-#pragma unroll
-      for (int u = 0; u < 2; u++) {
-        if (i + 4 * u >= npg) break;                    // wave-uniform
-        float acc[G];
-#pragma unroll
-        for (int g = 0; g < G; g++) {
-          float a = 0.f;
-#pragma unroll
-          for (int x = 0; x < SEGW / 4; x++) {
-            a = dot2(kr[u][x][0], qr[g][4 * x + 0], a);
-            a = dot2(kr[u][x][1], qr[g][4 * x + 1], a);
-            a = dot2(kr[u][x][2], qr[g][4 * x + 2], a);
-            a = dot2(kr[u][x][3], qr[g][4 * x + 3], a);
-          }
-          a += __shfl_xor(a, 1, 64);
-          a += __shfl_xor(a, 2, 64);
-          acc[g] = a;
-        }
-        if (seg == 0) {
-          const int t = (i + 4 * u) * 16 + tok;
-#pragma unroll
-          for (int g = 0; g < G; g++) if (t < nt) S[g][t] = acc[g] * scale_log2e;
-        }
-      }
-    };
-    u32x4 ka[2][SEGW / 4], kb[2][SEGW / 4];
-    load_k(wv, ka);
-    for (int i = wv; i < npg; i += 16) {
-      load_k(i + 8, kb);
-      score(i, ka);
-      load_k(i + 16, ka);
-      if (i + 8 < npg) score(i + 8, kb);
-    }
-  }
-  // first V^T pages: in flight during the softmax
-  u32x4 va[2][ROWS][2], vb[2][ROWS][2];
-  load_v(wv, va);
-  __syncthreads();
-
-  // ---- 2. softmax statistics and probabilities (wave w takes heads w, w+4, ...)
-  for (int g = wave; g < G; g += 4) {
-    float mx = -INFINITY;
-    for (int t = lane; t < nt; t += 64) mx = fmaxf(mx, S[g][t]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int t = lane; t < nt; t += 64) {
-      const float p = __builtin_amdgcn_exp2f(S[g][t] - mx);
-      sum += p;
-      P[g][t] = f2bf(p);
-    }
-    // zero the tail of the last page so that stale tokens contribute nothing
-    for (int t = nt + lane; t < ((nt + 15) & ~15); t += 64) P[g][t] = f2bf(0.f);
-    sum = wave_sum(sum);
-    if (lane == 0) { stat_m[g] = mx; stat_l[g] = sum; }
-  }
-  __syncthreads();
-
-  // ---- 3. P.V
-  float acc[G][ROWS];
-#pragma unroll
-  for (int g = 0; g < G; g++)
-#pragma unroll
-    for (int r = 0; r < ROWS; r++) acc[g][r] = 0.f;
-  auto pv = [&](int i, const u32x4 (&vr)[2][ROWS][2]) {
-#pragma unroll
-    for (int u = 0; u < 2; u++) {
-      if (i + 4 * u >= npg) break;                      // wave-uniform
-      const int tb = (i + 4 * u) * 16;
-#pragma unroll
-      for (int g = 0; g < G; g++) {
-        const u32x4 p0 = *reinterpret_cast<const u32x4*>(&P[g][tb]);
-        const u32x4 p1 = *reinterpret_cast<const u32x4*>(&P[g][tb + 8]);
-#pragma unroll
-        for (int r = 0; r < ROWS; r++) {
-          float a = acc[g][r];
-          a = dot2(vr[u][r][0][0], p0[0], a); a = dot2(vr[u][r][0][1], p0[1], a);
-          a = dot2(vr[u][r][0][2], p0[2], a); a = dot2(vr[u][r][0][3], p0[3], a);
-          a = dot2(vr[u][r][1][0], p1[0], a); a = dot2(vr[u][r][1][1], p1[1], a);
-          a = dot2(vr[u][r][1][2], p1[2], a); a = dot2(vr[u][r][1][3], p1[3], a);
-          acc[g][r] = a;
-        }
-      }
-    }
-  };
-  for (int i = wv; i < npg; i += 16) {
-    load_v(i + 8, vb);
-    pv(i, va);
-    load_v(i + 16, va);
-    if (i + 8 < npg) pv(i + 8, vb);
-  }
-#pragma unroll
-  for (int g = 0; g < G; g++)
-#pragma unroll
-    for (int r = 0; r < ROWS; r++) red[wave][g][lane + 64 * r] = acc[g][r];
-  __syncthreads();
-  for (int i = tid; i < G * D; i += 256) {
-    const int g = i / D, dd = i % D;
-    wout[g * (D + 2) + dd] = red[0][g][dd] + red[1][g][dd] + red[2][g][dd] + red[3][g][dd];
-  }
-  if (tid < G) { wout[tid * (D + 2) + D] = stat_m[tid]; wout[tid * (D + 2) + D + 1] = stat_l[tid]; }
-}
-
-// ---- matrix-core variant -----------------------------------------------------------------------
-// The same (request, kv head, chunk) decomposition, with the two contractions on MFMA so that the
-// vector ALUs only do the softmax: for a group of G query heads the dot products with
-// v_dot2_f32_bf16 cost about 8 wave instructions per key, enough to hold the kernel below the
-// bandwidth a CU can pull.
+// Both contractions run on the matrix cores although the path is memory-bound: with the G query
+// heads of a group as MFMA columns the vector ALUs only do the softmax, and the kernel pulls what a
+// CU can pull from memory (with dot-product instructions the G * 2 products per key cost about 8
+// wave instructions per key and held it well below that).
 //
 // A wave owns blocks of two pages (32 keys) of the chunk, four blocks apart. Per block:
 //   S^T[key, g] = K[key, :] . Q[g, :]       v_mfma_f32_32x32x16_bf16, A = K rows, B = Q rows (columns
@@ -225,6 +26,21 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const bf16* __restrict
 // (m & 3) | ((m >> 3) & 1) << 2 | ((m >> 2) & 1) << 3 of the page: with that order the eight
 // S^T registers a lane half holds for a page are its tokens 8*half .. 8*half+7, which is the
 // order the V^T operand has in memory. Partial (max, sum, O) of the four waves are merged in LDS.
+#include <cstdlib>
+
+#include "kernels.h"
+
+namespace sts {
+
+// A context of n_pages is cut into ceil(n_pages / chunk_pages) chunks of EQUAL size (the last may be
+// shorter by less than the chunk count) instead of full chunks and a remainder: a workgroup with a
+// page or two is bound by the latency of its few dependent loads, and while it waits it holds one
+// of the two workgroup slots of its CU.
+__device__ __forceinline__ int balanced_chunk_pages(int n_pages, int chunk_pages) {
+  const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
+  return (n_pages + chunks - 1) / chunks;
+}
+
 __device__ __forceinline__ float half_swap_max_f(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -448,12 +264,12 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
 // Merge the chunks of one (request, query head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 template <int D>
 __global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
-                                         int n_q, int n_kv, int G, int chunk_pages, int max_chunks, int skip_single) {
+                                         int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
   const int head = blockIdx.x, req = blockIdx.y, dd = threadIdx.x;
   const int kvh = head / G, g = head % G;
   const int n_pages = (seqs[req].cl + 1 + 15) >> 4;
   const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
-  if (skip_single && chunks == 1) return;          // the attention kernel stored this request's output itself
+  if (chunks == 1) return;                         // the attention kernel stored this request's output itself
   const float* base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * G * (D + 2) + g * (D + 2);
   const size_t cstride = (size_t)G * (D + 2);
   float m = -INFINITY;
@@ -470,27 +286,18 @@ __global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __
 
 size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks) { return (size_t)n * n_q * chunks * (d + 2); }
 
-// STS_ATTN_DECODE=dot2 selects the vector-ALU kernel (kept for comparison); the default is the matrix-core one.
-static bool use_mfma_decode() {
-  static const bool v = [] { const char* e = getenv("STS_ATTN_DECODE"); return !(e && e[0] == 'd'); }();
-  return v;
-}
-
-// The matrix-core kernel keeps a chunk's page ids one per lane: up to 64 pages.
-constexpr int MAX_CHUNK_TOKENS_MFMA = 1024;
-int attn_decode_max_chunk_tokens() { return use_mfma_decode() ? MAX_CHUNK_TOKENS_MFMA : MAX_CHUNK_TOKENS; }
+// The kernel keeps a chunk's page ids one per lane: up to 64 pages.
+constexpr int MAX_CHUNK_TOKENS = 1024;
+int attn_decode_max_chunk_tokens() { return MAX_CHUNK_TOKENS; }
 
 template <int D, int G>
 static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
                           const int* bt, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
-  if (use_mfma_decode()) {
-    constexpr int lds = attn_decode_mfma_lds<D>();
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_mfma_kernel<D, G>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    (void)attr;
-    hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, out, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  } else
-    hipLaunchKernelGGL((attn_decode_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), 0, s, q, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks, use_mfma_decode() ? 1 : 0);
+  constexpr int lds = attn_decode_mfma_lds<D>();
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_mfma_kernel<D, G>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  (void)attr;
+  hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, out, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
 }
 
 // q, out: [n, n_q * d] bf16 (q already rotated). A context is cut into chunks of `chunk_pages`

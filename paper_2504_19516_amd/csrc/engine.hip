@@ -109,6 +109,9 @@ struct sts_ctx {
   void* probe_src = nullptr; void* probe_dst = nullptr; size_t probe_bytes = 0;
   std::vector<void*> allocs;
   std::vector<hipStream_t> used_streams;       // every pooled stream this ctx ever selected (guarded by part_mu)
+  // what the tile choice of the prefill GEMMs assumes about the part (sts_set_tile_model): TFLOP/s per busy CU of
+  // the 128x128 tiles (two workgroups per CU) and of the 256x256 tiles (one), bytes/s per CU for partial tiles
+  double rate_128 = 3.5, rate_256 = 4.8, partial_bw = 20e9;
 };
 
 namespace {
@@ -231,17 +234,17 @@ int pick_cfg(int m, int n, int k, int cus) {
   // on a small partition is compute-bound (Section 2.1). One 256x256 workgroup fills a CU, so the
   // shape is taken only when its tiles times the deepest split-K still cover the partition.
   const bool covers = (long long)(n / 256) * std::min(8, std::max(1, k / 512)) >= cus;
-  return (m <= 128 || n % 256 != 0 || !covers) ? GEMM_128x128 : GEMM_256x256_W8;
+  return (m <= 128 || n % 256 != 0 || !covers) ? GEMM_128x128 : GEMM_256x256;
 }
 // Prefill GEMM tile choice for a partition of `cus` CUs: the candidate with the smallest
 // estimated time, which is where wave quantisation (paper Section 2.2.1) enters -- complete
 // waves of workgroups at the tile's busy-CU rate, then the last wave, whole or cut along K.
 // Rates are measured busy-CU throughputs in TFLOP/s per CU: 128x128 tiles run two workgroups
 // per CU, 256x256 (8 waves) one.
-int pick_prefill_cfg(int m, int n, int k, int cus, size_t tail_ws_bytes) {
+int pick_prefill_cfg(const sts_ctx* ctx, int m, int n, int k, int cus, size_t tail_ws_bytes) {
   if (m <= 64) return GEMM_64x128;
   struct Cand { int cfg; double rate; };
-  const Cand cands[2] = {{GEMM_128x128, 3.5}, {GEMM_256x256_W8, 4.8}};
+  const Cand cands[2] = {{GEMM_128x128, ctx->rate_128}, {GEMM_256x256, ctx->rate_256}};
   int best = GEMM_128x128; double best_cost = 1e300;
   for (const Cand& c : cands) {
     const int tm = gemm_tile_m(c.cfg), tn = gemm_tile_n(c.cfg), per_cu = gemm_wgs_per_cu(c.cfg);
@@ -252,12 +255,12 @@ int pick_prefill_cfg(int m, int n, int k, int cus, size_t tail_ws_bytes) {
     gemm_tail_plan(tiles, k / 64, slots, (long long)(tail_ws_bytes / ((size_t)tm * tn * sizeof(float))), &n_full, &f);
     // in units of this configuration's tile time: complete waves, then the last wave -- whole, or
     // in rounds of 1/f with a start-up charge per round, plus the partial tiles written and read
-    // back (4 bytes out, 4 in per element and piece, at about 20 GB/s per CU)
+    // back (4 bytes out, 4 in per element and piece, at the measured per-CU rate)
     const double tile_s = 2.0 * tm * tn * k / (c.rate * 1e12 / per_cu);
     double t;
     if (f > 1) {
       const int rest = tiles - n_full, rounds = (rest * f + slots - 1) / slots;
-      t = (n_full / slots + rounds * (1.0 / f + 0.03)) * tile_s + (double)rest * f * tm * tn * 8.0 / (std::max(cus, 8) * 20e9) + 6e-6;
+      t = (n_full / slots + rounds * (1.0 / f + 0.03)) * tile_s + (double)rest * f * tm * tn * 8.0 / (std::max(cus, 8) * ctx->partial_bw) + 6e-6;
     } else {
       t = (double)((tiles + slots - 1) / slots) * tile_s;
     }
@@ -267,22 +270,22 @@ int pick_prefill_cfg(int m, int n, int k, int cus, size_t tail_ws_bytes) {
   return best;
 }
 // A prefill GEMM on the phase's partition: tile choice, and the last wave of tiles cut along K.
-hipError_t prefill_gemm(Phase& ph, int epi, const bf16* A, int lda, const bf16* W, int ldw, void* C, int ldc, int m, int n, int k) {
-  int cfg = pick_prefill_cfg(m, n, k, ph.cus, ph.tail_ws_bytes);
+hipError_t prefill_gemm(const sts_ctx* ctx, Phase& ph, int epi, const bf16* A, int lda, const bf16* W, int ldw, void* C, int ldc, int m, int n, int k) {
+  int cfg = pick_prefill_cfg(ctx, m, n, k, ph.cus, ph.tail_ws_bytes);
   if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_64x128) cfg = GEMM_128x128;    // the wave tile must hold gate/up block pairs
   const GemmTail tail{gemm_wgs_per_cu(cfg) * ph.cus, ph.tail_ws, ph.tail_ws_bytes};
   return gemm_bf16(ph.stream, cfg, epi, A, lda, W, ldw, C, ldc, m, n, k, 1, 0, &tail);
 }
-int pick_splits(int cfg, int m, int n, int k, int cus) {
+int pick_splits(const sts_ctx* ctx, int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
   const int slots = gemm_wgs_per_cu(cfg) * std::max(cus, 8);
   const int s_max = std::min(8, std::max(1, k / 512));            // at least 8 K-steps per slice
   if (gemm_wgs_per_cu(cfg) == 1 && gemm_tile_m(cfg) >= 256) {
     // one workgroup owns a CU, so rounds of workgroups are strict: estimated time of s slices =
-    // ceil(tiles * s / slots) rounds of a 1/s tile at 4.8 TFLOP/s per CU, plus the fp32 partial
-    // sums written and read back (about 20 GB/s per CU); the cheapest s wins
-    const double tile_s = 2.0 * gemm_tile_m(cfg) * gemm_tile_n(cfg) * k / 4.8e12;
-    const double part_s = 8.0 * m * n / (std::max(cus, 8) * 20e9);
+    // ceil(tiles * s / slots) rounds of a 1/s tile at the measured rate of that tile, plus the fp32
+    // partial sums written and read back at the measured per-CU rate; the cheapest s wins
+    const double tile_s = 2.0 * gemm_tile_m(cfg) * gemm_tile_n(cfg) * k / (ctx->rate_256 * 1e12);
+    const double part_s = 8.0 * m * n / (std::max(cus, 8) * ctx->partial_bw);
     int best = 1; double best_t = 1e300;
     for (int s = 1; s <= s_max; s++) {
       const double t = (double)(((long long)tiles * s + slots - 1) / slots) * tile_s / s + s * part_s;
@@ -298,12 +301,12 @@ int pick_splits(int cfg, int m, int n, int k, int cus) {
 // workgroups per CU) and 64x256 tiles (one 8-wave workgroup per CU): the wide tile re-reads the
 // activation rows half as often, which measured 13 % faster per weight byte, but its rounds are
 // strict where two narrow workgroups per CU balance in half rounds.
-void pick_decode_gemm(int m, int n, int k, int cus, bool may_split, int* cfg, int* splits) {
+void pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool may_split, int* cfg, int* splits) {
   *cfg = pick_cfg(m, n, k, cus);
-  *splits = may_split ? pick_splits(*cfg, m, n, k, cus) : 1;
+  *splits = may_split ? pick_splits(ctx, *cfg, m, n, k, cus) : 1;
   if (*cfg != GEMM_64x128 || m <= 32 || n % 256 != 0) return;
   const int c = std::max(cus, 8);
-  const int sw = may_split ? pick_splits(GEMM_64x256, m, n, k, cus) : 1;
+  const int sw = may_split ? pick_splits(ctx, GEMM_64x256, m, n, k, cus) : 1;
   const double t_narrow = 0.5 * (((long long)(n / 128) * *splits + c - 1) / c) / *splits;
   const double t_wide = 0.87 * (((long long)(n / 256) * sw + c - 1) / c) / sw;
   if (t_wide < 0.95 * t_narrow) { *cfg = GEMM_64x256; *splits = sw; }     // a near tie goes to the tiles that balance
@@ -456,13 +459,13 @@ int prefill_launch_body(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32
   for (int l = lb; l < le; l++) {
     const LayerW& w = c->layers[l];
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g1, d.rms_eps, rows, h));
-    KL(ph, STS_K_QKV, prefill_gemm(ph, EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h));
+    KL(ph, STS_K_QKV, prefill_gemm(c, ph, EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h));
     KL(ph, STS_K_ROPE, rope_kv_write_prefill(st, ph.QKV, c->qkvn, ph.d_pseq, n_seqs, ph.d_bt, c->inv_freq, layer_pool(c, l), c->geo, rows, d.n_q_heads));
     KL(ph, STS_K_ATTN, attn_prefill(st, ph.QKV, c->qkvn, ph.A, c->qd, ph.d_pseq, ph.d_items, n_items, ph.d_bt, layer_pool(c, l), c->geo, d.n_q_heads));
-    KL(ph, STS_K_O, prefill_gemm(ph, EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd));
+    KL(ph, STS_K_O, prefill_gemm(c, ph, EPI_RESID_F32, ph.A, c->qd, w.wo, c->qd, ph.X, h, rows, h, c->qd));
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g2, d.rms_eps, rows, h));
-    KL(ph, STS_K_GATEUP, prefill_gemm(ph, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, rows, 2 * d.mlp, h));
-    KL(ph, STS_K_DOWN, prefill_gemm(ph, EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp));
+    KL(ph, STS_K_GATEUP, prefill_gemm(c, ph, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, rows, 2 * d.mlp, h));
+    KL(ph, STS_K_DOWN, prefill_gemm(c, ph, EPI_RESID_F32, ph.H, d.mlp, w.wd, d.mlp, ph.X, h, rows, h, d.mlp));
   }
   if (le == d.n_layers && want_logits) {
     KL(ph, STS_K_HEAD, gather_rows_f32(st, ph.Xlast, ph.X, ph.d_rows, n_seqs, h));
@@ -583,7 +586,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     const long long stride = (long long)n * N;
     *stride_out = stride;
     int cfg, splits;
-    pick_decode_gemm(n, N, K, ph.cus, true, &cfg, &splits);
+    pick_decode_gemm(c, n, N, K, ph.cus, true, &cfg, &splits);
     *splits_out = splits;
     KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
     return STS_OK;
@@ -604,7 +607,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
   }
   if (want_logits || want_next) {
     int head_cfg, head_splits;
-    pick_decode_gemm(n, d.vocab, h, ph.cus, false, &head_cfg, &head_splits);
+    pick_decode_gemm(c, n, d.vocab, h, ph.cus, false, &head_cfg, &head_splits);
     KL(ph, STS_K_HEAD, gemm_bf16(st, head_cfg, EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
     if (want_next) {
       KL(ph, STS_K_SAMPLE, argmax_rows(st, ph.next, ph.logits, n, d.vocab));
@@ -1139,6 +1142,38 @@ extern "C" int sts_kernel_times(sts_ctx* c, int32_t phase, int64_t* ns, int64_t*
     if (launches) launches[k] = ph.kcnt[k];
     if (reset) { ph.kns[k] = 0; ph.kcnt[k] = 0; }
   }
+  return STS_OK;
+}
+extern "C" int sts_set_tile_model(sts_ctx* c, int64_t gemm_rate_128, int64_t gemm_rate_256, int64_t partial_bw_cu) {
+  if (!c || gemm_rate_128 < 1 || gemm_rate_256 < 1 || partial_bw_cu < 1) return STS_EINVAL;
+  if (c->pend_prefill || c->pend_decode) return STS_ESTATE;
+  c->rate_128 = gemm_rate_128 * 1e-3; c->rate_256 = gemm_rate_256 * 1e-3; c->partial_bw = partial_bw_cu * 1e6;
+  return STS_OK;
+}
+extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t m, int32_t n, int32_t iters, int64_t* ns_out) {
+  if (!c || !ns_out || iters < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;
+  const sts_model_desc& d = c->d;
+  if (m < 1 || m > c->p.max_prefill_tokens || n < 64 || n > 2 * d.mlp || n % 64 || n % gemm_tile_n(tile_cfg)) return STS_EINVAL;
+  if (tile_cfg == GEMM_64x128 || tile_cfg == GEMM_64x256) return STS_EINVAL;        // the SwiGLU epilogue needs gate/up block pairs in a wave tile
+  if (c->pend_prefill) return STS_ESTATE;
+  hipStream_t st;
+  STSCK(get_stream(c, 0, cus, &st));
+  { std::lock_guard<std::mutex> g(c->part_mu); remember_stream(c, st); }
+  Phase& ph = c->ph[0];
+  struct Events {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ~Events() { if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); }
+  } ev;
+  HIPCK(hipEventCreate(&ev.e0)); HIPCK(hipEventCreate(&ev.e1));
+  auto run = [&]() { return gemm_bf16(st, tile_cfg, EPI_SWIGLU_BF16, ph.Xn, d.hidden, c->layers[0].wgu, d.hidden, ph.H, d.mlp, m, n, d.hidden, 1, 0); };
+  for (int i = 0; i < 2; i++) HIPCK(run());                         // warm-up
+  HIPCK(hipEventRecord(ev.e0, st));
+  for (int i = 0; i < iters; i++) HIPCK(run());
+  HIPCK(hipEventRecord(ev.e1, st));
+  HIPCK(hipEventSynchronize(ev.e1));
+  float ms = 0.f;
+  HIPCK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
+  *ns_out = (int64_t)((double)ms * 1e6);
   return STS_OK;
 }
 extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out) {

@@ -1,14 +1,22 @@
 // bf16 MFMA GEMM for gfx950:  C[M,N] (+)= A[M,K] * W[N,K]^T, fp32 accumulation.
 //
 // Both operands are K-contiguous, which is the layout v_mfma_f32_32x32x16_bf16 wants: a lane
-// holds 8 consecutive k of one A row (or one W row). A workgroup owns a BM x BN tile; tiles of
-// A and W are staged global -> registers -> LDS (double buffered, rows padded by 16 bytes so
-// the 16-byte operand reads are bank-conflict free) and each wave accumulates a
-// (BM/WGM) x (BN/WGN) sub-tile in 32x32 MFMA blocks.
+// holds 8 consecutive k of one A row (or one W row). A workgroup owns a BM x BN tile and each of
+// its waves accumulates a (BM/WGM) x (BN/WGN) sub-tile in 32x32 MFMA blocks.
 //
-// Two main loops share the tile mapping and the epilogue: gemm_kernel stages tiles through
-// registers into padded LDS rows (small and skinny tiles), gemm_dl_kernel moves them
-// global -> LDS directly into swizzled rows (the large prefill tiles).
+// One main loop, gemm_dl_kernel, serves every shape the engine launches: K tiles of 64 go
+// global -> LDS directly (no staging registers, no LDS store instructions) into 128-byte rows whose
+// 16-byte chunks are XOR-swizzled so that the 16-byte operand reads are bank-conflict free; two or
+// three LDS stages; operand reads of the next 16-wide step are slotted between the MFMAs of the
+// current one. Instantiations: 256x256 tiles with 8 waves and 128x128 tiles with 4 waves (two
+// workgroups per CU) for prefill, 64x128 (4 waves, two per CU) and 64x256 (8 waves) with split-K
+// for decode batches. Epilogues: bf16 store, fp32 store (split-K partial sums), fp32 residual add,
+// SwiGLU on interleaved gate/up rows.
+//
+// Wave quantisation (paper Section 2.2.1) is met in the launch: the tiles of a partly filled last
+// wave of workgroups are cut along K into pieces that fill the partition (gemm_tail_plan), the
+// pieces leave fp32 partial tiles, and gemm_tail_fixup sums them in a fixed order and applies the
+// epilogue.
 //
 // Lane layout of the 32x32 accumulator block (register r of lane l):
 //   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
@@ -18,9 +26,6 @@
 
 namespace sts {
 
-#ifndef GEMM_64x128_STAGES
-#define GEMM_64x128_STAGES 3
-#endif
 constexpr int GEMM_DL_LDS_BASE = 1024;   // the direct-to-LDS arena stays clear of LDS address 0
 
 struct GemmArgs {
@@ -116,129 +121,6 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, f32x16 (&acc)[BM /
       }
     }
   }
-}
-
-template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
-__global__ void __launch_bounds__(WGM* WGN * 64) gemm_kernel(GemmArgs g) {
-  constexpr int NT = WGM * WGN * 64;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
-  constexpr int LS = BK + 8;                       // LDS row stride in elements
-  constexpr int CPR = BK / 8;                      // 16-byte chunks per tile row
-  constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;
-  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/thread mismatch");
-  static_assert(EPI != EPI_SWIGLU_BF16 || TN % 2 == 0, "swiglu needs gate/up block pairs");
-  extern __shared__ __align__(16) unsigned char smem[];
-  bf16* As = reinterpret_cast<bf16*>(smem);        // [2][BM][LS]
-  bf16* Bs = As + 2 * BM * LS;                     // [2][BN][LS]
-
-  int v, kbeg, kend, piece;
-  if (!block_work<BK>(g, &v, &kbeg, &kend, &piece)) return;
-  int tm, tn;
-  tile_coords(g, v, &tm, &tn);
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, lh = lane >> 5;
-  const int wm = wave / WGN, wn = wave % WGN;
-
-  const bf16* a_src[A_CH];
-  const bf16* b_src[B_CH];
-  int a_dst[A_CH], b_dst[B_CH];
-#pragma unroll
-  for (int j = 0; j < A_CH; j++) {
-    int c = tid + j * NT, row = c / CPR, cc = c % CPR;
-    a_src[j] = g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + cc * 8;
-    a_dst[j] = row * LS + cc * 8;
-  }
-#pragma unroll
-  for (int j = 0; j < B_CH; j++) {
-    int c = tid + j * NT, row = c / CPR, cc = c % CPR;
-    b_src[j] = g.W + (size_t)(n0 + row) * g.ldw + cc * 8;
-    b_dst[j] = row * LS + cc * 8;
-  }
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
-
-  u32x4 ra[A_CH], rb[B_CH];
-#pragma unroll
-  for (int j = 0; j < A_CH; j++) ra[j] = *reinterpret_cast<const u32x4*>(a_src[j] + kbeg);
-#pragma unroll
-  for (int j = 0; j < B_CH; j++) rb[j] = *reinterpret_cast<const u32x4*>(b_src[j] + kbeg);
-#pragma unroll
-  for (int j = 0; j < A_CH; j++) *reinterpret_cast<u32x4*>(As + a_dst[j]) = ra[j];
-#pragma unroll
-  for (int j = 0; j < B_CH; j++) *reinterpret_cast<u32x4*>(Bs + b_dst[j]) = rb[j];
-  __syncthreads();
-
-  int cur = 0;
-  for (int k = kbeg; k < kend; k += BK) {
-    // Prefetch the next K tile into registers while this one is consumed from LDS. The last
-    // iteration re-reads its own tile (in bounds, never used) so the loop body has no branch.
-    const int kn = min(k + BK, kend - BK);
-#pragma unroll
-    for (int j = 0; j < A_CH; j++) ra[j] = *reinterpret_cast<const u32x4*>(a_src[j] + kn);
-#pragma unroll
-    for (int j = 0; j < B_CH; j++) rb[j] = *reinterpret_cast<const u32x4*>(b_src[j] + kn);
-    __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the MFMA block (the scheduler would sink them)
-    const bf16* Ac = As + cur * BM * LS + (wm * WTM + l32) * LS + 8 * lh;
-    const bf16* Bc = Bs + cur * BN * LS + (wn * WTN + l32) * LS + 8 * lh;
-    // operand fragments are double buffered in registers: the LDS reads of step kk+1 are in
-    // flight while the MFMAs of step kk issue
-    bf16x8 af[2][TM], bfr[2][TN];
-#pragma unroll
-    for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * LS);
-#pragma unroll
-    for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * LS);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
-      if (kk + 1 < BK / 16) {
-#pragma unroll
-        for (int i = 0; i < TM; i++) af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * LS + (kk + 1) * 16);
-#pragma unroll
-        for (int j = 0; j < TN; j++) bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * LS + (kk + 1) * 16);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-    }
-    // scheduling recipe: first the TM+TN fragment reads of step 0, then per step one LDS read
-    // after every MPR MFMAs (all reads of the next step are out before this step's last MFMAs),
-    // the last step pure MFMA
-    {
-      constexpr int MPR = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;
-      constexpr int REST = TM * TN > MPR * (TM + TN) ? TM * TN - MPR * (TM + TN) : 0;
-      __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
-#pragma unroll
-      for (int kk = 0; kk + 1 < BK / 16; kk++) {
-#pragma unroll
-        for (int x = 0; x < TM + TN; x++) {
-          __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    bf16* An = As + (cur ^ 1) * BM * LS;
-    bf16* Bn = Bs + (cur ^ 1) * BN * LS;
-#pragma unroll
-    for (int j = 0; j < A_CH; j++) *reinterpret_cast<u32x4*>(An + a_dst[j]) = ra[j];
-#pragma unroll
-    for (int j = 0; j < B_CH; j++) *reinterpret_cast<u32x4*>(Bn + b_dst[j]) = rb[j];
-    __syncthreads();
-    cur ^= 1;
-  }
-
-  store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
 
 // ---- direct-to-LDS main loop ---------------------------------------------------------------
@@ -465,20 +347,14 @@ void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int*
   *n_full = full; *f = best;
 }
 
-// DL = 0: register-staged loop; DL = n >= 2: direct-to-LDS loop with n stages.
-template <int BM, int BN, int BK, int WGM, int WGN, int EPI, int DL = 0>
+// NS: LDS stages of the main loop.
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
 static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTail* tail) {
-  constexpr int NT = WGM * WGN * 64;
-  static_assert(DL == 0 || BK == 64, "the direct-to-LDS loop is written for BK = 64");
-  constexpr size_t lds = DL ? GEMM_DL_LDS_BASE + DL * (size_t)(BM + BN) * BK * sizeof(bf16) : 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16);
-  void (*kern)(GemmArgs);
+  constexpr int NT = WGM * WGN * 64, BK = 64;
+  constexpr size_t lds = GEMM_DL_LDS_BASE + NS * (size_t)(BM + BN) * BK * sizeof(bf16);
+  void (*kern)(GemmArgs) = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
   void (*kern_split)(GemmArgs) = nullptr;          // the large prefill tile also exists with its tile loads issued in two halves
-  if constexpr (DL != 0) {
-    kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL>;
-    if constexpr (BM == 256 && BN == 256) kern_split = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, DL, true>;
-  } else {
-    kern = gemm_kernel<BM, BN, BK, WGM, WGN, EPI>;
-  }
+  if constexpr (BM == 256 && BN == 256) kern_split = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, true>;
   static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
   if (!attr_set.load()) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -517,45 +393,28 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
 template <int EPI>
 static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int splits, const GemmTail* tail) {
   switch (cfg) {
-    case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI, 2>(s, g, splits, tail);
-    case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 8, EPI, 3>(s, g, splits, tail);
-    case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI>(s, g, splits, tail);
-    case GEMM_64x128: return launch_cfg<64, 128, 64, 1, 4, EPI, GEMM_64x128_STAGES>(s, g, splits, tail);
-    case GEMM_64x64: return launch_cfg<64, 64, 64, 2, 2, EPI>(s, g, splits, tail);
-    case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI, 2>(s, g, splits, tail);
+    case GEMM_128x128: return launch_cfg<128, 128, 2, 2, EPI, 2>(s, g, splits, tail);
+    case GEMM_64x256: return launch_cfg<64, 256, 1, 8, EPI, 3>(s, g, splits, tail);
+    case GEMM_64x128: return launch_cfg<64, 128, 1, 4, EPI, 3>(s, g, splits, tail);
+    case GEMM_256x256: return launch_cfg<256, 256, 2, 4, EPI, 2>(s, g, splits, tail);
     default: return hipErrorInvalidValue;
   }
 }
 
-int gemm_tile_n(int cfg) {
-  switch (cfg) {
-    case GEMM_256x256: case GEMM_256x256_W8: case GEMM_64x256: case GEMM_32x256: return 256;
-    case GEMM_64x64: return 64;
-    default: return 128;
-  }
-}
-int gemm_tile_m(int cfg) {
-  switch (cfg) {
-    case GEMM_256x256: case GEMM_256x256_W8: case GEMM_256x128: return 256;
-    case GEMM_128x128: return 128;
-    case GEMM_32x256: return 32;
-    default: return 64;
-  }
-}
+int gemm_tile_n(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 ? 256 : 128; }
+int gemm_tile_m(int cfg) { return cfg == GEMM_256x256 ? 256 : cfg == GEMM_128x128 ? 128 : 64; }
+// resident workgroups per CU: the 8-wave tiles fill a CU, the 4-wave tiles share it in pairs
+int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 ? 1 : 2; }
 
 // C = A * W^T with the chosen tile configuration and epilogue. Requirements (checked):
 // K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1.
 // With splits > 1 (EPI_F32 only) partial sums go to C + z * split_stride. With `tail` (splits == 1)
 // the tiles of the last, partly filled wave of workgroups are cut along K (see GemmArgs).
-int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_256x256_W8 || cfg == GEMM_256x128 || cfg == GEMM_64x256 ? 1 : 2; }
-
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
                      void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail) {
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
-  if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128 || cfg == GEMM_64x64)) return hipErrorInvalidValue;   // wave tile of one block
+  if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128 || cfg == GEMM_64x256)) return hipErrorInvalidValue;   // wave tile of one 32-column block
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.split_stride = split_stride;
@@ -565,12 +424,8 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
     case EPI_RESID_F32: return launch_epi<EPI_RESID_F32>(s, cfg, g, splits, tail);
     case EPI_SWIGLU_BF16:
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
-        case GEMM_256x256: return launch_cfg<256, 256, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
-        case GEMM_256x256_W8: return launch_cfg<256, 256, 64, 2, 4, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
-        case GEMM_128x128: return launch_cfg<128, 128, 64, 2, 2, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
-        case GEMM_256x128: return launch_cfg<256, 128, 64, 2, 2, EPI_SWIGLU_BF16>(s, g, 1, tail);
-        case GEMM_64x256: return launch_cfg<64, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
-        case GEMM_32x256: return launch_cfg<32, 256, 64, 1, 4, EPI_SWIGLU_BF16>(s, g, 1, tail);
+        case GEMM_256x256: return launch_cfg<256, 256, 2, 4, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
+        case GEMM_128x128: return launch_cfg<128, 128, 2, 2, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
         default: return hipErrorInvalidValue;
       }
     default: return hipErrorInvalidValue;

@@ -6,7 +6,8 @@ namespace sts {
 
 // ---- GEMM -------------------------------------------------------------------------------
 enum GemmEpilogue { EPI_BF16 = 0, EPI_F32 = 1, EPI_RESID_F32 = 2, EPI_SWIGLU_BF16 = 3 };
-enum GemmConfig { GEMM_256x256 = 0, GEMM_128x128 = 1, GEMM_256x128 = 2, GEMM_64x256 = 3, GEMM_32x256 = 4, GEMM_64x128 = 5, GEMM_64x64 = 6, GEMM_256x256_W8 = 7, GEMM_NCFG = 8 };
+// the same numbering as STS_GEMM_* in sts.h
+enum GemmConfig { GEMM_128x128 = 0, GEMM_64x256 = 1, GEMM_64x128 = 2, GEMM_256x256 = 3, GEMM_NCFG = 4 };
 int gemm_tile_m(int cfg);
 int gemm_tile_n(int cfg);
 int gemm_wgs_per_cu(int cfg);                       // resident workgroups per CU of this configuration
@@ -20,7 +21,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
 // ---- paged KV layout ----------------------------------------------------------------------
 // One layer's pool is [n_pages][n_kv_heads][ K: page_tokens x d | V^T: d x page_tokens ] bf16.
 // V is kept transposed inside a page so that the P*V contraction (over tokens) reads
-// token-contiguous operands, as the MFMA and dot2 operand layouts want.
+// token-contiguous operands, as the MFMA operand layout wants.
 struct KvGeom {
   int n_kv, d, page_tokens;
   __host__ __device__ size_t head_elems() const { return (size_t)2 * page_tokens * d; }

@@ -21,6 +21,9 @@ struct Profile {
   int64_t n_cu = 256, granule = 32, c_peak = 2500000, d_peak = 8000, n_d = 64;
   int64_t tile_m = 256, tile_n = 256, tile_q = 128, wgs_per_cu = 1, use_waveq = 1;
   int64_t tail_cut = 0;                // > 0: GEMMs cut a partly filled last wave along K into at most this many pieces
+  // Measured on the part by the offline profiler and read by the engine's tile choice (not by the estimator):
+  // GFLOP/s per busy CU of the 128x128 and the 256x256 GEMM tiles, MB/s per CU for partial tiles written and read back.
+  int64_t gemm_rate_128 = 3500, gemm_rate_256 = 4800, partial_bw_cu = 20000;
   Grid bw;                             // D_{p,sl}; empty = use D_peak min(1, N_p/N_d)
   Grid prefill_corun;                  // slowdown (ppm, over the decode CUs beside it) of a prefill slice that shares HBM with a
                                        // running decode step; empty = none. Section 3.2.3 measures this side of the contention as

@@ -21,7 +21,8 @@ PPM = 1_000_000
 
 def profile_text(hw: dict, grids: dict) -> str:
     lines = ["sts-profile 1"]
-    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut"):
+    for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut",
+              "gemm_rate_128", "gemm_rate_256", "partial_bw_cu"):
         lines.append(f"{k} {int(hw[k])}")
     for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         if name not in grids:
@@ -44,7 +45,9 @@ class Profiler:
                               max_pages_per_seq=(max_ctx + 128) // 16)
         self.n_cu = self.eng.get_partition()[2]
         self.hw = dict(n_cu=self.n_cu, granule=granule, c_peak=2_500_000, d_peak=8_000, n_d=self.n_cu, tile_m=128, tile_n=128,
-                       tile_q=128, wgs_per_cu=2, use_waveq=1, tail_cut=16)
+                       tile_q=128, wgs_per_cu=2, use_waveq=1, tail_cut=16,
+                       gemm_rate_128=3500, gemm_rate_256=4800, partial_bw_cu=20000)      # the library's defaults until measured
+        self.max_tokens = max_tokens
         self.grids = {}
 
     def close(self):
@@ -122,6 +125,7 @@ class Profiler:
         n_d = next(c for c in cus if bws[c] >= 0.95 * d_peak)
         self.hw.update(d_peak=int(d_peak), n_d=n_d)
         log(f"copy bandwidth bytes/ns by CUs: { {c: round(b) for c, b in bws.items()} } -> D_peak {d_peak:.0f}, N_d {n_d}")
+        self.measure_tile_model(bws, log)
         # compute peak: the largest prefill GEMM at full GPU
         self.eng.kernel_timing(True)
         self.eng.kernel_times(0, reset=True)
@@ -134,6 +138,31 @@ class Profiler:
         self.hw.update(c_peak=int(c_peak))
         log(f"gate/up GEMM at {n} CUs: {c_peak / 1e3:.0f} TFLOP/s -> C_peak {c_peak:.0f} flop/ns")
         return bws
+
+    def measure_tile_model(self, bws, log=print):
+        """What the engine's GEMM tile choice needs to know about the part: the rate of a busy CU with each
+        prefill tile shape (the gate/up product on whole waves of tiles, on the partition prefill usually
+        gets: all CUs but one granule) and the per-CU rate at which partial tiles are written and read
+        back (the copy probe's). Stored in the profile and handed to the engine before alpha is calibrated."""
+        cus = max(self.granule, self.n_cu - self.granule)
+        m = min(2048, self.max_tokens) // 256 * 256
+        d = self.desc
+        for key, name, tm, tn, per_cu in (("gemm_rate_128", "128x128", 128, 128, 2), ("gemm_rate_256", "256x256", 256, 256, 1)):
+            slots, rows = per_cu * cus, m // tm if m else 0
+            if not rows or slots % rows:
+                continue
+            per_wave = slots // rows * tn                      # weight rows that make one whole wave of tiles
+            waves = min(4, 2 * d.mlp // per_wave)
+            if waves < 1:
+                continue                                       # a model too narrow to fill the partition: keep the default
+            n = waves * per_wave
+            ns = self.eng.probe_gemm(cus, name, m, n, iters=20) / 20
+            rate = 2 * m * n * d.hidden / ns / cus             # GFLOP/s per busy CU
+            self.hw[key] = int(rate)
+            log(f"{name} tiles, {m} x {n} x {d.hidden} on {cus} CUs ({waves} whole waves): {ns / 1e3:.1f} us -> {rate / 1e3:.2f} TFLOP/s per busy CU")
+        self.hw["partial_bw_cu"] = int(bws[cus] / cus * 1e3)
+        log(f"partial tiles: {self.hw['partial_bw_cu'] / 1e3:.1f} GB/s per CU (copy probe on {cus} CUs)")
+        self.eng.set_tile_model(self.hw["gemm_rate_128"], self.hw["gemm_rate_256"], self.hw["partial_bw_cu"])
 
     def sweep_contention(self, dms=(32, 64, 128, 192), sls=(0, 2048, 8192), log=print):
         vals = [[int(self.corun_copy_bw(dm, sl)) for sl in sls] for dm in dms]

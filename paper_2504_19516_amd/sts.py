@@ -17,7 +17,7 @@ _lib = None
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 K_NAMES = ["embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup", "swiglu", "down", "reduce", "head", "sample"]
-GEMM_CFGS = {"256x256": 0, "128x128": 1, "256x128": 2, "64x256": 3, "32x256": 4, "64x128": 5, "64x64": 6, "256x256w8": 7}
+GEMM_CFGS = {"128x128": 0, "64x256": 1, "64x128": 2, "256x256": 3}
 INF_NS = 1 << 60
 
 
@@ -92,7 +92,8 @@ EXPORTS = [
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_op_gemm_noalloc",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_op_gemm_noalloc", "sts_probe_gemm", "sts_set_tile_model",
+    "sts_profile_tile_model",
 ]
 
 
@@ -298,6 +299,16 @@ class Engine:
     def set_partition(self, prefill_cus, decode_cus):
         _ck(lib().sts_set_partition(self._ctx, prefill_cus, decode_cus), "sts_set_partition")
 
+    def set_tile_model(self, gemm_rate_128, gemm_rate_256, partial_bw_cu):
+        """GFLOP/s per busy CU of the two prefill tile shapes and MB/s per CU for partial tiles (Profile.tile_model())."""
+        _ck(lib().sts_set_tile_model(self._ctx, C.c_int64(int(gemm_rate_128)), C.c_int64(int(gemm_rate_256)), C.c_int64(int(partial_bw_cu))),
+            "sts_set_tile_model")
+
+    def probe_gemm(self, cus, tile_cfg, m, n, iters=10):
+        ns = C.c_int64()
+        _ck(lib().sts_probe_gemm(self._ctx, cus, GEMM_CFGS[tile_cfg], m, n, iters, C.byref(ns)), "sts_probe_gemm")
+        return ns.value
+
     def get_partition(self):
         a, b, t = C.c_int32(), C.c_int32(), C.c_int32()
         _ck(lib().sts_get_partition(self._ctx, C.byref(a), C.byref(b), C.byref(t)), "sts_get_partition")
@@ -384,6 +395,11 @@ class Profile:
         if getattr(self, "_p", None):
             lib().sts_profile_free(self._p)
             self._p = C.c_void_p()
+
+    def tile_model(self):
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+        _ck(lib().sts_profile_tile_model(self._p, C.byref(a), C.byref(b), C.byref(c)), "sts_profile_tile_model")
+        return a.value, b.value, c.value
 
     def dump(self) -> str:
         need = C.c_size_t()

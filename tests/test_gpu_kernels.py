@@ -27,8 +27,8 @@ def sts():
     return m
 
 
-@pytest.mark.parametrize("cfg,m", [("256x256", 300), ("128x128", 300), ("256x128", 257), ("64x256", 70), ("32x256", 20),
-                                   ("64x128", 64), ("128x128", 1), ("64x64", 50), ("256x256w8", 300)])
+@pytest.mark.parametrize("cfg,m", [("256x256", 300), ("128x128", 300), ("64x256", 70), ("64x256", 20), ("64x128", 64), ("128x128", 1),
+                                   ("64x128", 50), ("256x256", 513)])
 def test_gemm_fp32_accumulators(sts, cfg, m):
     n, k = 512, 320
     a = synth.normal_bf16(1, (m, k))
@@ -39,7 +39,8 @@ def test_gemm_fp32_accumulators(sts, cfg, m):
     assert rel(got, ref) <= 1e-5          # in practice fp32 accumulation of 320 terms
 
 
-@pytest.mark.parametrize("cfg,m,split", [("64x256", 64, 4), ("32x256", 8, 8), ("128x128", 130, 2), ("64x128", 33, 3), ("64x64", 64, 8)])
+@pytest.mark.parametrize("cfg,m,split", [("64x256", 64, 4), ("64x256", 8, 8), ("128x128", 130, 2), ("64x128", 33, 3), ("64x128", 64, 8),
+                                         ("256x256", 300, 2)])
 def test_gemm_split_k(sts, cfg, m, split):
     n, k = 256, 1024
     a = synth.normal_bf16(3, (m, k))
@@ -48,7 +49,7 @@ def test_gemm_split_k(sts, cfg, m, split):
     assert rel(sts.op_gemm(a, w, cfg, epilogue=1, split_k=split), ref) <= 1e-5
 
 
-@pytest.mark.parametrize("cfg", ["256x256", "128x128", "256x256w8"])
+@pytest.mark.parametrize("cfg", ["256x256", "128x128", "64x128", "64x256"])
 def test_gemm_bf16_store_and_residual(sts, cfg):
     m, n, k = 200, 256, 192
     a = synth.normal_bf16(5, (m, k))
@@ -62,7 +63,7 @@ def test_gemm_bf16_store_and_residual(sts, cfg):
     assert rel(got2, x.astype(np.float64) + ref) <= 1e-5
 
 
-@pytest.mark.parametrize("cfg,m", [("256x256", 260), ("128x128", 100), ("64x256", 40), ("32x256", 5), ("256x256w8", 513)])
+@pytest.mark.parametrize("cfg,m", [("256x256", 260), ("128x128", 100), ("128x128", 5), ("256x256", 513)])
 def test_gemm_swiglu_epilogue(sts, cfg, m):
     n2, k = 256, 128
     a = synth.normal_bf16(8, (m, k))
@@ -75,7 +76,7 @@ def test_gemm_swiglu_epilogue(sts, cfg, m):
 
 
 @pytest.mark.parametrize("cfg,m,n,slots", [("128x128", 300, 512, 8), ("128x128", 300, 512, 10), ("128x128", 300, 512, 40),
-                                           ("128x128", 300, 512, 16), ("256x256w8", 513, 512, 4), ("256x256w8", 513, 512, 15),
+                                           ("128x128", 300, 512, 16), ("256x256", 513, 512, 4), ("256x256", 513, 512, 15),
                                            ("64x128", 64, 640, 4)])
 @pytest.mark.parametrize("epilogue", [0, 1, 2, 3])
 def test_gemm_tail_wave_split(sts, cfg, m, n, slots, epilogue):
@@ -111,6 +112,9 @@ def test_gemm_rejects_bad_shapes(sts):
     assert e.value.code == sts.EINVAL
     with pytest.raises(sts.StsError):
         sts.op_gemm(np.zeros((4, 64), np.float32), np.zeros((192, 64), np.float32), "256x256")   # N not a multiple of the tile
+    with pytest.raises(sts.StsError) as e:
+        sts.op_gemm(np.zeros((4, 64), np.float32), np.zeros((512, 64), np.float32), "64x256", epilogue=3)   # no SwiGLU form of this tile
+    assert e.value.code == sts.EINVAL
 
 
 @pytest.mark.parametrize("t,prior,nq,nkv,d", [(128, 0, 4, 4, 64), (300, 0, 8, 2, 128), (70, 45, 4, 1, 128), (1, 0, 4, 4, 64),

@@ -60,7 +60,7 @@ def rel(a, b):
 CASES = [
     [(150, 1024, 2048, "64x128", 4, 0), (37, 512, 1024, "64x128", 3, 0)],
     [(300, 1024, 1024, "128x128", 1, 20), (130, 512, 512, "128x128", 1, 6)],
-    [(520, 1024, 1024, "256x256w8", 1, 10), (64, 256, 512, "64x128", 8, 0)],
+    [(520, 1024, 1024, "256x256", 1, 10), (64, 256, 512, "64x128", 8, 0)],
 ]
 
 
@@ -96,7 +96,7 @@ def test_noalloc_gemm_rejects_what_does_not_fit_its_scratch():
             sts.op_gemm_noalloc(buf, buf, buf, 2048, 1024, 512, "64x128", 8, 0)
         assert e.value.code == sts.EINVAL
         with pytest.raises(sts.StsError) as e:                               # 256 partial tiles of 256 x 256 floats = 64 MiB
-            sts.op_gemm_noalloc(buf, buf, buf, 512, 1024, 512, "256x256w8", 1, 256)
+            sts.op_gemm_noalloc(buf, buf, buf, 512, 1024, 512, "256x256", 1, 256)
         assert e.value.code == sts.EINVAL
         with pytest.raises(sts.StsError) as e:
             sts.op_gemm_noalloc(buf, buf, buf, 64, 128, 100, "64x128", 1, 0)  # k not a multiple of 64
