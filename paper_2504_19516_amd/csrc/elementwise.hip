@@ -29,41 +29,47 @@ __device__ __forceinline__ int phys_row(int r, int row_offset, int ib, int phase
   return ib > 0 ? (r / ib) * 2 * ib + phase * ib + r % ib : row_offset + r;
 }
 
-__global__ void init_weight_kernel(bf16* dst, int ld, uint64_t base, int rows, int cols, int row_offset, int ib, int phase) {
+// Where element (physical row r, column c) of a weight matrix with ld columns lives. Row-major, or the
+// packed layout of the GEMM weights (weight_packed_index in kernels.h).
+__device__ __forceinline__ size_t weight_elem(int r, int c, int ld, int packed) {
+  return packed ? weight_packed_index(r, c, ld) : (size_t)r * ld + c;
+}
+
+__global__ void init_weight_kernel(bf16* dst, int ld, uint64_t base, int rows, int cols, int row_offset, int ib, int phase, int packed) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (i >= (size_t)rows * cols) return;
   int r = (int)(i / cols), c = (int)(i % cols);
   float w = (float)irwin_hall12(base, i) * 0.02f * 1.52587890625e-05f;   // * 2^-16, exact
-  dst[(size_t)phys_row(r, row_offset, ib, phase) * ld + c] = f2bf(w);
+  dst[weight_elem(phys_row(r, row_offset, ib, phase), c, ld, packed)] = f2bf(w);
 }
 hipError_t init_weight(hipStream_t s, bf16* dst, int ld, uint64_t seed, uint64_t tensor_id, int rows, int cols,
-                       int row_offset, int ib, int phase) {
+                       int row_offset, int ib, int phase, int packed) {
   size_t n = (size_t)rows * cols;
   uint64_t base = mix64(seed ^ mix64(tensor_id));
-  hipLaunchKernelGGL(init_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, ld, base, rows, cols, row_offset, ib, phase);
+  hipLaunchKernelGGL(init_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, ld, base, rows, cols, row_offset, ib, phase, packed);
   return hipGetLastError();
 }
 
-__global__ void convert_weight_kernel(bf16* dst, int ld, const float* src, int rows, int cols, int row_offset, int ib, int phase) {
+__global__ void convert_weight_kernel(bf16* dst, int ld, const float* src, int rows, int cols, int row_offset, int ib, int phase, int packed) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (i >= (size_t)rows * cols) return;
   int r = (int)(i / cols), c = (int)(i % cols);
-  dst[(size_t)phys_row(r, row_offset, ib, phase) * ld + c] = f2bf(src[i]);
+  dst[weight_elem(phys_row(r, row_offset, ib, phase), c, ld, packed)] = f2bf(src[i]);
 }
-hipError_t convert_weight(hipStream_t s, bf16* dst, int ld, const float* src, int rows, int cols, int row_offset, int ib, int phase) {
+hipError_t convert_weight(hipStream_t s, bf16* dst, int ld, const float* src, int rows, int cols, int row_offset, int ib, int phase, int packed) {
   size_t n = (size_t)rows * cols;
-  hipLaunchKernelGGL(convert_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, ld, src, rows, cols, row_offset, ib, phase);
+  hipLaunchKernelGGL(convert_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, ld, src, rows, cols, row_offset, ib, phase, packed);
   return hipGetLastError();
 }
-__global__ void export_weight_kernel(float* dst, const bf16* src, int ld, int rows, int cols, int row_offset, int ib, int phase) {
+__global__ void export_weight_kernel(float* dst, const bf16* src, int ld, int rows, int cols, int row_offset, int ib, int phase, int packed) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (i >= (size_t)rows * cols) return;
   int r = (int)(i / cols), c = (int)(i % cols);
-  dst[i] = bf2f(src[(size_t)phys_row(r, row_offset, ib, phase) * ld + c]);
+  dst[i] = bf2f(src[weight_elem(phys_row(r, row_offset, ib, phase), c, ld, packed)]);
 }
-hipError_t export_weight(hipStream_t s, float* dst, const bf16* src, int ld, int rows, int cols, int row_offset, int ib, int phase) {
+hipError_t export_weight(hipStream_t s, float* dst, const bf16* src, int ld, int rows, int cols, int row_offset, int ib, int phase, int packed) {
   size_t n = (size_t)rows * cols;
-  hipLaunchKernelGGL(export_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, src, ld, rows, cols, row_offset, ib, phase);
+  hipLaunchKernelGGL(export_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, src, ld, rows, cols, row_offset, ib, phase, packed);
   return hipGetLastError();
 }
 

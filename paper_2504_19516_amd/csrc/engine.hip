@@ -576,6 +576,15 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
   n_items = 0;
   for (int i = 0; i < n; i++)
     for (int ch = 0; ch < (ph.h_dseq[i].n_pages + chunk_pages - 1) / chunk_pages; ch++) ph.h_ditems[n_items++] = DecodeItem{i, ch, ph.h_dseq[i].cl, ph.h_dseq[i].bt_off};
+  // longest chunks first (a context's chunks are equal, so its chunk length is pages / chunks): the workgroups
+  // that finish the launch are then the short ones
+  {
+    auto chunk_len = [&](const DecodeItem& it) {
+      const int np = ph.h_dseq[it.seq].n_pages, chunks = (np + chunk_pages - 1) / chunk_pages;
+      return (np + chunks - 1) / chunks;
+    };
+    std::stable_sort(ph.h_ditems, ph.h_ditems + n_items, [&](const DecodeItem& a, const DecodeItem& b) { return chunk_len(a) > chunk_len(b); });
+  }
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
   HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
@@ -676,12 +685,13 @@ int alloc_phase(sts_ctx* c, int side) {
   return STS_OK;
 }
 
-struct TensorRef { bf16* w = nullptr; float* g = nullptr; int ld = 0, rows = 0, cols = 0, row_off = 0, ib = 0, phase = 0; uint64_t tid = 0; };
+// packed: the tensor is a GEMM weight kept in the packed block layout; the embedding table, read by rows, is row-major
+struct TensorRef { bf16* w = nullptr; float* g = nullptr; int ld = 0, rows = 0, cols = 0, row_off = 0, ib = 0, phase = 0; uint64_t tid = 0; int packed = 1; };
 
 int find_tensor(sts_ctx* c, int layer, const char* name, TensorRef* t) {
   const sts_model_desc& d = c->d;
   const std::string n(name ? name : "");
-  if (n == "emb") { *t = TensorRef{c->emb, nullptr, d.hidden, d.vocab, d.hidden, 0, 0, 0, 0}; return STS_OK; }
+  if (n == "emb") { *t = TensorRef{c->emb, nullptr, d.hidden, d.vocab, d.hidden, 0, 0, 0, 0, 0}; return STS_OK; }
   if (n == "lm") { *t = TensorRef{c->lm, nullptr, d.hidden, d.vocab, d.hidden, 0, 0, 0, 1}; return STS_OK; }
   if (n == "gf") { *t = TensorRef{nullptr, c->gf, 0, 1, d.hidden}; return STS_OK; }
   if (layer < 0 || layer >= d.n_layers) return STS_EINVAL;
@@ -763,7 +773,7 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
       TensorRef t;
       if ((rc = find_tensor(c, l, name, &t))) return fail(rc);
       hipError_t e;
-      if (params->init_weights) e = init_weight(nullptr, t.w, t.ld, params->weight_seed, t.tid, t.rows, t.cols, t.row_off, t.ib, t.phase);
+      if (params->init_weights) e = init_weight(nullptr, t.w, t.ld, params->weight_seed, t.tid, t.rows, t.cols, t.row_off, t.ib, t.phase, t.packed);
       else e = hipMemset(t.w + (size_t)(t.ib ? 0 : t.row_off) * t.ld, 0, (size_t)(t.ib ? 2 * t.rows : t.rows) * t.ld * sizeof(bf16));
       if (e != hipSuccess) { g_hip_err = (int)e; return fail(STS_EHIP); }
     }
@@ -823,7 +833,7 @@ extern "C" int sts_load_weights(sts_ctx* c, int32_t layer, const char* name, con
   float* tmp = nullptr;
   HIPCK(hipMalloc(&tmp, count * sizeof(float)));
   hipError_t e = hipMemcpy(tmp, host, count * sizeof(float), hipMemcpyHostToDevice);
-  if (e == hipSuccess) e = convert_weight(nullptr, t.w, t.ld, tmp, t.rows, t.cols, t.row_off, t.ib, t.phase);
+  if (e == hipSuccess) e = convert_weight(nullptr, t.w, t.ld, tmp, t.rows, t.cols, t.row_off, t.ib, t.phase, t.packed);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   (void)hipFree(tmp);
   HIPCK(e);
@@ -838,7 +848,7 @@ extern "C" int sts_read_weights(sts_ctx* c, int32_t layer, const char* name, flo
   if (t.g) { HIPCK(hipMemcpy(host, t.g, count * sizeof(float), hipMemcpyDeviceToHost)); return STS_OK; }
   float* tmp = nullptr;
   HIPCK(hipMalloc(&tmp, count * sizeof(float)));
-  hipError_t e = export_weight(nullptr, tmp, t.w, t.ld, t.rows, t.cols, t.row_off, t.ib, t.phase);
+  hipError_t e = export_weight(nullptr, tmp, t.w, t.ld, t.rows, t.cols, t.row_off, t.ib, t.phase, t.packed);
   if (e == hipSuccess) e = hipMemcpy(host, tmp, count * sizeof(float), hipMemcpyDeviceToHost);
   (void)hipFree(tmp);
   HIPCK(e);

@@ -32,6 +32,7 @@ struct GemmArgs {
   const bf16* A; const bf16* W; void* C;
   int lda, ldw, ldc;
   int M, N, K;
+  int w_packed;               // W in the packed block layout (weight_packed_index) instead of row-major
   int tiles_m, tiles_n, group_m;
   int k_per_split;            // K range handled by one blockIdx.y
   long long split_stride;     // elements between consecutive split-K partial outputs
@@ -136,7 +137,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, f32x16 (&acc)[BM /
 // already in registers); the loads of the tile after next go out right behind the barrier, a
 // whole iteration ahead of their use; step 3 runs while the first operands of the next tile
 // are read. The LDS arena starts 1 KB above address 0.
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS, bool SPLIT = false>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS, bool SPLIT = false, bool WPACK = true>
 __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   constexpr int BK = 64, NT = WGM * WGN * 64;
   static_assert(NS >= 2 && (NS - 2) * (BM + BN) * 8 / NT < 64, "stages: at least two, outstanding loads within vmcnt's range");
@@ -165,7 +166,10 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   // into a scalar once): queuing a load takes no vector ALU work and sends 4 address bytes per lane.
   const int swave = __builtin_amdgcn_readfirstlane(wave);
   const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.A + (size_t)m0 * g.lda);
-  const unsigned char* b_base = reinterpret_cast<const unsigned char*>(g.W + (size_t)n0 * g.ldw);
+  // W: row-major, or (WPACK) 64 x 64 blocks that already hold the swizzled LDS image -- slot q of the tile is
+  // then simply the q-th 16-byte piece of the tile's blocks for this K step
+  const unsigned char* b_base = WPACK ? reinterpret_cast<const unsigned char*>(g.W) + (size_t)(n0 >> 6) * (g.K >> 6) * 8192
+                                      : reinterpret_cast<const unsigned char*>(g.W + (size_t)n0 * g.ldw);
   unsigned a_off[A_CH], b_off[B_CH];
 #pragma unroll
   for (int j = 0; j < A_CH; j++) {
@@ -175,7 +179,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
 #pragma unroll
   for (int j = 0; j < B_CH; j++) {
     const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
-    b_off[j] = (unsigned)row * (unsigned)g.ldw * 2u + ch * 16;
+    b_off[j] = WPACK ? (unsigned)(q >> 9) * (unsigned)(g.K >> 6) * 8192u + (unsigned)(q & 511) * 16u
+                     : (unsigned)row * (unsigned)g.ldw * 2u + ch * 16;
   }
   auto issue_a = [&](int stage, int k) {
     unsigned char* sa = arena + stage * STAGE + swave * 1024;
@@ -185,7 +190,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   };
   auto issue_b = [&](int stage, int k) {
     unsigned char* sb = arena + stage * STAGE + swave * 1024 + BM * ROWB;
-    const unsigned char* bk = b_base + (size_t)k * 2;
+    const unsigned char* bk = b_base + (WPACK ? (size_t)(k >> 6) * 8192 : (size_t)k * 2);
 #pragma unroll
     for (int j = 0; j < B_CH; j++) lds_dma16(bk, b_off[j], sb + j * NT * 16);
   };
@@ -354,11 +359,15 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   constexpr size_t lds = GEMM_DL_LDS_BASE + NS * (size_t)(BM + BN) * BK * sizeof(bf16);
   void (*kern)(GemmArgs) = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
   void (*kern_split)(GemmArgs) = nullptr;          // the large prefill tile also exists with its tile loads issued in two halves
+  void (*kern_rowmajor)(GemmArgs) = nullptr;       // row-major W: the fp32-store epilogue only (callers that bring their own weights)
   if constexpr (BM == 256 && BN == 256) kern_split = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, true>;
+  if constexpr (EPI == EPI_F32) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false, false>;
+  if (!g.w_packed && !kern_rowmajor) return hipErrorInvalidValue;
   static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
   if (!attr_set.load()) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e == hipSuccess && kern_split) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess && kern_rowmajor) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_rowmajor), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set.store(true);
   }
@@ -383,7 +392,8 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   const int ny = (ksteps + per - 1) / per;
   // fewer than two full waves of workgroups on the partition: CUs idle for part of the launch
   const long long n_wg = (long long)(g.n_full + g.n_pieces) * ny;
-  if (kern_split && tail && tail->slots > 0 && n_wg < 2LL * tail->slots) kern = kern_split;
+  if (!g.w_packed) kern = kern_rowmajor;
+  else if (kern_split && tail && tail->slots > 0 && n_wg < 2LL * tail->slots) kern = kern_split;
   hipLaunchKernelGGL(kern, dim3((g.full_per_xcd + g.piece_per_xcd) * 8, ny), dim3(NT), lds, s, g);
   if (g.n_pieces > 0)
     hipLaunchKernelGGL((gemm_tail_fixup<BM, BN, EPI>), dim3(tiles - g.n_full, BM * BN / 1024), dim3(256), 0, s, g);
@@ -407,17 +417,19 @@ int gemm_tile_m(int cfg) { return cfg == GEMM_256x256 ? 256 : cfg == GEMM_128x12
 int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 ? 1 : 2; }
 
 // C = A * W^T with the chosen tile configuration and epilogue. Requirements (checked):
-// K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1.
+// K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1; W packed (ldw == K) or,
+// for the fp32-store epilogue, row-major.
 // With splits > 1 (EPI_F32 only) partial sums go to C + z * split_stride. With `tail` (splits == 1)
 // the tiles of the last, partly filled wave of workgroups are cut along K (see GemmArgs).
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
-                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail) {
+                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail, bool w_packed) {
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
+  if (w_packed && ldw != K) return hipErrorInvalidValue;          // packed blocks are addressed by K alone
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128 || cfg == GEMM_64x256)) return hipErrorInvalidValue;   // wave tile of one 32-column block
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
-  g.split_stride = split_stride;
+  g.split_stride = split_stride; g.w_packed = w_packed ? 1 : 0;
   switch (epi) {
     case EPI_BF16: return launch_epi<EPI_BF16>(s, cfg, g, splits, tail);
     case EPI_F32: return launch_epi<EPI_F32>(s, cfg, g, splits, tail);

@@ -14,9 +14,21 @@ int gemm_wgs_per_cu(int cfg);                       // resident workgroups per C
 // Tail splitting: `slots` = workgroups the stream's CU partition holds at once, `ws` = fp32 scratch.
 struct GemmTail { int slots; float* ws; size_t ws_bytes; };
 void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int* n_full, int* f);
+// W is either row-major [N, ldw] or (w_packed, the engine's weights; needs ldw == K and N % 64 == 0) in
+// the packed layout below. The row-major form exists for the fp32-store epilogue only.
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
                      void* C, int ldc, int M, int N, int K, int splits, long long split_stride,
-                     const GemmTail* tail = nullptr);
+                     const GemmTail* tail = nullptr, bool w_packed = true);
+
+// Packed GEMM weights: blocks of 64 rows x 64 columns (8 KiB), stored one after the other along K, then
+// along N; inside a block a row is 128 bytes and its 16-byte chunk c sits at slot c ^ ((row >> 1) & 7) --
+// the very image a K tile has in LDS. A wave's direct-to-LDS load of 64 consecutive slots therefore reads
+// 1 KiB of consecutive memory, and a tile's share of a K step is whole 8 KiB blocks instead of one 128-byte
+// piece out of each of its rows (rows are K * 2 bytes apart), which is what HBM-bound decode GEMMs want.
+__host__ __device__ __forceinline__ size_t weight_packed_index(int row, int col, int ld) {
+  const size_t block = (size_t)(row >> 6) * (ld >> 6) + (col >> 6);
+  return block * 4096 + (size_t)(row & 63) * 64 + ((((col & 63) >> 3) ^ ((row >> 1) & 7)) << 3) + (col & 7);
+}
 
 // ---- paged KV layout ----------------------------------------------------------------------
 // One layer's pool is [n_pages][n_kv_heads][ K: page_tokens x d | V^T: d x page_tokens ] bf16.
@@ -51,11 +63,11 @@ struct DecodeItem { int seq; int chunk; int cl; int bt_off; };
 
 // ---- element-wise / small kernels ---------------------------------------------------------
 hipError_t init_weight(hipStream_t s, bf16* dst, int ld, uint64_t seed, uint64_t tensor_id, int rows, int cols,
-                       int row_offset, int interleave_block, int interleave_phase);
+                       int row_offset, int interleave_block, int interleave_phase, int packed);
 hipError_t convert_weight(hipStream_t s, bf16* dst, int ld, const float* src, int rows, int cols,
-                          int row_offset, int interleave_block, int interleave_phase);
+                          int row_offset, int interleave_block, int interleave_phase, int packed);
 hipError_t export_weight(hipStream_t s, float* dst, const bf16* src, int ld, int rows, int cols,
-                         int row_offset, int interleave_block, int interleave_phase);
+                         int row_offset, int interleave_block, int interleave_phase, int packed);
 hipError_t fill_f32(hipStream_t s, float* dst, float v, size_t n);
 hipError_t embed_rows(hipStream_t s, float* X, const bf16* emb, const int* tokens, int n, int h);
 hipError_t rmsnorm_rows(hipStream_t s, bf16* out, const float* X, const float* gain, float eps, int n, int h);

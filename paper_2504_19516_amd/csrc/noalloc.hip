@@ -57,7 +57,7 @@ extern "C" int sts_op_gemm_noalloc(const void* a_dev, const void* w_dev, float* 
   const bf16* W = reinterpret_cast<const bf16*>(w_dev);
   hipError_t e;
   if (split_k > 1) {
-    e = gemm_bf16(st, tile_cfg, EPI_F32, A, k, W, k, ws, n, m, n, k, split_k, (long long)m * n, nullptr);
+    e = gemm_bf16(st, tile_cfg, EPI_F32, A, k, W, k, ws, n, m, n, k, split_k, (long long)m * n, nullptr, false);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
     // the tiled kernel launches only as many splits as the K extent can feed: sum exactly those
     const int ksteps = k / 64, per = (ksteps + split_k - 1) / split_k;
@@ -66,7 +66,7 @@ extern "C" int sts_op_gemm_noalloc(const void* a_dev, const void* w_dev, float* 
   } else {
     // one partial tile per slot, as sts_op_gemm sizes its temporary buffer
     const GemmTail tail{tail_slots, ws, (size_t)tail_slots * tile_floats * sizeof(float)};
-    e = gemm_bf16(st, tile_cfg, EPI_F32, A, k, W, k, c_dev, n, m, n, k, 1, 0, tail_slots > 0 ? &tail : nullptr);
+    e = gemm_bf16(st, tile_cfg, EPI_F32, A, k, W, k, c_dev, n, m, n, k, 1, 0, tail_slots > 0 ? &tail : nullptr, false);
   }
   if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
   return STS_OK;

@@ -54,6 +54,7 @@ int download_bf16(DevBufs& b, float* host, const bf16* dev, size_t n) {
 extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                            int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots) {
   if (!a || !w || !c_inout || m < 1 || n < 1 || k < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;
+  if (k % 64 != 0 || (epilogue == EPI_SWIGLU_BF16 ? 2 * n : n) % gemm_tile_n(tile_cfg) != 0) return STS_EINVAL;    // checked before the weights are packed into 64 x 64 blocks
   if (epilogue < 0 || epilogue > 3 || split_k < 1 || split_k > 8 || tail_slots < 0 || (tail_slots > 0 && split_k != 1)) return STS_EINVAL;
   DevBufs b;
   GemmTail tail{tail_slots, nullptr, 0};
@@ -73,10 +74,10 @@ extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32
     hipError_t e;
     if (epilogue == EPI_SWIGLU_BF16) {
       if (n % 32) return STS_EINVAL;
-      e = convert_weight(nullptr, dW, k, tmp, n, k, 0, 32, 0);
-      if (e == hipSuccess) e = convert_weight(nullptr, dW, k, tmp + (size_t)n * k, n, k, 0, 32, 1);
+      e = convert_weight(nullptr, dW, k, tmp, n, k, 0, 32, 0, 1);
+      if (e == hipSuccess) e = convert_weight(nullptr, dW, k, tmp + (size_t)n * k, n, k, 0, 32, 1, 1);
     } else {
-      e = convert_weight(nullptr, dW, k, tmp, n, k, 0, 0, 0);
+      e = convert_weight(nullptr, dW, k, tmp, n, k, 0, 0, 0, 1);
     }
     if (e != hipSuccess) return STS_EHIP;
   }
