@@ -71,16 +71,24 @@ class Workload:
         self.ptokens = synth.tokens(1, PREFILL_TOKENS, self.desc.vocab)
         self.dtokens = synth.tokens(5, DECODE_BATCH, self.desc.vocab)
         self.steps_done = 0
+        self.next_pseq = None
 
     def step(self, concurrent=True):
-        """One pass of the whole path: the prefill chunk and the decode step."""
+        """One pass of the whole path: the prefill chunk and the decode step. The concurrent step is issued through the
+        launch / finish calls of the serving loop (Section 3.5.2's asynchronous control flow): both phases are queued, the
+        host then does its bookkeeping for the next step (a fresh sequence for the next chunk) while the GPU works, and
+        only then waits for the two phases."""
         e = self.eng
-        pseq = e.seq_create()
         if concurrent:
-            e.step_concurrent([pseq], [self.ptokens], 0, 1, self.dseqs, self.dtokens, want_plogits=False,
-                              want_dlogits=False, want_dnext=False)
+            pseq = self.next_pseq if self.next_pseq is not None else e.seq_create()
+            e.prefill_launch([pseq], [self.ptokens], 0, 1, want_logits=False)
+            e.decode_launch(self.dseqs, self.dtokens, want_logits=False, want_next=False)
+            self.next_pseq = e.seq_create()
+            e.prefill_finish()
+            e.decode_finish(len(self.dseqs), want_logits=False, want_next=False)
             tp, td, _ = e.last_timing()
         else:
+            pseq = e.seq_create()
             e.prefill_append(pseq, self.ptokens, want_logits=False)
             tp = e.last_timing()[0]
             e.decode_step(self.dseqs, self.dtokens, want_logits=False, want_next=False)
@@ -203,6 +211,18 @@ def stored_traffic(prefill_cus, key="gateup_hbm_bytes_per_launch"):
     return rec.get(key)
 
 
+def traffic_source():
+    """Says that the traffic figures are stored ones, and which kernels they were measured on."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2504_19516_amd", "data", "pmc_traffic.json")
+    try:
+        with open(path) as f:
+            commit = json.load(f).get("measured_at_commit", "unknown")
+    except (OSError, ValueError):
+        return None
+    return ("stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this benchmark, scaled by the copy kernel "
+            f"(paper_2504_19516_amd/pmc_traffic.py, profiles/config2_pmc_hbm_traffic.txt), measured at commit {commit}; not re-measured in this run")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,6 +231,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split", type=int, default=0, help="fix the prefill CU count instead of sweeping")
     ap.add_argument("--no-serving", action="store_true", help="skip the live configuration-3 leg")
+    ap.add_argument("--release-streams", action="store_true",
+                    help="destroy the library's CU-masked streams before exit (for runs under rocprofv3, whose exit handler "
+                         "faults on a masked stream left open by an interpreter-loaded HIP runtime)")
     ap.add_argument("--serve-rate", type=float, default=24.0, help="request rate of the configuration-3 leg (req/s)")
     ap.add_argument("--serve-window", type=float, default=15.0, help="arrival window of the configuration-3 leg (s); the run then drains")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -292,9 +315,9 @@ def main():
                                                 "decode_ms": round(ov_td / 1e6, 4)},
                    "slo_per_layer_ms": {"ttft": ttft_budget / 1e6, "tpot": tpot_budget / 1e6},
                    "sweep": sweep},
-        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4,SwiGLU,2 stages>)",
+        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4,SwiGLU,2 stages>: 256x256 tiles, 8 waves, packed weights)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16,
-                     "traffic": stored_traffic(pm), "avg_launch_ms": gu_avg_s * 1e3, "partition_cus": pm,
+                     "traffic": stored_traffic(pm), "traffic_source": traffic_source(), "avg_launch_ms": gu_avg_s * 1e3, "partition_cus": pm,
                      "frac_of_partition_peak": achieved / (PEAK_BF16 * pm / 256),
                      "prefill_layer_tflops": prefill_flop / (tp * 1e-9) / 1e12,
                      "ms_per_step_with_kernel_events": kt_step_s * 1e3},
@@ -348,7 +371,9 @@ def main():
     if os.environ.get("STS_DUMP_MAPS"):          # for symbolising a crash in an exit handler: where every library was mapped
         with open("/proc/self/maps") as f, open(os.environ["STS_DUMP_MAPS"], "w") as g:
             g.write(f.read())
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    if args.release_streams:
+        sts.release_streams()
 
 
 if __name__ == "__main__":

@@ -149,6 +149,7 @@ void meta_take(Phase& ph, T** host, T** dev, size_t count) {
 // come and go reuse the same hardware queues, and no masked queue is ever torn down.
 std::mutex g_stream_mu;
 std::map<std::pair<int, int>, hipStream_t> g_streams;
+std::atomic<int> g_live_ctx{0};            // engines alive in this process (sts_release_streams refuses while any is)
 
 void trace(const char* what) {
   static const bool on = std::getenv("STS_TRACE") != nullptr;
@@ -732,6 +733,7 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
   hipDeviceProp_t prop;
   HIPCK(hipGetDeviceProperties(&prop, 0));
   sts_ctx* c = new sts_ctx();
+  g_live_ctx++;
   c->d = d; c->p = *params; c->n_cu = prop.multiProcessorCount;
   c->qd = d.n_q_heads * d.head_dim; c->kvd = d.n_kv_heads * d.head_dim; c->qkvn = c->qd + 2 * c->kvd;
   c->geo = KvGeom{d.n_kv_heads, d.head_dim, d.page_tokens};
@@ -820,7 +822,20 @@ extern "C" int sts_destroy(sts_ctx* c) {
   if (c->probe_src) (void)hipFree(c->probe_src);
   if (c->probe_dst) (void)hipFree(c->probe_dst);
   delete c;
+  g_live_ctx--;
   trace("destroy: done");
+  return STS_OK;
+}
+
+extern "C" int sts_release_streams(void) {
+  std::lock_guard<std::mutex> g(g_stream_mu);
+  if (g_live_ctx.load() != 0) return STS_ESTATE;
+  for (auto& kv : g_streams) (void)hipStreamSynchronize(kv.second);
+  while (!g_streams.empty()) {
+    hipStream_t s = g_streams.begin()->second;
+    g_streams.erase(g_streams.begin());
+    HIPCK(hipStreamDestroy(s));
+  }
   return STS_OK;
 }
 

@@ -2,8 +2,8 @@
 
 Takes the counter CSVs of two runs of the benchmark with the copy-kernel reference switched on,
 
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir1> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --pmc-probe
-    rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir2> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --pmc-probe
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir1> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --no-serving --pmc-probe
+    rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir2> -o out -- python3 bench.py --split 224 --steps 5 --warmup 1 --no-cpu-baseline --no-serving --pmc-probe
 
 scales each counter by what it reads for the copy kernel (which moves a known number of bytes
 each way) and prints the per-launch figures of the gate/up GEMM and the per-step sum over the
@@ -20,6 +20,7 @@ import csv
 import json
 import os
 import re
+import subprocess
 
 COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
 GATEUP_KERNEL = "gemm_dl_kernel"           # the SwiGLU instantiation is the gate/up GEMM
@@ -49,6 +50,14 @@ def pick(rows, needle, pattern=None):
     return vals
 
 
+def git_head():
+    try:
+        return subprocess.run(["git", "rev-parse", "--short", "HEAD"], cwd=os.path.dirname(os.path.abspath(__file__)), capture_output=True,
+                              text=True, check=True).stdout.strip()
+    except Exception:
+        return "unknown"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("fetch_csv")
@@ -56,6 +65,7 @@ def main():
     ap.add_argument("--prefill-cus", type=int, required=True)
     ap.add_argument("--json", action="store_true")
     ap.add_argument("--list", action="store_true", help="also print every kernel's mean bytes per launch")
+    ap.add_argument("--commit", default=None, help="commit of the kernels that were measured (default: this checkout's HEAD)")
     args = ap.parse_args()
     out = {}
     lines = []
@@ -66,7 +76,7 @@ def main():
         # partition); the reference launches are the largest ones
         copy = [v for v in copy if v >= 0.75 * max(copy)] if copy else copy
         # SwiGLU epilogue = fifth template argument 3 (the sixth is the stage count), demangled or mangled name
-        gate = pick(rows, GATEUP_KERNEL, r"<\d+, \d+, \d+, \d+, 3, \d+>|ELi3ELi\d+EE")
+        gate = pick(rows, GATEUP_KERNEL, r"<256, 256, \d+, \d+, 3, \d+[,>]|ILi256ELi256ELi\d+ELi\d+ELi3ELi\d+E")
         if not copy or not gate:
             raise SystemExit(f"{counter}: kernels not found in {path} (copy launches {len(copy)}, gate/up launches {len(gate)})")
         copy_mean, gate_mean = sum(copy) / len(copy), sum(gate) / len(gate)
@@ -99,7 +109,8 @@ def main():
                    read_bytes=out["FETCH_SIZE"]["gateup_bytes"], written_bytes=out["WRITE_SIZE"]["gateup_bytes"],
                    decode_hbm_bytes_per_step=dec_total, decode_read_bytes=out["FETCH_SIZE"]["decode_bytes"],
                    decode_written_bytes=out["WRITE_SIZE"]["decode_bytes"],
-                   fetch_factor=out["FETCH_SIZE"]["factor_bytes_per_unit"], write_factor=out["WRITE_SIZE"]["factor_bytes_per_unit"])
+                   fetch_factor=out["FETCH_SIZE"]["factor_bytes_per_unit"], write_factor=out["WRITE_SIZE"]["factor_bytes_per_unit"],
+                   measured_at_commit=args.commit or git_head())
         path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data", "pmc_traffic.json")
         with open(path, "w") as f:
             json.dump(rec, f, indent=1)

@@ -84,7 +84,7 @@ class ReplayStats(C.Structure):
 
 
 EXPORTS = [
-    "sts_strerror", "sts_last_hip_error", "sts_init", "sts_destroy", "sts_load_weights", "sts_read_weights",
+    "sts_strerror", "sts_last_hip_error", "sts_init", "sts_destroy", "sts_release_streams", "sts_load_weights", "sts_read_weights",
     "sts_seq_create", "sts_seq_free", "sts_seq_length", "sts_seq_reserve", "sts_pages_free", "sts_seq_set_block_table",
     "sts_seq_get_block_table", "sts_kv_write", "sts_kv_read", "sts_kv_fill_random", "sts_prefill_batch",
     "sts_prefill_append", "sts_prefill_launch", "sts_decode_launch", "sts_phase_done", "sts_prefill_finish",
@@ -361,6 +361,12 @@ def op_attn_decode(q, k, v, ctx, chunk_pages):
     _ck(lib().sts_op_attn_decode(_p(q, C.c_float), _p(k, C.c_float), _p(v, C.c_float), _p(out, C.c_float), n, _p(ctx),
                                  n_q, k.shape[1], d, chunk_pages), "sts_op_attn_decode")
     return out
+
+
+def release_streams():
+    """Destroys the process-wide CU-masked streams (every Engine must be closed). For the end of a
+    program that runs under a profiler."""
+    _ck(lib().sts_release_streams(), "sts_release_streams")
 
 
 def max_pages_per_seq_limit(page_tokens=16):

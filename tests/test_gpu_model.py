@@ -351,6 +351,19 @@ def test_error_paths_leave_state_unchanged(sts, tiny):
     eng.close()
 
 
+def test_masked_streams_are_not_released_under_a_live_engine(sts, tiny):
+    """The process-wide CU-masked streams can only be destroyed once every engine is closed."""
+    desc, _ = tiny
+    eng = new_engine(sts, desc)
+    with pytest.raises(sts.StsError) as e:
+        sts.release_streams()
+    assert e.value.code == sts.ESTATE
+    s = eng.seq_create()
+    eng.prefill_append(s, synth.tokens(3, 40, desc.vocab), want_logits=False)      # the streams still work
+    assert eng.seq_length(s) == 40
+    eng.close()
+
+
 def test_failed_concurrent_step_commits_nothing(sts, tiny):
     """A concurrent step whose decode side cannot get its page (or is invalid) fails before anything
     is queued: the prefill side has not run, no length moved, no page was taken, and the same
