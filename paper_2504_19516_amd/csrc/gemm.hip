@@ -4,14 +4,17 @@
 // holds 8 consecutive k of one A row (or one W row). A workgroup owns a BM x BN tile and each of
 // its waves accumulates a (BM/WGM) x (BN/WGN) sub-tile in 32x32 MFMA blocks.
 //
-// One main loop, gemm_dl_kernel, serves every shape the engine launches: K tiles of 64 go
-// global -> LDS directly (no staging registers, no LDS store instructions) into 128-byte rows whose
-// 16-byte chunks are XOR-swizzled so that the 16-byte operand reads are bank-conflict free; two or
-// three LDS stages; operand reads of the next 16-wide step are slotted between the MFMAs of the
-// current one. Instantiations: 256x256 tiles with 8 waves and 128x128 tiles with 4 waves (two
-// workgroups per CU) for prefill, 64x128 (4 waves, two per CU) and 64x256 (8 waves) with split-K
-// for decode batches. Epilogues: bf16 store, fp32 store (split-K partial sums), fp32 residual add,
-// SwiGLU on interleaved gate/up rows.
+// Two main loops. gemm_dl_kernel: K tiles of 64 of both operands go global -> LDS directly (no
+// staging registers, no LDS store instructions): activations into 128-byte rows whose 16-byte chunks
+// are XOR-swizzled so that the 16-byte operand reads are bank-conflict free, packed weights as the
+// operand-order blocks they are in memory; two or three LDS stages;
+// operand reads of the next 16-wide step are slotted between the MFMAs of the current one. It runs
+// the 128x128 tiles with 4 waves (two workgroups per CU) for prefill, the 64x128 (4 waves, two per
+// CU) and 64x256 (8 waves) tiles with split-K for decode batches, and row-major W of callers that
+// bring their own weights. gemm_wreg_kernel: the 256x256 prefill tile (8 waves); only the activation
+// tile goes through LDS, the W operands go from the packed weight layout straight into registers.
+// Epilogues: bf16 store, fp32 store (split-K partial sums), fp32 residual add, SwiGLU on interleaved
+// gate/up rows.
 //
 // Wave quantisation (paper Section 2.2.1) is met in the launch: the tiles of a partly filled last
 // wave of workgroups are cut along K into pieces that fill the partition (gemm_tail_plan), the
@@ -21,6 +24,7 @@
 // Lane layout of the 32x32 accumulator block (register r of lane l):
 //   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
 #include <atomic>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -137,7 +141,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, f32x16 (&acc)[BM /
 // already in registers); the loads of the tile after next go out right behind the barrier, a
 // whole iteration ahead of their use; step 3 runs while the first operands of the next tile
 // are read. The LDS arena starts 1 KB above address 0.
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS, bool SPLIT = false, bool WPACK = true>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS, bool WPACK = true>
 __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   constexpr int BK = 64, NT = WGM * WGN * 64;
   static_assert(NS >= 2 && (NS - 2) * (BM + BN) * 8 / NT < 64, "stages: at least two, outstanding loads within vmcnt's range");
@@ -166,9 +170,9 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   // into a scalar once): queuing a load takes no vector ALU work and sends 4 address bytes per lane.
   const int swave = __builtin_amdgcn_readfirstlane(wave);
   const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.A + (size_t)m0 * g.lda);
-  // W: row-major, or (WPACK) 64 x 64 blocks that already hold the swizzled LDS image -- slot q of the tile is
-  // then simply the q-th 16-byte piece of the tile's blocks for this K step
-  const unsigned char* b_base = WPACK ? reinterpret_cast<const unsigned char*>(g.W) + (size_t)(n0 >> 6) * (g.K >> 6) * 8192
+  // W: row-major (its tile is laid out in LDS like the A tile), or (WPACK) 32 x 64 blocks of 4 KiB in matrix-core operand
+  // order (weight_packed_index), copied to LDS as they are.
+  const unsigned char* b_base = WPACK ? reinterpret_cast<const unsigned char*>(g.W) + (size_t)(n0 >> 5) * (g.K >> 6) * 4096
                                       : reinterpret_cast<const unsigned char*>(g.W + (size_t)n0 * g.ldw);
   unsigned a_off[A_CH], b_off[B_CH];
 #pragma unroll
@@ -179,7 +183,9 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
 #pragma unroll
   for (int j = 0; j < B_CH; j++) {
     const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
-    b_off[j] = WPACK ? (unsigned)(q >> 9) * (unsigned)(g.K >> 6) * 8192u + (unsigned)(q & 511) * 16u
+    // packed: slot q is the q-th 16-byte piece of the tile's 4 KiB blocks for this K step, so a wave's load reads 1 KiB of
+    // consecutive memory
+    b_off[j] = WPACK ? (unsigned)(q >> 8) * (unsigned)(g.K >> 6) * 4096u + (unsigned)(q & 255) * 16u
                      : (unsigned)row * (unsigned)g.ldw * 2u + ch * 16;
   }
   auto issue_a = [&](int stage, int k) {
@@ -190,7 +196,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   };
   auto issue_b = [&](int stage, int k) {
     unsigned char* sb = arena + stage * STAGE + swave * 1024 + BM * ROWB;
-    const unsigned char* bk = b_base + (WPACK ? (size_t)(k >> 6) * 8192 : (size_t)k * 2);
+    const unsigned char* bk = b_base + (WPACK ? (size_t)(k >> 6) * 4096 : (size_t)k * 2);
 #pragma unroll
     for (int j = 0; j < B_CH; j++) lds_dma16(bk, b_off[j], sb + j * NT * 16);
   };
@@ -205,10 +211,16 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
   // byte offset of this lane's operand chunk inside its row, for each of the four K steps
-  int koff[4];
+  // and of its W operand: the same for a row-major W tile; a packed W tile is in LDS what it is in memory, 1 KiB per
+  // 32-row block and step with lane l's operand at byte 16 l
+  int koff[4], kboff[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; kk++) koff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 7)) * 16;
-  const int a_row = (wm * WTM + l32) * ROWB, b_row = BM * ROWB + (wn * WTN + l32) * ROWB;
+  for (int kk = 0; kk < 4; kk++) {
+    koff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 7)) * 16;
+    kboff[kk] = WPACK ? kk * 1024 : koff[kk];
+  }
+  const int a_row = (wm * WTM + l32) * ROWB;
+  const int b_row = BM * ROWB + (WPACK ? wn * WTN * ROWB + lane * 16 : (wn * WTN + l32) * ROWB);
 
   constexpr int MPR = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;       // MFMAs per LDS read
   constexpr int REST = TM * TN > MPR * (TM + TN) ? TM * TN - MPR * (TM + TN) : 0;
@@ -226,7 +238,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(arena + a_row + i * 32 * ROWB + koff[0]);
 #pragma unroll
-  for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(arena + b_row + j * 32 * ROWB + koff[0]);
+  for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(arena + b_row + j * 32 * ROWB + kboff[0]);
 
   int cur = 0;                                               // stage of tile t
   for (int t = 0; t < nk; t++) {
@@ -241,7 +253,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
 #pragma unroll
       for (int i = 0; i < TM; i++) af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * ROWB + koff[kk + 1]);
 #pragma unroll
-      for (int j = 0; j < TN; j++) bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * ROWB + koff[kk + 1]);
+      for (int j = 0; j < TN; j++) bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bc + j * 32 * ROWB + kboff[kk + 1]);
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
@@ -261,16 +273,14 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
     // tile t+1 must have landed; the NS-2 tiles issued after it may still be in flight
     if (t + NS - 1 < nk) wait_vmem<(NS - 2) * LOADS>(); else wait_vmem<0>();
     __syncthreads();
-    // The tile after the ones in flight goes into the stage just retired: in one burst right here, or
-    // (SPLIT) the A half here and the W half behind the last step's MFMAs. The burst is the better
-    // form when every CU of the partition is busy, the split one when the launch leaves CUs idle.
-    if (t + NS < nk) { if constexpr (SPLIT) issue_a(cur, kbeg + (t + NS) * BK); else issue(cur, kbeg + (t + NS) * BK); }
+    // the tile after the ones in flight goes into the stage just retired
+    if (t + NS < nk) issue(cur, kbeg + (t + NS) * BK);
     __builtin_amdgcn_sched_barrier(0);
     if (t + 1 < nk) {
 #pragma unroll
       for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(An + i * 32 * ROWB + koff[0]);
 #pragma unroll
-      for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(Bn + j * 32 * ROWB + koff[0]);
+      for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(Bn + j * 32 * ROWB + kboff[0]);
     }
 #pragma unroll
     for (int i = 0; i < TM; i++)
@@ -284,12 +294,177 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
     }
     if (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (SPLIT) {
-      if (t + NS < nk) issue_b(cur, kbeg + (t + NS) * BK);
-      __builtin_amdgcn_sched_barrier(0);
-    }
     cur = nxt;
   }
+  store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
+}
+
+// ---- main loop of the 256 x 256 prefill tile: W operands straight from global memory -------------
+// With both operands staged through LDS the 256 x 256 tile moves 256 KB through LDS per 64-wide K tile
+// (64 KB written by the tile loads, 192 KB read as operands by the 8 waves), which at 128 bytes per cycle
+// is as long as the tile's matrix-core work: the loop ran at the LDS's pace, not the MFMAs'. Here only the
+// activation tile goes through LDS (three stages of 32 KB, loaded as above). Each wave reads its W
+// operands -- 64 columns, so two 32-row blocks of the packed layout -- directly into registers, one
+// 16-byte load per lane and 16-wide step from 1 KiB of consecutive memory. One register set serves: the
+// operands of step kk of the next K tile are requested right after step kk of this one has used them, a
+// whole iteration before they are needed. The two waves that share a column block load it twice; those
+// bytes come from L2.
+//
+// A wave's vector-memory operations complete in order, and in iteration t it queues: the A loads of tile
+// t + 2 (4), then after each step kk the two W loads of (tile t + 1, step kk). When step kk of tile t waits
+// for its operands, the operations queued after them are the W loads of the later steps of tile t, the A
+// loads of tile t + 2 and the W loads of the earlier steps of tile t + 1: 10 in the steady state, fewer in
+// the last two iterations. The A tile of iteration t + 1 was queued before the operands step 2 waits for,
+// so it has landed when the wave reaches the barrier. The W loads are written in assembly, so the compiler
+// does not know when their registers are valid; the wait names them as in/out operands, which keeps every
+// use behind it.
+__device__ __forceinline__ void load_w16(bf16x8& dst, const unsigned char* base, unsigned lane_off, int step) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  switch (step) {   // the step's 1 KiB piece is addressed by the instruction's immediate offset
+    case 0: asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+    case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+    case 2: asm volatile("global_load_dwordx4 %0, %1, %2 offset:2048" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+    default: asm volatile("global_load_dwordx4 %0, %1, %2 offset:3072" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+  }
+#endif
+}
+// Wait until at most N vector-memory operations of this wave are outstanding; a and b are valid afterwards.
+template <int N>
+__device__ __forceinline__ void wait_vmem_for(bf16x8& a, bf16x8& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+#endif
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(512) gemm_wreg_kernel(GemmArgs g) {
+  constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, BK = 64, NT = 512, NS = 3;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+  constexpr int ROWB = BK * 2, A_CH = BM * 8 / NT, STAGE = BM * ROWB;
+  static_assert(TN == 2 && A_CH == 4, "the waits below count 4 A loads per tile and 2 W loads per step");
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* arena = smem + GEMM_DL_LDS_BASE;
+
+  int v, kbeg, kend, piece;
+  if (!block_work<BK>(g, &v, &kbeg, &kend, &piece)) return;
+  int tm, tn;
+  tile_coords(g, v, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int swave = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = swave / WGN, wn = swave % WGN;
+
+  const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.A + (size_t)m0 * g.lda);
+  unsigned a_off[A_CH];
+#pragma unroll
+  for (int j = 0; j < A_CH; j++) {
+    const int q = j * NT + tid, row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
+    a_off[j] = (unsigned)(min(m0 + row, g.M - 1) - m0) * (unsigned)g.lda * 2u + ch * 16;
+  }
+  auto issue_a = [&](int stage, int k) {
+    unsigned char* sa = arena + stage * STAGE + swave * 1024;
+    const unsigned char* ak = a_base + (size_t)k * 2;
+#pragma unroll
+    for (int j = 0; j < A_CH; j++) lds_dma16(ak, a_off[j], sa + j * NT * 16);
+  };
+  // this wave's two 32-row blocks of W: 4 KiB per K tile each, the blocks of one row K / 64 * 4 KiB apart
+  const size_t wrow = (size_t)(g.K >> 6) * 4096;
+  const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.W) + (size_t)((n0 >> 5) + wn * TN) * wrow;
+  const unsigned w_lane = (unsigned)lane * 16u;
+  bf16x8 w[TN][4];
+#pragma unroll
+  for (int j = 0; j < TN; j++)
+#pragma unroll
+    for (int kk = 0; kk < 4; kk++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) w[j][kk][e] = 0;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  int koff[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; kk++) koff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 7)) * 16;
+  const int a_row = (wm * WTM + l32) * ROWB;
+
+  const int nk = (kend - kbeg) / BK;
+  // Every iteration queues the same operations, also the last ones, whose loads have no tile left to fetch and
+  // re-read the last K tile into a stage (or registers) nobody uses any more: the waits then count alike throughout.
+  auto tile_k = [&](int t) { return kbeg + min(t, nk - 1) * BK; };
+  // prologue: A(0), A(1), then W(0) step by step; A(0) has landed once at most A(1) and W(0) are outstanding
+  issue_a(0, tile_k(0));
+  issue_a(1, tile_k(1));
+  {
+    const unsigned char* wk = w_base + (size_t)(tile_k(0) >> 6) * 4096;
+#pragma unroll
+    for (int kk = 0; kk < 4; kk++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) load_w16(w[j][kk], wk + j * wrow, w_lane, kk);
+  }
+  wait_vmem<A_CH + 4 * TN>();
+  __syncthreads();
+  bf16x8 af[2][TM];
+#pragma unroll
+  for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(arena + a_row + i * 32 * ROWB + koff[0]);
+
+  int cur = 0;
+  for (int t = 0; t < nk; t++) {
+    const int nxt = cur + 1 == NS ? 0 : cur + 1;
+    const int nx2 = nxt + 1 == NS ? 0 : nxt + 1;
+    const unsigned char* Ac = arena + cur * STAGE + a_row;
+    const unsigned char* An = arena + nxt * STAGE + a_row;
+    const unsigned char* wk = w_base + (size_t)(tile_k(t + 1) >> 6) * 4096;       // W of tile t + 1
+    __builtin_amdgcn_sched_barrier(0);
+    // tile t + 2 goes into the stage that tile t - 1 left at the last barrier
+    issue_a(nx2, tile_k(t + 2));
+    auto step = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      __builtin_amdgcn_sched_barrier(0);
+      // queued after these operands: the W loads of the later steps of this tile (6 - 2 kk), the A loads of tile
+      // t + 2 (4), the W loads of the earlier steps of the next tile (2 kk)
+      wait_vmem_for<2 * TN + A_CH + 2>(w[0][kk], w[1][kk]);
+      if (kk == 3) {
+        // every wave's A loads of tile t + 1 landed before its step-2 operands did: publish the tile, retire this one
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(An + i * 32 * ROWB + koff[0]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; i++) af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * ROWB + koff[kk + 1]);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], w[j][kk], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int x = 0; x < TM; x++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, TN, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < TN; j++) load_w16(w[j][kk], wk + j * wrow, w_lane, kk);
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+    cur = nxt;
+  }
+  // the surplus loads of the last iterations must not land in registers the epilogue reuses
+  wait_vmem_for<0>(w[0][0], w[1][0]);
+  wait_vmem_for<0>(w[0][1], w[1][1]);
+  wait_vmem_for<0>(w[0][2], w[1][2]);
+  wait_vmem_for<0>(w[0][3], w[1][3]);
   store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
 
@@ -356,18 +531,19 @@ void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int*
 template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
 static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTail* tail) {
   constexpr int NT = WGM * WGN * 64, BK = 64;
-  constexpr size_t lds = GEMM_DL_LDS_BASE + NS * (size_t)(BM + BN) * BK * sizeof(bf16);
+  constexpr size_t lds_dl = GEMM_DL_LDS_BASE + NS * (size_t)(BM + BN) * BK * sizeof(bf16);
+  constexpr size_t lds_wreg = GEMM_DL_LDS_BASE + 3 * (size_t)BM * BK * sizeof(bf16);    // gemm_wreg_kernel: three stages of the A tile
+  constexpr bool WREG = BM == 256 && BN == 256;     // packed W: the large prefill tile takes its W operands straight from global memory
   void (*kern)(GemmArgs) = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
-  void (*kern_split)(GemmArgs) = nullptr;          // the large prefill tile also exists with its tile loads issued in two halves
   void (*kern_rowmajor)(GemmArgs) = nullptr;       // row-major W: the fp32-store epilogue only (callers that bring their own weights)
-  if constexpr (BM == 256 && BN == 256) kern_split = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, true>;
-  if constexpr (EPI == EPI_F32) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false, false>;
+  if constexpr (WREG) kern = gemm_wreg_kernel<EPI>;
+  if constexpr (EPI == EPI_F32) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false>;
   if (!g.w_packed && !kern_rowmajor) return hipErrorInvalidValue;
+  const size_t lds = !g.w_packed ? lds_dl : WREG ? lds_wreg : lds_dl;
   static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
   if (!attr_set.load()) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e == hipSuccess && kern_split) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e == hipSuccess && kern_rowmajor) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_rowmajor), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(WREG ? lds_wreg : lds_dl));
+    if (e == hipSuccess && kern_rowmajor) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_rowmajor), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dl);
     if (e != hipSuccess) return e;
     attr_set.store(true);
   }
@@ -390,10 +566,7 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   const int per = (ksteps + splits - 1) / splits;
   g.k_per_split = per * BK;
   const int ny = (ksteps + per - 1) / per;
-  // fewer than two full waves of workgroups on the partition: CUs idle for part of the launch
-  const long long n_wg = (long long)(g.n_full + g.n_pieces) * ny;
   if (!g.w_packed) kern = kern_rowmajor;
-  else if (kern_split && tail && tail->slots > 0 && n_wg < 2LL * tail->slots) kern = kern_split;
   hipLaunchKernelGGL(kern, dim3((g.full_per_xcd + g.piece_per_xcd) * 8, ny), dim3(NT), lds, s, g);
   if (g.n_pieces > 0)
     hipLaunchKernelGGL((gemm_tail_fixup<BM, BN, EPI>), dim3(tiles - g.n_full, BM * BN / 1024), dim3(256), 0, s, g);
@@ -426,7 +599,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (w_packed && ldw != K) return hipErrorInvalidValue;          // packed blocks are addressed by K alone
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
-  if (epi == EPI_SWIGLU_BF16 && (cfg == GEMM_64x128 || cfg == GEMM_64x256)) return hipErrorInvalidValue;   // wave tile of one 32-column block
+  if (epi == EPI_SWIGLU_BF16 && cfg != GEMM_128x128 && cfg != GEMM_256x256) return hipErrorInvalidValue;   // wave tiles of whole gate/up block pairs only
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.split_stride = split_stride; g.w_packed = w_packed ? 1 : 0;

@@ -14,20 +14,24 @@ int gemm_wgs_per_cu(int cfg);                       // resident workgroups per C
 // Tail splitting: `slots` = workgroups the stream's CU partition holds at once, `ws` = fp32 scratch.
 struct GemmTail { int slots; float* ws; size_t ws_bytes; };
 void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int* n_full, int* f);
-// W is either row-major [N, ldw] or (w_packed, the engine's weights; needs ldw == K and N % 64 == 0) in
+// W is either row-major [N, ldw] or (w_packed, the engine's weights; needs ldw == K) in
 // the packed layout below. The row-major form exists for the fp32-store epilogue only.
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
                      void* C, int ldc, int M, int N, int K, int splits, long long split_stride,
                      const GemmTail* tail = nullptr, bool w_packed = true);
 
-// Packed GEMM weights: blocks of 64 rows x 64 columns (8 KiB), stored one after the other along K, then
-// along N; inside a block a row is 128 bytes and its 16-byte chunk c sits at slot c ^ ((row >> 1) & 7) --
-// the very image a K tile has in LDS. A wave's direct-to-LDS load of 64 consecutive slots therefore reads
-// 1 KiB of consecutive memory, and a tile's share of a K step is whole 8 KiB blocks instead of one 128-byte
-// piece out of each of its rows (rows are K * 2 bytes apart), which is what HBM-bound decode GEMMs want.
+// Packed GEMM weights: blocks of 32 rows x 64 columns (4 KiB), stored one after the other along K, then
+// along N. A block is laid out the way the matrix cores take a W operand: four pieces of 1 KiB, one per
+// 16-column step, each holding for lane l = 32 * h + n of a wave the 8 consecutive elements
+// W[row n][16 * step + 8 * h .. + 8). A wave therefore loads an operand straight into registers with one
+// 16-byte load per lane from 1 KiB of consecutive memory (the large prefill tile does that, and keeps W
+// out of LDS), and the direct-to-LDS loads of the other tiles gather the same bytes in whole 128-byte
+// pieces (8 rows of one half-step). A tile's share of a K step is whole 4 KiB blocks instead of one
+// 128-byte piece out of each of its rows (rows are K * 2 bytes apart), which is what HBM-bound decode
+// GEMMs want. N must be a multiple of 32 and K of 64.
 __host__ __device__ __forceinline__ size_t weight_packed_index(int row, int col, int ld) {
-  const size_t block = (size_t)(row >> 6) * (ld >> 6) + (col >> 6);
-  return block * 4096 + (size_t)(row & 63) * 64 + ((((col & 63) >> 3) ^ ((row >> 1) & 7)) << 3) + (col & 7);
+  const size_t block = (size_t)(row >> 5) * (ld >> 6) + (col >> 6);
+  return block * 2048 + (size_t)((col & 63) >> 4) * 512 + (size_t)((((col >> 3) & 1) << 5) + (row & 31)) * 8 + (col & 7);
 }
 
 // ---- paged KV layout ----------------------------------------------------------------------

@@ -54,7 +54,7 @@ int download_bf16(DevBufs& b, float* host, const bf16* dev, size_t n) {
 extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                            int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots) {
   if (!a || !w || !c_inout || m < 1 || n < 1 || k < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;
-  if (k % 64 != 0 || (epilogue == EPI_SWIGLU_BF16 ? 2 * n : n) % gemm_tile_n(tile_cfg) != 0) return STS_EINVAL;    // checked before the weights are packed into 64 x 64 blocks
+  if (k % 64 != 0 || (epilogue == EPI_SWIGLU_BF16 ? 2 * n : n) % gemm_tile_n(tile_cfg) != 0) return STS_EINVAL;    // checked before the weights are packed into 32 x 64 blocks
   if (epilogue < 0 || epilogue > 3 || split_k < 1 || split_k > 8 || tail_slots < 0 || (tail_slots > 0 && split_k != 1)) return STS_EINVAL;
   DevBufs b;
   GemmTail tail{tail_slots, nullptr, 0};
