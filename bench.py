@@ -100,13 +100,10 @@ class Workload:
         return tp, td
 
     def reset_contexts(self):
-        for i, (s, c) in enumerate(zip(self.dseqs, self.ctx)):
-            bt = self.eng.seq_get_block_table(s)
-            self.eng.seq_free(s)
-            s2 = self.eng.seq_create()
-            self.eng.seq_set_block_table(s2, bt)
-            self.eng.kv_fill_random(s2, int(c), 1000 + i)
-            self.dseqs[i] = s2
+        """Back to the drawn context lengths: the tokens the decode steps appended are dropped (a rollback of the
+        sequence length; the cache contents before them are untouched)."""
+        for s, c in zip(self.dseqs, self.ctx):
+            self.eng.seq_truncate(s, int(c))
 
     def timed(self, n, concurrent=True):
         t0 = time.perf_counter()

@@ -94,6 +94,9 @@ int sts_seq_create(sts_ctx* ctx, int32_t* seq_out);
 int sts_seq_free(sts_ctx* ctx, int32_t seq);                       /* pages return to the pool; STS_ESTATE while the sequence is part of
                                                                       a layer-sliced prefill batch or of a launch whose finish is due */
 int sts_seq_length(sts_ctx* ctx, int32_t seq, int32_t* len_out);
+/* Drop the tokens from position new_len on (a rollback: the cache entries before it stay as they are, the pages stay with
+ * the sequence). STS_EINVAL if new_len exceeds the length, STS_ESTATE as for sts_seq_free. */
+int sts_seq_truncate(sts_ctx* ctx, int32_t seq, int32_t new_len);
 int sts_seq_reserve(sts_ctx* ctx, int32_t seq, int32_t n_tokens);  /* make pages cover n_tokens; STS_ENOMEM leaves state unchanged */
 int sts_pages_free(sts_ctx* ctx, int32_t* n_out);
 /* Test hooks. set_block_table: give an EMPTY sequence these pool pages, in this order (they are

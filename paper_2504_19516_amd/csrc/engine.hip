@@ -898,6 +898,19 @@ extern "C" int sts_seq_length(sts_ctx* c, int32_t seq, int32_t* len_out) {
   *len_out = c->seqs[seq].len;
   return STS_OK;
 }
+extern "C" int sts_seq_truncate(sts_ctx* c, int32_t seq, int32_t new_len) {
+  if (!c || !valid_seq(c, seq) || new_len < 0) return STS_EINVAL;
+  {
+    std::lock_guard<std::mutex> g(c->state_mu);      // not under kernels that append to it or read its length
+    if (c->pf_active) for (int s : c->pf_seqs) if (s == seq) return STS_ESTATE;
+    for (int s : c->pend_pseqs) if (s == seq) return STS_ESTATE;
+    for (int s : c->pend_dseqs) if (s == seq) return STS_ESTATE;
+  }
+  std::lock_guard<std::mutex> g(c->alloc_mu);
+  if (new_len > c->seqs[seq].len) return STS_EINVAL;
+  c->seqs[seq].len = new_len;
+  return STS_OK;
+}
 extern "C" int sts_seq_reserve(sts_ctx* c, int32_t seq, int32_t n_tokens) {
   if (!c || !valid_seq(c, seq) || n_tokens < 0) return STS_EINVAL;
   return reserve_pages(c, {{seq, n_tokens}});

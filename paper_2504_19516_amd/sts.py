@@ -85,7 +85,7 @@ class ReplayStats(C.Structure):
 
 EXPORTS = [
     "sts_strerror", "sts_last_hip_error", "sts_init", "sts_destroy", "sts_release_streams", "sts_load_weights", "sts_read_weights",
-    "sts_seq_create", "sts_seq_free", "sts_seq_length", "sts_seq_reserve", "sts_pages_free", "sts_seq_set_block_table",
+    "sts_seq_create", "sts_seq_free", "sts_seq_length", "sts_seq_truncate", "sts_seq_reserve", "sts_pages_free", "sts_seq_set_block_table",
     "sts_seq_get_block_table", "sts_kv_write", "sts_kv_read", "sts_kv_fill_random", "sts_prefill_batch",
     "sts_prefill_append", "sts_prefill_launch", "sts_decode_launch", "sts_phase_done", "sts_prefill_finish",
     "sts_decode_finish", "sts_prefill_abort", "sts_decode_step", "sts_step_concurrent", "sts_last_timing", "sts_read_hidden",
@@ -184,6 +184,9 @@ class Engine:
         n = C.c_int32()
         _ck(lib().sts_seq_length(self._ctx, seq, C.byref(n)), "sts_seq_length")
         return n.value
+
+    def seq_truncate(self, seq, new_len):
+        _ck(lib().sts_seq_truncate(self._ctx, seq, new_len), "sts_seq_truncate")
 
     def seq_reserve(self, seq, n_tokens):
         _ck(lib().sts_seq_reserve(self._ctx, seq, n_tokens), "sts_seq_reserve")

@@ -242,6 +242,32 @@ def test_decode_equals_row_of_full_recompute(sts, tiny, eng):
     free_all(eng, [a, b])
 
 
+def test_truncated_sequence_decodes_as_it_did_at_that_length(sts, tiny, eng):
+    """Rolling a sequence back to an earlier length: the next decode step sees exactly the cache of that length."""
+    desc, _ = tiny
+    toks = synth.tokens(33, 80, desc.vocab)
+    a = eng.seq_create()
+    eng.prefill_append(a, toks[:70], want_logits=False)
+    first, _ = eng.decode_step([a], [toks[70]])
+    for i in range(71, 76):
+        eng.decode_step([a], [toks[i]], want_logits=False)
+    assert eng.seq_length(a) == 76
+    pages_before = eng.seq_get_block_table(a)
+    free_before = eng.pages_free()
+    with pytest.raises(sts.StsError) as e:
+        eng.seq_truncate(a, 77)
+    assert e.value.code == sts.EINVAL and eng.seq_length(a) == 76
+    eng.seq_truncate(a, 70)
+    assert eng.seq_length(a) == 70 and eng.pages_free() == free_before
+    assert list(eng.seq_get_block_table(a)) == list(pages_before)
+    again, _ = eng.decode_step([a], [toks[70]])
+    assert np.array_equal(again, first)
+    b = eng.seq_create()                                               # and as a sequence that never went further does
+    full = eng.prefill_append(b, toks[:71])
+    assert rel(again[0], full) <= TOL
+    free_all(eng, [a, b])
+
+
 def test_page_order_independence(sts, tiny, eng):
     desc, _ = tiny
     toks = synth.tokens(32, 100, desc.vocab)
