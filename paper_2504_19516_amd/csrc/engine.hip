@@ -273,7 +273,6 @@ int pick_prefill_cfg(const sts_ctx* ctx, int m, int n, int k, int cus, size_t ta
 // A prefill GEMM on the phase's partition: tile choice, and the last wave of tiles cut along K.
 hipError_t prefill_gemm(const sts_ctx* ctx, Phase& ph, int epi, const bf16* A, int lda, const bf16* W, int ldw, void* C, int ldc, int m, int n, int k) {
   int cfg = pick_prefill_cfg(ctx, m, n, k, ph.cus, ph.tail_ws_bytes);
-  if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_64x128) cfg = GEMM_128x128;    // the wave tile must hold gate/up block pairs
   const GemmTail tail{gemm_wgs_per_cu(cfg) * ph.cus, ph.tail_ws, ph.tail_ws_bytes};
   return gemm_bf16(ph.stream, cfg, epi, A, lda, W, ldw, C, ldc, m, n, k, 1, 0, &tail);
 }
@@ -609,8 +608,17 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_ditems, n_items, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
     STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
-    STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
-    KL(ph, STS_K_SWIGLU, reduce_swiglu(st, ph.H, ph.part, sp, ss, n, d.mlp));
+    {
+      // gate/up: when the tiles fill the partition without a split along K, SwiGLU is the GEMM's epilogue
+      int gu_cfg, gu_splits;
+      pick_decode_gemm(c, n, 2 * d.mlp, h, ph.cus, true, &gu_cfg, &gu_splits);
+      if (gu_splits == 1 && gu_cfg == GEMM_64x128) {
+        KL(ph, STS_K_GATEUP, gemm_bf16(st, gu_cfg, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, n, 2 * d.mlp, h, 1, 0));
+      } else {
+        STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
+        KL(ph, STS_K_SWIGLU, reduce_swiglu(st, ph.H, ph.part, sp, ss, n, d.mlp));
+      }
+    }
     STSCK(skinny(STS_K_DOWN, ph.H, d.mlp, w.wd, h, d.mlp, &sp, &ss));
     const float* next_gain = (l + 1 < d.n_layers) ? c->layers[l + 1].g1 : c->gf;
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, next_gain, d.rms_eps, n, h));
@@ -1192,7 +1200,7 @@ extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t
   if (!c || !ns_out || iters < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;
   const sts_model_desc& d = c->d;
   if (m < 1 || m > c->p.max_prefill_tokens || n < 64 || n > 2 * d.mlp || n % 64 || n % gemm_tile_n(tile_cfg)) return STS_EINVAL;
-  if (tile_cfg == GEMM_64x128 || tile_cfg == GEMM_64x256) return STS_EINVAL;        // the SwiGLU epilogue needs gate/up block pairs in a wave tile
+  if (tile_cfg == GEMM_64x256) return STS_EINVAL;        // the SwiGLU epilogue needs gate/up block pairs in a wave tile
   if (c->pend_prefill) return STS_ESTATE;
   hipStream_t st;
   STSCK(get_stream(c, 0, cus, &st));

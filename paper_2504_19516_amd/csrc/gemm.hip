@@ -599,7 +599,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (w_packed && ldw != K) return hipErrorInvalidValue;          // packed blocks are addressed by K alone
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
-  if (epi == EPI_SWIGLU_BF16 && cfg != GEMM_128x128 && cfg != GEMM_256x256) return hipErrorInvalidValue;   // wave tiles of whole gate/up block pairs only
+  if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_64x256) return hipErrorInvalidValue;   // its wave tile is one 32-column block, not a gate/up pair
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.split_stride = split_stride; g.w_packed = w_packed ? 1 : 0;
@@ -611,6 +611,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
         case GEMM_256x256: return launch_cfg<256, 256, 2, 4, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
         case GEMM_128x128: return launch_cfg<128, 128, 2, 2, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
+        case GEMM_64x128: return launch_cfg<64, 128, 2, 2, EPI_SWIGLU_BF16, 3>(s, g, 1, tail);    // wave tiles of 32 x 64: one gate/up pair
         default: return hipErrorInvalidValue;
       }
     default: return hipErrorInvalidValue;
