@@ -10,7 +10,10 @@ each way) and prints the per-launch figures of the gate/up GEMM and the per-step
 decode phase's kernels. With --json it also writes the record bench.py reports as
 roofline.traffic and roofline_decode.traffic.
 
-    python -m paper_2504_19516_amd.pmc_traffic <fetch.csv> <write.csv> --prefill-cus 224 [--json]
+    python -m paper_2504_19516_amd.pmc_traffic <fetch.csv> <write.csv> --prefill-cus 224 [--json] [--l2 <l2.csv>]
+
+--l2 takes the CSV of a third pass with the L2 request counters (--pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum, same command) and
+prints requests, hits and misses per launch of every kernel.
 """
 from __future__ import annotations
 
@@ -23,7 +26,7 @@ import re
 import subprocess
 
 COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
-GATEUP_KERNEL = "gemm_dl_kernel"           # the SwiGLU instantiation is the gate/up GEMM
+GATEUP_KERNEL = "gemm_wreg_kernel"         # the 256 x 256 prefill tile; its SwiGLU instantiation is the gate/up GEMM
 COPY_KERNEL = "copy_kernel"
 # kernels that only the decode phase launches; one attn_decode_mfma launch = one decode layer-step.
 # (Its embedding and first RMSNorm launches share kernels with the prefill phase and are left out:
@@ -65,6 +68,7 @@ def main():
     ap.add_argument("--prefill-cus", type=int, required=True)
     ap.add_argument("--json", action="store_true")
     ap.add_argument("--list", action="store_true", help="also print every kernel's mean bytes per launch")
+    ap.add_argument("--l2", default=None, help="counter CSV of a TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum pass")
     ap.add_argument("--commit", default=None, help="commit of the kernels that were measured (default: this checkout's HEAD)")
     args = ap.parse_args()
     out = {}
@@ -75,8 +79,8 @@ def main():
         # the benchmark also runs the copy kernel on smaller buffers (its bandwidth probes of the decode
         # partition); the reference launches are the largest ones
         copy = [v for v in copy if v >= 0.75 * max(copy)] if copy else copy
-        # SwiGLU epilogue = fifth template argument 3 (the sixth is the stage count), demangled or mangled name
-        gate = pick(rows, GATEUP_KERNEL, r"<256, 256, \d+, \d+, 3, \d+[,>]|ILi256ELi256ELi\d+ELi\d+ELi3ELi\d+E")
+        # SwiGLU epilogue = template argument 3, demangled or mangled name
+        gate = pick(rows, GATEUP_KERNEL, r"gemm_wreg_kernel<3>|gemm_wreg_kernelILi3E")
         if not copy or not gate:
             raise SystemExit(f"{counter}: kernels not found in {path} (copy launches {len(copy)}, gate/up launches {len(gate)})")
         copy_mean, gate_mean = sum(copy) / len(copy), sum(gate) / len(gate)
@@ -103,6 +107,13 @@ def main():
     dec_total = out["FETCH_SIZE"]["decode_bytes"] + out["WRITE_SIZE"]["decode_bytes"]
     lines.append(f"decode layer-step HBM traffic (its own kernels, mean of {out['FETCH_SIZE']['decode_steps']} steps): {dec_total / 1e6:.1f} MB "
                  f"(read {out['FETCH_SIZE']['decode_bytes'] / 1e6:.1f}, written {out['WRITE_SIZE']['decode_bytes'] / 1e6:.1f})")
+    if args.l2:
+        req, hit, miss = (per_kernel(args.l2, n) for n in ("TCC_REQ_sum", "TCC_HIT_sum", "TCC_MISS_sum"))
+        lines.append("L2 (all 8 XCDs summed), mean per launch: requests, hits, misses (millions), hit rate")
+        for name, v in sorted(req.items(), key=lambda kv: -sum(kv[1]) / len(kv[1])):
+            r, h, m = (sum(x[name]) / len(x[name]) / 1e6 for x in (req, hit, miss))
+            if r >= 0.05:
+                lines.append(f"  {r:9.2f} {h:9.2f} {m:9.2f}  {100 * h / r:5.1f} %  x {len(v):4d}  {name[:80]}")
     print("\n".join(lines))
     if args.json:
         rec = dict(workload="config2", prefill_cus=args.prefill_cus, gateup_hbm_bytes_per_launch=total,
