@@ -312,7 +312,7 @@ def main():
                                                 "decode_ms": round(ov_td / 1e6, 4)},
                    "slo_per_layer_ms": {"ttft": ttft_budget / 1e6, "tpot": tpot_budget / 1e6},
                    "sweep": sweep},
-        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_dl_kernel<256,256,2,4,SwiGLU,2 stages>: 256x256 tiles, 8 waves, packed weights)",
+        "roofline": {"bound": "mfma", "kernel": "prefill gate/up GEMM (gemm_wreg_kernel<SwiGLU>: 256x256 tiles, 8 waves, activations through LDS, packed weights straight into registers)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16,
                      "traffic": stored_traffic(pm), "traffic_source": traffic_source(), "avg_launch_ms": gu_avg_s * 1e3, "partition_cus": pm,
                      "frac_of_partition_peak": achieved / (PEAK_BF16 * pm / 256),
@@ -358,6 +358,16 @@ def main():
         eng.prefill_finish()
         eng.seq_free(pseq)
         out["roofline_decode"]["partition_copy_gbps_beside_prefill"] = 2 * copy_bytes * 2 / co_ns
+        # the same decode step on the same partition with the prefill partition idle: what running beside the
+        # prefill slice costs the memory-bound phase
+        alone = []
+        for _ in range(12):
+            eng.decode_step(wl.dseqs, wl.dtokens, want_logits=False, want_next=False)
+            alone.append(eng.last_timing()[1])
+        wl.reset_contexts()
+        alone_ns = float(np.mean(alone[2:]))
+        out["roofline_decode"]["alone_ms"] = alone_ns / 1e6
+        out["roofline_decode"]["frac_alone"] = decode_bytes / (alone_ns * 1e-9) / PEAK_HBM
     if args.pmc_probe:
         eng.probe_copy(0, 256, PMC_PROBE_BYTES, 2)
     if not args.no_cpu_baseline:

@@ -465,6 +465,51 @@ __global__ void __launch_bounds__(512) gemm_wreg_kernel(GemmArgs g) {
   wait_vmem_for<0>(w[0][1], w[1][1]);
   wait_vmem_for<0>(w[0][2], w[1][2]);
   wait_vmem_for<0>(w[0][3], w[1][3]);
+  if constexpr (EPI == EPI_BF16 || EPI == EPI_SWIGLU_BF16) {
+    // bf16 outputs leave through LDS: a lane holds one column of its accumulator blocks, so stored directly a wave
+    // instruction writes 64-byte pieces of rows; staged as a [rows][columns] image in the (now free) A stages, every
+    // lane stores 16 bytes and a row of the tile goes out as whole 128-byte lines.
+    if (piece < 0) {
+      constexpr bool SW = EPI == EPI_SWIGLU_BF16;
+      constexpr int OC = SW ? BN / 2 : BN;                    // output columns of the tile
+      constexpr int PR = 64 * 1024 / (OC * 2);                // rows per pass: 64 KB of LDS
+      constexpr int PASSES = BM / PR;                         // SwiGLU: all 256 rows at once; bf16 store: the two wave rows in turn
+      static_assert(PR % WTM == 0 && 3 * STAGE >= 64 * 1024, "a pass holds whole wave rows and fits the A stages");
+      bf16* img = reinterpret_cast<bf16*>(arena);
+      bf16* outp = reinterpret_cast<bf16*>(g.C);
+      const int oc0 = SW ? (n0 >> 1) : n0;
+#pragma unroll
+      for (int pass = 0; pass < PASSES; pass++) {
+        __syncthreads();                                      // the stage reads of the main loop (or the last pass's copy) are done
+        if (wm * WTM / PR == pass) {
+          const int rb = wm * WTM % PR + 4 * lh;
+#pragma unroll
+          for (int i = 0; i < TM; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+              bf16* dst = img + (size_t)(rb + i * 32 + 8 * (r >> 2) + (r & 3)) * OC;
+              if constexpr (SW) {
+                const float gate = acc[i][0][r], up = acc[i][1][r];
+                dst[wn * (WTN / 2) + l32] = f2bf(gate / (1.f + __expf(-gate)) * up);
+              } else {
+#pragma unroll
+                for (int j = 0; j < TN; j++) dst[wn * WTN + j * 32 + l32] = f2bf(acc[i][j][r]);
+              }
+            }
+        }
+        __syncthreads();
+        constexpr int CPRW = OC / 8;                          // 16-byte chunks per row
+#pragma unroll
+        for (int c = 0; c < PR * CPRW / NT; c++) {
+          const int q = c * NT + tid, row = q / CPRW, cc = q % CPRW;
+          const int grow = m0 + pass * PR + row;
+          if (grow < g.M)
+            *reinterpret_cast<u32x4*>(outp + (size_t)grow * g.ldc + oc0 + cc * 8) = *reinterpret_cast<const u32x4*>(img + (size_t)row * OC + cc * 8);
+        }
+      }
+      return;
+    }
+  }
   store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
 
@@ -599,6 +644,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (w_packed && ldw != K) return hipErrorInvalidValue;          // packed blocks are addressed by K alone
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
+  if (cfg == GEMM_256x256 && (epi == EPI_BF16 || epi == EPI_SWIGLU_BF16) && ldc % 8 != 0) return hipErrorInvalidValue;   // 16-byte output stores
   if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_64x256) return hipErrorInvalidValue;   // its wave tile is one 32-column block, not a gate/up pair
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;

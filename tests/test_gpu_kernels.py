@@ -39,6 +39,20 @@ def test_gemm_fp32_accumulators(sts, cfg, m):
     assert rel(got, ref) <= 1e-5          # in practice fp32 accumulation of 320 terms
 
 
+@pytest.mark.parametrize("cfg", ["256x256", "128x128", "64x128", "64x256"])
+@pytest.mark.parametrize("k", [64, 128, 192, 576])
+@pytest.mark.parametrize("epilogue", [0, 1])
+def test_gemm_short_and_odd_k_extents(sts, cfg, k, epilogue):
+    """One, two, three and nine K tiles: the prologue, the steady loop and the surplus loads of the last iterations of every
+    main loop (the 256x256 loop keeps three activation stages and requests operands a tile ahead), rows that end inside a tile."""
+    m, n = 290, 512
+    a = synth.normal_bf16(11, (m, k))
+    w = synth.normal_bf16(12, (n, k), 0.1)
+    ref = T.op_linear(a.astype(np.float64), w.astype(np.float64))
+    got = sts.op_gemm(a, w, cfg, epilogue=epilogue)
+    assert rel(got, ref) <= (BF16_TOL if epilogue == 0 else 1e-5)
+
+
 @pytest.mark.parametrize("cfg,m,split", [("64x256", 64, 4), ("64x256", 8, 8), ("128x128", 130, 2), ("64x128", 33, 3), ("64x128", 64, 8),
                                          ("256x256", 300, 2)])
 def test_gemm_split_k(sts, cfg, m, split):
