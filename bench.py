@@ -255,7 +255,7 @@ def main():
     best = None
     for pm in ([args.split] if args.split else range(32, 225, 32)):
         eng.set_partition(pm, 256 - pm)
-        wl.timed(3)                                 # the clocks and the tile choice settle on the new partition
+        wl.timed(20)                                # the clocks settle on the new partition's load within about 20 ms of work
         s, tp, td = wl.timed(12)
         ok = tp <= ttft_budget and td <= tpot_budget
         sweep[str(pm)] = {"step_ms": round(s * 1e3, 4), "prefill_ms": round(tp / 1e6, 4), "decode_ms": round(td / 1e6, 4), "slo_ok": ok}

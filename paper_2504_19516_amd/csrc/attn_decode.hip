@@ -264,12 +264,12 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
 // Merge the chunks of one (request, query head): out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 template <int D>
 __global__ void attn_decode_merge_kernel(bf16* __restrict__ out, const float* __restrict__ ws, const DecodeSeq* __restrict__ seqs,
-                                         int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
-  const int head = blockIdx.x, req = blockIdx.y, dd = threadIdx.x;
+                                         const int* __restrict__ multi, int n_q, int n_kv, int G, int chunk_pages, int max_chunks) {
+  const int head = blockIdx.x, req = multi[blockIdx.y], dd = threadIdx.x;
   const int kvh = head / G, g = head % G;
   const int n_pages = (seqs[req].cl + 1 + 15) >> 4;
   const int chunks = (n_pages + chunk_pages - 1) / chunk_pages;
-  if (chunks == 1) return;                         // the attention kernel stored this request's output itself
+  if (chunks == 1) return;                         // (not listed by the caller: the attention kernel stored this request's output itself)
   const float* base = ws + (((size_t)req * n_kv + kvh) * max_chunks) * G * (D + 2) + g * (D + 2);
   const size_t cstride = (size_t)G * (D + 2);
   float m = -INFINITY;
@@ -291,30 +291,34 @@ constexpr int MAX_CHUNK_TOKENS = 1024;
 int attn_decode_max_chunk_tokens() { return MAX_CHUNK_TOKENS; }
 
 template <int D, int G>
-static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
-                          const int* bt, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
+static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items, const int* multi, int n_multi,
+                          const int* bt, const bf16* pool, KvGeom geo, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
   constexpr int lds = attn_decode_mfma_lds<D>();
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_mfma_kernel<D, G>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   (void)attr;
   hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, out, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n), dim3(D), 0, s, out, ws, seqs, n_q, geo.n_kv, G, chunk_pages, max_chunks);
+  if (n_multi > 0)
+    hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n_multi), dim3(D), 0, s, out, ws, seqs, multi, n_q, geo.n_kv, G, chunk_pages, max_chunks);
 }
 
 // q, out: [n, n_q * d] bf16 (q already rotated). A context is cut into chunks of `chunk_pages`
 // pages (at most attn_decode_max_chunk_tokens() tokens); `max_chunks` must be at least
 // the chunk count of the longest context. items: one (request, chunk index) record per chunk
-// that exists, n_items of them (device memory). ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
-hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
+// that exists, n_items of them (device memory). multi: the n_multi requests whose context has more than
+// one chunk (device memory; only these need the merge kernel, and with none of them it is not launched).
+// ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
+hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items, const int* multi, int n_multi,
                        const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws) {
   if (n == 0 || n_items == 0) return hipSuccess;
+  if (n_multi < 0 || n_multi > n || (n_multi > 0 && !multi)) return hipErrorInvalidValue;
   if (geo.page_tokens != 16 || n_q % geo.n_kv != 0 || chunk_pages < 1 || chunk_pages * 16 > attn_decode_max_chunk_tokens() || max_chunks < 1) return hipErrorInvalidValue;
   const int G = n_q / geo.n_kv;
   const float sc = 1.4426950408889634f / sqrtf((float)geo.d);
-  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, items, n_items, block_tables, pool, geo, n, n_q, chunk_pages, max_chunks, ws, sc);
+  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

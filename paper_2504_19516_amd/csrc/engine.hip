@@ -585,6 +585,11 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     };
     std::stable_sort(ph.h_ditems, ph.h_ditems + n_items, [&](const DecodeItem& a, const DecodeItem& b) { return chunk_len(a) > chunk_len(b); });
   }
+  // requests whose context has more than one chunk: only they need the merge kernel
+  int *h_multi = nullptr, *d_multi = nullptr, n_multi = 0;
+  meta_take(ph, &h_multi, &d_multi, (size_t)n);
+  if (ph.meta_used > ph.meta_bytes) return STS_EINVAL;
+  for (int i = 0; i < n; i++) if (ph.h_dseq[i].n_pages > chunk_pages) h_multi[n_multi++] = i;
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
   HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
@@ -605,7 +610,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     int sp; long long ss;
     STSCK(skinny(STS_K_QKV, ph.Xn, h, w.wqkv, c->qkvn, h, &sp, &ss));
     KL(ph, STS_K_ROPE, decode_qkv_finish(st, ph.part, sp, ss, c->qkvn, ph.d_dseq, ph.d_bt, c->inv_freq, ph.Q, layer_pool(c, l), c->geo, n, d.n_q_heads));
-    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_ditems, n_items, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
+    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_ditems, n_items, d_multi, n_multi, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
     STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
     {
@@ -672,7 +677,7 @@ int alloc_phase(sts_ctx* c, int side) {
     const size_t items = rows / attn_prefill_tile_q() + nseq + 1;
     // decode attention items: a context has at most 128 chunks, and fewer than one per 4 pages (chunks hold >= 8)
     const size_t dec_items = side == 1 ? nseq * (size_t)decode_max_chunks((int)mp) : 0;
-    ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + sizeof(int)) + items * sizeof(AttnItem) + dec_items * sizeof(DecodeItem) +
+    ph.meta_bytes = nseq * (sizeof(PrefillSeq) + sizeof(DecodeSeq) + 2 * sizeof(int)) + items * sizeof(AttnItem) + dec_items * sizeof(DecodeItem) +
                     rows * sizeof(int) + nseq * mp * sizeof(int) + 8 * 256;
     STSCK(dev_alloc(c, &ph.d_meta, ph.meta_bytes));
     STSCK(host_alloc(&ph.h_meta, ph.meta_bytes));

@@ -102,7 +102,7 @@ hipError_t attn_prefill(hipStream_t s, const bf16* qkv, int ld, bf16* out, int l
                         KvGeom geo, int n_q);
 int attn_prefill_tile_q();
 size_t attn_decode_ws_floats(int n, int n_q, int d, int max_chunks);
-hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
+hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items, const int* multi, int n_multi,
                        const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws);
 int attn_decode_max_chunk_tokens();
 

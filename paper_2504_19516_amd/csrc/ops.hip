@@ -195,7 +195,11 @@ extern "C" int sts_op_attn_decode(const float* q, const float* k, const float* v
     for (int ch = 0; ch < (seqs[i].n_pages + chunk_pages - 1) / chunk_pages; ch++) items.push_back(DecodeItem{i, ch, seqs[i].cl, seqs[i].bt_off});
   DecodeItem* d_items = b.get<DecodeItem>(items.size());
   if (!d_items || hipMemcpy(d_items, items.data(), items.size() * sizeof(DecodeItem), hipMemcpyHostToDevice) != hipSuccess) return STS_EHIP;
-  hipError_t e = attn_decode(nullptr, dq, dout, d_seq, d_items, (int)items.size(), d_bt, pool, geo, n, n_q, chunk_pages, max_chunks, ws);
+  std::vector<int> multi;
+  for (int i = 0; i < n; i++) if (seqs[i].n_pages > chunk_pages) multi.push_back(i);
+  int* d_multi = b.get<int>(std::max<size_t>(1, multi.size()));
+  if (!d_multi || (!multi.empty() && hipMemcpy(d_multi, multi.data(), multi.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess)) return STS_EHIP;
+  hipError_t e = attn_decode(nullptr, dq, dout, d_seq, d_items, (int)items.size(), d_multi, (int)multi.size(), d_bt, pool, geo, n, n_q, chunk_pages, max_chunks, ws);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? STS_EINVAL : STS_EHIP;
   int rc = download_bf16(b, out, dout, (size_t)n * n_q * d);
   if (hipDeviceSynchronize() != hipSuccess) return STS_EHIP;
