@@ -27,6 +27,7 @@ import subprocess
 
 COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
 GATEUP_KERNEL = "gemm_wreg_kernel"         # the 256 x 256 prefill tile; its SwiGLU instantiation is the gate/up GEMM
+GATEUP_PATTERN = r"gemm_wreg_kernel<3>|gemm_wreg_kernelILi3E"    # SwiGLU epilogue = template argument 3, demangled or mangled name
 COPY_KERNEL = "copy_kernel"
 # kernels that only the decode phase launches; one attn_decode_mfma launch = one decode layer-step.
 # (Its embedding and first RMSNorm launches share kernels with the prefill phase and are left out:
@@ -36,12 +37,24 @@ DECODE_KERNELS = (r"attn_decode_mfma_kernel", r"attn_decode_merge_kernel", r"dec
                   r"reduce_swiglu_kernel", r"gemm_dl_kernel<64, |gemm_dl_kernelILi64E")
 
 
-def per_kernel(path, counter):
-    rows = collections.defaultdict(list)
+def per_kernel(path, counter, queue_of=None):
+    """kernel name -> counter values, one per launch. With queue_of (a kernel-name pattern), only the launches on the
+    hardware queue that carries most launches of that kernel are kept: the benchmark also runs its time-multiplexed
+    reference (other streams, other launch shapes), which is not what the stored figures describe."""
+    recs = []
     with open(path) as f:
         for r in csv.DictReader(f):
             if r["Counter_Name"] == counter:
-                rows[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+                recs.append((r["Kernel_Name"], float(r["Counter_Value"]), r.get("Queue_Id", "")))
+    keep = None
+    if queue_of is not None:
+        queues = collections.Counter(q for name, _, q in recs if re.search(queue_of, name))
+        if queues:
+            keep = queues.most_common(1)[0][0]
+    rows = collections.defaultdict(list)
+    for name, v, q in recs:
+        if keep is None or q == keep:
+            rows[name].append(v)
     return rows
 
 
@@ -75,18 +88,19 @@ def main():
     lines = []
     for counter, path in (("FETCH_SIZE", args.fetch_csv), ("WRITE_SIZE", args.write_csv)):
         rows = per_kernel(path, counter)
+        prefill_rows = per_kernel(path, counter, GATEUP_PATTERN)              # the prefill partition's queue
+        decode_rows = per_kernel(path, counter, DECODE_STEP_KERNEL)           # the decode partition's queue
         copy = pick(rows, COPY_KERNEL)
         # the benchmark also runs the copy kernel on smaller buffers (its bandwidth probes of the decode
         # partition); the reference launches are the largest ones
         copy = [v for v in copy if v >= 0.75 * max(copy)] if copy else copy
-        # SwiGLU epilogue = template argument 3, demangled or mangled name
-        gate = pick(rows, GATEUP_KERNEL, r"gemm_wreg_kernel<3>|gemm_wreg_kernelILi3E")
+        gate = pick(prefill_rows, GATEUP_KERNEL, GATEUP_PATTERN)
         if not copy or not gate:
             raise SystemExit(f"{counter}: kernels not found in {path} (copy launches {len(copy)}, gate/up launches {len(gate)})")
         copy_mean, gate_mean = sum(copy) / len(copy), sum(gate) / len(gate)
         factor = COPY_BYTES / copy_mean                     # bytes per counter unit
-        steps = len(pick(rows, DECODE_STEP_KERNEL))
-        dec_units = sum(sum(v) for name, v in rows.items() if any(re.search(pat, name) for pat in DECODE_KERNELS))
+        steps = len(pick(decode_rows, DECODE_STEP_KERNEL))
+        dec_units = sum(sum(v) for name, v in decode_rows.items() if any(re.search(pat, name) for pat in DECODE_KERNELS))
         if not steps:
             raise SystemExit(f"{counter}: no decode step found in {path}")
         out[counter] = dict(copy_counter=copy_mean, factor_bytes_per_unit=factor, gateup_counter=gate_mean,

@@ -151,7 +151,8 @@ def test_host_overheads_tool_runs_without_a_gpu(sts, capsys, monkeypatch):
 def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, monkeypatch):
     """The counter arithmetic on hand-made rocprofv3 CSVs: the unit of each counter comes from the largest
     copy-kernel launches (512 MiB each way; smaller probe launches are ignored), the gate/up GEMM is the
-    SwiGLU instantiation, and the decode step sums the decode-only kernels per attention launch."""
+    SwiGLU instantiation, the decode step sums the decode-only kernels per attention launch, and only the launches on the
+    benchmarked partitions' queues count."""
     import sys
     from paper_2504_19516_amd import pmc_traffic
     gateup = "void sts::gemm_wreg_kernel<3>(sts::GemmArgs)"
@@ -161,14 +162,17 @@ def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, m
     copy = "sts::copy_kernel(a, b, c)"
 
     def write(name, counter, unit):
-        rows = [(copy, (512 << 20) // unit)] * 3 + [(copy, (256 << 20) // unit)] * 5           # reference launches, then probes
-        rows += [(gateup, 800_000_000 // unit), (gateup, 780_000_000 // unit), (other, 123)]
-        rows += [(attn, 300_000_000 // unit)] * 2 + [(skinny, 100_000_000 // unit)] * 8         # two decode steps
+        # (kernel, counter value, hardware queue): queue 4 = prefill partition, 5 = decode partition, 2 = the streams of the
+        # time-multiplexed reference, whose launches must not enter the figures
+        rows = [(copy, (512 << 20) // unit, 1)] * 3 + [(copy, (256 << 20) // unit, 1)] * 5      # reference launches, then probes
+        rows += [(gateup, 800_000_000 // unit, 4), (gateup, 780_000_000 // unit, 4), (other, 123, 4), (gateup, 500_000_000 // unit, 2)]
+        rows += [(attn, 300_000_000 // unit, 5)] * 2 + [(skinny, 100_000_000 // unit, 5)] * 8   # two decode steps
+        rows += [(attn, 900_000_000 // unit, 2), (skinny, 900_000_000 // unit, 2)]
         path = tmp_path / name
         with open(path, "w") as f:
-            f.write("Counter_Name,Kernel_Name,Counter_Value\n")
-            for k, v in rows:
-                f.write(f'{counter},"{k}",{v}\n')
+            f.write("Counter_Name,Kernel_Name,Counter_Value,Queue_Id\n")
+            for k, v, q in rows:
+                f.write(f'{counter},"{k}",{v},{q}\n')
         return str(path)
     fetch, wr = write("fetch.csv", "FETCH_SIZE", 2048), write("write.csv", "WRITE_SIZE", 1024)
     monkeypatch.setattr(sys, "argv", ["pmc_traffic", fetch, wr, "--prefill-cus", "224"])
