@@ -65,12 +65,13 @@ int sts_init(const sts_model_desc* desc, const sts_init_params* params, sts_ctx*
  * null stream), then releases its memory. The CU-masked streams themselves belong to the process
  * and stay. */
 int sts_destroy(sts_ctx* ctx);
-/* Optional, at the end of a process: waits on and destroys the process-wide CU-masked streams
+/* Optional, as the last call of a process: waits on and destroys the process-wide CU-masked streams
  * (Section 3.5.2's partitions are streams with a CU mask; the library creates one per side and CU
  * count on first use and otherwise keeps them until the process ends). STS_ESTATE while any ctx is
- * alive. For programs that load the HIP runtime late (an interpreter) and run under a profiler
+ * alive; afterwards sts_init returns STS_ESTATE (masked streams are not created a second time in one
+ * process). For programs that load the HIP runtime late (an interpreter) and run under a profiler
  * whose exit handler walks the queues still open: a masked stream left open there has ended such
- * runs with a fault after all output was written. Later sts_init calls create streams again. */
+ * runs with a fault after all output was written. */
 int sts_release_streams(void);
 /* Longest block table sts_init accepts: decode attention cuts a context into at most 128 chunks of
  * at most 64 pages (Section 3.5.1's pool is shared, a sequence's share of it is bounded by this). */

@@ -150,6 +150,7 @@ void meta_take(Phase& ph, T** host, T** dev, size_t count) {
 std::mutex g_stream_mu;
 std::map<std::pair<int, int>, hipStream_t> g_streams;
 std::atomic<int> g_live_ctx{0};            // engines alive in this process (sts_release_streams refuses while any is)
+std::atomic<bool> g_streams_released{false};   // set by sts_release_streams: the process is ending, no further engine is created
 
 void trace(const char* what) {
   static const bool on = std::getenv("STS_TRACE") != nullptr;
@@ -739,6 +740,7 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
       params->max_decode_batch < 1 || params->max_seqs < 1 || params->max_pages_per_seq < 1) return STS_EINVAL;
   // decode attention cuts a context into at most 128 chunks (the merge workspace and the work list are sized for that)
   if (params->max_pages_per_seq > sts_max_pages_per_seq_limit(d.page_tokens)) return STS_EINVAL;
+  if (g_streams_released.load()) return STS_ESTATE;
   int ndev = 0;
   HIPCK(hipGetDeviceCount(&ndev));
   if (ndev < 1) { g_hip_err = (int)hipErrorNoDevice; return STS_EHIP; }
@@ -843,6 +845,7 @@ extern "C" int sts_destroy(sts_ctx* c) {
 extern "C" int sts_release_streams(void) {
   std::lock_guard<std::mutex> g(g_stream_mu);
   if (g_live_ctx.load() != 0) return STS_ESTATE;
+  g_streams_released.store(true);
   for (auto& kv : g_streams) (void)hipStreamSynchronize(kv.second);
   while (!g_streams.empty()) {
     hipStream_t s = g_streams.begin()->second;

@@ -367,8 +367,8 @@ def op_attn_decode(q, k, v, ctx, chunk_pages):
 
 
 def release_streams():
-    """Destroys the process-wide CU-masked streams (every Engine must be closed). For the end of a
-    program that runs under a profiler."""
+    """Destroys the process-wide CU-masked streams (every Engine must be closed; no Engine can be created
+    afterwards). The last library call of a program that runs under a profiler."""
     _ck(lib().sts_release_streams(), "sts_release_streams")
 
 

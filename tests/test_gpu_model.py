@@ -6,6 +6,8 @@ CU split 50/50 — plus the invariants the method must keep on the GPU.
 Tolerance: logits max |gpu - ref| / max |ref| <= 2e-2 (bf16 weights and activations, fp32
 accumulation, against an fp64 oracle holding the unrounded fp32 weights).
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -388,6 +390,32 @@ def test_masked_streams_are_not_released_under_a_live_engine(sts, tiny):
     eng.prefill_append(s, synth.tokens(3, 40, desc.vocab), want_logits=False)      # the streams still work
     assert eng.seq_length(s) == 40
     eng.close()
+
+
+def test_releasing_the_masked_streams_ends_the_library_use_of_a_process():
+    """In a process of its own: after the last engine is closed the masked streams can be released, once, and no
+    engine is created afterwards; the process then exits normally."""
+    import subprocess
+    import sys
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "from paper_2504_19516_amd import sts, synth\n"
+        "desc = synth.tiny_model('fp32')\n"
+        "eng = sts.Engine(desc, weight_seed=1, init_weights=True, kv_pool_pages=64, max_prefill_tokens=128, max_prefill_seqs=2,\n"
+        "                 max_decode_batch=4, max_seqs=8, max_pages_per_seq=16)\n"
+        "eng.set_partition(128, 128)\n"
+        "s = eng.seq_create(); eng.prefill_append(s, synth.tokens(1, 40, desc.vocab), want_logits=False)\n"
+        "eng.decode_step([s], synth.tokens(2, 1, desc.vocab))\n"
+        "eng.close()\n"
+        "sts.release_streams()\n"
+        "try:\n"
+        "    sts.Engine(desc, weight_seed=1, kv_pool_pages=64, max_prefill_tokens=128, max_prefill_seqs=2, max_decode_batch=4, max_seqs=8, max_pages_per_seq=16)\n"
+        "except sts.StsError as e:\n"
+        "    print('refused', e.code == sts.ESTATE)\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert "refused True" in r.stdout
 
 
 def test_failed_concurrent_step_commits_nothing(sts, tiny):
