@@ -189,17 +189,22 @@ const char* sts_kernel_name(int32_t kind);
  * iteration; returns device ns for `iters` iterations. */
 int sts_probe_copy(sts_ctx* ctx, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out);
 
-/* The prefill side's gate/up GEMM (SwiGLU epilogue, K = hidden, layer 0's weights, whatever the workspace holds
- * as activations) with a given tile configuration on `cus` CUs, whole tiles only: m rows (<= max_prefill_tokens),
- * n <= 2 * mlp weight rows (a multiple of the tile width). Returns device ns for `iters` launches. The offline
- * profiler (Section 3.2.4) times the tile shapes with it. */
-int sts_probe_gemm(sts_ctx* ctx, int32_t cus, int32_t tile_cfg, int32_t m, int32_t n, int32_t iters, int64_t* ns_out);
+/* One of the prefill side's GEMMs (layer 0's weights, whatever the workspace holds as activations; the residual
+ * stream of the workspace is overwritten) with a given tile configuration on `cus` CUs, whole tiles only: m rows
+ * (<= max_prefill_tokens) and n weight rows (a multiple of the tile width). product 0: gate/up with its SwiGLU
+ * epilogue, K = hidden, n <= 2 * mlp (not for the tile shapes without a SwiGLU form); 1: the O projection, K = the
+ * query width, n <= hidden, residual epilogue; 2: the down projection, K = mlp, n <= hidden, residual epilogue.
+ * Returns device ns for `iters` launches. The offline profiler (Section 3.2.4) times the tile shapes with it. */
+int sts_probe_gemm(sts_ctx* ctx, int32_t cus, int32_t tile_cfg, int32_t product, int32_t m, int32_t n, int32_t iters, int64_t* ns_out);
 /* What the engine's choice of GEMM tile and of the cut of a partly filled last wave (Section 2.2.1) assumes about
- * the part: GFLOP/s per busy CU of the 128x128 tiles (two workgroups per CU) and of the 256x256 tiles (one), and
- * MB/s per CU for partial tiles written and read back. The offline profiler measures them and stores them in the
+ * the part: GFLOP/s per busy CU of the 128x128 tiles (two workgroups per CU), of the 256x256 tiles (one) and of the
+ * 128x256 tiles (planned one per CU, for the projections with a residual epilogue; their start-up and epilogue are
+ * not hidden behind a second workgroup, so a tile costs gemm_fixed_128x256 ns plus its flops at the rate), and MB/s
+ * per CU for partial tiles written and read back. The offline profiler measures them and stores them in the
  * profile (sts_profile_tile_model reads them back); until set, figures measured on the 8B shape apply. Takes
  * effect for the next launch; STS_ESTATE while a launch is outstanding. */
-int sts_set_tile_model(sts_ctx* ctx, int64_t gemm_rate_128, int64_t gemm_rate_256, int64_t partial_bw_cu);
+int sts_set_tile_model(sts_ctx* ctx, int64_t gemm_rate_128, int64_t gemm_rate_256, int64_t gemm_rate_128x256, int64_t gemm_fixed_128x256,
+                       int64_t partial_bw_cu);
 
 /* ---- single operations on host data, for per-kernel parity tests. Inputs are fp32 and are
  * rounded to bf16 on upload; outputs are the kernel's fp32 accumulators (or its bf16 result
@@ -211,7 +216,7 @@ int sts_set_tile_model(sts_ctx* ctx, int64_t gemm_rate_128, int64_t gemm_rate_25
  * workgroups at once -- the tiles of the last, partly filled wave (Section 2.2.1) are cut along
  * K into pieces that fill the wave, and a second kernel sums the pieces. 0 = whole tiles only. */
 enum { STS_GEMM_128x128 = 0 /* 4 waves, two workgroups per CU */, STS_GEMM_64x256 /* 8 waves */, STS_GEMM_64x128 /* 4 waves, two per CU */,
-       STS_GEMM_256x256 /* 8 waves */ };
+       STS_GEMM_256x256 /* 8 waves */, STS_GEMM_128x256 /* 4 waves, planned one per CU; no SwiGLU epilogue */ };
 int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                 int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots);
 /* sts_op_gemm's fp32-store form (epilogue 1) for callers that cannot allocate -- code under HIP
@@ -258,7 +263,8 @@ int sts_profile_load(const char* path, sts_profile** out);
 int sts_profile_dump(const sts_profile* p, char* buf, size_t cap, size_t* needed);
 int sts_profile_free(sts_profile* p);
 /* The profile's tile-model entries (see sts_set_tile_model); each output may be NULL. */
-int sts_profile_tile_model(const sts_profile* p, int64_t* gemm_rate_128, int64_t* gemm_rate_256, int64_t* partial_bw_cu);
+int sts_profile_tile_model(const sts_profile* p, int64_t* gemm_rate_128, int64_t* gemm_rate_256, int64_t* gemm_rate_128x256,
+                           int64_t* gemm_fixed_128x256, int64_t* partial_bw_cu);
 
 /* Execution state ES (Section 3.2.1): prefill lengths sl_i with their cached contexts, prefill
  * CUs pm, decode contexts cl_i (batch size = n_decode), decode CUs dm; plus the layer slice. */

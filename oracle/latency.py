@@ -65,9 +65,11 @@ class Profile:
     use_waveq: int = 1
     tail_cut: int = 0                  # > 0: the GEMMs cut the tiles of a partly filled last wave along K, into at most this many pieces
     # measured rates the GPU library's tile choice reads from the same file; the estimator does not use them:
-    # GFLOP/s per busy CU of the 128x128 and 256x256 GEMM tiles, MB/s per CU for partial tiles written and read back
+    # GFLOP/s per busy CU of the 128x128, 256x256 and 128x256 GEMM tiles, MB/s per CU for partial tiles written and read back
     gemm_rate_128: int = 3500
     gemm_rate_256: int = 4800
+    gemm_rate_128x256: int = 5000
+    gemm_fixed_128x256: int = 25000    # ns: start-up and epilogue of that tile, which runs one per CU
     partial_bw_cu: int = 20000
     bw: Grid | None = None             # D_{p,sl}: axes (decode CUs, co-running prefill tokens) -> bytes/ns
     # slowdown (ppm) of a prefill slice beside a decode step, over the decode CUs it shares the GPU
@@ -365,7 +367,7 @@ def _nest(flat, dims):
 def dump_profile(hw: Profile) -> str:
     lines = ["sts-profile 1"]
     for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut",
-              "gemm_rate_128", "gemm_rate_256", "partial_bw_cu"):
+              "gemm_rate_128", "gemm_rate_256", "gemm_rate_128x256", "gemm_fixed_128x256", "partial_bw_cu"):
         lines.append(f"{k} {getattr(hw, k)}")
     for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         g = getattr(hw, name)

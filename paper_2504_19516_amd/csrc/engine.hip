@@ -111,7 +111,7 @@ struct sts_ctx {
   std::vector<hipStream_t> used_streams;       // every pooled stream this ctx ever selected (guarded by part_mu)
   // what the tile choice of the prefill GEMMs assumes about the part (sts_set_tile_model): TFLOP/s per busy CU of
   // the 128x128 tiles (two workgroups per CU) and of the 256x256 tiles (one), bytes/s per CU for partial tiles
-  double rate_128 = 3.5, rate_256 = 4.8, partial_bw = 20e9;
+  double rate_128 = 3.5, rate_256 = 4.8, rate_128x256 = 5.0, fixed_128x256 = 25e-6, partial_bw = 20e9;
 };
 
 namespace {
@@ -243,12 +243,16 @@ int pick_cfg(int m, int n, int k, int cus) {
 // waves of workgroups at the tile's busy-CU rate, then the last wave, whole or cut along K.
 // Rates are measured busy-CU throughputs in TFLOP/s per CU: 128x128 tiles run two workgroups
 // per CU, 256x256 (8 waves) one.
-int pick_prefill_cfg(const sts_ctx* ctx, int m, int n, int k, int cus, size_t tail_ws_bytes) {
+int pick_prefill_cfg(const sts_ctx* ctx, int epi, int m, int n, int k, int cus, size_t tail_ws_bytes) {
   if (m <= 64) return GEMM_64x128;
   struct Cand { int cfg; double rate; };
-  const Cand cands[2] = {{GEMM_128x128, ctx->rate_128}, {GEMM_256x256, ctx->rate_256}};
+  const Cand cands[3] = {{GEMM_128x128, ctx->rate_128}, {GEMM_256x256, ctx->rate_256}, {GEMM_128x256, ctx->rate_128x256}};
   int best = GEMM_128x128; double best_cost = 1e300;
   for (const Cand& c : cands) {
+    // 128x256: planned one tile per CU although two fit, so the pieces of a cut last wave run in the second slot beside
+    // the whole tiles; the shape of the O and down projections (a little more than one such tile per CU), instantiated
+    // for their residual epilogue
+    if (c.cfg == GEMM_128x256 && epi != EPI_RESID_F32) continue;
     const int tm = gemm_tile_m(c.cfg), tn = gemm_tile_n(c.cfg), per_cu = gemm_wgs_per_cu(c.cfg);
     if (n % tn != 0) continue;
     const int tiles = ((m + tm - 1) / tm) * (n / tn);
@@ -258,7 +262,8 @@ int pick_prefill_cfg(const sts_ctx* ctx, int m, int n, int k, int cus, size_t ta
     // in units of this configuration's tile time: complete waves, then the last wave -- whole, or
     // in rounds of 1/f with a start-up charge per round, plus the partial tiles written and read
     // back (4 bytes out, 4 in per element and piece, at the measured per-CU rate)
-    const double tile_s = 2.0 * tm * tn * k / (c.rate * 1e12 / per_cu);
+    // one 128x256 tile per CU: start-up and epilogue are exposed, a measured fixed time on top of the flops
+    const double tile_s = 2.0 * tm * tn * k / (c.rate * 1e12 / per_cu) + (c.cfg == GEMM_128x256 ? ctx->fixed_128x256 : 0.0);
     double t;
     if (f > 1) {
       const int rest = tiles - n_full, rounds = (rest * f + slots - 1) / slots;
@@ -273,7 +278,7 @@ int pick_prefill_cfg(const sts_ctx* ctx, int m, int n, int k, int cus, size_t ta
 }
 // A prefill GEMM on the phase's partition: tile choice, and the last wave of tiles cut along K.
 hipError_t prefill_gemm(const sts_ctx* ctx, Phase& ph, int epi, const bf16* A, int lda, const bf16* W, int ldw, void* C, int ldc, int m, int n, int k) {
-  int cfg = pick_prefill_cfg(ctx, m, n, k, ph.cus, ph.tail_ws_bytes);
+  int cfg = pick_prefill_cfg(ctx, epi, m, n, k, ph.cus, ph.tail_ws_bytes);
   const GemmTail tail{gemm_wgs_per_cu(cfg) * ph.cus, ph.tail_ws, ph.tail_ws_bytes};
   return gemm_bf16(ph.stream, cfg, epi, A, lda, W, ldw, C, ldc, m, n, k, 1, 0, &tail);
 }
@@ -1198,17 +1203,21 @@ extern "C" int sts_kernel_times(sts_ctx* c, int32_t phase, int64_t* ns, int64_t*
   }
   return STS_OK;
 }
-extern "C" int sts_set_tile_model(sts_ctx* c, int64_t gemm_rate_128, int64_t gemm_rate_256, int64_t partial_bw_cu) {
-  if (!c || gemm_rate_128 < 1 || gemm_rate_256 < 1 || partial_bw_cu < 1) return STS_EINVAL;
+extern "C" int sts_set_tile_model(sts_ctx* c, int64_t gemm_rate_128, int64_t gemm_rate_256, int64_t gemm_rate_128x256, int64_t gemm_fixed_128x256,
+                                  int64_t partial_bw_cu) {
+  if (!c || gemm_rate_128 < 1 || gemm_rate_256 < 1 || gemm_rate_128x256 < 1 || gemm_fixed_128x256 < 0 || partial_bw_cu < 1) return STS_EINVAL;
   if (c->pend_prefill || c->pend_decode) return STS_ESTATE;
-  c->rate_128 = gemm_rate_128 * 1e-3; c->rate_256 = gemm_rate_256 * 1e-3; c->partial_bw = partial_bw_cu * 1e6;
+  c->rate_128 = gemm_rate_128 * 1e-3; c->rate_256 = gemm_rate_256 * 1e-3; c->rate_128x256 = gemm_rate_128x256 * 1e-3;
+  c->fixed_128x256 = gemm_fixed_128x256 * 1e-9; c->partial_bw = partial_bw_cu * 1e6;
   return STS_OK;
 }
-extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t m, int32_t n, int32_t iters, int64_t* ns_out) {
-  if (!c || !ns_out || iters < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;
+extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t product, int32_t m, int32_t n, int32_t iters, int64_t* ns_out) {
+  if (!c || !ns_out || iters < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG || product < 0 || product > 2) return STS_EINVAL;
   const sts_model_desc& d = c->d;
-  if (m < 1 || m > c->p.max_prefill_tokens || n < 64 || n > 2 * d.mlp || n % 64 || n % gemm_tile_n(tile_cfg)) return STS_EINVAL;
-  if (tile_cfg == GEMM_64x256) return STS_EINVAL;        // the SwiGLU epilogue needs gate/up block pairs in a wave tile
+  const int n_max = product == 0 ? 2 * d.mlp : d.hidden;
+  if (m < 1 || m > c->p.max_prefill_tokens || n < 64 || n > n_max || n % 64 || n % gemm_tile_n(tile_cfg)) return STS_EINVAL;
+  // gate/up runs with its SwiGLU epilogue, which needs gate/up block pairs in a wave tile
+  if (product == 0 && (tile_cfg == GEMM_64x256 || tile_cfg == GEMM_128x256)) return STS_EINVAL;
   if (c->pend_prefill) return STS_ESTATE;
   hipStream_t st;
   STSCK(get_stream(c, 0, cus, &st));
@@ -1219,7 +1228,12 @@ extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t
     ~Events() { if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); }
   } ev;
   HIPCK(hipEventCreate(&ev.e0)); HIPCK(hipEventCreate(&ev.e1));
-  auto run = [&]() { return gemm_bf16(st, tile_cfg, EPI_SWIGLU_BF16, ph.Xn, d.hidden, c->layers[0].wgu, d.hidden, ph.H, d.mlp, m, n, d.hidden, 1, 0); };
+  const LayerW& w0 = c->layers[0];
+  auto run = [&]() {
+    if (product == 1) return gemm_bf16(st, tile_cfg, EPI_RESID_F32, ph.A, c->qd, w0.wo, c->qd, ph.X, d.hidden, m, n, c->qd, 1, 0);
+    if (product == 2) return gemm_bf16(st, tile_cfg, EPI_RESID_F32, ph.H, d.mlp, w0.wd, d.mlp, ph.X, d.hidden, m, n, d.mlp, 1, 0);
+    return gemm_bf16(st, tile_cfg, EPI_SWIGLU_BF16, ph.Xn, d.hidden, w0.wgu, d.hidden, ph.H, d.mlp, m, n, d.hidden, 1, 0);
+  };
   for (int i = 0; i < 2; i++) HIPCK(run());                         // warm-up
   HIPCK(hipEventRecord(ev.e0, st));
   for (int i = 0; i < iters; i++) HIPCK(run());

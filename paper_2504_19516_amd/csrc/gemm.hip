@@ -337,9 +337,9 @@ __device__ __forceinline__ void wait_vmem_for(bf16x8& a, bf16x8& b) {
 #endif
 }
 
-template <int EPI>
-__global__ void __launch_bounds__(512) gemm_wreg_kernel(GemmArgs g) {
-  constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, BK = 64, NT = 512, NS = 3;
+template <int EPI, int WGM>
+__global__ void __launch_bounds__(WGM * 256, 2) gemm_wreg_kernel(GemmArgs g) {
+  constexpr int BM = WGM * 128, BN = 256, WGN = 4, BK = 64, NT = WGM * 256, NS = 3;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
   constexpr int ROWB = BK * 2, A_CH = BM * 8 / NT, STAGE = BM * ROWB;
   static_assert(TN == 2 && A_CH == 4, "the waits below count 4 A loads per tile and 2 W loads per step");
@@ -465,7 +465,7 @@ __global__ void __launch_bounds__(512) gemm_wreg_kernel(GemmArgs g) {
   wait_vmem_for<0>(w[0][1], w[1][1]);
   wait_vmem_for<0>(w[0][2], w[1][2]);
   wait_vmem_for<0>(w[0][3], w[1][3]);
-  if constexpr (EPI == EPI_BF16 || EPI == EPI_SWIGLU_BF16) {
+  if constexpr ((EPI == EPI_BF16 || EPI == EPI_SWIGLU_BF16) && WGM == 2) {
     // bf16 outputs leave through LDS: a lane holds one column of its accumulator blocks, so stored directly a wave
     // instruction writes 64-byte pieces of rows; staged as a [rows][columns] image in the (now free) A stages, every
     // lane stores 16 bytes and a row of the tile goes out as whole 128-byte lines.
@@ -578,10 +578,12 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   constexpr int NT = WGM * WGN * 64, BK = 64;
   constexpr size_t lds_dl = GEMM_DL_LDS_BASE + NS * (size_t)(BM + BN) * BK * sizeof(bf16);
   constexpr size_t lds_wreg = GEMM_DL_LDS_BASE + 3 * (size_t)BM * BK * sizeof(bf16);    // gemm_wreg_kernel: three stages of the A tile
-  constexpr bool WREG = BM == 256 && BN == 256;     // packed W: the large prefill tile takes its W operands straight from global memory
-  void (*kern)(GemmArgs) = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
+  // packed W: tiles of 256 columns with wave tiles of 128 x 64 take their W operands straight from global memory
+  constexpr bool WREG = BN == 256 && WGN == 4 && BM == WGM * 128;
+  void (*kern)(GemmArgs) = nullptr;
   void (*kern_rowmajor)(GemmArgs) = nullptr;       // row-major W: the fp32-store epilogue only (callers that bring their own weights)
-  if constexpr (WREG) kern = gemm_wreg_kernel<EPI>;
+  if constexpr (WREG) kern = gemm_wreg_kernel<EPI, WGM>;
+  else kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
   if constexpr (EPI == EPI_F32) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false>;
   if (!g.w_packed && !kern_rowmajor) return hipErrorInvalidValue;
   const size_t lds = !g.w_packed ? lds_dl : WREG ? lds_wreg : lds_dl;
@@ -625,14 +627,18 @@ static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int spli
     case GEMM_64x256: return launch_cfg<64, 256, 1, 8, EPI, 3>(s, g, splits, tail);
     case GEMM_64x128: return launch_cfg<64, 128, 1, 4, EPI, 3>(s, g, splits, tail);
     case GEMM_256x256: return launch_cfg<256, 256, 2, 4, EPI, 2>(s, g, splits, tail);
+    case GEMM_128x256: return launch_cfg<128, 256, 1, 4, EPI, 2>(s, g, splits, tail);
     default: return hipErrorInvalidValue;
   }
 }
 
-int gemm_tile_n(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 ? 256 : 128; }
-int gemm_tile_m(int cfg) { return cfg == GEMM_256x256 ? 256 : cfg == GEMM_128x128 ? 128 : 64; }
-// resident workgroups per CU: the 8-wave tiles fill a CU, the 4-wave tiles share it in pairs
-int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 ? 1 : 2; }
+int gemm_tile_n(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 || cfg == GEMM_128x256 ? 256 : 128; }
+int gemm_tile_m(int cfg) { return cfg == GEMM_256x256 ? 256 : cfg == GEMM_128x128 || cfg == GEMM_128x256 ? 128 : 64; }
+// Workgroups per CU the launch plan counts: the 8-wave tiles fill a CU, the 4-wave tiles share it in pairs. The 128x256
+// tile (4 waves, wave tiles of 128 x 64) is planned one per CU although two fit: it is the shape for launches with little
+// more than one tile per CU, where the whole tiles take one slot of every CU and the K pieces of the surplus tiles run
+// beside them in the second.
+int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 || cfg == GEMM_128x256 ? 1 : 2; }
 
 // C = A * W^T with the chosen tile configuration and epilogue. Requirements (checked):
 // K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1; W packed (ldw == K) or,
@@ -646,6 +652,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
   if (cfg == GEMM_256x256 && (epi == EPI_BF16 || epi == EPI_SWIGLU_BF16) && ldc % 8 != 0) return hipErrorInvalidValue;   // 16-byte output stores
   if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_64x256) return hipErrorInvalidValue;   // its wave tile is one 32-column block, not a gate/up pair
+  if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_128x256) return hipErrorInvalidValue;  // not instantiated: the shape serves the O and down projections
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.split_stride = split_stride; g.w_packed = w_packed ? 1 : 0;

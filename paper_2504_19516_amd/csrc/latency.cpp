@@ -246,12 +246,13 @@ bool parse_profile(const std::string& text, Profile* hw) {
     else if (key == "tile_n") hw->tile_n = v; else if (key == "tile_q") hw->tile_q = v; else if (key == "wgs_per_cu") hw->wgs_per_cu = v; else if (key == "use_waveq") hw->use_waveq = v;
     else if (key == "tail_cut") hw->tail_cut = v;
     else if (key == "gemm_rate_128") hw->gemm_rate_128 = v; else if (key == "gemm_rate_256") hw->gemm_rate_256 = v;
+    else if (key == "gemm_rate_128x256") hw->gemm_rate_128x256 = v; else if (key == "gemm_fixed_128x256") hw->gemm_fixed_128x256 = v;
     else if (key == "partial_bw_cu") hw->partial_bw_cu = v;
     else return false;
   }
   return header && hw->n_cu > 0 && hw->granule > 0 && hw->c_peak > 0 && hw->d_peak > 0 && hw->n_d > 0 && hw->tile_m > 0 &&
          hw->tile_n > 0 && hw->tile_q > 0 && hw->wgs_per_cu > 0 && hw->tail_cut >= 0 && hw->tail_cut <= 64 &&
-         hw->gemm_rate_128 > 0 && hw->gemm_rate_256 > 0 && hw->partial_bw_cu > 0;
+         hw->gemm_rate_128 > 0 && hw->gemm_rate_256 > 0 && hw->gemm_rate_128x256 > 0 && hw->gemm_fixed_128x256 >= 0 && hw->partial_bw_cu > 0;
 }
 
 static void dump_grid(std::ostringstream& o, const char* name, const Grid& g) {
@@ -265,7 +266,7 @@ std::string dump_profile(const Profile& hw) {
   o << "sts-profile 1\n";
   o << "n_cu " << hw.n_cu << "\ngranule " << hw.granule << "\nc_peak " << hw.c_peak << "\nd_peak " << hw.d_peak << "\nn_d " << hw.n_d
     << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nwgs_per_cu " << hw.wgs_per_cu << "\nuse_waveq " << hw.use_waveq << "\ntail_cut " << hw.tail_cut
-    << "\ngemm_rate_128 " << hw.gemm_rate_128 << "\ngemm_rate_256 " << hw.gemm_rate_256 << "\npartial_bw_cu " << hw.partial_bw_cu << "\n";
+    << "\ngemm_rate_128 " << hw.gemm_rate_128 << "\ngemm_rate_256 " << hw.gemm_rate_256 << "\ngemm_rate_128x256 " << hw.gemm_rate_128x256 << "\ngemm_fixed_128x256 " << hw.gemm_fixed_128x256 << "\npartial_bw_cu " << hw.partial_bw_cu << "\n";
   dump_grid(o, "bw", hw.bw);
   dump_grid(o, "prefill_corun", hw.prefill_corun);
   dump_grid(o, "alpha_prefill", hw.alpha_prefill);
@@ -290,10 +291,13 @@ extern "C" int sts_wave_quant(int64_t g, int64_t n, int64_t b, int64_t* waves, i
   if (idle_den) *idle_den = n * w;
   return STS_OK;
 }
-extern "C" int sts_profile_tile_model(const sts_profile* p, int64_t* gemm_rate_128, int64_t* gemm_rate_256, int64_t* partial_bw_cu) {
+extern "C" int sts_profile_tile_model(const sts_profile* p, int64_t* gemm_rate_128, int64_t* gemm_rate_256, int64_t* gemm_rate_128x256,
+                                      int64_t* gemm_fixed_128x256, int64_t* partial_bw_cu) {
   if (!p) return STS_EINVAL;
   if (gemm_rate_128) *gemm_rate_128 = p->hw.gemm_rate_128;
   if (gemm_rate_256) *gemm_rate_256 = p->hw.gemm_rate_256;
+  if (gemm_rate_128x256) *gemm_rate_128x256 = p->hw.gemm_rate_128x256;
+  if (gemm_fixed_128x256) *gemm_fixed_128x256 = p->hw.gemm_fixed_128x256;
   if (partial_bw_cu) *partial_bw_cu = p->hw.partial_bw_cu;
   return STS_OK;
 }

@@ -22,8 +22,10 @@ struct Profile {
   int64_t tile_m = 256, tile_n = 256, tile_q = 128, wgs_per_cu = 1, use_waveq = 1;
   int64_t tail_cut = 0;                // > 0: GEMMs cut a partly filled last wave along K into at most this many pieces
   // Measured on the part by the offline profiler and read by the engine's tile choice (not by the estimator):
-  // GFLOP/s per busy CU of the 128x128 and the 256x256 GEMM tiles, MB/s per CU for partial tiles written and read back.
-  int64_t gemm_rate_128 = 3500, gemm_rate_256 = 4800, partial_bw_cu = 20000;
+  // GFLOP/s per busy CU of the 128x128, the 256x256 and the 128x256 GEMM tiles, MB/s per CU for partial tiles written and
+  // read back. The 128x256 tile runs one per CU, so its start-up and epilogue are not hidden behind another workgroup:
+  // its time is gemm_fixed_128x256 ns plus the flops at gemm_rate_128x256.
+  int64_t gemm_rate_128 = 3500, gemm_rate_256 = 4800, gemm_rate_128x256 = 5000, gemm_fixed_128x256 = 25000, partial_bw_cu = 20000;
   Grid bw;                             // D_{p,sl}; empty = use D_peak min(1, N_p/N_d)
   Grid prefill_corun;                  // slowdown (ppm, over the decode CUs beside it) of a prefill slice that shares HBM with a
                                        // running decode step; empty = none. Section 3.2.3 measures this side of the contention as

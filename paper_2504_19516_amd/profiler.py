@@ -22,7 +22,7 @@ PPM = 1_000_000
 def profile_text(hw: dict, grids: dict) -> str:
     lines = ["sts-profile 1"]
     for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut",
-              "gemm_rate_128", "gemm_rate_256", "partial_bw_cu"):
+              "gemm_rate_128", "gemm_rate_256", "gemm_rate_128x256", "gemm_fixed_128x256", "partial_bw_cu"):
         lines.append(f"{k} {int(hw[k])}")
     for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         if name not in grids:
@@ -46,7 +46,7 @@ class Profiler:
         self.n_cu = self.eng.get_partition()[2]
         self.hw = dict(n_cu=self.n_cu, granule=granule, c_peak=2_500_000, d_peak=8_000, n_d=self.n_cu, tile_m=128, tile_n=128,
                        tile_q=128, wgs_per_cu=2, use_waveq=1, tail_cut=16,
-                       gemm_rate_128=3500, gemm_rate_256=4800, partial_bw_cu=20000)      # the library's defaults until measured
+                       gemm_rate_128=3500, gemm_rate_256=4800, gemm_rate_128x256=5000, gemm_fixed_128x256=25000, partial_bw_cu=20000)      # the library's defaults until measured
         self.max_tokens = max_tokens
         self.grids = {}
 
@@ -147,6 +147,8 @@ class Profiler:
         cus = max(self.granule, self.n_cu - self.granule)
         m = min(2048, self.max_tokens) // 256 * 256
         d = self.desc
+        if m:
+            self.prefill_ns(cus, m, layers=1, reps=0)          # the probes run on what the workspace holds: real activations
         for key, name, tm, tn, per_cu in (("gemm_rate_128", "128x128", 128, 128, 2), ("gemm_rate_256", "256x256", 256, 256, 1)):
             slots, rows = per_cu * cus, m // tm if m else 0
             if not rows or slots % rows:
@@ -160,9 +162,24 @@ class Profiler:
             rate = 2 * m * n * d.hidden / ns / cus             # GFLOP/s per busy CU
             self.hw[key] = int(rate)
             log(f"{name} tiles, {m} x {n} x {d.hidden} on {cus} CUs ({waves} whole waves): {ns / 1e3:.1f} us -> {rate / 1e3:.2f} TFLOP/s per busy CU")
+        # 128x256 tiles run one per CU (the O and down projections: little more than one tile per CU), so a tile's start-up
+        # and residual epilogue are exposed: time one wave of tiles of both projections and fit fixed + flops / rate
+        rows = m // 128 if m else 0
+        if rows and cus % rows == 0 and cus // rows * 256 <= d.hidden:
+            n = cus // rows * 256
+            qd = d.n_q_heads * d.head_dim
+            t_o = self.eng.probe_gemm(cus, "128x256", m, n, iters=20, product="o") / 20
+            t_d = self.eng.probe_gemm(cus, "128x256", m, n, iters=20, product="down") / 20
+            if d.mlp > qd and t_d > t_o:
+                rate = 2 * 128 * 256 * (d.mlp - qd) / (t_d - t_o)              # flop/ns = GFLOP/s of one CU
+                fixed = max(0.0, t_o - 2 * 128 * 256 * qd / rate)
+                self.hw["gemm_rate_128x256"], self.hw["gemm_fixed_128x256"] = int(rate), int(fixed)
+                log(f"128x256 tiles, one per CU on {cus} CUs, {m} x {n}: K = {qd} {t_o / 1e3:.1f} us, K = {d.mlp} {t_d / 1e3:.1f} us -> "
+                    f"{fixed / 1e3:.1f} us + flops at {rate / 1e3:.2f} TFLOP/s per CU")
         self.hw["partial_bw_cu"] = int(bws[cus] / cus * 1e3)
         log(f"partial tiles: {self.hw['partial_bw_cu'] / 1e3:.1f} GB/s per CU (copy probe on {cus} CUs)")
-        self.eng.set_tile_model(self.hw["gemm_rate_128"], self.hw["gemm_rate_256"], self.hw["partial_bw_cu"])
+        self.eng.set_tile_model(self.hw["gemm_rate_128"], self.hw["gemm_rate_256"], self.hw["gemm_rate_128x256"], self.hw["gemm_fixed_128x256"],
+                                self.hw["partial_bw_cu"])
 
     def sweep_contention(self, dms=(32, 64, 128, 192), sls=(0, 2048, 8192), log=print):
         vals = [[int(self.corun_copy_bw(dm, sl)) for sl in sls] for dm in dms]

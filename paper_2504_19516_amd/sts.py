@@ -17,7 +17,7 @@ _lib = None
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 K_NAMES = ["embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup", "swiglu", "down", "reduce", "head", "sample"]
-GEMM_CFGS = {"128x128": 0, "64x256": 1, "64x128": 2, "256x256": 3}
+GEMM_CFGS = {"128x128": 0, "64x256": 1, "64x128": 2, "256x256": 3, "128x256": 4}
 INF_NS = 1 << 60
 
 
@@ -302,14 +302,16 @@ class Engine:
     def set_partition(self, prefill_cus, decode_cus):
         _ck(lib().sts_set_partition(self._ctx, prefill_cus, decode_cus), "sts_set_partition")
 
-    def set_tile_model(self, gemm_rate_128, gemm_rate_256, partial_bw_cu):
-        """GFLOP/s per busy CU of the two prefill tile shapes and MB/s per CU for partial tiles (Profile.tile_model())."""
-        _ck(lib().sts_set_tile_model(self._ctx, C.c_int64(int(gemm_rate_128)), C.c_int64(int(gemm_rate_256)), C.c_int64(int(partial_bw_cu))),
-            "sts_set_tile_model")
+    def set_tile_model(self, gemm_rate_128, gemm_rate_256, gemm_rate_128x256, gemm_fixed_128x256, partial_bw_cu):
+        """GFLOP/s per busy CU of the three prefill tile shapes, the fixed ns of a 128x256 tile and MB/s per CU for partial
+        tiles (Profile.tile_model())."""
+        _ck(lib().sts_set_tile_model(self._ctx, C.c_int64(int(gemm_rate_128)), C.c_int64(int(gemm_rate_256)), C.c_int64(int(gemm_rate_128x256)),
+                                     C.c_int64(int(gemm_fixed_128x256)), C.c_int64(int(partial_bw_cu))), "sts_set_tile_model")
 
-    def probe_gemm(self, cus, tile_cfg, m, n, iters=10):
+    def probe_gemm(self, cus, tile_cfg, m, n, iters=10, product="gateup"):
         ns = C.c_int64()
-        _ck(lib().sts_probe_gemm(self._ctx, cus, GEMM_CFGS[tile_cfg], m, n, iters, C.byref(ns)), "sts_probe_gemm")
+        _ck(lib().sts_probe_gemm(self._ctx, cus, GEMM_CFGS[tile_cfg], {"gateup": 0, "o": 1, "down": 2}[product], m, n, iters, C.byref(ns)),
+            "sts_probe_gemm")
         return ns.value
 
     def get_partition(self):
@@ -406,9 +408,9 @@ class Profile:
             self._p = C.c_void_p()
 
     def tile_model(self):
-        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
-        _ck(lib().sts_profile_tile_model(self._p, C.byref(a), C.byref(b), C.byref(c)), "sts_profile_tile_model")
-        return a.value, b.value, c.value
+        v = [C.c_int64() for _ in range(5)]
+        _ck(lib().sts_profile_tile_model(self._p, *[C.byref(x) for x in v]), "sts_profile_tile_model")
+        return tuple(x.value for x in v)
 
     def dump(self) -> str:
         need = C.c_size_t()
