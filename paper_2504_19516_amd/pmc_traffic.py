@@ -27,7 +27,8 @@ import subprocess
 
 COPY_BYTES = 512 << 20                     # bench.py --pmc-probe: bytes read (and bytes written) per copy launch
 GATEUP_KERNEL = "gemm_wreg_kernel"         # the 256 x 256 prefill tile; its SwiGLU instantiation is the gate/up GEMM
-GATEUP_PATTERN = r"gemm_wreg_kernel<3>|gemm_wreg_kernelILi3E"    # SwiGLU epilogue = template argument 3, demangled or mangled name
+# SwiGLU epilogue = first template argument 3 (the second is the tile's wave rows: 2 = 256 x 256), demangled or mangled name
+GATEUP_PATTERN = r"gemm_wreg_kernel<3, 2>|gemm_wreg_kernelILi3ELi2E"
 COPY_KERNEL = "copy_kernel"
 # kernels that only the decode phase launches; one attn_decode_mfma launch = one decode layer-step.
 # (Its embedding and first RMSNorm launches share kernels with the prefill phase and are left out:

@@ -155,8 +155,8 @@ def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, m
     benchmarked partitions' queues count."""
     import sys
     from paper_2504_19516_amd import pmc_traffic
-    gateup = "void sts::gemm_wreg_kernel<3>(sts::GemmArgs)"
-    other = "void sts::gemm_wreg_kernel<0>(sts::GemmArgs)"
+    gateup = "void sts::gemm_wreg_kernel<3, 2>(sts::GemmArgs)"
+    other = "void sts::gemm_wreg_kernel<0, 2>(sts::GemmArgs)"
     skinny = "void sts::gemm_dl_kernel<64, 128, 1, 4, 1, 3, true>(sts::GemmArgs)"
     attn = "void sts::attn_decode_mfma_kernel<128, 4>(args)"
     copy = "sts::copy_kernel(a, b, c)"
