@@ -71,7 +71,9 @@ int sts_destroy(sts_ctx* ctx);
  * alive; afterwards sts_init returns STS_ESTATE (masked streams are not created a second time in one
  * process). For programs that load the HIP runtime late (an interpreter) and run under a profiler
  * whose exit handler walks the queues still open: a masked stream left open there has ended such
- * runs with a fault after all output was written. */
+ * runs with a fault after all output was written. Destroying a masked stream after work has run on it
+ * has twice been seen not to return on this software stack: call this only where a kill timer guards
+ * the process (profiler runs); a program that simply exits needs no call. */
 int sts_release_streams(void);
 /* Longest block table sts_init accepts: decode attention cuts a context into at most 128 chunks of
  * at most 64 pages (Section 3.5.1's pool is shared, a sequence's share of it is bounded by this). */

@@ -195,6 +195,55 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(bf16* out, const float* X,
     }
   }
 }
+// Embedding rows and the first layer's RMSNorm in one pass: the row is in registers anyway, so the residual stream
+// (fp32) and its normalised bf16 copy are written together and the stream is not read back. One workgroup per row,
+// 8 elements per thread and 2048-column slab, rows of up to 8192 elements.
+__global__ void __launch_bounds__(256) embed_norm_kernel(float* X, bf16* out, const bf16* emb, const int* tokens, const float* gain, float eps, int h) {
+  constexpr int PER = 4;
+  __shared__ float red[4];
+  const int row = blockIdx.x;
+  const bf16* e = emb + (size_t)tokens[row] * h;
+  bf16x8 v[PER];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; i++) {
+    const int c = threadIdx.x * 8 + i * 2048;
+    if (c < h) {
+      v[i] = *reinterpret_cast<const bf16x8*>(e + c);
+#pragma unroll
+      for (int j = 0; j < 8; j++) { const float f = bf2f(v[i][j]); ss += f * f; }
+    }
+  }
+  const float w = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
+  __syncthreads();
+  const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)h + eps);
+#pragma unroll
+  for (int i = 0; i < PER; i++) {
+    const int c = threadIdx.x * 8 + i * 2048;
+    if (c < h) {
+      float* x = X + (size_t)row * h + c;
+      const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c), g1 = *reinterpret_cast<const f32x4*>(gain + c + 4);
+      f32x4 x0, x1;
+      bf16x8 o;
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        x0[j] = bf2f(v[i][j]); x1[j] = bf2f(v[i][j + 4]);
+        o[j] = f2bf(x0[j] * inv * g0[j]); o[j + 4] = f2bf(x1[j] * inv * g1[j]);
+      }
+      *reinterpret_cast<f32x4*>(x) = x0;
+      *reinterpret_cast<f32x4*>(x + 4) = x1;
+      *reinterpret_cast<bf16x8*>(out + (size_t)row * h + c) = o;
+    }
+  }
+}
+hipError_t embed_norm_rows(hipStream_t s, float* X, bf16* out, const bf16* emb, const int* tokens, const float* gain, float eps, int n, int h) {
+  if (n == 0) return hipSuccess;
+  if (h > 8192 || h % 8 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(embed_norm_kernel, dim3(n), dim3(256), 0, s, X, out, emb, tokens, gain, eps, h);
+  return hipGetLastError();
+}
+
 hipError_t rmsnorm_rows(hipStream_t s, bf16* out, const float* X, const float* gain, float eps, int n, int h) {
   if (n == 0) return hipSuccess;
   if (n >= 1024) hipLaunchKernelGGL((rmsnorm_kernel<2, 4>), dim3((n + 1) / 2), dim3(256), 0, s, out, X, gain, eps, h, n);

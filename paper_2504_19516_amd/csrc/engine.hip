@@ -460,11 +460,13 @@ int prefill_launch_body(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32
   HIPCK(hipEventRecord(ph.ev0, st));
   if (lb == 0) std::memcpy(ph.h_tokens, tokens, rows * sizeof(int));
   HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
-  if (lb == 0) KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, rows, d.hidden));
   const int h = d.hidden;
+  const bool fused_embed = lb == 0 && h <= 8192;             // the embedding kernel also writes layer 0's normalised rows
+  if (fused_embed) KL(ph, STS_K_EMBED, embed_norm_rows(st, ph.X, ph.Xn, c->emb, ph.d_tokens, c->layers[0].g1, d.rms_eps, rows, h));
+  else if (lb == 0) KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, rows, h));
   for (int l = lb; l < le; l++) {
     const LayerW& w = c->layers[l];
-    KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g1, d.rms_eps, rows, h));
+    if (!(fused_embed && l == 0)) KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, w.g1, d.rms_eps, rows, h));
     KL(ph, STS_K_QKV, prefill_gemm(c, ph, EPI_BF16, ph.Xn, h, w.wqkv, h, ph.QKV, c->qkvn, rows, c->qkvn, h));
     KL(ph, STS_K_ROPE, rope_kv_write_prefill(st, ph.QKV, c->qkvn, ph.d_pseq, n_seqs, ph.d_bt, c->inv_freq, layer_pool(c, l), c->geo, rows, d.n_q_heads));
     KL(ph, STS_K_ATTN, attn_prefill(st, ph.QKV, c->qkvn, ph.A, c->qd, ph.d_pseq, ph.d_items, n_items, ph.d_bt, layer_pool(c, l), c->geo, d.n_q_heads));
@@ -599,9 +601,13 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
   hipStream_t st = ph.stream;
   HIPCK(hipEventRecord(ph.ev0, st));
   HIPCK(hipMemcpyAsync(ph.d_meta, ph.h_meta, ph.meta_used, hipMemcpyHostToDevice, st));
-  KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, n, d.hidden));
   const int h = d.hidden;
-  KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, c->layers[0].g1, d.rms_eps, n, h));
+  if (h <= 8192) {
+    KL(ph, STS_K_EMBED, embed_norm_rows(st, ph.X, ph.Xn, c->emb, ph.d_tokens, c->layers[0].g1, d.rms_eps, n, h));
+  } else {
+    KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, n, h));
+    KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, c->layers[0].g1, d.rms_eps, n, h));
+  }
   auto skinny = [&](int kind, const bf16* A, int lda, const bf16* W, int N, int K, int* splits_out, long long* stride_out) -> int {
     const long long stride = (long long)n * N;
     *stride_out = stride;

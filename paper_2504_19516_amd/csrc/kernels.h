@@ -74,6 +74,8 @@ hipError_t export_weight(hipStream_t s, float* dst, const bf16* src, int ld, int
                          int row_offset, int interleave_block, int interleave_phase, int packed);
 hipError_t fill_f32(hipStream_t s, float* dst, float v, size_t n);
 hipError_t embed_rows(hipStream_t s, float* X, const bf16* emb, const int* tokens, int n, int h);
+// embedding rows into the fp32 residual stream X and, in the same pass, their RMSNorm into out (bf16); h <= 8192
+hipError_t embed_norm_rows(hipStream_t s, float* X, bf16* out, const bf16* emb, const int* tokens, const float* gain, float eps, int n, int h);
 hipError_t rmsnorm_rows(hipStream_t s, bf16* out, const float* X, const float* gain, float eps, int n, int h);
 hipError_t gather_rows_f32(hipStream_t s, float* dst, const float* src, const int* rows, int n, int h);
 hipError_t rope_kv_write_prefill(hipStream_t s, bf16* qkv, int ld, const PrefillSeq* seqs, int n_seqs,
