@@ -211,6 +211,11 @@ int sts_set_tile_model(sts_ctx* ctx, int64_t gemm_rate_128, int64_t gemm_rate_25
 /* ---- single operations on host data, for per-kernel parity tests. Inputs are fp32 and are
  * rounded to bf16 on upload; outputs are the kernel's fp32 accumulators (or its bf16 result
  * widened). They use the default stream and their own temporary device buffers. */
+/* Host-only: element index of W[row][col] (ld = K columns, a multiple of 64) in the packed layout the GEMM weights are
+ * kept in -- blocks of 32 rows x 64 columns, each four 1 KiB pieces in the order the matrix cores take a W operand
+ * (lane 32 h + n of a wave holds W[row n][16 step + 8 h .. + 8)). -1 for arguments out of range. Needs no GPU. */
+int64_t sts_weight_packed_index(int32_t row, int32_t col, int32_t ld);
+
 /* C[M,N] = A[M,K] * W[N,K]^T. tile_cfg: STS_GEMM_*; epilogue 0 = bf16 store, 1 = fp32 store
  * (split_k >= 1 partial sums are added up on the device), 2 = C += (C given in c_inout),
  * 3 = SwiGLU: W holds gate rows then up rows ([2*N2, K]); output [M, N2].

@@ -51,6 +51,11 @@ int download_bf16(DevBufs& b, float* host, const bf16* dev, size_t n) {
 
 }  // namespace
 
+extern "C" int64_t sts_weight_packed_index(int32_t row, int32_t col, int32_t ld) {
+  if (row < 0 || col < 0 || ld < 64 || ld % 64 != 0 || col >= ld) return -1;
+  return (int64_t)weight_packed_index(row, col, ld);
+}
+
 extern "C" int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                            int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots) {
   if (!a || !w || !c_inout || m < 1 || n < 1 || k < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG) return STS_EINVAL;

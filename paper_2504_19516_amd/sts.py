@@ -92,7 +92,7 @@ EXPORTS = [
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_op_gemm_noalloc", "sts_probe_gemm", "sts_set_tile_model",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_op_gemm_noalloc", "sts_weight_packed_index", "sts_probe_gemm", "sts_set_tile_model",
     "sts_profile_tile_model",
 ]
 

@@ -35,6 +35,28 @@ def test_library_exports_every_declared_symbol(sts):
     assert sorted(sts.EXPORTS) == names
 
 
+def test_packed_weight_layout_is_the_documented_operand_order(sts):
+    """The packed GEMM weight layout, checked on the host against its definition: 32 x 64 blocks along K then along N,
+    a block = four 1 KiB pieces (one per 16-column step), lane 32 h + n of a piece holding the 8 consecutive elements
+    W[row n][16 step + 8 h .. + 8) -- and every element has exactly one place."""
+    import ctypes as C
+    f = sts.lib().sts_weight_packed_index
+    f.restype = C.c_int64
+    rows, ld = 96, 192
+    seen = set()
+    for r in range(rows):
+        for c in range(ld):
+            block = (r // 32) * (ld // 64) + c // 64
+            step, h, e = (c % 64) // 16, (c % 16) // 8, c % 8
+            lane = 32 * h + r % 32
+            want = block * 2048 + step * 512 + lane * 8 + e
+            got = f(r, c, ld)
+            assert got == want, (r, c, got, want)
+            seen.add(got)
+    assert seen == set(range(rows * ld))
+    assert f(0, ld, ld) == -1 and f(-1, 0, ld) == -1 and f(0, 0, 100) == -1
+
+
 def test_error_strings(sts):
     assert sts.lib().sts_strerror(0) == b"ok"
     assert b"invalid" in sts.lib().sts_strerror(sts.EINVAL)
