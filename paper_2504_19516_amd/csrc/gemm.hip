@@ -11,8 +11,9 @@
 // operand reads of the next 16-wide step are slotted between the MFMAs of the current one. It runs
 // the 128x128 tiles with 4 waves (two workgroups per CU) for prefill, the 64x128 (4 waves, two per
 // CU) and 64x256 (8 waves) tiles with split-K for decode batches, and row-major W of callers that
-// bring their own weights. gemm_wreg_kernel: the 256x256 prefill tile (8 waves); only the activation
-// tile goes through LDS, the W operands go from the packed weight layout straight into registers.
+// bring their own weights. gemm_wreg_kernel: the 256x256 (8 waves) and 128x256 (4 waves) prefill tiles;
+// only the activation tile goes through LDS, the W operands go from the packed weight layout straight
+// into registers.
 // Epilogues: bf16 store, fp32 store (split-K partial sums), fp32 residual add, SwiGLU on interleaved
 // gate/up rows.
 //
@@ -299,7 +300,9 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
   store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
 
-// ---- main loop of the 256 x 256 prefill tile: W operands straight from global memory -------------
+// ---- main loop of the 256-column prefill tiles: W operands straight from global memory -----------
+// (WGM = 2: 256 x 256, eight waves; WGM = 1: 128 x 256, four waves with the same 128 x 64 wave tiles, where no W
+// block is shared by two waves and the activation stages are 16 KB)
 // With both operands staged through LDS the 256 x 256 tile moves 256 KB through LDS per 64-wide K tile
 // (64 KB written by the tile loads, 192 KB read as operands by the 8 waves), which at 128 bytes per cycle
 // is as long as the tile's matrix-core work: the loop ran at the LDS's pace, not the MFMAs'. Here only the
@@ -307,8 +310,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
 // operands -- 64 columns, so two 32-row blocks of the packed layout -- directly into registers, one
 // 16-byte load per lane and 16-wide step from 1 KiB of consecutive memory. One register set serves: the
 // operands of step kk of the next K tile are requested right after step kk of this one has used them, a
-// whole iteration before they are needed. The two waves that share a column block load it twice; those
-// bytes come from L2.
+// whole iteration before they are needed. The two waves of a 256 x 256 tile that share a column block load
+// it twice; those bytes come from L2.
 //
 // A wave's vector-memory operations complete in order, and in iteration t it queues: the A loads of tile
 // t + 2 (4), then after each step kk the two W loads of (tile t + 1, step kk). When step kk of tile t waits
