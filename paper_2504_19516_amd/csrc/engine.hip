@@ -228,8 +228,8 @@ int k_collect(sts_ctx* c, Phase& ph) {
   } while (0)
 
 int pick_cfg(int m, int n, int k, int cus) {
-  // decode batches: 64x128 tiles, two workgroups (8 waves) per CU streaming weights
-  // (pick_decode_gemm may widen them to 64x256)
+  // up to 64 rows: 64x128 tiles, two workgroups (8 waves) per CU streaming weights (decode GEMMs whose N allows
+  // it take the skinny tiles instead, see pick_decode_gemm)
   if (m <= 64) return GEMM_64x128;
   // up to 128 rows: one row of 128x128 tiles, two workgroups per CU. Above that both shapes compute
   // 256 rows and the 256x256 tile's larger wave tiles run the MFMAs faster; a large decode batch
@@ -303,19 +303,54 @@ int pick_splits(const sts_ctx* ctx, int cfg, int m, int n, int k, int cus) {
   return std::max(1, std::min(s, s_max));
 }
 
-// Tile shape and split-K of one decode GEMM. Up to 64 rows the choice is between 64x128 tiles (two
-// workgroups per CU) and 64x256 tiles (one 8-wave workgroup per CU): the wide tile re-reads the
-// activation rows half as often, which measured 13 % faster per weight byte, but its rounds are
-// strict where two narrow workgroups per CU balance in half rounds.
-void pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool may_split, int* cfg, int* splits) {
-  *cfg = pick_cfg(m, n, k, cus);
-  *splits = may_split ? pick_splits(ctx, *cfg, m, n, k, cus) : 1;
-  if (*cfg != GEMM_64x128 || m <= 32 || n % 256 != 0) return;
+// Tile shape and split-K of one decode GEMM. Above 64 rows: the prefill shapes (pick_cfg) with a split that
+// fills the partition. Up to 64 rows the GEMM streams its weights once and runs at the pace at which the
+// partition's CUs pull bytes, and everything a workgroup reads counts: its K range of the W columns and, beside
+// them, the 64 activation rows of that range again for every workgroup. The candidates are the 64x128 tiles
+// through LDS and the skinny tiles of 4 to 8 waves (256 to 512 columns, 64 per wave; the four-wave tiles run two
+// workgroups per CU) whose width divides N, each with 1 .. 8 slices along K, and the estimate is
+//   rounds of workgroups x (bytes of the workgroups a CU holds / per-CU streaming rate + a start-up time),
+// not less than the weight bytes at the rate the memory system gives a whole GPU, plus -- when the output
+// leaves as fp32 partial sums for a reduce kernel -- those partial sums written and read back. A wide tile reads
+// the activations less often (a small partition is bound by what its CUs can pull); a narrow one, or a deeper
+// split, makes more workgroups (a large partition needs them all busy) and fills the last round better: with
+// 7 x 2^k columns (the MLP width of the Llama shapes) on 32 or 64 CUs only the 7-wave tile comes out in whole
+// rounds.
+// `partials`: the output goes through fp32 partial sums (a split needs that; the caller's next kernel reads them).
+// Returns the estimated seconds.
+double pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits) {
   const int c = std::max(cus, 8);
-  const int sw = may_split ? pick_splits(ctx, GEMM_64x256, m, n, k, cus) : 1;
-  const double t_narrow = 0.5 * (((long long)(n / 128) * *splits + c - 1) / c) / *splits;
-  const double t_wide = 0.87 * (((long long)(n / 256) * sw + c - 1) / c) / sw;
-  if (t_wide < 0.95 * t_narrow) { *cfg = GEMM_64x256; *splits = sw; }     // a near tie goes to the tiles that balance
+  constexpr double cu_rate = 55e9;       // bytes/s one CU pulls from memory when streaming (measured: 59e9 for plain reads)
+  constexpr double mem_rate = 5.5e12;    // bytes/s the memory system gives a full GPU of such streams
+  constexpr double start_s = 2.5e-6;     // a workgroup's first loads and its epilogue
+  auto estimate = [&](int cand, int s) {
+    const int bn = gemm_tile_n(cand), bm = gemm_tile_m(cand), per_cu = gemm_wgs_per_cu(cand);
+    const long long wgs = (long long)((m + bm - 1) / bm) * (n / bn) * s, slots = (long long)c * per_cu;
+    const long long rounds = (wgs + slots - 1) / slots, last = wgs - (rounds - 1) * slots;
+    const double wg_s = 2.0 * (k / s) * (bn + bm) / cu_rate;                      // one workgroup alone on its CU
+    // complete rounds hold per_cu workgroups on every CU; the last round what is left, dealt over the CUs
+    double t = ((rounds - 1) * per_cu + (last + c - 1) / c) * wg_s;
+    t = std::max(t, 2.0 * n * k / mem_rate) + rounds * start_s;
+    if (partials) t += 8.0 * s * m * n / (c * ctx->partial_bw);
+    return t;
+  };
+  if (m > 64 || n % 128 != 0) {
+    *cfg = pick_cfg(m, n, k, cus);
+    *splits = may_split ? pick_splits(ctx, *cfg, m, n, k, cus) : 1;
+    return estimate(*cfg, *splits);
+  }
+  const int s_max = may_split ? std::min(8, std::max(1, k / 512)) : 1;
+  double best_t = 1e300;
+  *cfg = GEMM_64x128; *splits = 1;
+  const int cands[6] = {GEMM_64x128, GEMM_64x256S, GEMM_64x320S, GEMM_64x384S, GEMM_64x448S, GEMM_64x512S};
+  for (int cand : cands) {
+    if (n % gemm_tile_n(cand) != 0) continue;
+    for (int s = 1; s <= s_max; s++) {
+      const double t = estimate(cand, s);
+      if (t < best_t - 1e-12) { best_t = t; *cfg = cand; *splits = s; }
+    }
+  }
+  return best_t;
 }
 
 int64_t now_ns();
@@ -612,7 +647,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     const long long stride = (long long)n * N;
     *stride_out = stride;
     int cfg, splits;
-    pick_decode_gemm(c, n, N, K, ph.cus, true, &cfg, &splits);
+    pick_decode_gemm(c, n, N, K, ph.cus, true, true, &cfg, &splits);
     *splits_out = splits;
     KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
     return STS_OK;
@@ -626,11 +661,14 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
     {
-      // gate/up: when the tiles fill the partition without a split along K, SwiGLU is the GEMM's epilogue
-      int gu_cfg, gu_splits;
-      pick_decode_gemm(c, n, 2 * d.mlp, h, ph.cus, true, &gu_cfg, &gu_splits);
-      if (gu_splits == 1 && gu_cfg == GEMM_64x128) {
-        KL(ph, STS_K_GATEUP, gemm_bf16(st, gu_cfg, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, n, 2 * d.mlp, h, 1, 0));
+      // gate/up: SwiGLU is the GEMM's epilogue unless cutting K, with its partial sums and the kernel that reduces them
+      // (taken as 4 us of launch and start-up), is estimated faster
+      int gu_cfg, gu_splits, fu_cfg, fu_splits;
+      const double t_split = pick_decode_gemm(c, n, 2 * d.mlp, h, ph.cus, true, true, &gu_cfg, &gu_splits) + 4e-6;
+      const double t_fused = pick_decode_gemm(c, n, 2 * d.mlp, h, ph.cus, false, false, &fu_cfg, &fu_splits);
+      const bool can_fuse = fu_cfg == GEMM_64x128 || (fu_cfg >= GEMM_64x256S && fu_cfg <= GEMM_64x512S);
+      if (can_fuse && (t_fused <= t_split || gu_splits == 1)) {
+        KL(ph, STS_K_GATEUP, gemm_bf16(st, fu_cfg, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, n, 2 * d.mlp, h, 1, 0));
       } else {
         STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
         KL(ph, STS_K_SWIGLU, reduce_swiglu(st, ph.H, ph.part, sp, ss, n, d.mlp));
@@ -642,7 +680,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
   }
   if (want_logits || want_next) {
     int head_cfg, head_splits;
-    pick_decode_gemm(c, n, d.vocab, h, ph.cus, false, &head_cfg, &head_splits);
+    pick_decode_gemm(c, n, d.vocab, h, ph.cus, false, false, &head_cfg, &head_splits);
     KL(ph, STS_K_HEAD, gemm_bf16(st, head_cfg, EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
     if (want_next) {
       KL(ph, STS_K_SAMPLE, argmax_rows(st, ph.next, ph.logits, n, d.vocab));

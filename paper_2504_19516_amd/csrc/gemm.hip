@@ -4,7 +4,7 @@
 // holds 8 consecutive k of one A row (or one W row). A workgroup owns a BM x BN tile and each of
 // its waves accumulates a (BM/WGM) x (BN/WGN) sub-tile in 32x32 MFMA blocks.
 //
-// Two main loops. gemm_dl_kernel: K tiles of 64 of both operands go global -> LDS directly (no
+// Three main loops. gemm_dl_kernel: K tiles of 64 of both operands go global -> LDS directly (no
 // staging registers, no LDS store instructions): activations into 128-byte rows whose 16-byte chunks
 // are XOR-swizzled so that the 16-byte operand reads are bank-conflict free, packed weights as the
 // operand-order blocks they are in memory; two or three LDS stages;
@@ -13,7 +13,8 @@
 // CU) and 64x256 (8 waves) tiles with split-K for decode batches, and row-major W of callers that
 // bring their own weights. gemm_wreg_kernel: the 256x256 (8 waves) and 128x256 (4 waves) prefill tiles;
 // only the activation tile goes through LDS, the W operands go from the packed weight layout straight
-// into registers.
+// into registers. gemm_skinny_kernel: the same for decode batches of up to 64 rows -- tiles of 256 to 512
+// columns, the W operands three K tiles deep in registers.
 // Epilogues: bf16 store, fp32 store (split-K partial sums), fp32 residual add, SwiGLU on interleaved
 // gate/up rows.
 //
@@ -32,6 +33,9 @@
 namespace sts {
 
 constexpr int GEMM_DL_LDS_BASE = 1024;   // the direct-to-LDS arena stays clear of LDS address 0
+#ifndef GEMM_SKINNY_PD
+#define GEMM_SKINNY_PD 3                 // K tiles of W operands a wave of gemm_skinny_kernel keeps in flight
+#endif
 
 struct GemmArgs {
   const bf16* A; const bf16* W; void* C;
@@ -433,7 +437,7 @@ __global__ void __launch_bounds__(WGM * 256, 2) gemm_wreg_kernel(GemmArgs g) {
       // queued after these operands: the W loads of the later steps of this tile (6 - 2 kk), the A loads of tile
       // t + 2 (4), the W loads of the earlier steps of the next tile (2 kk)
       wait_vmem_for<2 * TN + A_CH + 2>(w[0][kk], w[1][kk]);
-      if (kk == 3) {
+      if constexpr (kk == 3) {
         // every wave's A loads of tile t + 1 landed before its step-2 operands did: publish the tile, retire this one
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
@@ -516,6 +520,164 @@ __global__ void __launch_bounds__(WGM * 256, 2) gemm_wreg_kernel(GemmArgs g) {
   store_tile<BM, BN, WGM, WGN, EPI>(g, acc, m0, n0, piece, wm, wn, l32, lh);
 }
 
+// ---- decode batches (up to 64 rows per tile): weights streamed through registers, several K tiles deep ----
+// A decode GEMM reads every weight byte once and runs at the rate at which its CUs pull bytes from memory; what
+// a workgroup reads beside its weights -- the 64 activation rows of its K range, again for every workgroup --
+// comes out of that rate. A workgroup here is 4 to 8 waves (the launch's block size; a tile is 64 columns per
+// wave wide), so that a width can be chosen that divides N into whole rounds of workgroups on the partition
+// while the activation tile is shared by as many waves as possible. A wave reads the W operands of its 64
+// columns (two 32-row blocks of the packed layout) straight into registers and keeps PD K tiles of them -- 8 PD
+// loads of 1 KiB -- under way. Only the activation tile passes through LDS (PD + 2 stages of 8 KB, fetched by
+// the first four waves as in the loops above).
+//
+// Order of a wave's vector-memory operations (they complete in order): iteration t queues the A loads of
+// tile t + PD + 1 (2), then after each step kk the two W loads of (tile t + PD, step kk) into the registers
+// that step just used; the prologue queues A(0) and then, for s < PD, A(s + 1) and W(s) in the same order.
+// When step kk of tile t waits for its operands, 10 PD - 2 operations were queued after them (the W loads
+// of the later steps of tile t: 6 - 2 kk; A and W of the PD - 1 tiles between: 10 each; this iteration's A
+// loads: 2; its W loads so far: 2 kk), in every iteration: the last ones re-read the last K tile into
+// registers and stages nobody uses. A(t + 1) was queued before the operands step 3 of tile t waits for, so
+// it has landed at the barrier there, which also retires the stage of tile t for the A loads of iteration
+// t + 1.
+template <int EPI, int PD>
+__global__ void __launch_bounds__(512, 2) gemm_skinny_kernel(GemmArgs g) {
+  constexpr int BM = 64, BK = 64, NS = PD + 2, DUTY = 4;     // DUTY waves load the A tile
+  constexpr int TM = 2, TN = 2, ROWB = BK * 2, A_CH = BM * 8 / (DUTY * 64), STAGE = BM * ROWB;
+  constexpr int WAIT = 10 * PD - 2;
+  static_assert(A_CH == 2 && WAIT < 64, "the waits count 2 A loads per tile and 2 W loads per step, within vmcnt's range");
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* arena = smem + GEMM_DL_LDS_BASE;
+
+  int v, kbeg, kend, piece;
+  if (!block_work<BK>(g, &v, &kbeg, &kend, &piece)) return;
+  int tm, tn;
+  tile_coords(g, v, &tm, &tn);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int swave = __builtin_amdgcn_readfirstlane(wave);
+  const int wn = swave;
+  const int m0 = tm * BM, n0 = tn * (int)(blockDim.x >> 6) * 64;     // a tile is 64 columns per wave wide
+
+  const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.A + (size_t)m0 * g.lda);
+  // The first DUTY waves fetch the A tile. The others queue as many 16-byte loads of the tile's first bytes into a
+  // spare KB behind the stages, so that every wave's queue has the same shape and the waits below count alike.
+  const bool duty = swave < DUTY;
+  unsigned a_off[A_CH];
+#pragma unroll
+  for (int j = 0; j < A_CH; j++) {
+    const int q = j * (DUTY * 64) + (tid & (DUTY * 64 - 1)), row = q >> 3, ch = (q & 7) ^ ((row >> 1) & 7);
+    a_off[j] = duty ? (unsigned)(min(m0 + row, g.M - 1) - m0) * (unsigned)g.lda * 2u + ch * 16 : 0u;
+  }
+  auto issue_a = [&](int stage, int k) {
+    unsigned char* sa = duty ? arena + stage * STAGE + swave * 1024 : arena + NS * STAGE;
+    const unsigned char* ak = a_base + (size_t)k * 2;
+#pragma unroll
+    for (int j = 0; j < A_CH; j++) lds_dma16(ak, a_off[j], duty ? sa + j * (DUTY * 64) * 16 : sa);
+  };
+  const size_t wrow = (size_t)(g.K >> 6) * 4096;
+  const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.W) + (size_t)((n0 >> 5) + wn * TN) * wrow;
+  const unsigned w_lane = (unsigned)lane * 16u;
+  bf16x8 w[PD][TN][4];
+#pragma unroll
+  for (int s = 0; s < PD; s++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) w[s][j][kk][e] = 0;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  int koff[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; kk++) koff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 7)) * 16;
+  const int a_row = l32 * ROWB;
+
+  const int nk = (kend - kbeg) / BK;
+  auto tile_k = [&](int t) { return kbeg + min(t, nk - 1) * BK; };
+  issue_a(0, tile_k(0));
+#pragma unroll
+  for (int s = 0; s < PD; s++) {
+    issue_a(s + 1, tile_k(s + 1));
+    const unsigned char* wk = w_base + (size_t)(tile_k(s) >> 6) * 4096;
+#pragma unroll
+    for (int kk = 0; kk < 4; kk++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) load_w16(w[s][j][kk], wk + j * wrow, w_lane, kk);
+  }
+  wait_vmem<10 * PD>();                                      // A(0) has landed
+  __syncthreads();
+  bf16x8 af[2][TM];
+#pragma unroll
+  for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(arena + a_row + i * 32 * ROWB + koff[0]);
+
+  int cur = 0;                                               // stage of tile t
+  int ahead = PD + 1;                                        // stage of tile t + PD + 1
+  for (int t0 = 0; t0 < nk; t0 += PD) {
+    auto tile = [&](auto s_c) {
+      constexpr int s = decltype(s_c)::value;                // register set of tile t: t % PD
+      const int t = t0 + s;
+      const bool live = t < nk;                              // the surplus tiles of the last round only keep the queue's shape
+      const int nxt = cur + 1 == NS ? 0 : cur + 1;
+      const unsigned char* Ac = arena + cur * STAGE + a_row;
+      const unsigned char* An = arena + nxt * STAGE + a_row;
+      const unsigned char* wk = w_base + (size_t)(tile_k(t + PD) >> 6) * 4096;
+      __builtin_amdgcn_sched_barrier(0);
+      issue_a(ahead, tile_k(t + PD + 1));
+      auto step = [&](auto kk_c) {
+        constexpr int kk = decltype(kk_c)::value;
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmem_for<WAIT>(w[s][0][kk], w[s][1][kk]);
+        if constexpr (kk == 3) {
+          __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(An + i * 32 * ROWB + koff[0]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < TM; i++) af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(Ac + i * 32 * ROWB + koff[kk + 1]);
+        }
+        if (live) {
+#pragma unroll
+          for (int i = 0; i < TM; i++)
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], w[s][j][kk], acc[i][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < TN; j++) load_w16(w[s][j][kk], wk + j * wrow, w_lane, kk);
+      };
+      step(std::integral_constant<int, 0>{});
+      step(std::integral_constant<int, 1>{});
+      step(std::integral_constant<int, 2>{});
+      step(std::integral_constant<int, 3>{});
+      cur = nxt;
+      ahead = ahead + 1 == NS ? 0 : ahead + 1;
+    };
+    tile(std::integral_constant<int, 0>{});
+    if constexpr (PD > 1) tile(std::integral_constant<int, 1>{});
+    if constexpr (PD > 2) tile(std::integral_constant<int, 2>{});
+    if constexpr (PD > 3) tile(std::integral_constant<int, 3>{});
+    if constexpr (PD > 4) tile(std::integral_constant<int, 4>{});
+    if constexpr (PD > 5) tile(std::integral_constant<int, 5>{});
+  }
+  // the surplus loads of the last iterations must not land in registers the epilogue reuses
+#pragma unroll
+  for (int s = 0; s < PD; s++)
+#pragma unroll
+    for (int kk = 0; kk < 4; kk++) wait_vmem_for<0>(w[s][0][kk], w[s][1][kk]);
+  // a wave's 64 x 64 block: the tile store of a four-wave row, placed by the wave's index
+  store_tile<BM, 256, 1, 4, EPI>(g, acc, m0, n0, piece, 0, wn, l32, lh);
+}
+
 // Adds the tail pieces of each split tile in piece order and applies the epilogue. One thread per
 // four consecutive columns.
 template <int BM, int BN, int EPI>
@@ -583,16 +745,21 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   constexpr size_t lds_wreg = GEMM_DL_LDS_BASE + 3 * (size_t)BM * BK * sizeof(bf16);    // gemm_wreg_kernel: three stages of the A tile
   // packed W: tiles of 256 columns with wave tiles of 128 x 64 take their W operands straight from global memory
   constexpr bool WREG = BN == 256 && WGN == 4 && BM == WGM * 128;
+  // decode batches: 64-row tiles, 64 columns per wave, the W operands GEMM_SKINNY_PD tiles deep in registers
+  constexpr bool SKINNY = BM == 64 && WGM == 1 && BN == WGN * 64;
+  constexpr size_t lds_skinny = GEMM_DL_LDS_BASE + (size_t)(GEMM_SKINNY_PD + 2) * BM * BK * sizeof(bf16) + 1024;
   void (*kern)(GemmArgs) = nullptr;
   void (*kern_rowmajor)(GemmArgs) = nullptr;       // row-major W: the fp32-store epilogue only (callers that bring their own weights)
   if constexpr (WREG) kern = gemm_wreg_kernel<EPI, WGM>;
+  else if constexpr (SKINNY) kern = gemm_skinny_kernel<EPI, GEMM_SKINNY_PD>;
   else kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
-  if constexpr (EPI == EPI_F32) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false>;
+  if constexpr (EPI == EPI_F32 && !SKINNY) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false>;
   if (!g.w_packed && !kern_rowmajor) return hipErrorInvalidValue;
-  const size_t lds = !g.w_packed ? lds_dl : WREG ? lds_wreg : lds_dl;
+  constexpr size_t lds_packed = WREG ? lds_wreg : SKINNY ? lds_skinny : lds_dl;
+  const size_t lds = !g.w_packed ? lds_dl : lds_packed;
   static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
   if (!attr_set.load()) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(WREG ? lds_wreg : lds_dl));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_packed);
     if (e == hipSuccess && kern_rowmajor) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_rowmajor), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dl);
     if (e != hipSuccess) return e;
     attr_set.store(true);
@@ -618,8 +785,10 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   const int ny = (ksteps + per - 1) / per;
   if (!g.w_packed) kern = kern_rowmajor;
   hipLaunchKernelGGL(kern, dim3((g.full_per_xcd + g.piece_per_xcd) * 8, ny), dim3(NT), lds, s, g);
-  if (g.n_pieces > 0)
-    hipLaunchKernelGGL((gemm_tail_fixup<BM, BN, EPI>), dim3(tiles - g.n_full, BM * BN / 1024), dim3(256), 0, s, g);
+  if constexpr (!SKINNY) {
+    if (g.n_pieces > 0)
+      hipLaunchKernelGGL((gemm_tail_fixup<BM, BN, EPI>), dim3(tiles - g.n_full, BM * BN / 1024), dim3(256), 0, s, g);
+  }
   return hipGetLastError();
 }
 
@@ -631,17 +800,25 @@ static hipError_t launch_epi(hipStream_t s, int cfg, const GemmArgs& g, int spli
     case GEMM_64x128: return launch_cfg<64, 128, 1, 4, EPI, 3>(s, g, splits, tail);
     case GEMM_256x256: return launch_cfg<256, 256, 2, 4, EPI, 2>(s, g, splits, tail);
     case GEMM_128x256: return launch_cfg<128, 256, 1, 4, EPI, 2>(s, g, splits, tail);
+    case GEMM_64x256S: return launch_cfg<64, 256, 1, 4, EPI, 3>(s, g, splits, nullptr);
+    case GEMM_64x320S: return launch_cfg<64, 320, 1, 5, EPI, 3>(s, g, splits, nullptr);
+    case GEMM_64x384S: return launch_cfg<64, 384, 1, 6, EPI, 3>(s, g, splits, nullptr);
+    case GEMM_64x448S: return launch_cfg<64, 448, 1, 7, EPI, 3>(s, g, splits, nullptr);
+    case GEMM_64x512S: return launch_cfg<64, 512, 1, 8, EPI, 3>(s, g, splits, nullptr);
     default: return hipErrorInvalidValue;
   }
 }
 
-int gemm_tile_n(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 || cfg == GEMM_128x256 ? 256 : 128; }
+int gemm_tile_n(int cfg) {
+  if (cfg >= GEMM_64x256S && cfg <= GEMM_64x512S) return 256 + 64 * (cfg - GEMM_64x256S);
+  return cfg == GEMM_256x256 || cfg == GEMM_64x256 || cfg == GEMM_128x256 ? 256 : 128;
+}
 int gemm_tile_m(int cfg) { return cfg == GEMM_256x256 ? 256 : cfg == GEMM_128x128 || cfg == GEMM_128x256 ? 128 : 64; }
 // Workgroups per CU the launch plan counts: the 8-wave tiles fill a CU, the 4-wave tiles share it in pairs. The 128x256
 // tile (4 waves, wave tiles of 128 x 64) is planned one per CU although two fit: it is the shape for launches with little
 // more than one tile per CU, where the whole tiles take one slot of every CU and the K pieces of the surplus tiles run
 // beside them in the second.
-int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 || cfg == GEMM_128x256 ? 1 : 2; }
+int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 || cfg == GEMM_128x256 || cfg > GEMM_64x256S ? 1 : 2; }
 
 // C = A * W^T with the chosen tile configuration and epilogue. Requirements (checked):
 // K % 64 == 0, N % tile_n == 0, leading dimensions multiples of 8 elements, M >= 1; W packed (ldw == K) or,
@@ -667,6 +844,11 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
       switch (cfg) {   // instantiated only where the wave tile holds gate/up block pairs
         case GEMM_256x256: return launch_cfg<256, 256, 2, 4, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
         case GEMM_128x128: return launch_cfg<128, 128, 2, 2, EPI_SWIGLU_BF16, 2>(s, g, 1, tail);
+        case GEMM_64x256S: return launch_cfg<64, 256, 1, 4, EPI_SWIGLU_BF16, 3>(s, g, 1, nullptr);
+        case GEMM_64x320S: return launch_cfg<64, 320, 1, 5, EPI_SWIGLU_BF16, 3>(s, g, 1, nullptr);
+        case GEMM_64x384S: return launch_cfg<64, 384, 1, 6, EPI_SWIGLU_BF16, 3>(s, g, 1, nullptr);
+        case GEMM_64x448S: return launch_cfg<64, 448, 1, 7, EPI_SWIGLU_BF16, 3>(s, g, 1, nullptr);
+        case GEMM_64x512S: return launch_cfg<64, 512, 1, 8, EPI_SWIGLU_BF16, 3>(s, g, 1, nullptr);
         case GEMM_64x128: return launch_cfg<64, 128, 2, 2, EPI_SWIGLU_BF16, 3>(s, g, 1, tail);    // wave tiles of 32 x 64: one gate/up pair
         default: return hipErrorInvalidValue;
       }

@@ -7,7 +7,8 @@ namespace sts {
 // ---- GEMM -------------------------------------------------------------------------------
 enum GemmEpilogue { EPI_BF16 = 0, EPI_F32 = 1, EPI_RESID_F32 = 2, EPI_SWIGLU_BF16 = 3 };
 // the same numbering as STS_GEMM_* in sts.h
-enum GemmConfig { GEMM_128x128 = 0, GEMM_64x256 = 1, GEMM_64x128 = 2, GEMM_256x256 = 3, GEMM_128x256 = 4, GEMM_NCFG = 5 };
+enum GemmConfig { GEMM_128x128 = 0, GEMM_64x256 = 1, GEMM_64x128 = 2, GEMM_256x256 = 3, GEMM_128x256 = 4, GEMM_64x256S = 5, GEMM_64x320S = 6, GEMM_64x384S = 7,
+                  GEMM_64x448S = 8, GEMM_64x512S = 9, GEMM_NCFG = 10 };
 int gemm_tile_m(int cfg);
 int gemm_tile_n(int cfg);
 int gemm_wgs_per_cu(int cfg);                       // resident workgroups per CU of this configuration

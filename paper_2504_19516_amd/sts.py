@@ -17,7 +17,8 @@ _lib = None
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 K_NAMES = ["embed", "norm", "qkv", "rope", "attn", "attn_merge", "o", "gateup", "swiglu", "down", "reduce", "head", "sample"]
-GEMM_CFGS = {"128x128": 0, "64x256": 1, "64x128": 2, "256x256": 3, "128x256": 4}
+GEMM_CFGS = {"128x128": 0, "64x256": 1, "64x128": 2, "256x256": 3, "128x256": 4,
+             "64x256s": 5, "64x320s": 6, "64x384s": 7, "64x448s": 8, "64x512s": 9}
 INF_NS = 1 << 60
 
 

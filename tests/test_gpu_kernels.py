@@ -90,6 +90,39 @@ def test_gemm_swiglu_epilogue(sts, cfg, m):
     assert rel(got, ref) <= BF16_TOL
 
 
+SKINNY = [("64x256s", 256), ("64x320s", 320), ("64x384s", 384), ("64x448s", 448), ("64x512s", 512)]
+
+
+@pytest.mark.parametrize("cfg,width", SKINNY)
+@pytest.mark.parametrize("m,k,split", [(64, 64, 1), (37, 128, 1), (1, 192, 1), (64, 256, 1), (130, 576, 1), (64, 1024, 4), (50, 1088, 3), (8, 2048, 8)])
+def test_gemm_skinny_tiles_fp32(sts, cfg, width, m, k, split):
+    """The decode tiles (64 rows, 64 columns per wave, weights streamed into registers three K tiles deep): fewer K tiles than
+    the pipeline is deep, a K extent that leaves surplus iterations in its last round, rows that end inside a tile and more
+    than one tile of rows, slices along K of unequal length."""
+    n = 2 * width
+    a = synth.normal_bf16(21, (m, k))
+    w = synth.normal_bf16(22, (n, k), 0.05)
+    ref = T.op_linear(a.astype(np.float64), w.astype(np.float64))
+    assert rel(sts.op_gemm(a, w, cfg, epilogue=1, split_k=split), ref) <= 1e-5
+
+
+@pytest.mark.parametrize("cfg,width", SKINNY)
+@pytest.mark.parametrize("m,k", [(64, 448), (29, 128)])
+def test_gemm_skinny_tiles_epilogues(sts, cfg, width, m, k):
+    n = 2 * width
+    a = synth.normal_bf16(23, (m, k))
+    a64 = a.astype(np.float64)
+    w = synth.normal_bf16(24, (n, k), 0.1)
+    ref = T.op_linear(a64, w.astype(np.float64))
+    got = sts.op_gemm(a, w, cfg, epilogue=0)
+    assert rel(got, ref) <= BF16_TOL and np.array_equal(got, synth.to_bf16(got))
+    x = np.random.default_rng(25).standard_normal((m, n)).astype(np.float32)
+    assert rel(sts.op_gemm(a, w, cfg, epilogue=2, c_in=x), x.astype(np.float64) + ref) <= 1e-5
+    wg, wu = w[:width], w[width:]
+    ref3 = T.silu(T.op_linear(a64, wg.astype(np.float64))) * T.op_linear(a64, wu.astype(np.float64))
+    assert rel(sts.op_gemm(a, w, cfg, epilogue=3), ref3) <= BF16_TOL
+
+
 @pytest.mark.parametrize("cfg,m,n,slots", [("128x128", 300, 512, 8), ("128x128", 300, 512, 10), ("128x128", 300, 512, 40),
                                            ("128x128", 300, 512, 16), ("256x256", 513, 512, 4), ("256x256", 513, 512, 15),
                                            ("64x128", 64, 640, 4), ("128x256", 300, 768, 7), ("128x256", 513, 512, 8)])
