@@ -513,7 +513,9 @@ int prefill_launch_body(sts_ctx* c, int n_seqs, const int32_t* seqs, const int32
   if (le == d.n_layers && want_logits) {
     KL(ph, STS_K_HEAD, gather_rows_f32(st, ph.Xlast, ph.X, ph.d_rows, n_seqs, h));
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xlast_n, ph.Xlast, c->gf, d.rms_eps, n_seqs, h));
-    KL(ph, STS_K_HEAD, gemm_bf16(st, pick_cfg(n_seqs, d.vocab, h, ph.cus), EPI_F32, ph.Xlast_n, h, c->lm, h, ph.logits, d.vocab, n_seqs, d.vocab, h, 1, 0));
+    int head_cfg, head_splits;
+    pick_decode_gemm(c, n_seqs, d.vocab, h, ph.cus, false, false, &head_cfg, &head_splits);
+    KL(ph, STS_K_HEAD, gemm_bf16(st, head_cfg, EPI_F32, ph.Xlast_n, h, c->lm, h, ph.logits, d.vocab, n_seqs, d.vocab, h, 1, 0));
     HIPCK(hipMemcpyAsync(ph.h_logits, ph.logits, (size_t)n_seqs * d.vocab * sizeof(float), hipMemcpyDeviceToHost, st));
   }
   HIPCK(hipEventRecord(ph.ev1, st));
