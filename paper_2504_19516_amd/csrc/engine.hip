@@ -327,9 +327,13 @@ double pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool m
     const int bn = gemm_tile_n(cand), bm = gemm_tile_m(cand), per_cu = gemm_wgs_per_cu(cand);
     const long long wgs = (long long)((m + bm - 1) / bm) * (n / bn) * s, slots = (long long)c * per_cu;
     const long long rounds = (wgs + slots - 1) / slots, last = wgs - (rounds - 1) * slots;
-    const double wg_s = 2.0 * (k / s) * (bn + bm) / cu_rate;                      // one workgroup alone on its CU
+    const double wg_bytes = 2.0 * (k / s) * (bn + bm);
+    // one workgroup alone pulls what its loads in flight allow: about 10 GB/s per wave of a skinny tile on a busy
+    // memory system, 34 GB/s for the four waves of a tile staged through LDS
+    const double wg_rate = cand >= GEMM_64x256S ? std::min(cu_rate, 10e9 * (bn / 64)) : 34e9;
+    auto cu_time = [&](long long held) { return std::max(held * wg_bytes / cu_rate, wg_bytes / wg_rate); };
     // complete rounds hold per_cu workgroups on every CU; the last round what is left, dealt over the CUs
-    double t = ((rounds - 1) * per_cu + (last + c - 1) / c) * wg_s;
+    double t = (rounds - 1) * cu_time(per_cu) + cu_time((last + c - 1) / c);
     t = std::max(t, 2.0 * n * k / mem_rate) + rounds * start_s;
     if (partials) t += 8.0 * s * m * n / (c * ctx->partial_bw);
     return t;
@@ -342,9 +346,12 @@ double pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool m
   const int s_max = may_split ? std::min(8, std::max(1, k / 512)) : 1;
   double best_t = 1e300;
   *cfg = GEMM_64x128; *splits = 1;
-  const int cands[6] = {GEMM_64x128, GEMM_64x256S, GEMM_64x320S, GEMM_64x384S, GEMM_64x448S, GEMM_64x512S};
+  const int cands[6] = {GEMM_64x256S, GEMM_64x320S, GEMM_64x384S, GEMM_64x448S, GEMM_64x512S, GEMM_64x128};
   for (int cand : cands) {
     if (n % gemm_tile_n(cand) != 0) continue;
+    // a GEMM that keeps its output (no partial sums) may carry the SwiGLU epilogue, and the 64x128 tile's form of it
+    // (wave tiles of 32 x 64) is slow when a CU holds one workgroup: taken only if no skinny width divides N
+    if (!partials && cand == GEMM_64x128 && best_t < 1e300) continue;
     for (int s = 1; s <= s_max; s++) {
       const double t = estimate(cand, s);
       if (t < best_t - 1e-12) { best_t = t; *cfg = cand; *splits = s; }
