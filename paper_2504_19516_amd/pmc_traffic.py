@@ -35,7 +35,7 @@ COPY_KERNEL = "copy_kernel"
 # 64 rows, under 2 MB per step.)
 DECODE_STEP_KERNEL = "attn_decode_mfma_kernel"
 DECODE_KERNELS = (r"attn_decode_mfma_kernel", r"attn_decode_merge_kernel", r"decode_qkv_finish_kernel", r"reduce_resid_norm_kernel",
-                  r"reduce_swiglu_kernel", r"gemm_dl_kernel<64, |gemm_dl_kernelILi64E")
+                  r"reduce_swiglu_kernel", r"gemm_dl_kernel<64, |gemm_dl_kernelILi64E", r"gemm_skinny_kernel")
 
 
 def per_kernel(path, counter, queue_of=None):

@@ -180,6 +180,7 @@ def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, m
     gateup = "void sts::gemm_wreg_kernel<3, 2>(sts::GemmArgs)"
     other = "void sts::gemm_wreg_kernel<0, 2>(sts::GemmArgs)"
     skinny = "void sts::gemm_dl_kernel<64, 128, 1, 4, 1, 3, true>(sts::GemmArgs)"
+    skinny2 = "void sts::gemm_skinny_kernel<1, 3>(sts::GemmArgs)"
     attn = "void sts::attn_decode_mfma_kernel<128, 4>(args)"
     copy = "sts::copy_kernel(a, b, c)"
 
@@ -188,7 +189,7 @@ def test_pmc_traffic_tool_scales_counters_by_the_copy_kernel(tmp_path, capsys, m
         # time-multiplexed reference, whose launches must not enter the figures
         rows = [(copy, (512 << 20) // unit, 1)] * 3 + [(copy, (256 << 20) // unit, 1)] * 5      # reference launches, then probes
         rows += [(gateup, 800_000_000 // unit, 4), (gateup, 780_000_000 // unit, 4), (other, 123, 4), (gateup, 500_000_000 // unit, 2)]
-        rows += [(attn, 300_000_000 // unit, 5)] * 2 + [(skinny, 100_000_000 // unit, 5)] * 8   # two decode steps
+        rows += [(attn, 300_000_000 // unit, 5)] * 2 + [(skinny, 100_000_000 // unit, 5)] * 4 + [(skinny2, 100_000_000 // unit, 5)] * 4   # two decode steps
         rows += [(attn, 900_000_000 // unit, 2), (skinny, 900_000_000 // unit, 2)]
         path = tmp_path / name
         with open(path, "w") as f:
