@@ -50,7 +50,7 @@ constexpr int MFMA_LDS_BASE = 1024;                 // buffers filled by direct-
 template <int D>
 constexpr int attn_decode_mfma_lds() { return MFMA_LDS_BASE + 4 * 2 * 2 * 16 * D * 2; }   // 4 waves x 2 stages x 2 pages of K
 
-template <int D, int G>
+template <int D, int G, bool NT>
 __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __restrict__ q, bf16* __restrict__ out, const DecodeSeq* __restrict__ seqs,
                                                                const DecodeItem* __restrict__ items,
                                                                const int* __restrict__ block_tables, const bf16* __restrict__ pool,
@@ -102,7 +102,10 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
     for (int u = 0; u < 2; u++) {
       const bf16* kb = page_base(2 * b + u);
 #pragma unroll
-      for (int j = 0; j < IPP; j++) load_to_lds16(kb + ksrc[j], kbuf + stage * STAGE + u * PAGE_KB + j * 1024);
+      for (int j = 0; j < IPP; j++) {
+        if constexpr (NT) load_to_lds16_nt(kb + ksrc[j], kbuf + stage * STAGE + u * PAGE_KB + j * 1024);
+        else load_to_lds16(kb + ksrc[j], kbuf + stage * STAGE + u * PAGE_KB + j * 1024);
+      }
     }
   };
   auto load_v = [&](int b, u32x4 (&vr)[2][DB]) {
@@ -110,7 +113,10 @@ __global__ void __launch_bounds__(256, 2) attn_decode_mfma_kernel(const bf16* __
     for (int u = 0; u < 2; u++) {
       const bf16* vb = page_base(2 * b + u) + (size_t)16 * D;
 #pragma unroll
-      for (int bb = 0; bb < DB; bb++) vr[u][bb] = *reinterpret_cast<const u32x4*>(vb + (bb * 32 + l32) * 16 + lh * 8);
+      for (int bb = 0; bb < DB; bb++) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(vb + (bb * 32 + l32) * 16 + lh * 8);
+        if constexpr (NT) vr[u][bb] = __builtin_nontemporal_load(src); else vr[u][bb] = *src;
+      }
     }
   };
 
@@ -290,13 +296,20 @@ size_t attn_decode_ws_floats(int n, int n_q, int d, int chunks) { return (size_t
 constexpr int MAX_CHUNK_TOKENS = 1024;
 int attn_decode_max_chunk_tokens() { return MAX_CHUNK_TOKENS; }
 
+template <int D, int G, bool NT>
+static void launch_decode_kernel(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items,
+                                 const int* bt, const bf16* pool, KvGeom geo, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
+  constexpr int lds = attn_decode_mfma_lds<D>();
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_mfma_kernel<D, G, NT>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  (void)attr;
+  hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G, NT>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, out, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+}
+
 template <int D, int G>
 static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items, const int* multi, int n_multi,
-                          const int* bt, const bf16* pool, KvGeom geo, int n_q, int chunk_pages, int max_chunks, float* ws, float sc) {
-  constexpr int lds = attn_decode_mfma_lds<D>();
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_mfma_kernel<D, G>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  (void)attr;
-  hipLaunchKernelGGL((attn_decode_mfma_kernel<D, G>), dim3(n_items, geo.n_kv), dim3(256), lds, s, q, out, seqs, items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+                          const int* bt, const bf16* pool, KvGeom geo, int n_q, int chunk_pages, int max_chunks, float* ws, float sc, bool stream_nt) {
+  if (stream_nt) launch_decode_kernel<D, G, true>(s, q, out, seqs, items, n_items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  else launch_decode_kernel<D, G, false>(s, q, out, seqs, items, n_items, bt, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
   if (n_multi > 0)
     hipLaunchKernelGGL(attn_decode_merge_kernel<D>, dim3(n_q, n_multi), dim3(D), 0, s, out, ws, seqs, multi, n_q, geo.n_kv, G, chunk_pages, max_chunks);
 }
@@ -306,19 +319,19 @@ static void launch_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeS
 // the chunk count of the longest context. items: one (request, chunk index) record per chunk
 // that exists, n_items of them (device memory). multi: the n_multi requests whose context has more than
 // one chunk (device memory; only these need the merge kernel, and with none of them it is not launched).
-// ws: attn_decode_ws_floats(n, n_q, d, max_chunks).
+// ws: attn_decode_ws_floats(n, n_q, d, max_chunks). stream_nt: fetch K and V with the non-temporal hint.
 hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items, const int* multi, int n_multi,
-                       const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws) {
+                       const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws, bool stream_nt) {
   if (n == 0 || n_items == 0) return hipSuccess;
   if (n_multi < 0 || n_multi > n || (n_multi > 0 && !multi)) return hipErrorInvalidValue;
   if (geo.page_tokens != 16 || n_q % geo.n_kv != 0 || chunk_pages < 1 || chunk_pages * 16 > attn_decode_max_chunk_tokens() || max_chunks < 1) return hipErrorInvalidValue;
   const int G = n_q / geo.n_kv;
   const float sc = 1.4426950408889634f / sqrtf((float)geo.d);
-  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
-  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc);
+  if (geo.d == 128 && G == 4) launch_decode<128, 4>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc, stream_nt);
+  else if (geo.d == 128 && G == 8) launch_decode<128, 8>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc, stream_nt);
+  else if (geo.d == 128 && G == 1) launch_decode<128, 1>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc, stream_nt);
+  else if (geo.d == 64 && G == 1) launch_decode<64, 1>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc, stream_nt);
+  else if (geo.d == 64 && G == 4) launch_decode<64, 4>(s, q, out, seqs, items, n_items, multi, n_multi, block_tables, pool, geo, n_q, chunk_pages, max_chunks, ws, sc, stream_nt);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -39,6 +39,13 @@ __device__ __forceinline__ void load_to_lds16(const void* gsrc, void* lds_dst) {
                                    (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 #endif
 }
+// The same with the non-temporal hint: for bytes that are read once.
+__device__ __forceinline__ void load_to_lds16_nt(const void* gsrc, void* lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 2);
+#endif
+}
 // The same transfer with the address given as a wave-uniform base plus a 32-bit byte offset per lane
 // (the scalar-base form of the instruction: 4 address bytes per lane travel to the memory pipeline
 // instead of 8, and advancing along K is scalar arithmetic). lds_dst must be wave-uniform. The

@@ -652,13 +652,17 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     KL(ph, STS_K_EMBED, embed_rows(st, ph.X, c->emb, ph.d_tokens, n, h));
     KL(ph, STS_K_NORM, rmsnorm_rows(st, ph.Xn, ph.X, c->layers[0].g1, d.rms_eps, n, h));
   }
+  // On a large partition the decode streams (K and V, the weights of the skinny tiles) are fetched with the non-temporal
+  // hint: measured on a 6-layer model, the layer-step is 6 % shorter on 256 CUs (attention 72 -> 63 us), 3 % on 128,
+  // and no different on 32, where the same hint cost a prefill slice running beside it 0.5 %.
+  const bool nt_attn = ph.cus >= 128, nt_w = nt_attn;
   auto skinny = [&](int kind, const bf16* A, int lda, const bf16* W, int N, int K, int* splits_out, long long* stride_out) -> int {
     const long long stride = (long long)n * N;
     *stride_out = stride;
     int cfg, splits;
     pick_decode_gemm(c, n, N, K, ph.cus, true, true, &cfg, &splits);
     *splits_out = splits;
-    KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride));
+    KL(ph, kind, gemm_bf16(st, cfg, EPI_F32, A, lda, W, K, ph.part, N, n, N, K, splits, stride, nullptr, true, nt_w));
     return STS_OK;
   };
   for (int l = 0; l < d.n_layers; l++) {
@@ -666,7 +670,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
     int sp; long long ss;
     STSCK(skinny(STS_K_QKV, ph.Xn, h, w.wqkv, c->qkvn, h, &sp, &ss));
     KL(ph, STS_K_ROPE, decode_qkv_finish(st, ph.part, sp, ss, c->qkvn, ph.d_dseq, ph.d_bt, c->inv_freq, ph.Q, layer_pool(c, l), c->geo, n, d.n_q_heads));
-    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_ditems, n_items, d_multi, n_multi, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws));
+    KL(ph, STS_K_ATTN, attn_decode(st, ph.Q, ph.A, ph.d_dseq, ph.d_ditems, n_items, d_multi, n_multi, ph.d_bt, layer_pool(c, l), c->geo, n, d.n_q_heads, chunk_pages, max_chunks, ph.attn_ws, nt_attn));
     STSCK(skinny(STS_K_O, ph.A, c->qd, w.wo, h, c->qd, &sp, &ss));
     KL(ph, STS_K_REDUCE, reduce_resid_norm(st, ph.X, ph.part, sp, ss, ph.Xn, w.g2, d.rms_eps, n, h));
     {
@@ -677,7 +681,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
       const double t_fused = pick_decode_gemm(c, n, 2 * d.mlp, h, ph.cus, false, false, &fu_cfg, &fu_splits);
       const bool can_fuse = fu_cfg == GEMM_64x128 || (fu_cfg >= GEMM_64x256S && fu_cfg <= GEMM_64x512S);
       if (can_fuse && (t_fused <= t_split || gu_splits == 1)) {
-        KL(ph, STS_K_GATEUP, gemm_bf16(st, fu_cfg, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, n, 2 * d.mlp, h, 1, 0));
+        KL(ph, STS_K_GATEUP, gemm_bf16(st, fu_cfg, EPI_SWIGLU_BF16, ph.Xn, h, w.wgu, h, ph.H, d.mlp, n, 2 * d.mlp, h, 1, 0, nullptr, true, nt_w));
       } else {
         STSCK(skinny(STS_K_GATEUP, ph.Xn, h, w.wgu, 2 * d.mlp, h, &sp, &ss));
         KL(ph, STS_K_SWIGLU, reduce_swiglu(st, ph.H, ph.part, sp, ss, n, d.mlp));
@@ -690,7 +694,7 @@ int decode_launch_checked(sts_ctx* c, const int32_t* seqs, const int32_t* in_tok
   if (want_logits || want_next) {
     int head_cfg, head_splits;
     pick_decode_gemm(c, n, d.vocab, h, ph.cus, false, false, &head_cfg, &head_splits);
-    KL(ph, STS_K_HEAD, gemm_bf16(st, head_cfg, EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0));
+    KL(ph, STS_K_HEAD, gemm_bf16(st, head_cfg, EPI_F32, ph.Xn, h, c->lm, h, ph.logits, d.vocab, n, d.vocab, h, 1, 0, nullptr, true, nt_w));
     if (want_next) {
       KL(ph, STS_K_SAMPLE, argmax_rows(st, ph.next, ph.logits, n, d.vocab));
       HIPCK(hipMemcpyAsync(ph.h_next, ph.next, n * sizeof(int), hipMemcpyDeviceToHost, st));

@@ -42,6 +42,7 @@ struct GemmArgs {
   int lda, ldw, ldc;
   int M, N, K;
   int w_packed;               // W in the packed block layout (weight_packed_index) instead of row-major
+  int stream_nt;              // skinny tiles: fetch W with the non-temporal hint
   int tiles_m, tiles_n, group_m;
   int k_per_split;            // K range handled by one blockIdx.y
   long long split_stride;     // elements between consecutive split-K partial outputs
@@ -325,8 +326,18 @@ __global__ void __launch_bounds__(WGM* WGN * 64) gemm_dl_kernel(GemmArgs g) {
 // so it has landed when the wave reaches the barrier. The W loads are written in assembly, so the compiler
 // does not know when their registers are valid; the wait names them as in/out operands, which keeps every
 // use behind it.
+template <bool NT = false>
 __device__ __forceinline__ void load_w16(bf16x8& dst, const unsigned char* base, unsigned lane_off, int step) {
 #if defined(__HIP_DEVICE_COMPILE__)
+  if constexpr (NT) {   // the same loads with the non-temporal hint
+    switch (step) {
+      case 0: asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+      case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024 nt" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+      case 2: asm volatile("global_load_dwordx4 %0, %1, %2 offset:2048 nt" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+      default: asm volatile("global_load_dwordx4 %0, %1, %2 offset:3072 nt" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
+    }
+    return;
+  }
   switch (step) {   // the step's 1 KiB piece is addressed by the instruction's immediate offset
     case 0: asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
     case 1: asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=v"(dst) : "v"(lane_off), "s"(base) : "memory"); break;
@@ -539,7 +550,7 @@ __global__ void __launch_bounds__(WGM * 256, 2) gemm_wreg_kernel(GemmArgs g) {
 // registers and stages nobody uses. A(t + 1) was queued before the operands step 3 of tile t waits for, so
 // it has landed at the barrier there, which also retires the stage of tile t for the A loads of iteration
 // t + 1.
-template <int EPI, int PD>
+template <int EPI, int PD, bool NT>
 __global__ void __launch_bounds__(512, 2) gemm_skinny_kernel(GemmArgs g) {
   constexpr int BM = 64, BK = 64, NS = PD + 2, DUTY = 4;     // DUTY waves load the A tile
   constexpr int TM = 2, TN = 2, ROWB = BK * 2, A_CH = BM * 8 / (DUTY * 64), STAGE = BM * ROWB;
@@ -610,7 +621,7 @@ __global__ void __launch_bounds__(512, 2) gemm_skinny_kernel(GemmArgs g) {
 #pragma unroll
     for (int kk = 0; kk < 4; kk++)
 #pragma unroll
-      for (int j = 0; j < TN; j++) load_w16(w[s][j][kk], wk + j * wrow, w_lane, kk);
+      for (int j = 0; j < TN; j++) load_w16<NT>(w[s][j][kk], wk + j * wrow, w_lane, kk);
   }
   wait_vmem<10 * PD>();                                      // A(0) has landed
   __syncthreads();
@@ -653,7 +664,7 @@ __global__ void __launch_bounds__(512, 2) gemm_skinny_kernel(GemmArgs g) {
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < TN; j++) load_w16(w[s][j][kk], wk + j * wrow, w_lane, kk);
+        for (int j = 0; j < TN; j++) load_w16<NT>(w[s][j][kk], wk + j * wrow, w_lane, kk);
       };
       step(std::integral_constant<int, 0>{});
       step(std::integral_constant<int, 1>{});
@@ -751,7 +762,7 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   void (*kern)(GemmArgs) = nullptr;
   void (*kern_rowmajor)(GemmArgs) = nullptr;       // row-major W: the fp32-store epilogue only (callers that bring their own weights)
   if constexpr (WREG) kern = gemm_wreg_kernel<EPI, WGM>;
-  else if constexpr (SKINNY) kern = gemm_skinny_kernel<EPI, GEMM_SKINNY_PD>;
+  else if constexpr (SKINNY) kern = g.stream_nt ? gemm_skinny_kernel<EPI, GEMM_SKINNY_PD, true> : gemm_skinny_kernel<EPI, GEMM_SKINNY_PD, false>;
   else kern = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS>;
   if constexpr (EPI == EPI_F32 && !SKINNY) kern_rowmajor = gemm_dl_kernel<BM, BN, WGM, WGN, EPI, NS, false>;
   if (!g.w_packed && !kern_rowmajor) return hipErrorInvalidValue;
@@ -760,6 +771,10 @@ static hipError_t launch_cfg(hipStream_t s, GemmArgs g, int splits, const GemmTa
   static std::atomic<bool> attr_set{false};        // the two phases' control threads may launch the same shape
   if (!attr_set.load()) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_packed);
+    if constexpr (SKINNY) {      // both forms of the kernel, whichever this call takes
+      void (*other)(GemmArgs) = g.stream_nt ? gemm_skinny_kernel<EPI, GEMM_SKINNY_PD, false> : gemm_skinny_kernel<EPI, GEMM_SKINNY_PD, true>;
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(other), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_packed);
+    }
     if (e == hipSuccess && kern_rowmajor) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_rowmajor), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dl);
     if (e != hipSuccess) return e;
     attr_set.store(true);
@@ -826,7 +841,7 @@ int gemm_wgs_per_cu(int cfg) { return cfg == GEMM_256x256 || cfg == GEMM_64x256 
 // With splits > 1 (EPI_F32 only) partial sums go to C + z * split_stride. With `tail` (splits == 1)
 // the tiles of the last, partly filled wave of workgroups are cut along K (see GemmArgs).
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
-                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail, bool w_packed) {
+                     void* C, int ldc, int M, int N, int K, int splits, long long split_stride, const GemmTail* tail, bool w_packed, bool stream_nt) {
   if (M < 1 || K % 64 != 0 || N % gemm_tile_n(cfg) != 0 || lda % 8 != 0 || ldw % 8 != 0) return hipErrorInvalidValue;
   if (w_packed && ldw != K) return hipErrorInvalidValue;          // packed blocks are addressed by K alone
   if (splits < 1 || (splits > 1 && epi != EPI_F32)) return hipErrorInvalidValue;
@@ -835,7 +850,7 @@ hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, co
   if (epi == EPI_SWIGLU_BF16 && cfg == GEMM_128x256) return hipErrorInvalidValue;  // not instantiated: the shape serves the O and down projections
   GemmArgs g{};
   g.A = A; g.W = W; g.C = C; g.lda = lda; g.ldw = ldw; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
-  g.split_stride = split_stride; g.w_packed = w_packed ? 1 : 0;
+  g.split_stride = split_stride; g.w_packed = w_packed ? 1 : 0; g.stream_nt = stream_nt ? 1 : 0;
   switch (epi) {
     case EPI_BF16: return launch_epi<EPI_BF16>(s, cfg, g, splits, tail);
     case EPI_F32: return launch_epi<EPI_F32>(s, cfg, g, splits, tail);

@@ -19,7 +19,7 @@ void gemm_tail_plan(int tiles, int ksteps, int slots, long long max_pieces, int*
 // the packed layout below. The row-major form exists for the fp32-store epilogue only.
 hipError_t gemm_bf16(hipStream_t s, int cfg, int epi, const bf16* A, int lda, const bf16* W, int ldw,
                      void* C, int ldc, int M, int N, int K, int splits, long long split_stride,
-                     const GemmTail* tail = nullptr, bool w_packed = true);
+                     const GemmTail* tail = nullptr, bool w_packed = true, bool stream_nt = false);
 
 // Packed GEMM weights: blocks of 32 rows x 64 columns (4 KiB), stored one after the other along K, then
 // along N. A block is laid out the way the matrix cores take a W operand: four pieces of 1 KiB, one per
@@ -106,7 +106,8 @@ hipError_t attn_prefill(hipStream_t s, const bf16* qkv, int ld, bf16* out, int l
 int attn_prefill_tile_q();
 size_t attn_decode_ws_floats(int n, int n_q, int d, int max_chunks);
 hipError_t attn_decode(hipStream_t s, const bf16* q, bf16* out, const DecodeSeq* seqs, const DecodeItem* items, int n_items, const int* multi, int n_multi,
-                       const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws);
+                       const int* block_tables, const bf16* pool, KvGeom geo, int n, int n_q, int chunk_pages, int max_chunks, float* ws,
+                       bool stream_nt = false);
 int attn_decode_max_chunk_tokens();
 
 }  // namespace sts
