@@ -85,6 +85,18 @@ int sts_max_pages_per_seq_limit(int32_t page_tokens);
 int sts_decode_chunk_plan(const int32_t* n_pages, int32_t n, int32_t n_kv_heads, int32_t cus, int32_t page_tokens,
                           int32_t max_pages_per_seq, int32_t* chunk_pages, int32_t* max_chunks, int32_t* allocated_chunks);
 
+/* Host only, no GPU state: tile configuration (STS_GEMM_*) and split along K the engine gives a decode-side GEMM of m rows
+ * (one token per request), n weight rows and k columns on a partition of `cus` CUs. Up to 64 rows the GEMM streams its
+ * weights once and is planned by an estimate of rounds of workgroups and bytes per CU over the 64x128 tile and the skinny tiles
+ * whose width divides n (Section 2.1: decode is bound by memory bandwidth; Section 3.2.1: what a partition can pull grows with
+ * its CUs only up to a point); above that it takes a prefill tile shape. may_split: a split along K is allowed (its fp32 partial
+ * sums are reduced by the caller's next kernel); partials: the output leaves as fp32 partial sums even when unsplit (0 = the
+ * GEMM's own epilogue finishes it, as the fused SwiGLU of an unsplit gate/up GEMM does). gemm_rate_256 and partial_bw_cu: the
+ * tile model's values (see sts_set_tile_model). est_ns (may be NULL): the estimate behind the choice. n: a multiple of 128,
+ * k: a multiple of 64, else STS_EINVAL. */
+int sts_decode_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t cus, int32_t may_split, int32_t partials, int64_t gemm_rate_256,
+                         int64_t partial_bw_cu, int32_t* tile_cfg, int32_t* split_k, int64_t* est_ns);
+
 /* Weights. `name`: "emb", "lm" (layer ignored), "wq","wk","wv","wo","wg","wu","wd" (matrices,
  * row-major [out_features, in_features] fp32, rounded to bf16 on upload) or "g1","g2","gf"
  * (gains, fp32 [hidden]). `count` = number of fp32 elements and must match the tensor. */

@@ -282,7 +282,9 @@ hipError_t prefill_gemm(const sts_ctx* ctx, Phase& ph, int epi, const bf16* A, i
   const GemmTail tail{gemm_wgs_per_cu(cfg) * ph.cus, ph.tail_ws, ph.tail_ws_bytes};
   return gemm_bf16(ph.stream, cfg, epi, A, lda, W, ldw, C, ldc, m, n, k, 1, 0, &tail);
 }
-int pick_splits(const sts_ctx* ctx, int cfg, int m, int n, int k, int cus) {
+int plan_splits(double rate_256, double partial_bw, int cfg, int m, int n, int k, int cus);
+int pick_splits(const sts_ctx* ctx, int cfg, int m, int n, int k, int cus) { return plan_splits(ctx->rate_256, ctx->partial_bw, cfg, m, n, k, cus); }
+int plan_splits(double rate_256, double partial_bw, int cfg, int m, int n, int k, int cus) {
   const int tiles = ((m + gemm_tile_m(cfg) - 1) / gemm_tile_m(cfg)) * (n / gemm_tile_n(cfg));
   const int slots = gemm_wgs_per_cu(cfg) * std::max(cus, 8);
   const int s_max = std::min(8, std::max(1, k / 512));            // at least 8 K-steps per slice
@@ -290,8 +292,8 @@ int pick_splits(const sts_ctx* ctx, int cfg, int m, int n, int k, int cus) {
     // one workgroup owns a CU, so rounds of workgroups are strict: estimated time of s slices =
     // ceil(tiles * s / slots) rounds of a 1/s tile at the measured rate of that tile, plus the fp32
     // partial sums written and read back at the measured per-CU rate; the cheapest s wins
-    const double tile_s = 2.0 * gemm_tile_m(cfg) * gemm_tile_n(cfg) * k / (ctx->rate_256 * 1e12);
-    const double part_s = 8.0 * m * n / (std::max(cus, 8) * ctx->partial_bw);
+    const double tile_s = 2.0 * gemm_tile_m(cfg) * gemm_tile_n(cfg) * k / (rate_256 * 1e12);
+    const double part_s = 8.0 * m * n / (std::max(cus, 8) * partial_bw);
     int best = 1; double best_t = 1e300;
     for (int s = 1; s <= s_max; s++) {
       const double t = (double)(((long long)tiles * s + slots - 1) / slots) * tile_s / s + s * part_s;
@@ -318,7 +320,12 @@ int pick_splits(const sts_ctx* ctx, int cfg, int m, int n, int k, int cus) {
 // rounds.
 // `partials`: the output goes through fp32 partial sums (a split needs that; the caller's next kernel reads them).
 // Returns the estimated seconds.
+double plan_decode_gemm(double rate_256, double partial_bw, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits);
 double pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits) {
+  return plan_decode_gemm(ctx->rate_256, ctx->partial_bw, m, n, k, cus, may_split, partials, cfg, splits);
+}
+// rate_256 (TFLOP/s per busy CU of the 256x256 tile) and partial_bw (bytes/s per CU for partial sums): the tile model's.
+double plan_decode_gemm(double rate_256, double partial_bw, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits) {
   const int c = std::max(cus, 8);
   constexpr double cu_rate = 55e9;       // bytes/s one CU pulls from memory when streaming (measured: 59e9 for plain reads)
   constexpr double mem_rate = 5.5e12;    // bytes/s the memory system gives a full GPU of such streams
@@ -335,12 +342,12 @@ double pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool m
     // complete rounds hold per_cu workgroups on every CU; the last round what is left, dealt over the CUs
     double t = (rounds - 1) * cu_time(per_cu) + cu_time((last + c - 1) / c);
     t = std::max(t, 2.0 * n * k / mem_rate) + rounds * start_s;
-    if (partials) t += 8.0 * s * m * n / (c * ctx->partial_bw);
+    if (partials) t += 8.0 * s * m * n / (c * partial_bw);
     return t;
   };
   if (m > 64 || n % 128 != 0) {
     *cfg = pick_cfg(m, n, k, cus);
-    *splits = may_split ? pick_splits(ctx, *cfg, m, n, k, cus) : 1;
+    *splits = may_split ? plan_splits(rate_256, partial_bw, *cfg, m, n, k, cus) : 1;
     return estimate(*cfg, *splits);
   }
   const int s_max = may_split ? std::min(8, std::max(1, k / 512)) : 1;
@@ -867,6 +874,15 @@ extern "C" int sts_init(const sts_model_desc* desc, const sts_init_params* param
 
 extern "C" int sts_max_pages_per_seq_limit(int32_t page_tokens) {
   return page_tokens > 0 ? 128 * (attn_decode_max_chunk_tokens() / page_tokens) : 0;
+}
+extern "C" int sts_decode_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t cus, int32_t may_split, int32_t partials, int64_t gemm_rate_256,
+                                    int64_t partial_bw_cu, int32_t* tile_cfg, int32_t* split_k, int64_t* est_ns) {
+  if (m < 1 || n < 128 || n % 128 != 0 || k < 64 || k % 64 != 0 || cus < 1 || gemm_rate_256 < 1 || partial_bw_cu < 1 || !tile_cfg || !split_k) return STS_EINVAL;
+  int cfg = 0, splits = 1;
+  const double t = plan_decode_gemm(gemm_rate_256 * 1e-3, partial_bw_cu * 1e6, m, n, k, cus, may_split != 0, partials != 0, &cfg, &splits);
+  *tile_cfg = cfg; *split_k = splits;
+  if (est_ns) *est_ns = (int64_t)(t * 1e9);
+  return STS_OK;
 }
 extern "C" int sts_decode_chunk_plan(const int32_t* n_pages, int32_t n, int32_t n_kv_heads, int32_t cus, int32_t page_tokens,
                                      int32_t max_pages_per_seq, int32_t* chunk_pages, int32_t* max_chunks, int32_t* allocated_chunks) {

@@ -93,7 +93,7 @@ EXPORTS = [
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_op_gemm_noalloc", "sts_weight_packed_index", "sts_probe_gemm", "sts_set_tile_model",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_decode_gemm_plan", "sts_op_gemm_noalloc", "sts_weight_packed_index", "sts_probe_gemm", "sts_set_tile_model",
     "sts_profile_tile_model",
 ]
 
@@ -386,6 +386,15 @@ def decode_chunk_plan(n_pages, n_kv_heads, cus, page_tokens, max_pages_per_seq):
     _ck(lib().sts_decode_chunk_plan(_p(a), a.size, n_kv_heads, cus, page_tokens, max_pages_per_seq, C.byref(cp), C.byref(mc), C.byref(ac)),
         "sts_decode_chunk_plan")
     return cp.value, mc.value, ac.value
+
+
+def decode_gemm_plan(m, n, k, cus, may_split=True, partials=True, gemm_rate_256=4967, partial_bw_cu=22504):
+    """(tile configuration name, split along K, estimated ns) of a decode-side GEMM; host only."""
+    cfg, sp, ns = C.c_int32(), C.c_int32(), C.c_int64()
+    _ck(lib().sts_decode_gemm_plan(m, n, k, cus, int(may_split), int(partials), C.c_int64(int(gemm_rate_256)), C.c_int64(int(partial_bw_cu)),
+                                   C.byref(cfg), C.byref(sp), C.byref(ns)), "sts_decode_gemm_plan")
+    name = {v: k_ for k_, v in GEMM_CFGS.items()}[cfg.value]
+    return name, sp.value, ns.value
 
 
 # ---- performance estimator and scheduler (host only)

@@ -250,3 +250,40 @@ def test_decode_chunk_sizing_stays_within_what_the_engine_allocates(sts):
                 assert mc <= alloc <= 128, (mp, cus, cp, mc, alloc)
     with pytest.raises(sts.StsError):
         sts.decode_chunk_plan([limit + 1], 8, 32, 16, limit)       # a context longer than the block table
+
+
+def test_decode_gemm_plan_fits_tiles_to_the_partition():
+    """Host logic of the decode GEMM planner (no GPU): the tile width divides N, the split stays within what the K extent
+    feeds and the library accepts (at most 8 slices of at least 512 columns); a GEMM that has to finish its own output is
+    never split; the Llama MLP width (7 * 2^k columns for gate and up together) comes out in whole rounds of 7-wave tiles on
+    32 and 64 CUs, where every power-of-two width would leave a last round three quarters full; a whole GPU gets many
+    small workgroups instead of a few wide ones; above 64 rows the decode GEMM takes a prefill tile shape."""
+    from paper_2504_19516_amd import sts
+    width = {"64x128": 128, "64x256s": 256, "64x320s": 320, "64x384s": 384, "64x448s": 448, "64x512s": 512}
+    shapes = [(6144, 4096), (4096, 4096), (28672, 4096), (4096, 14336), (128256, 4096), (10240, 8192), (57344, 8192), (8192, 28672),
+              (768, 256), (2048, 256), (256, 1024), (1024, 256), (640, 128)]
+    for cus in (8, 32, 64, 96, 128, 160, 192, 224, 256):
+        for n, k in shapes:
+            for m in (1, 8, 37, 64):
+                for may_split, partials in ((True, True), (False, False), (False, True)):
+                    name, split, ns = sts.decode_gemm_plan(m, n, k, cus, may_split, partials)
+                    assert name in width and n % width[name] == 0, (name, n)
+                    assert 1 <= split <= max(1, min(8, k // 512)) and ns > 0
+                    if not may_split:
+                        assert split == 1
+    for cus in (32, 64):
+        assert sts.decode_gemm_plan(64, 28672, 4096, cus, may_split=False, partials=False)[:2] == ("64x448s", 1)
+        assert sts.decode_gemm_plan(64, 57344, 8192, cus, may_split=False, partials=False)[:2] == ("64x448s", 1)
+    # one wide tile per CU cannot keep 256 CUs busy with 4096 columns: narrow tiles, split deep
+    name, split, _ = sts.decode_gemm_plan(64, 4096, 14336, 256)
+    assert name == "64x128" and split >= 4
+    # on a small partition the same GEMM takes wide tiles (the activation rows are re-read once per workgroup)
+    assert width[sts.decode_gemm_plan(64, 4096, 14336, 32)[0]] >= 384
+    # a slower estimate for fewer CUs, and never below the weight bytes at the memory system's rate
+    t32, t256 = sts.decode_gemm_plan(64, 28672, 4096, 32)[2], sts.decode_gemm_plan(64, 28672, 4096, 256)[2]
+    assert t32 > 2.5 * t256 and t256 >= 2 * 28672 * 4096 / 5.5e12 * 1e9
+    assert sts.decode_gemm_plan(200, 28672, 4096, 32)[0] in ("128x128", "256x256")
+    for bad in ((64, 100, 4096, 32), (64, 4096, 100, 32), (0, 4096, 4096, 32), (64, 4096, 4096, 0)):
+        with pytest.raises(sts.StsError) as e:
+            sts.decode_gemm_plan(*bad)
+        assert e.value.code == sts.EINVAL
