@@ -57,7 +57,9 @@ class Workload:
                               max_prefill_tokens=PREFILL_TOKENS, max_prefill_seqs=1, max_decode_batch=DECODE_BATCH,
                               max_seqs=DECODE_BATCH + 4, max_pages_per_seq=(8192 + 128) // 16)
         # the GEMM tile choice reads the rates the offline profiler measured on this part
-        self.eng.set_tile_model(*sts.Profile(path=PROFILE_8B).tile_model())
+        prof = sts.Profile(path=PROFILE_8B)
+        self.eng.set_tile_model(*prof.tile_model())
+        self.eng.set_stream_model(*prof.stream_model())         # ... and the decode GEMM planner the stream rates
         perm = synth.page_permutation(3, pages_needed + 256)
         off = 0
         self.dseqs = []

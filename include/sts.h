@@ -92,10 +92,11 @@ int sts_decode_chunk_plan(const int32_t* n_pages, int32_t n, int32_t n_kv_heads,
  * its CUs only up to a point); above that it takes a prefill tile shape. may_split: a split along K is allowed (its fp32 partial
  * sums are reduced by the caller's next kernel); partials: the output leaves as fp32 partial sums even when unsplit (0 = the
  * GEMM's own epilogue finishes it, as the fused SwiGLU of an unsplit gate/up GEMM does). gemm_rate_256 and partial_bw_cu: the
- * tile model's values (see sts_set_tile_model). est_ns (may be NULL): the estimate behind the choice. n: a multiple of 128,
- * k: a multiple of 64, else STS_EINVAL. */
+ * tile model's values (see sts_set_tile_model); stream_bw_cu and stream_bw_gpu: the stream model's (sts_set_stream_model).
+ * est_ns (may be NULL): the estimate behind the choice. n: a multiple of 128, k: a multiple of 64, else STS_EINVAL. */
 int sts_decode_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t cus, int32_t may_split, int32_t partials, int64_t gemm_rate_256,
-                         int64_t partial_bw_cu, int32_t* tile_cfg, int32_t* split_k, int64_t* est_ns);
+                         int64_t partial_bw_cu, int64_t stream_bw_cu, int64_t stream_bw_gpu, int32_t* tile_cfg, int32_t* split_k,
+                         int64_t* est_ns);
 
 /* Weights. `name`: "emb", "lm" (layer ignored), "wq","wk","wv","wo","wg","wu","wd" (matrices,
  * row-major [out_features, in_features] fp32, rounded to bf16 on upload) or "g1","g2","gf"
@@ -202,6 +203,10 @@ const char* sts_kernel_name(int32_t kind);
  * side): the memory-copy probe of Section 3.2.2. Moves `bytes` (read + written = 2*bytes) per
  * iteration; returns device ns for `iters` iterations. */
 int sts_probe_copy(sts_ctx* ctx, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out);
+/* The same probe without the writes: a read-only stream over `bytes` per iteration (non-temporal loads). What a decode
+ * partition can pull at best; the offline profiler stores its rate per CU at 32 CUs and on the whole GPU in the profile
+ * (stream_bw_cu, stream_bw_gpu) for the decode GEMM planner. */
+int sts_probe_read(sts_ctx* ctx, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out);
 
 /* One of the prefill side's GEMMs (layer 0's weights, whatever the workspace holds as activations; the residual
  * stream of the workspace is overwritten) with a given tile configuration on `cus` CUs, whole tiles only: m rows
@@ -219,6 +224,10 @@ int sts_probe_gemm(sts_ctx* ctx, int32_t cus, int32_t tile_cfg, int32_t product,
  * effect for the next launch; STS_ESTATE while a launch is outstanding. */
 int sts_set_tile_model(sts_ctx* ctx, int64_t gemm_rate_128, int64_t gemm_rate_256, int64_t gemm_rate_128x256, int64_t gemm_fixed_128x256,
                        int64_t partial_bw_cu);
+/* What the planner of the decode GEMMs (sts_decode_gemm_plan) assumes about the memory system: MB/s a read-only stream reaches
+ * per CU of a 32-CU partition, and on the whole GPU (sts_probe_read measures both; the profile keeps them, see
+ * sts_profile_stream_model). Until set, figures measured on one MI355X apply (59000, 6400000). stream_bw_gpu >= stream_bw_cu. */
+int sts_set_stream_model(sts_ctx* ctx, int64_t stream_bw_cu, int64_t stream_bw_gpu);
 
 /* ---- single operations on host data, for per-kernel parity tests. Inputs are fp32 and are
  * rounded to bf16 on upload; outputs are the kernel's fp32 accumulators (or its bf16 result
@@ -287,6 +296,8 @@ int sts_profile_free(sts_profile* p);
 /* The profile's tile-model entries (see sts_set_tile_model); each output may be NULL. */
 int sts_profile_tile_model(const sts_profile* p, int64_t* gemm_rate_128, int64_t* gemm_rate_256, int64_t* gemm_rate_128x256,
                            int64_t* gemm_fixed_128x256, int64_t* partial_bw_cu);
+/* The profile's stream-model entries (see sts_set_stream_model); each output may be NULL. */
+int sts_profile_stream_model(const sts_profile* p, int64_t* stream_bw_cu, int64_t* stream_bw_gpu);
 
 /* Execution state ES (Section 3.2.1): prefill lengths sl_i with their cached contexts, prefill
  * CUs pm, decode contexts cl_i (batch size = n_decode), decode CUs dm; plus the layer slice. */

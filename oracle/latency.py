@@ -71,6 +71,9 @@ class Profile:
     gemm_rate_128x256: int = 5000
     gemm_fixed_128x256: int = 25000    # ns: start-up and epilogue of that tile, which runs one per CU
     partial_bw_cu: int = 20000
+    # MB/s of a plain read-only stream, per CU of a 32-CU partition and of the whole GPU (the GPU library plans its decode GEMMs with them)
+    stream_bw_cu: int = 59000
+    stream_bw_gpu: int = 6400000
     bw: Grid | None = None             # D_{p,sl}: axes (decode CUs, co-running prefill tokens) -> bytes/ns
     # slowdown (ppm) of a prefill slice beside a decode step, over the decode CUs it shares the GPU
     # with; None = none. Section 3.2.3 measures this direction of the contention as small and
@@ -367,7 +370,7 @@ def _nest(flat, dims):
 def dump_profile(hw: Profile) -> str:
     lines = ["sts-profile 1"]
     for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut",
-              "gemm_rate_128", "gemm_rate_256", "gemm_rate_128x256", "gemm_fixed_128x256", "partial_bw_cu"):
+              "gemm_rate_128", "gemm_rate_256", "gemm_rate_128x256", "gemm_fixed_128x256", "partial_bw_cu", "stream_bw_cu", "stream_bw_gpu"):
         lines.append(f"{k} {getattr(hw, k)}")
     for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         g = getattr(hw, name)

@@ -519,6 +519,27 @@ __global__ void __launch_bounds__(256) copy_kernel(uint4* __restrict__ dst, cons
   }
   for (; i < n; i += stride) dst[i] = src[i];
 }
+// The read half of the copy alone: what a partition pulls from memory when nothing is written back. The loads carry the
+// non-temporal hint (every byte is used once); `sink` receives a word only if the data's XOR hits one particular value,
+// which keeps the loads alive.
+__global__ void __launch_bounds__(256) read_kernel(const u32x4* __restrict__ src, size_t n, unsigned* __restrict__ sink) {
+  size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (; i + 7 * stride < n; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < 8; u++) acc ^= v[u];
+  }
+  for (; i < n; i += stride) acc ^= src[i];
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x5a17c0deu) *sink = 1u;
+}
+hipError_t read_probe(hipStream_t s, const void* src, size_t bytes, unsigned* sink, int grid) {
+  hipLaunchKernelGGL(read_kernel, dim3(grid), dim3(256), 0, s, (const u32x4*)src, bytes / 16, sink);
+  return hipGetLastError();
+}
 hipError_t copy_probe(hipStream_t s, void* dst, const void* src, size_t bytes, int grid) {
   hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, bytes / 16);
   return hipGetLastError();

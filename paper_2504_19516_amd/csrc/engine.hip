@@ -112,6 +112,7 @@ struct sts_ctx {
   // what the tile choice of the prefill GEMMs assumes about the part (sts_set_tile_model): TFLOP/s per busy CU of
   // the 128x128 tiles (two workgroups per CU) and of the 256x256 tiles (one), bytes/s per CU for partial tiles
   double rate_128 = 3.5, rate_256 = 4.8, rate_128x256 = 5.0, fixed_128x256 = 25e-6, partial_bw = 20e9;
+  double stream_bw_cu = 59e9, stream_bw_gpu = 6.4e12;          // read-only streams: bytes/s per CU of a 32-CU partition, bytes/s of the whole GPU
 };
 
 namespace {
@@ -320,24 +321,29 @@ int plan_splits(double rate_256, double partial_bw, int cfg, int m, int n, int k
 // rounds.
 // `partials`: the output goes through fp32 partial sums (a split needs that; the caller's next kernel reads them).
 // Returns the estimated seconds.
-double plan_decode_gemm(double rate_256, double partial_bw, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits);
+struct StreamRates { double rate_256, partial_bw, stream_bw_cu, stream_bw_gpu; };
+double plan_decode_gemm(const StreamRates& r, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits);
 double pick_decode_gemm(const sts_ctx* ctx, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits) {
-  return plan_decode_gemm(ctx->rate_256, ctx->partial_bw, m, n, k, cus, may_split, partials, cfg, splits);
+  return plan_decode_gemm(StreamRates{ctx->rate_256, ctx->partial_bw, ctx->stream_bw_cu, ctx->stream_bw_gpu}, m, n, k, cus, may_split, partials, cfg, splits);
 }
-// rate_256 (TFLOP/s per busy CU of the 256x256 tile) and partial_bw (bytes/s per CU for partial sums): the tile model's.
-double plan_decode_gemm(double rate_256, double partial_bw, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits) {
+// r: measured on the part by the offline profiler -- rate_256 (TFLOP/s per busy CU of the 256x256 tile) and partial_bw (bytes/s
+// per CU for partial sums) of the tile model; stream_bw_cu and stream_bw_gpu, what a plain read-only stream reaches per CU of a
+// 32-CU partition and on the whole GPU. A GEMM's weight stream gets 0.93 and 0.85 of those (its loads share the CU with the
+// operand reads and the matrix cores; the best decode GEMMs measured 55 of 58-59 GB/s per CU and 5.1 of 6 TB/s).
+double plan_decode_gemm(const StreamRates& r, int m, int n, int k, int cus, bool may_split, bool partials, int* cfg, int* splits) {
   const int c = std::max(cus, 8);
-  constexpr double cu_rate = 55e9;       // bytes/s one CU pulls from memory when streaming (measured: 59e9 for plain reads)
-  constexpr double mem_rate = 5.5e12;    // bytes/s the memory system gives a full GPU of such streams
-  constexpr double start_s = 2.5e-6;     // a workgroup's first loads and its epilogue
+  const double rate_256 = r.rate_256, partial_bw = r.partial_bw;
+  const double cu_rate = 0.93 * r.stream_bw_cu;      // bytes/s one CU pulls from memory for a GEMM's streams
+  const double mem_rate = 0.85 * r.stream_bw_gpu;    // bytes/s the memory system gives a full GPU of such streams
+  constexpr double start_s = 2.5e-6;                 // a workgroup's first loads and its epilogue
   auto estimate = [&](int cand, int s) {
     const int bn = gemm_tile_n(cand), bm = gemm_tile_m(cand), per_cu = gemm_wgs_per_cu(cand);
     const long long wgs = (long long)((m + bm - 1) / bm) * (n / bn) * s, slots = (long long)c * per_cu;
     const long long rounds = (wgs + slots - 1) / slots, last = wgs - (rounds - 1) * slots;
     const double wg_bytes = 2.0 * (k / s) * (bn + bm);
-    // one workgroup alone pulls what its loads in flight allow: about 10 GB/s per wave of a skinny tile on a busy
-    // memory system, 34 GB/s for the four waves of a tile staged through LDS
-    const double wg_rate = cand >= GEMM_64x256S ? std::min(cu_rate, 10e9 * (bn / 64)) : 34e9;
+    // one workgroup alone pulls what its loads in flight allow: on a busy memory system a wave of a skinny tile a
+    // sixth of the CU's rate (10 GB/s), the four waves of a tile staged through LDS 0.6 of it (34 GB/s)
+    const double wg_rate = cand >= GEMM_64x256S ? std::min(cu_rate, cu_rate / 5.5 * (bn / 64)) : 0.62 * cu_rate;
     auto cu_time = [&](long long held) { return std::max(held * wg_bytes / cu_rate, wg_bytes / wg_rate); };
     // complete rounds hold per_cu workgroups on every CU; the last round what is left, dealt over the CUs
     double t = (rounds - 1) * cu_time(per_cu) + cu_time((last + c - 1) / c);
@@ -876,10 +882,12 @@ extern "C" int sts_max_pages_per_seq_limit(int32_t page_tokens) {
   return page_tokens > 0 ? 128 * (attn_decode_max_chunk_tokens() / page_tokens) : 0;
 }
 extern "C" int sts_decode_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t cus, int32_t may_split, int32_t partials, int64_t gemm_rate_256,
-                                    int64_t partial_bw_cu, int32_t* tile_cfg, int32_t* split_k, int64_t* est_ns) {
-  if (m < 1 || n < 128 || n % 128 != 0 || k < 64 || k % 64 != 0 || cus < 1 || gemm_rate_256 < 1 || partial_bw_cu < 1 || !tile_cfg || !split_k) return STS_EINVAL;
+                                    int64_t partial_bw_cu, int64_t stream_bw_cu, int64_t stream_bw_gpu, int32_t* tile_cfg, int32_t* split_k, int64_t* est_ns) {
+  if (m < 1 || n < 128 || n % 128 != 0 || k < 64 || k % 64 != 0 || cus < 1 || gemm_rate_256 < 1 || partial_bw_cu < 1 || stream_bw_cu < 1 ||
+      stream_bw_gpu < 1 || !tile_cfg || !split_k) return STS_EINVAL;
   int cfg = 0, splits = 1;
-  const double t = plan_decode_gemm(gemm_rate_256 * 1e-3, partial_bw_cu * 1e6, m, n, k, cus, may_split != 0, partials != 0, &cfg, &splits);
+  const StreamRates r{gemm_rate_256 * 1e-3, partial_bw_cu * 1e6, stream_bw_cu * 1e6, stream_bw_gpu * 1e6};
+  const double t = plan_decode_gemm(r, m, n, k, cus, may_split != 0, partials != 0, &cfg, &splits);
   *tile_cfg = cfg; *split_k = splits;
   if (est_ns) *est_ns = (int64_t)(t * 1e9);
   return STS_OK;
@@ -1284,6 +1292,11 @@ extern "C" int sts_set_tile_model(sts_ctx* c, int64_t gemm_rate_128, int64_t gem
   c->fixed_128x256 = gemm_fixed_128x256 * 1e-9; c->partial_bw = partial_bw_cu * 1e6;
   return STS_OK;
 }
+extern "C" int sts_set_stream_model(sts_ctx* c, int64_t stream_bw_cu, int64_t stream_bw_gpu) {
+  if (!c || stream_bw_cu < 1 || stream_bw_gpu < stream_bw_cu) return STS_EINVAL;
+  c->stream_bw_cu = stream_bw_cu * 1e6; c->stream_bw_gpu = stream_bw_gpu * 1e6;
+  return STS_OK;
+}
 extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t product, int32_t m, int32_t n, int32_t iters, int64_t* ns_out) {
   if (!c || !ns_out || iters < 1 || tile_cfg < 0 || tile_cfg >= GEMM_NCFG || product < 0 || product > 2) return STS_EINVAL;
   const sts_model_desc& d = c->d;
@@ -1317,7 +1330,7 @@ extern "C" int sts_probe_gemm(sts_ctx* c, int32_t cus, int32_t tile_cfg, int32_t
   *ns_out = (int64_t)((double)ms * 1e6);
   return STS_OK;
 }
-extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out) {
+static int probe_stream(sts_ctx* c, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out, bool read_only) {
   if (!c || side < 0 || side > 1 || bytes < 4096 || bytes % 16 || iters < 1 || !ns_out) return STS_EINVAL;
   hipStream_t st;
   STSCK(get_stream(c, side, cus, &st));
@@ -1334,14 +1347,30 @@ extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t byte
     ~Events() { if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); }
   } ev;
   HIPCK(hipEventCreate(&ev.e0)); HIPCK(hipEventCreate(&ev.e1));
-  const int grid = cus * 8;
-  HIPCK(copy_probe(st, c->probe_dst, c->probe_src, bytes, grid));   // warm-up
-  HIPCK(hipEventRecord(ev.e0, st));
-  for (int i = 0; i < iters; i++) HIPCK(copy_probe(st, c->probe_dst, c->probe_src, bytes, grid));
-  HIPCK(hipEventRecord(ev.e1, st));
-  HIPCK(hipEventSynchronize(ev.e1));
-  float ms = 0.f;
-  HIPCK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
-  *ns_out = (int64_t)((double)ms * 1e6);
+  // The copy runs 8 workgroups per CU. The read stream's rate depends on how many workgroups share a CU (on the whole GPU
+  // two per CU read a fifth more than eight), and the probe reports what the memory system can give: the best of 2, 4 and 8.
+  // Its sink is the first word of the copy's destination buffer.
+  float best_ms = 0.f;
+  for (int per_cu : {8, 4, 2}) {
+    const int grid = cus * per_cu;
+    auto launch = [&]() { return read_only ? read_probe(st, c->probe_src, bytes, reinterpret_cast<unsigned*>(c->probe_dst), grid)
+                                           : copy_probe(st, c->probe_dst, c->probe_src, bytes, grid); };
+    HIPCK(launch());   // warm-up
+    HIPCK(hipEventRecord(ev.e0, st));
+    for (int i = 0; i < iters; i++) HIPCK(launch());
+    HIPCK(hipEventRecord(ev.e1, st));
+    HIPCK(hipEventSynchronize(ev.e1));
+    float ms = 0.f;
+    HIPCK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
+    if (best_ms == 0.f || ms < best_ms) best_ms = ms;
+    if (!read_only) break;
+  }
+  *ns_out = (int64_t)((double)best_ms * 1e6);
   return STS_OK;
+}
+extern "C" int sts_probe_copy(sts_ctx* c, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out) {
+  return probe_stream(c, side, cus, bytes, iters, ns_out, false);
+}
+extern "C" int sts_probe_read(sts_ctx* c, int32_t side, int32_t cus, size_t bytes, int32_t iters, int64_t* ns_out) {
+  return probe_stream(c, side, cus, bytes, iters, ns_out, true);
 }

@@ -92,6 +92,7 @@ hipError_t reduce_swiglu(hipStream_t s, bf16* H, const float* partials, int spli
 hipError_t reduce_f32(hipStream_t s, float* out, const float* partials, int splits, long long split_stride, size_t n);
 hipError_t argmax_rows(hipStream_t s, int* out, const float* logits, int n, int vocab);
 hipError_t copy_probe(hipStream_t s, void* dst, const void* src, size_t bytes, int grid);
+hipError_t read_probe(hipStream_t s, const void* src, size_t bytes, unsigned* sink, int grid);    // the read half alone; sink: 4 bytes of device memory
 hipError_t kv_fill_random(hipStream_t s, bf16* pool, KvGeom geo, const int* block_table, int pos0, int n,
                           uint64_t seed, int layer);
 hipError_t kv_write_tokens(hipStream_t s, bf16* pool, KvGeom geo, const int* block_table, int pos0, int n,

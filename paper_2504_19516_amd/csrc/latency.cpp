@@ -248,11 +248,13 @@ bool parse_profile(const std::string& text, Profile* hw) {
     else if (key == "gemm_rate_128") hw->gemm_rate_128 = v; else if (key == "gemm_rate_256") hw->gemm_rate_256 = v;
     else if (key == "gemm_rate_128x256") hw->gemm_rate_128x256 = v; else if (key == "gemm_fixed_128x256") hw->gemm_fixed_128x256 = v;
     else if (key == "partial_bw_cu") hw->partial_bw_cu = v;
+    else if (key == "stream_bw_cu") hw->stream_bw_cu = v; else if (key == "stream_bw_gpu") hw->stream_bw_gpu = v;
     else return false;
   }
   return header && hw->n_cu > 0 && hw->granule > 0 && hw->c_peak > 0 && hw->d_peak > 0 && hw->n_d > 0 && hw->tile_m > 0 &&
          hw->tile_n > 0 && hw->tile_q > 0 && hw->wgs_per_cu > 0 && hw->tail_cut >= 0 && hw->tail_cut <= 64 &&
-         hw->gemm_rate_128 > 0 && hw->gemm_rate_256 > 0 && hw->gemm_rate_128x256 > 0 && hw->gemm_fixed_128x256 >= 0 && hw->partial_bw_cu > 0;
+         hw->gemm_rate_128 > 0 && hw->gemm_rate_256 > 0 && hw->gemm_rate_128x256 > 0 && hw->gemm_fixed_128x256 >= 0 && hw->partial_bw_cu > 0 &&
+         hw->stream_bw_cu > 0 && hw->stream_bw_gpu >= hw->stream_bw_cu;
 }
 
 static void dump_grid(std::ostringstream& o, const char* name, const Grid& g) {
@@ -266,7 +268,8 @@ std::string dump_profile(const Profile& hw) {
   o << "sts-profile 1\n";
   o << "n_cu " << hw.n_cu << "\ngranule " << hw.granule << "\nc_peak " << hw.c_peak << "\nd_peak " << hw.d_peak << "\nn_d " << hw.n_d
     << "\ntile_m " << hw.tile_m << "\ntile_n " << hw.tile_n << "\ntile_q " << hw.tile_q << "\nwgs_per_cu " << hw.wgs_per_cu << "\nuse_waveq " << hw.use_waveq << "\ntail_cut " << hw.tail_cut
-    << "\ngemm_rate_128 " << hw.gemm_rate_128 << "\ngemm_rate_256 " << hw.gemm_rate_256 << "\ngemm_rate_128x256 " << hw.gemm_rate_128x256 << "\ngemm_fixed_128x256 " << hw.gemm_fixed_128x256 << "\npartial_bw_cu " << hw.partial_bw_cu << "\n";
+    << "\ngemm_rate_128 " << hw.gemm_rate_128 << "\ngemm_rate_256 " << hw.gemm_rate_256 << "\ngemm_rate_128x256 " << hw.gemm_rate_128x256 << "\ngemm_fixed_128x256 " << hw.gemm_fixed_128x256 << "\npartial_bw_cu " << hw.partial_bw_cu
+    << "\nstream_bw_cu " << hw.stream_bw_cu << "\nstream_bw_gpu " << hw.stream_bw_gpu << "\n";
   dump_grid(o, "bw", hw.bw);
   dump_grid(o, "prefill_corun", hw.prefill_corun);
   dump_grid(o, "alpha_prefill", hw.alpha_prefill);
@@ -299,6 +302,12 @@ extern "C" int sts_profile_tile_model(const sts_profile* p, int64_t* gemm_rate_1
   if (gemm_rate_128x256) *gemm_rate_128x256 = p->hw.gemm_rate_128x256;
   if (gemm_fixed_128x256) *gemm_fixed_128x256 = p->hw.gemm_fixed_128x256;
   if (partial_bw_cu) *partial_bw_cu = p->hw.partial_bw_cu;
+  return STS_OK;
+}
+extern "C" int sts_profile_stream_model(const sts_profile* p, int64_t* stream_bw_cu, int64_t* stream_bw_gpu) {
+  if (!p) return STS_EINVAL;
+  if (stream_bw_cu) *stream_bw_cu = p->hw.stream_bw_cu;
+  if (stream_bw_gpu) *stream_bw_gpu = p->hw.stream_bw_gpu;
   return STS_OK;
 }
 extern "C" int sts_profile_parse(const char* text, sts_profile** out) {

@@ -26,6 +26,8 @@ struct Profile {
   // read back. The 128x256 tile runs one per CU, so its start-up and epilogue are not hidden behind another workgroup:
   // its time is gemm_fixed_128x256 ns plus the flops at gemm_rate_128x256.
   int64_t gemm_rate_128 = 3500, gemm_rate_256 = 4800, gemm_rate_128x256 = 5000, gemm_fixed_128x256 = 25000, partial_bw_cu = 20000;
+  // MB/s of a plain read-only stream: per CU of a 32-CU partition, and of the whole GPU (the decode GEMM planner's rates)
+  int64_t stream_bw_cu = 59000, stream_bw_gpu = 6400000;
   Grid bw;                             // D_{p,sl}; empty = use D_peak min(1, N_p/N_d)
   Grid prefill_corun;                  // slowdown (ppm, over the decode CUs beside it) of a prefill slice that shares HBM with a
                                        // running decode step; empty = none. Section 3.2.3 measures this side of the contention as

@@ -22,7 +22,7 @@ PPM = 1_000_000
 def profile_text(hw: dict, grids: dict) -> str:
     lines = ["sts-profile 1"]
     for k in ("n_cu", "granule", "c_peak", "d_peak", "n_d", "tile_m", "tile_n", "tile_q", "wgs_per_cu", "use_waveq", "tail_cut",
-              "gemm_rate_128", "gemm_rate_256", "gemm_rate_128x256", "gemm_fixed_128x256", "partial_bw_cu"):
+              "gemm_rate_128", "gemm_rate_256", "gemm_rate_128x256", "gemm_fixed_128x256", "partial_bw_cu", "stream_bw_cu", "stream_bw_gpu"):
         lines.append(f"{k} {int(hw[k])}")
     for name in ("bw", "prefill_corun", "alpha_prefill", "alpha_decode"):
         if name not in grids:
@@ -46,7 +46,8 @@ class Profiler:
         self.n_cu = self.eng.get_partition()[2]
         self.hw = dict(n_cu=self.n_cu, granule=granule, c_peak=2_500_000, d_peak=8_000, n_d=self.n_cu, tile_m=128, tile_n=128,
                        tile_q=128, wgs_per_cu=2, use_waveq=1, tail_cut=16,
-                       gemm_rate_128=3500, gemm_rate_256=4800, gemm_rate_128x256=5000, gemm_fixed_128x256=25000, partial_bw_cu=20000)      # the library's defaults until measured
+                       gemm_rate_128=3500, gemm_rate_256=4800, gemm_rate_128x256=5000, gemm_fixed_128x256=25000, partial_bw_cu=20000,
+                       stream_bw_cu=59000, stream_bw_gpu=6400000)      # the library's defaults until measured
         self.max_tokens = max_tokens
         self.grids = {}
 
@@ -180,6 +181,14 @@ class Profiler:
         log(f"partial tiles: {self.hw['partial_bw_cu'] / 1e3:.1f} GB/s per CU (copy probe on {cus} CUs)")
         self.eng.set_tile_model(self.hw["gemm_rate_128"], self.hw["gemm_rate_256"], self.hw["gemm_rate_128x256"], self.hw["gemm_fixed_128x256"],
                                 self.hw["partial_bw_cu"])
+        # what a read-only stream reaches on a small decode partition (per CU) and on the whole GPU: the decode GEMM planner's rates
+        small = min(32, self.n_cu)
+        nbytes, iters = 512 << 20, 5
+        per_cu = nbytes * iters / self.eng.probe_read(1, small, nbytes, iters) / small * 1e3          # bytes/ns -> MB/s, per CU
+        whole = nbytes * iters / self.eng.probe_read(1, self.n_cu, nbytes, iters) * 1e3
+        self.hw["stream_bw_cu"], self.hw["stream_bw_gpu"] = int(per_cu), int(max(whole, per_cu))
+        log(f"read-only stream: {per_cu / 1e3:.1f} GB/s per CU on {small} CUs, {whole / 1e6:.2f} TB/s on {self.n_cu} CUs")
+        self.eng.set_stream_model(self.hw["stream_bw_cu"], self.hw["stream_bw_gpu"])
 
     def sweep_contention(self, dms=(32, 64, 128, 192), sls=(0, 2048, 8192), log=print):
         vals = [[int(self.corun_copy_bw(dm, sl)) for sl in sls] for dm in dms]

@@ -56,6 +56,7 @@ class LiveServer:
                               max_prefill_tokens=max_batch_tokens, max_prefill_seqs=64, max_decode_batch=max_decode_batch,
                               max_seqs=4096, max_pages_per_seq=(max_ctx + PAGE - 1) // PAGE)
         self.eng.set_tile_model(*self.profile.tile_model())      # the GEMM tile choice uses the rates measured for this profile
+        self.eng.set_stream_model(*self.profile.stream_model())  # ... and the decode GEMM planner its read-stream rates
         self.n_cu = self.eng.get_partition()[2]
         self.max_ctx = max_ctx
         # Live-mode replay (Algorithm 1's decisions must be reproducible from a per-cycle log): when this is a

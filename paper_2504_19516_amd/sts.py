@@ -93,7 +93,7 @@ EXPORTS = [
     "sts_set_partition", "sts_get_partition", "sts_kernel_timing", "sts_kernel_times", "sts_kernel_name",
     "sts_probe_copy", "sts_profile_observe", "sts_op_gemm", "sts_op_attn_prefill", "sts_op_attn_decode", "sts_wave_quant",
     "sts_profile_parse", "sts_profile_load", "sts_profile_dump", "sts_profile_free", "sts_latency_query",
-    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_decode_gemm_plan", "sts_op_gemm_noalloc", "sts_weight_packed_index", "sts_probe_gemm", "sts_set_tile_model",
+    "sts_latency_roofline", "sts_sched_decide", "sts_sched_replay", "sts_max_pages_per_seq_limit", "sts_decode_chunk_plan", "sts_decode_gemm_plan", "sts_probe_read", "sts_set_stream_model", "sts_profile_stream_model", "sts_op_gemm_noalloc", "sts_weight_packed_index", "sts_probe_gemm", "sts_set_tile_model",
     "sts_profile_tile_model",
 ]
 
@@ -309,6 +309,9 @@ class Engine:
         _ck(lib().sts_set_tile_model(self._ctx, C.c_int64(int(gemm_rate_128)), C.c_int64(int(gemm_rate_256)), C.c_int64(int(gemm_rate_128x256)),
                                      C.c_int64(int(gemm_fixed_128x256)), C.c_int64(int(partial_bw_cu))), "sts_set_tile_model")
 
+    def set_stream_model(self, stream_bw_cu, stream_bw_gpu):
+        _ck(lib().sts_set_stream_model(self._ctx, C.c_int64(int(stream_bw_cu)), C.c_int64(int(stream_bw_gpu))), "sts_set_stream_model")
+
     def probe_gemm(self, cus, tile_cfg, m, n, iters=10, product="gateup"):
         ns = C.c_int64()
         _ck(lib().sts_probe_gemm(self._ctx, cus, GEMM_CFGS[tile_cfg], {"gateup": 0, "o": 1, "down": 2}[product], m, n, iters, C.byref(ns)),
@@ -331,6 +334,11 @@ class Engine:
     def probe_copy(self, side, cus, nbytes, iters):
         ns = C.c_int64()
         _ck(lib().sts_probe_copy(self._ctx, side, cus, C.c_size_t(nbytes), iters, C.byref(ns)), "sts_probe_copy")
+        return ns.value
+
+    def probe_read(self, side, cus, nbytes, iters):
+        ns = C.c_int64()
+        _ck(lib().sts_probe_read(self._ctx, side, cus, C.c_size_t(nbytes), iters, C.byref(ns)), "sts_probe_read")
         return ns.value
 
 
@@ -388,11 +396,13 @@ def decode_chunk_plan(n_pages, n_kv_heads, cus, page_tokens, max_pages_per_seq):
     return cp.value, mc.value, ac.value
 
 
-def decode_gemm_plan(m, n, k, cus, may_split=True, partials=True, gemm_rate_256=4967, partial_bw_cu=22504):
+def decode_gemm_plan(m, n, k, cus, may_split=True, partials=True, gemm_rate_256=4967, partial_bw_cu=22504, stream_bw_cu=59000,
+                     stream_bw_gpu=6400000):
     """(tile configuration name, split along K, estimated ns) of a decode-side GEMM; host only."""
     cfg, sp, ns = C.c_int32(), C.c_int32(), C.c_int64()
     _ck(lib().sts_decode_gemm_plan(m, n, k, cus, int(may_split), int(partials), C.c_int64(int(gemm_rate_256)), C.c_int64(int(partial_bw_cu)),
-                                   C.byref(cfg), C.byref(sp), C.byref(ns)), "sts_decode_gemm_plan")
+                                   C.c_int64(int(stream_bw_cu)), C.c_int64(int(stream_bw_gpu)), C.byref(cfg), C.byref(sp), C.byref(ns)),
+        "sts_decode_gemm_plan")
     name = {v: k_ for k_, v in GEMM_CFGS.items()}[cfg.value]
     return name, sp.value, ns.value
 
@@ -420,6 +430,11 @@ class Profile:
     def tile_model(self):
         v = [C.c_int64() for _ in range(5)]
         _ck(lib().sts_profile_tile_model(self._p, *[C.byref(x) for x in v]), "sts_profile_tile_model")
+        return tuple(x.value for x in v)
+
+    def stream_model(self):
+        v = [C.c_int64() for _ in range(2)]
+        _ck(lib().sts_profile_stream_model(self._p, *[C.byref(x) for x in v]), "sts_profile_stream_model")
         return tuple(x.value for x in v)
 
     def dump(self) -> str:

@@ -635,6 +635,12 @@ def test_profiler_builds_a_profile_the_estimator_loads(sts):
         assert table in text
     prof = sts.Profile(text=text)
     assert prof.dump() == text
+    # the read-only stream probe behind the decode GEMM planner's rates: a CU of a small partition pulls tens of GB/s, the
+    # whole GPU several TB/s and at least what 32 CUs do; the copy probe over the same buffer moves no more bytes per ns
+    per_cu, whole = prof.stream_model()
+    assert 20_000 < per_cu < 150_000 and 32 * per_cu <= whole * 1.05 and 2_000_000 < whole < 8_000_000
+    nb = 256 << 20
+    assert nb * 3 / pr.eng.probe_read(1, 256, nb, 3) > 0.9 * nb * 3 / pr.eng.probe_copy(1, 256, nb, 3)
     ns, layers = pr.prefill_ns(256, 1024)
     pred = prof.query(desc, dict(prefill_len=[1024], prefill_ctx=[0], prefill_cus=256, decode_cus=0, layer_begin=0, n_layers_step=layers))[0]
     assert 0.6 < pred / ns < 1.6

@@ -283,7 +283,14 @@ def test_decode_gemm_plan_fits_tiles_to_the_partition():
     t32, t256 = sts.decode_gemm_plan(64, 28672, 4096, 32)[2], sts.decode_gemm_plan(64, 28672, 4096, 256)[2]
     assert t32 > 2.5 * t256 and t256 >= 2 * 28672 * 4096 / 5.5e12 * 1e9
     assert sts.decode_gemm_plan(200, 28672, 4096, 32)[0] in ("128x128", "256x256")
+    # the estimate follows the measured stream rates it is given: half the per-CU rate doubles a small partition's time,
+    # and a whole GPU is held to the memory system's rate
+    slow = sts.decode_gemm_plan(64, 28672, 4096, 32, stream_bw_cu=29500)[2]
+    assert 1.7 * t32 < slow < 2.1 * t32
+    assert sts.decode_gemm_plan(64, 28672, 4096, 256, stream_bw_gpu=3200000)[2] > 1.5 * t256
     for bad in ((64, 100, 4096, 32), (64, 4096, 100, 32), (0, 4096, 4096, 32), (64, 4096, 4096, 0)):
         with pytest.raises(sts.StsError) as e:
             sts.decode_gemm_plan(*bad)
         assert e.value.code == sts.EINVAL
+    with pytest.raises(sts.StsError):
+        sts.decode_gemm_plan(64, 4096, 4096, 32, stream_bw_cu=0)
