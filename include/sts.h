@@ -246,7 +246,8 @@ int64_t sts_weight_packed_index(int32_t row, int32_t col, int32_t ld);
 enum { STS_GEMM_128x128 = 0 /* 4 waves, two workgroups per CU */, STS_GEMM_64x256 /* 8 waves */, STS_GEMM_64x128 /* 4 waves, two per CU */,
        STS_GEMM_256x256 /* 8 waves */, STS_GEMM_128x256 /* 4 waves, planned one per CU; no SwiGLU epilogue */,
        /* decode batches: 64-row tiles of 4 to 8 waves, 64 columns per wave, the weights of the library's packed
-          layout streamed straight into registers (no row-major form: sts_op_gemm_noalloc rejects them) */
+          layout streamed straight into registers (no row-major form: sts_op_gemm_noalloc rejects them; whole tiles
+          only: tail_slots is ignored) */
        STS_GEMM_64x256S /* two workgroups per CU */, STS_GEMM_64x320S, STS_GEMM_64x384S, STS_GEMM_64x448S, STS_GEMM_64x512S };
 int sts_op_gemm(const float* a, const float* w, float* c_inout, int32_t m, int32_t n, int32_t k,
                 int32_t tile_cfg, int32_t epilogue, int32_t split_k, int32_t tail_slots);
